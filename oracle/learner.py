@@ -1,0 +1,66 @@
+"""CPU oracle: one PPO minibatch step of the VER learner, end to end.
+
+TEST INFRASTRUCTURE ONLY.  Chains the oracle's parts in the order of the
+paper's learning phase (section 2.2): advantages once per rollout, then for
+every minibatch: cut it out of the randomly ordered sequences, run the
+recurrent policy over each of its pieces, evaluate the PPO loss, and
+back-propagate through time.  Nothing in the product path may import this
+file.
+"""
+import numpy as np
+
+from . import lstm, pack, ppo_loss
+
+
+def minibatch_step(rollout_fields, weights, meta, cfg, adv, ret, logp_old, h0=None, c0=None,
+                   weight=None, want_dx=False):
+    """One minibatch: forward, loss, backward.
+
+    rollout_fields: dict with flat per-step "obs" [S, D] and "actions".
+    meta: result of pack.pack_minibatch.  adv, ret, logp_old: flat [S].
+    cfg: dict with dist, clip, value_coef, entropy_coef.
+    Returns dict: u, v (packed rows), scalars, d_u, d_v, grads (incl. log_std), d_x.
+    """
+    w64 = lstm.weights_f64(weights)
+    gidx = meta["gather_idx"]
+    fwd = lstm.minibatch_forward(rollout_fields["obs"], meta["seq_first"], meta["seq_len"], w64, h0, c0)
+    u = lstm.to_packed([f[0] for f in fwd], meta["t_off"])
+    v = lstm.to_packed([f[1] for f in fwd], meta["t_off"])
+    scalars, d_u, d_v, d_log_std = ppo_loss.ppo_loss(
+        cfg["dist"], u, v, w64["log_std"], pack.gather_rows(rollout_fields["actions"], gidx),
+        pack.gather_rows(logp_old, gidx), pack.gather_rows(adv, gidx), pack.gather_rows(ret, gidx),
+        cfg["clip"], cfg["value_coef"], cfg["entropy_coef"],
+        None if weight is None else pack.gather_rows(weight, gidx))
+    grads = lstm.zero_grads(w64)
+    du_pieces = lstm.from_packed(d_u, meta["t_off"], meta["seq_len"])
+    dv_pieces = lstm.from_packed(d_v, meta["t_off"], meta["seq_len"])
+    dx_pieces = []
+    for j in range(meta["n_seq"]):
+        dx_pieces.append(lstm.piece_backward(du_pieces[j], dv_pieces[j], w64, fwd[j][2], grads))
+    grads["log_std"] = d_log_std
+    out = {"u": u, "v": v, "scalars": scalars, "d_u": d_u, "d_v": d_v, "grads": grads}
+    if want_dx:
+        out["d_x"] = lstm.to_packed(dx_pieces, meta["t_off"])
+    return out
+
+
+def collection_logp(rollout_fields, weights, dones, env_off, dist, env_started_episode=None,
+                    rnn_h=None, rnn_c=None):
+    """Log-probability of every stored action under `weights`, evaluated over
+    whole sequences (what the policy assigned when the step was collected).
+    Used by tests to build logp_old; returns flat [S] fp64."""
+    w64 = lstm.weights_f64(weights)
+    first, length, ep_start = pack.find_sequences(dones, env_off, env_started_episode)
+    S = int(env_off[-1])
+    logp = np.zeros(S)
+    h0 = c0 = None
+    if rnn_h is not None:
+        h0 = pack.initial_states(rnn_h, first, ep_start)
+        c0 = pack.initial_states(rnn_c, first, ep_start)
+    fwd = lstm.minibatch_forward(rollout_fields["obs"], first, length, w64, h0, c0)
+    for j, (f0, n) in enumerate(zip(first, length)):
+        u = fwd[j][0]
+        for t in range(n):
+            logp[f0 + t] = ppo_loss.row_logp_entropy(dist, u[t], rollout_fields["actions"][f0 + t],
+                                                     w64["log_std"])[0]
+    return logp

@@ -1,0 +1,76 @@
+"""End-to-end pin of the oracle's minibatch step on the Tiny workload: the
+same chain rebuilt from library parts (packed-sequence LSTM, distributions,
+autograd).  CPU only."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gae as ogae, learner, pack, lstm
+from paper_2210_05064_amd import workloads as wl
+
+
+@pytest.mark.parametrize("name,dist,A", [("tiny", 0, 4), ("tiny", 1, 3)])
+def test_minibatch_step_against_library_chain(name, dist, A):
+    w = wl.scaled(wl.WORKLOADS[name], dist=dist, act_dim=A, hidden=16, input_dim=8, n_layers=2, minibatches=2)
+    ro = wl.make_rollout(w, seed=11, bias_scale=0.2)
+    adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
+    logp_old = learner.collection_logp(ro, ro["weights"], ro["dones"], ro["env_off"], dist,
+                                       ro["env_started_episode"], ro["rnn_h"], ro["rnn_c"]) + ro["logp_noise"]
+    cfg = dict(dist=dist, clip=w.clip, value_coef=w.value_coef, entropy_coef=0.01)
+    for b in range(2):
+        meta = pack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][0], 2, b, ro["env_started_episode"])
+        h0 = pack.initial_states(ro["rnn_h"], meta["seq_first"], meta["seq_is_ep_start"])
+        c0 = pack.initial_states(ro["rnn_c"], meta["seq_first"], meta["seq_is_ep_start"])
+        out = learner.minibatch_step(ro, ro["weights"], meta, cfg, adv, ret, logp_old, h0, c0, want_dx=True)
+
+        W = lstm.weights_f64(ro["weights"])
+        net = torch.nn.LSTM(w.input_dim, w.hidden, w.n_layers).double()
+        with torch.no_grad():
+            for l, lw in enumerate(W["layers"]):
+                getattr(net, f"weight_ih_l{l}").copy_(torch.from_numpy(lw["W_ih"]))
+                getattr(net, f"weight_hh_l{l}").copy_(torch.from_numpy(lw["W_hh"]))
+                getattr(net, f"bias_ih_l{l}").copy_(torch.from_numpy(lw["b_ih"]))
+                getattr(net, f"bias_hh_l{l}").copy_(torch.from_numpy(lw["b_hh"]))
+        heads = {k: torch.tensor(W[k], requires_grad=True) for k in ("W_a", "b_a", "w_v", "b_v", "log_std")}
+        g = torch.from_numpy(meta["gather_idx"].astype(np.int64))
+        x = torch.tensor(ro["obs"].astype(np.float64))[g].requires_grad_(True)
+        ps = torch.nn.utils.rnn.PackedSequence(x, torch.from_numpy(meta["batch_sizes"].astype(np.int64)))
+        y, _ = net(ps, (torch.tensor(h0.astype(np.float64)), torch.tensor(c0.astype(np.float64))))
+        h = y.data                                              # packed rows, same order as ours
+        u = h @ heads["W_a"].T + heads["b_a"]
+        v = h @ heads["w_v"] + heads["b_v"]
+        act = torch.from_numpy(ro["actions"])[g]
+        if dist == 0:
+            pi = torch.distributions.Categorical(logits=u)
+            logp, ent = pi.log_prob(act.long()), pi.entropy()
+        else:
+            pi = torch.distributions.Normal(u, heads["log_std"].exp())
+            logp, ent = pi.log_prob(act.double()).sum(-1), pi.entropy().sum(-1)
+        ratio = (logp - torch.tensor(logp_old)[g]).exp()
+        a, r = torch.tensor(adv)[g], torch.tensor(ret)[g]
+        total = (-torch.min(ratio * a, ratio.clamp(1 - w.clip, 1 + w.clip) * a).mean()
+                 + w.value_coef * (0.5 * (v - r) ** 2).mean() - 0.01 * ent.mean())
+        total.backward()
+        assert abs(out["scalars"]["total"] - total.item()) < 1e-12
+        np.testing.assert_allclose(out["u"], u.detach().numpy(), atol=1e-12)
+        np.testing.assert_allclose(out["d_x"], x.grad.numpy(), atol=1e-12)
+        for l in range(w.n_layers):
+            for ours, theirs in (("W_ih", "weight_ih"), ("W_hh", "weight_hh"), ("b_ih", "bias_ih"), ("b_hh", "bias_hh")):
+                np.testing.assert_allclose(out["grads"]["layers"][l][ours],
+                                           getattr(net, f"{theirs}_l{l}").grad.numpy(), atol=1e-12)
+        for k in ("W_a", "b_a", "w_v", "b_v"):
+            np.testing.assert_allclose(out["grads"][k], heads[k].grad.numpy(), atol=1e-12)
+        if dist == 1:
+            np.testing.assert_allclose(out["grads"]["log_std"], heads["log_std"].grad.numpy(), atol=1e-12)
+
+
+def test_workload_generator_shapes():
+    for name, w in wl.WORKLOADS.items():
+        rng = np.random.default_rng(1)
+        L = wl.env_lengths(w, rng)
+        assert len(L) == w.n_envs and L.min() >= 1
+        if w.budget:
+            assert L.sum() == w.budget
+        assert L.sum() % w.minibatches == 0
+    L = wl.apportion_steps(10, np.array([1.0, 1.0, 2.0]))
+    assert L.tolist() == [3, 3, 4]
