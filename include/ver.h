@@ -1,0 +1,271 @@
+/*
+ * ver.h - C ABI of the VER learner step on one MI355X (gfx950).
+ *
+ * The library computes the learning phase of Variable Experience Rollout
+ * (paper section 2.2) for a recurrent actor-critic trained with PPO:
+ *
+ *     ver_gae              once per rollout
+ *     for every epoch, for every minibatch b:
+ *         ver_pack_minibatch -> ver_lstm_fwd -> ver_ppo_loss -> ver_lstm_bwd
+ *
+ * Conventions that hold for every entry point
+ *  - "device" pointers are HIP device memory owned by the caller; "host"
+ *    pointers are ordinary host memory.  The library never allocates, frees or
+ *    keeps a pointer after the call returns, and never synchronises the
+ *    stream: all work is enqueued on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream) and the call returns at once.
+ *  - Scratch memory comes from a caller-provided device `workspace` of at
+ *    least the size the matching *_workspace_bytes() query returns; its
+ *    contents need not be initialised and are undefined afterwards, except
+ *    that ver_lstm_bwd must be given the workspace ver_lstm_fwd filled.
+ *  - Return value: VER_OK or a negative code.  Arguments are checked on the
+ *    host only (null pointers, negative or inconsistent sizes); values that
+ *    live in device memory (done flags, offsets) are not validated.
+ *  - Rollout buffer layout (paper section 2.2: N environments contribute
+ *    S = T x N steps in total, L_i >= 0 from environment i): flat step
+ *    k = env_off[i] + t is step t of environment i; env_off[N+1] is the
+ *    exclusive prefix sum of L, env_off[N] = S.  dones[k] = 1 means the
+ *    episode ended WITH step k.
+ *  - Packed layout (paper section 2.2, "Batching computation for learning",
+ *    figure 2C): the M rows of a minibatch are time-major; timestep t holds
+ *    batch_sizes[t] rows starting at row t_off[t]; row j of timestep t
+ *    continues row j of timestep t-1 (pieces are ordered longest first).
+ */
+#ifndef VER_H
+#define VER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    VER_OK = 0,
+    VER_EINVAL = -1,       /* null pointer, negative size, b outside [0,B), B does not divide S ... */
+    VER_EWORKSPACE = -2,   /* workspace missing or too small */
+    VER_EUNSUPPORTED = -3, /* shape outside what the kernels handle (see each call) */
+    VER_EHIP = -4          /* a HIP call or kernel launch failed */
+};
+
+/* Text for a status code; never NULL.  Host only. */
+const char* ver_status_string(int status);
+
+/* ------------------------------------------------------------------------
+ * ver_gae - advantages and value targets over the ragged buffer.
+ * Paper: section 4 "Training" (PPO with Generalized Advantage Estimation),
+ * hyper-parameter table (gamma 0.99, lambda 0.95); ragged stretches and
+ * episode ends inside them from section 2.2 / figure 2B.
+ *
+ * Per environment i, backwards over its stretch, with nd = 1 - dones[k]:
+ *     delta_k = rewards[k] + gamma * nd * V_next - values[k]
+ *     adv[k]  = delta_k + gamma * lambda * nd * adv_next
+ *     ret[k]  = adv[k] + values[k]
+ * where V_next / adv_next are values[k+1] / adv[k+1] inside the stretch and
+ * last_values[i] / 0 after its last step.  No normalisation.
+ *
+ * All pointers device.  rewards, values, adv, ret: float[S]; dones: uint8[S];
+ * last_values: float[N]; env_off: int32[N+1].  S = 0 is legal (no work).
+ * Output is deterministic (no atomics on floats).
+ */
+size_t ver_gae_workspace_bytes(int32_t S);
+int ver_gae(const float* rewards, const float* values, const uint8_t* dones,
+            const float* last_values, const int32_t* env_off, int32_t N, int32_t S,
+            float gamma, float lambda, float* adv, float* ret,
+            void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * ver_pack_minibatch - VER minibatch creation + packed-sequence layout.
+ * Paper: section 2.2 "Learning mini-batch creation" (sequences start at a
+ * stretch start or after an episode end; randomly ordered; the first S/B
+ * steps form minibatch 0, the next S/B minibatch 1, ...) and "Batching
+ * computation for learning" (all elements of a timestep contiguous).
+ *
+ * Rule implemented (the parts the paper leaves open are fixed as follows):
+ *  1. sequences are discovered in (environment, time) order; that order is
+ *     the sequence id;
+ *  2. random order = ascending (seq_key[first step of the sequence], id);
+ *     seq_key holds one caller-drawn 32-bit key per step, only keys at
+ *     sequence heads are read;
+ *  3. the sequences laid end to end form a stream of S steps; minibatch b
+ *     is stream positions [b*M, (b+1)*M), M = S/B; a sequence crossing a
+ *     cut is split, the tail piece is not an episode start;
+ *  4. pieces of the minibatch are ordered longest first, ties by stream
+ *     position;
+ *  5. a piece is an episode start if it begins right after a done step, or
+ *     begins a stretch whose env_started_episode[i] is non-zero.
+ *
+ * Index outputs (device, caller sizes them for the upper bound M):
+ *   info[4]            n_seq, T_max, K (sequences in the whole buffer), 0
+ *   seq_first[M]       flat step of each piece's first step
+ *   seq_len[M]         piece lengths (non-increasing)
+ *   seq_is_ep_start[M] uint8
+ *   batch_sizes[M]     rows per timestep (entries >= T_max are zero)
+ *   t_off[M+1]         exclusive prefix sum of batch_sizes (entries > T_max = M)
+ *   gather_idx[M]      packed row -> flat step
+ * Only the first n_seq (resp. T_max) entries carry pieces (timesteps).
+ *
+ * Optional gathers, each skipped when its source or destination is NULL:
+ *   obs[S,D] float        -> obs_packed[M,D]  float, or bf16 when obs_packed_bf16 != 0
+ *   actions[S,act_bytes]  -> actions_packed[M,act_bytes]   (raw bytes per step)
+ *   logp_old/adv/ret[S]   -> *_packed[M]
+ *   rnn_h/rnn_c[n_layers,S,H] (state each layer had BEFORE step k at
+ *   collection time) -> h0/c0[n_layers,seq_cap,H]: row j = state of piece j's
+ *   first step, zeros if the piece is an episode start.  seq_cap >= n_seq
+ *   must hold (M always suffices); rows >= n_seq are left untouched.
+ *
+ * Errors: VER_EINVAL if B <= 0, b outside [0,B), B does not divide S, or a
+ * required pointer is NULL.  Integer outputs are bit-reproducible.
+ */
+typedef struct {
+    /* rollout buffer */
+    const uint8_t* dones;               /* [S] */
+    const int32_t* env_off;             /* [N+1] */
+    const uint8_t* env_started_episode; /* [N] or NULL (= all 0) */
+    const uint32_t* seq_key;            /* [S] */
+    int32_t N, S, B, b;
+    /* index outputs */
+    int32_t* info;
+    int32_t* seq_first;
+    int32_t* seq_len;
+    uint8_t* seq_is_ep_start;
+    int32_t* batch_sizes;
+    int32_t* t_off;
+    int32_t* gather_idx;
+    /* optional gathers */
+    const float* obs;
+    int32_t D;
+    void* obs_packed;
+    int32_t obs_packed_bf16;
+    const void* actions;
+    int32_t act_bytes;
+    void* actions_packed;
+    const float* logp_old;
+    const float* adv;
+    const float* ret;
+    float* logp_old_packed;
+    float* adv_packed;
+    float* ret_packed;
+    const float* rnn_h;
+    const float* rnn_c;
+    int32_t n_layers, H, seq_cap;
+    float* h0;
+    float* c0;
+    /* scratch */
+    void* workspace;
+    size_t workspace_bytes;
+} ver_pack_args;
+
+size_t ver_pack_workspace_bytes(int32_t N, int32_t S, int32_t B);
+int ver_pack_minibatch(const ver_pack_args* args /* host */, void* stream);
+
+/* ------------------------------------------------------------------------
+ * ver_lstm_fwd / ver_lstm_bwd - multi-layer LSTM actor-critic over a packed
+ * minibatch, and back-propagation through time.
+ * Paper: section 4 "Architecture" and section 3 (embedding joined with the
+ * state vector -> 2-layer LSTM -> action distribution and value); sequences
+ * for back-propagation through time from section 2.2.
+ *
+ * Cell (gate order i, f, g, o; two bias vectors; no peepholes/projection):
+ *     z = W_ih x_t + b_ih + W_hh h_{t-1} + b_hh
+ *     c_t = sigm(z_f) * c_{t-1} + sigm(z_i) * tanh(z_g);  h_t = sigm(z_o) * tanh(c_t)
+ * Layer l+1 reads h_t of layer l.  Heads on the top layer:
+ *     head_out = W_a h + b_a  [act_dim],   value = w_v . h + b_v.
+ *
+ * cfg.compute: 0 = all contractions in fp32 (fp32 MFMA); 1 = operands of the
+ * contractions rounded to bf16 (round to nearest even), accumulation, biases,
+ * gate non-linearities, cell state, saved activations and all outputs fp32.
+ * cfg.x_bf16: x_packed holds bf16 (only with compute = 1) instead of float.
+ *
+ * weights (host array of 4*n_layers + 4 device pointers, all float):
+ *   per layer l: W_ih[4H, D_l], W_hh[4H, H], b_ih[4H], b_hh[4H]  (D_0 = input_dim, D_l = H)
+ *   then W_a[act_dim, H], b_a[act_dim], w_v[H], b_v[1].
+ * weight_grads: same order and shapes; OVERWRITTEN with the gradient of the
+ * minibatch loss (not accumulated).
+ *
+ * info, batch_sizes, t_off: as written by ver_pack_minibatch (device; the
+ * kernels read n_seq and T_max from info on the device, so no host round trip
+ * is needed between pack and the LSTM).  h0, c0: float[n_layers, seq_cap, H]
+ * initial state per piece, or NULL for zeros.
+ * head_out: float[M, act_dim]; value: float[M].
+ * ver_lstm_bwd: d_head_out[M, act_dim], d_value[M] are the loss gradients
+ * (e.g. from ver_ppo_loss); d_x: float[M, input_dim] or NULL.  It must be
+ * called with the same cfg, M, metadata, x_packed, h0/c0, weights and
+ * workspace as the forward call it differentiates.
+ *
+ * Errors: VER_EUNSUPPORTED unless hidden is a multiple of 64, 64 <= hidden
+ * <= 2048, input_dim a multiple of 4, 1 <= n_layers <= 8, 1 <= act_dim <= 63.
+ * workspace word 0 (int32) is non-zero after the stream has drained if a
+ * device-side wait timed out (should never happen; results are then
+ * undefined).  Outputs are deterministic.
+ */
+typedef struct {
+    int32_t n_layers;
+    int32_t input_dim;
+    int32_t hidden;
+    int32_t act_dim;
+    int32_t compute;
+    int32_t x_bf16;
+} ver_lstm_cfg;
+
+size_t ver_lstm_workspace_bytes(const ver_lstm_cfg* cfg, int32_t M);
+int ver_lstm_fwd(const ver_lstm_cfg* cfg, const void* x_packed, int32_t M,
+                 const int32_t* info, const int32_t* batch_sizes, const int32_t* t_off,
+                 const float* h0, const float* c0, int32_t seq_cap,
+                 const float* const* weights /* host array */,
+                 float* head_out, float* value,
+                 void* workspace, size_t workspace_bytes, void* stream);
+int ver_lstm_bwd(const ver_lstm_cfg* cfg, const void* x_packed, int32_t M,
+                 const int32_t* info, const int32_t* batch_sizes, const int32_t* t_off,
+                 const float* h0, const float* c0, int32_t seq_cap,
+                 const float* const* weights /* host array */,
+                 const float* d_head_out, const float* d_value,
+                 float* const* weight_grads /* host array */, float* d_x,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * ver_ppo_loss - fused PPO loss and its gradient w.r.t. the heads' outputs.
+ * Paper: section 2.2 "Learning method" (PPO); hyper-parameter table: clip
+ * 0.2, value coefficient 0.5, no clipped value loss, no advantage
+ * normalisation; fixed entropy coefficient 1e-4 for benchmarks (appendix,
+ * "Hyperparamaters"); categorical or independent-Gaussian actions
+ * (section 4 "Architecture").
+ *
+ * Per packed row p (w_p = is_weight[p], 1 when is_weight is NULL):
+ *   categorical (dist 0): logp = head_out[p, a_p] - logsumexp(head_out[p, :]),
+ *       entropy of softmax(head_out[p, :]); actions int32[M]
+ *   Gaussian (dist 1): mean = head_out[p, :], std = exp(log_std), independent
+ *       dims; actions float[M, act_dim]
+ *   rho = exp(logp - logp_old[p])
+ *   l_pi = -min(rho * adv, clamp(rho, 1-clip, 1+clip) * adv);  l_v = 0.5 * (value - ret)^2
+ * total = mean(w l_pi) + value_coef * mean(w l_v) - entropy_coef * mean(w entropy),
+ * means over the M rows.  The gradient through min/clamp follows the selected
+ * branch; the unclipped branch wins ties.
+ *
+ * scalars (device float[6]): total, policy, value, entropy (mean),
+ * approx_kl = mean(logp_old - logp), clip_frac = mean(|rho - 1| > clip).
+ * d_head_out[M, act_dim], d_value[M], d_log_std[act_dim] (Gaussian only, may
+ * be NULL for categorical): gradient of total.  Reductions are done in a
+ * fixed order: results are bit-reproducible.  M = 0 is VER_EINVAL.
+ */
+typedef struct {
+    float clip;
+    float value_coef;
+    float entropy_coef;
+    int32_t dist;     /* 0 categorical, 1 diagonal Gaussian */
+    int32_t act_dim;  /* 1..63 */
+} ver_ppo_cfg;
+
+size_t ver_ppo_loss_workspace_bytes(int32_t M, int32_t act_dim);
+int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M,
+                 const float* head_out, const float* value, const float* log_std,
+                 const void* actions_packed, const float* logp_old, const float* adv,
+                 const float* ret, const float* is_weight,
+                 float* scalars, float* d_head_out, float* d_value, float* d_log_std,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VER_H */

@@ -1,0 +1,184 @@
+"""ctypes binding of libver.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/ver.h) and
+takes torch tensors that already live on the GPU; nothing is computed here and
+there is no fallback: importing this module without the built library raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libver.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2210_05064_amd.build` "
+                      "(or __graft_entry__.build()) first; there is no CPU fallback")
+lib = C.CDLL(LIB_PATH)
+
+VER_OK = 0
+_vp, _i32, _sz, _f = C.c_void_p, C.c_int32, C.c_size_t, C.c_float
+
+
+class PackArgs(C.Structure):
+    _fields_ = [
+        ("dones", _vp), ("env_off", _vp), ("env_started_episode", _vp), ("seq_key", _vp),
+        ("N", _i32), ("S", _i32), ("B", _i32), ("b", _i32),
+        ("info", _vp), ("seq_first", _vp), ("seq_len", _vp), ("seq_is_ep_start", _vp),
+        ("batch_sizes", _vp), ("t_off", _vp), ("gather_idx", _vp),
+        ("obs", _vp), ("D", _i32), ("obs_packed", _vp), ("obs_packed_bf16", _i32),
+        ("actions", _vp), ("act_bytes", _i32), ("actions_packed", _vp),
+        ("logp_old", _vp), ("adv", _vp), ("ret", _vp),
+        ("logp_old_packed", _vp), ("adv_packed", _vp), ("ret_packed", _vp),
+        ("rnn_h", _vp), ("rnn_c", _vp), ("n_layers", _i32), ("H", _i32), ("seq_cap", _i32),
+        ("h0", _vp), ("c0", _vp),
+        ("workspace", _vp), ("workspace_bytes", _sz),
+    ]
+
+
+class LstmCfg(C.Structure):
+    _fields_ = [("n_layers", _i32), ("input_dim", _i32), ("hidden", _i32), ("act_dim", _i32),
+                ("compute", _i32), ("x_bf16", _i32)]
+
+
+class PpoCfg(C.Structure):
+    _fields_ = [("clip", _f), ("value_coef", _f), ("entropy_coef", _f), ("dist", _i32), ("act_dim", _i32)]
+
+
+lib.ver_status_string.restype = C.c_char_p
+lib.ver_status_string.argtypes = [C.c_int]
+lib.ver_gae_workspace_bytes.restype = _sz
+lib.ver_gae_workspace_bytes.argtypes = [_i32]
+lib.ver_gae.restype = C.c_int
+lib.ver_gae.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _f, _f, _vp, _vp, _vp, _sz, _vp]
+lib.ver_pack_workspace_bytes.restype = _sz
+lib.ver_pack_workspace_bytes.argtypes = [_i32, _i32, _i32]
+lib.ver_pack_minibatch.restype = C.c_int
+lib.ver_pack_minibatch.argtypes = [C.POINTER(PackArgs), _vp]
+lib.ver_lstm_workspace_bytes.restype = _sz
+lib.ver_lstm_workspace_bytes.argtypes = [C.POINTER(LstmCfg), _i32]
+lib.ver_lstm_fwd.restype = C.c_int
+lib.ver_lstm_fwd.argtypes = [C.POINTER(LstmCfg), _vp, _i32, _vp, _vp, _vp, _vp, _vp, _i32,
+                             C.POINTER(_vp), _vp, _vp, _vp, _sz, _vp]
+lib.ver_lstm_bwd.restype = C.c_int
+lib.ver_lstm_bwd.argtypes = [C.POINTER(LstmCfg), _vp, _i32, _vp, _vp, _vp, _vp, _vp, _i32,
+                             C.POINTER(_vp), _vp, _vp, C.POINTER(_vp), _vp, _vp, _sz, _vp]
+lib.ver_ppo_loss_workspace_bytes.restype = _sz
+lib.ver_ppo_loss_workspace_bytes.argtypes = [_i32, _i32]
+lib.ver_ppo_loss.restype = C.c_int
+lib.ver_ppo_loss.argtypes = [C.POINTER(PpoCfg), _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                             _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+
+
+class VerError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"libver: {lib.ver_status_string(status).decode()} ({status})")
+
+
+def _check(status: int) -> None:
+    if status != VER_OK:
+        raise VerError(status)
+
+
+def _ptr(t) -> int | None:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ws(ws):
+    return (_ptr(ws), ws.numel() * ws.element_size()) if ws is not None else (None, 0)
+
+
+def ver_status_string(status: int) -> str:
+    return lib.ver_status_string(status).decode()
+
+
+def ver_gae_workspace_bytes(S: int) -> int:
+    return lib.ver_gae_workspace_bytes(S)
+
+
+def ver_gae(rewards, values, dones, last_values, env_off, N, S, gamma, lam, adv, ret, workspace):
+    p, n = _ws(workspace)
+    _check(lib.ver_gae(_ptr(rewards), _ptr(values), _ptr(dones), _ptr(last_values), _ptr(env_off),
+                       N, S, gamma, lam, _ptr(adv), _ptr(ret), p, n, _stream()))
+
+
+def ver_pack_workspace_bytes(N: int, S: int, B: int) -> int:
+    return lib.ver_pack_workspace_bytes(N, S, B)
+
+
+def ver_pack_minibatch(**kw):
+    """Keyword arguments are the fields of ver_pack_args; tensors or ints."""
+    a = PackArgs()
+    names = {f[0] for f in PackArgs._fields_}
+    for k, v in kw.items():
+        if k not in names:
+            raise TypeError(f"unknown ver_pack_args field {k}")
+        if k == "workspace":
+            a.workspace, a.workspace_bytes = _ws(v)
+        elif isinstance(v, torch.Tensor):
+            setattr(a, k, _ptr(v))
+        elif v is not None:
+            setattr(a, k, v)
+    _check(lib.ver_pack_minibatch(C.byref(a), _stream()))
+
+
+def _ptr_array(tensors):
+    arr = (_vp * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def lstm_cfg(n_layers, input_dim, hidden, act_dim, compute=0, x_bf16=0) -> LstmCfg:
+    return LstmCfg(n_layers, input_dim, hidden, act_dim, compute, x_bf16)
+
+
+def ver_lstm_workspace_bytes(cfg: LstmCfg, M: int) -> int:
+    return lib.ver_lstm_workspace_bytes(C.byref(cfg), M)
+
+
+def ver_lstm_fwd(cfg, x_packed, M, info, batch_sizes, t_off, h0, c0, seq_cap, weights, head_out, value,
+                 workspace):
+    p, n = _ws(workspace)
+    _check(lib.ver_lstm_fwd(C.byref(cfg), _ptr(x_packed), M, _ptr(info), _ptr(batch_sizes), _ptr(t_off),
+                            _ptr(h0), _ptr(c0), seq_cap, _ptr_array(weights), _ptr(head_out), _ptr(value),
+                            p, n, _stream()))
+
+
+def ver_lstm_bwd(cfg, x_packed, M, info, batch_sizes, t_off, h0, c0, seq_cap, weights, d_head_out, d_value,
+                 weight_grads, d_x, workspace):
+    p, n = _ws(workspace)
+    _check(lib.ver_lstm_bwd(C.byref(cfg), _ptr(x_packed), M, _ptr(info), _ptr(batch_sizes), _ptr(t_off),
+                            _ptr(h0), _ptr(c0), seq_cap, _ptr_array(weights), _ptr(d_head_out), _ptr(d_value),
+                            _ptr_array(weight_grads), _ptr(d_x), p, n, _stream()))
+
+
+def ppo_cfg(clip, value_coef, entropy_coef, dist, act_dim) -> PpoCfg:
+    return PpoCfg(clip, value_coef, entropy_coef, dist, act_dim)
+
+
+def ver_ppo_loss_workspace_bytes(M: int, act_dim: int) -> int:
+    return lib.ver_ppo_loss_workspace_bytes(M, act_dim)
+
+
+def ver_ppo_loss(cfg, M, head_out, value, log_std, actions_packed, logp_old, adv, ret, is_weight,
+                 scalars, d_head_out, d_value, d_log_std, workspace):
+    p, n = _ws(workspace)
+    _check(lib.ver_ppo_loss(C.byref(cfg), M, _ptr(head_out), _ptr(value), _ptr(log_std), _ptr(actions_packed),
+                            _ptr(logp_old), _ptr(adv), _ptr(ret), _ptr(is_weight), _ptr(scalars),
+                            _ptr(d_head_out), _ptr(d_value), _ptr(d_log_std), p, n, _stream()))
+
+
+def workspace(n_bytes: int) -> torch.Tensor:
+    """Device scratch of at least n_bytes (torch owns the memory)."""
+    return torch.empty(max(1, (n_bytes + 3) // 4), dtype=torch.int32, device="cuda")

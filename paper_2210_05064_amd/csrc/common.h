@@ -1,0 +1,64 @@
+// Shared host/device helpers of the VER learner kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/ver.h"
+
+#define VER_WAVE 64
+
+namespace ver {
+
+inline int launch_status() {
+    return hipGetLastError() == hipSuccess ? VER_OK : VER_EHIP;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Bump allocator over a caller-provided workspace; every block 256-byte aligned.
+struct Carver {
+    char* base;
+    size_t used;
+    explicit Carver(void* p) : base(static_cast<char*>(p)), used(0) {}
+    template <typename T>
+    T* take(size_t n) {
+        T* p = reinterpret_cast<T*>(base + used);
+        used += align_up(n * sizeof(T), 256);
+        return p;
+    }
+};
+
+// Loads/stores that are coherent across the whole device (all XCDs): used for
+// data exchanged between workgroups inside one kernel.
+__device__ __forceinline__ int ld_agent(const int* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_agent(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(int* p, int v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_agent(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void fence_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+__device__ __forceinline__ void fence_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
+
+// Largest i in [0, n) with off[i] <= k, given off[0] <= k < off[n] (off non-decreasing).
+__device__ __forceinline__ int segment_of(const int32_t* __restrict__ off, int n, int k) {
+    int lo = 0, hi = n;  // invariant: off[lo] <= k < off[hi]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (off[mid] <= k) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Fills n 32-bit words with v (used instead of memset nodes so that callers may
+// capture the stream into a graph).
+__global__ void fill_words_kernel(int32_t* p, size_t n, int32_t v);
+void fill_words(int32_t* p, size_t n, int32_t v, hipStream_t s);
+
+}  // namespace ver

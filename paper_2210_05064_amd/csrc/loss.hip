@@ -1,0 +1,224 @@
+// ver_ppo_loss: PPO clipped surrogate + value + entropy loss over the packed
+// rows of a minibatch, its six scalars and the gradient w.r.t. the heads'
+// outputs, in ONE kernel (plus a tiny counter reset).
+//
+// Paper: section 2.2 "Learning method" (PPO), appendix hyper-parameter table
+// (clip 0.2, value coefficient 0.5, no clipped value loss, no advantage
+// normalisation) and the fixed entropy coefficient of the benchmark runs.
+//
+// One thread owns a row: it reads the row's head outputs, action, old
+// log-probability, advantage and return once, writes the row's gradients once
+// (56 B/row categorical-4, 156 B/row Gaussian-11: HBM bound).  Sums are reduced
+// wave -> workgroup -> per-workgroup partials in the workspace; the workgroup
+// that finishes last adds the partials in index order, so the result does not
+// depend on scheduling.
+#include "common.h"
+
+namespace ver {
+namespace {
+
+constexpr int LOSS_THREADS = 256;
+constexpr int LOSS_MAX_BLOCKS = 1024;
+constexpr int LOSS_SCALARS = 5;  // policy, value, entropy, kl, clipped count
+constexpr float HALF_LOG_2PI = 0.91893853320467274178f;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int d = VER_WAVE / 2; d > 0; d >>= 1) v += __shfl_down(v, d, VER_WAVE);
+    return v;  // valid in lane 0
+}
+
+// Sum over the workgroup, valid in thread 0.  s_red has one slot per wave.
+__device__ __forceinline__ float block_sum(float v, float* s_red) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & (VER_WAVE - 1), wave = threadIdx.x / VER_WAVE;
+    __syncthreads();  // s_red may still be read from the previous call
+    if (lane == 0) s_red[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+    if (threadIdx.x == 0)
+        for (int w = 0; w < LOSS_THREADS / VER_WAVE; ++w) t += s_red[w];
+    return t;
+}
+
+template <int DIST>
+__global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
+    ver_ppo_cfg cfg, int M, const float* __restrict__ u, const float* __restrict__ value,
+    const float* __restrict__ log_std, const void* __restrict__ actions,
+    const float* __restrict__ logp_old, const float* __restrict__ adv, const float* __restrict__ ret,
+    const float* __restrict__ is_weight, float* __restrict__ scalars, float* __restrict__ d_u,
+    float* __restrict__ d_value, float* __restrict__ d_log_std, float* __restrict__ partials,
+    int* __restrict__ counter) {
+    __shared__ float s_red[LOSS_THREADS / VER_WAVE];
+    __shared__ float s_ls[64], s_inv_sigma[64];
+    __shared__ int s_last;
+    __shared__ float s_hand, s_out[LOSS_SCALARS];
+    const int A = cfg.act_dim;
+    const int width = LOSS_SCALARS + (DIST == 1 ? A : 0);  // partial sums per workgroup
+    const float inv_m = 1.f / (float)M;
+    if (DIST == 1) {
+        if (threadIdx.x < A) {
+            s_ls[threadIdx.x] = log_std[threadIdx.x];
+            s_inv_sigma[threadIdx.x] = expf(-log_std[threadIdx.x]);
+        }
+        __syncthreads();
+    }
+
+    float acc[LOSS_SCALARS] = {0.f, 0.f, 0.f, 0.f, 0.f};
+    const int stride = gridDim.x * LOSS_THREADS;
+    // Rows are visited in rounds so that the Gaussian log-std sums can be reduced round by round.
+    const int rounds = (M + stride - 1) / stride;
+    float* my_partial = partials + (size_t)blockIdx.x * width;
+    float ls_acc = 0.f;  // thread d < A of the workgroup accumulates dimension d
+    for (int round = 0; round < rounds; ++round) {
+        const int p = round * stride + blockIdx.x * LOSS_THREADS + threadIdx.x;
+        const bool live = p < M;
+        float coef_logp = 0.f, coef_ent = 0.f;
+        const float* up = u + (size_t)(live ? p : 0) * A;
+        if (live) {
+            const float w = is_weight ? is_weight[p] : 1.f;
+            float logp, ent;
+            if (DIST == 0) {
+                const int a = static_cast<const int32_t*>(actions)[p];
+                float mx = up[0];
+                for (int j = 1; j < A; ++j) mx = fmaxf(mx, up[j]);
+                float se = 0.f;
+                for (int j = 0; j < A; ++j) se += expf(up[j] - mx);
+                const float lse = mx + logf(se);
+                logp = up[a] - lse;
+                ent = 0.f;
+                for (int j = 0; j < A; ++j) {
+                    const float lq = up[j] - lse;
+                    ent -= expf(lq) * lq;
+                }
+                const float rho = expf(logp - logp_old[p]);
+                const float adv_p = adv[p];
+                const float s1 = rho * adv_p;
+                const float s2 = fminf(fmaxf(rho, 1.f - cfg.clip), 1.f + cfg.clip) * adv_p;
+                coef_logp = (s1 <= s2) ? -w * adv_p * rho * inv_m : 0.f;
+                coef_ent = -cfg.entropy_coef * w * inv_m;
+                float* dp = d_u + (size_t)p * A;
+                for (int j = 0; j < A; ++j) {
+                    const float lq = up[j] - lse;
+                    const float q = expf(lq);
+                    dp[j] = coef_logp * ((j == a ? 1.f : 0.f) - q) - coef_ent * q * (lq + ent);
+                }
+                acc[0] += -w * fminf(s1, s2);
+                acc[3] += logp_old[p] - logp;
+                acc[4] += (fabsf(rho - 1.f) > cfg.clip) ? 1.f : 0.f;
+            } else {
+                const float* ap = static_cast<const float*>(actions) + (size_t)p * A;
+                logp = 0.f;
+                ent = 0.f;
+                for (int d = 0; d < A; ++d) {
+                    const float zed = (ap[d] - up[d]) * s_inv_sigma[d];
+                    logp += -0.5f * zed * zed - s_ls[d] - HALF_LOG_2PI;
+                    ent += s_ls[d] + 0.5f + HALF_LOG_2PI;
+                }
+                const float rho = expf(logp - logp_old[p]);
+                const float adv_p = adv[p];
+                const float s1 = rho * adv_p;
+                const float s2 = fminf(fmaxf(rho, 1.f - cfg.clip), 1.f + cfg.clip) * adv_p;
+                coef_logp = (s1 <= s2) ? -w * adv_p * rho * inv_m : 0.f;
+                coef_ent = -cfg.entropy_coef * w * inv_m;
+                float* dp = d_u + (size_t)p * A;
+                for (int d = 0; d < A; ++d)
+                    dp[d] = coef_logp * (ap[d] - up[d]) * s_inv_sigma[d] * s_inv_sigma[d];
+                acc[0] += -w * fminf(s1, s2);
+                acc[3] += logp_old[p] - logp;
+                acc[4] += (fabsf(rho - 1.f) > cfg.clip) ? 1.f : 0.f;
+            }
+            const float dv = value[p] - ret[p];
+            acc[1] += w * 0.5f * dv * dv;
+            acc[2] += w * ent;
+            d_value[p] = cfg.value_coef * w * dv * inv_m;
+        }
+        if (DIST == 1) {
+            // d total / d log_std[d] = sum_rows coef_logp * (zed^2 - 1) + coef_ent
+            const float* ap = static_cast<const float*>(actions) + (size_t)(live ? p : 0) * A;
+            for (int d = 0; d < A; ++d) {
+                float term = 0.f;
+                if (live) {
+                    const float zed = (ap[d] - up[d]) * s_inv_sigma[d];
+                    term = coef_logp * (zed * zed - 1.f) + coef_ent;
+                }
+                const float t = block_sum(term, s_red);
+                if (threadIdx.x == 0) s_hand = t;
+                __syncthreads();
+                if (threadIdx.x == d) ls_acc += s_hand;
+            }
+        }
+    }
+    for (int q = 0; q < LOSS_SCALARS; ++q) {
+        const float t = block_sum(acc[q], s_red);
+        if (threadIdx.x == 0) my_partial[q] = t;
+    }
+    if (DIST == 1 && threadIdx.x < A) my_partial[LOSS_SCALARS + threadIdx.x] = ls_acc;
+
+    // Last workgroup to arrive adds the partials in index order.
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = (atomicAdd(counter, 1) == (int)gridDim.x - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    if (threadIdx.x < width) {
+        float t = 0.f;
+        for (int g = 0; g < (int)gridDim.x; ++g) t += ld_agent(&partials[(size_t)g * width + threadIdx.x]);
+        if (threadIdx.x < LOSS_SCALARS) s_out[threadIdx.x] = t * inv_m;  // means
+        else d_log_std[threadIdx.x - LOSS_SCALARS] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const float pol = s_out[0], val = s_out[1], ent = s_out[2];
+        scalars[0] = pol + cfg.value_coef * val - cfg.entropy_coef * ent;
+        scalars[1] = pol;
+        scalars[2] = val;
+        scalars[3] = ent;
+        scalars[4] = s_out[3];
+        scalars[5] = s_out[4];
+        *counter = 0;
+    }
+}
+
+inline int loss_blocks(int M) {
+    int b = (M + LOSS_THREADS - 1) / LOSS_THREADS;
+    return b > LOSS_MAX_BLOCKS ? LOSS_MAX_BLOCKS : b;
+}
+
+}  // namespace
+}  // namespace ver
+
+extern "C" size_t ver_ppo_loss_workspace_bytes(int32_t M, int32_t act_dim) {
+    if (M <= 0 || act_dim <= 0) return 0;
+    return 256 + ver::align_up((size_t)ver::loss_blocks(M) * (ver::LOSS_SCALARS + act_dim) * 4, 256);
+}
+
+extern "C" int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M, const float* head_out, const float* value,
+                            const float* log_std, const void* actions_packed, const float* logp_old,
+                            const float* adv, const float* ret, const float* is_weight, float* scalars,
+                            float* d_head_out, float* d_value, float* d_log_std, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    if (!cfg || M <= 0 || !head_out || !value || !actions_packed || !logp_old || !adv || !ret || !scalars ||
+        !d_head_out || !d_value)
+        return VER_EINVAL;
+    if (cfg->dist != 0 && cfg->dist != 1) return VER_EINVAL;
+    if (cfg->act_dim < 1 || cfg->act_dim > 63) return VER_EUNSUPPORTED;
+    if (cfg->dist == 1 && (!log_std || !d_log_std)) return VER_EINVAL;
+    if (!workspace || workspace_bytes < ver_ppo_loss_workspace_bytes(M, cfg->act_dim)) return VER_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ver::Carver cv(workspace);
+    int* counter = cv.take<int>(64);
+    float* partials = cv.take<float>((size_t)ver::loss_blocks(M) * (ver::LOSS_SCALARS + cfg->act_dim));
+    ver::fill_words(counter, 1, 0, s);
+    const int blocks = ver::loss_blocks(M);
+    if (cfg->dist == 0)
+        hipLaunchKernelGGL(ver::ppo_loss_kernel<0>, dim3(blocks), dim3(ver::LOSS_THREADS), 0, s, *cfg, M, head_out,
+                           value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out,
+                           d_value, d_log_std, partials, counter);
+    else
+        hipLaunchKernelGGL(ver::ppo_loss_kernel<1>, dim3(blocks), dim3(ver::LOSS_THREADS), 0, s, *cfg, M, head_out,
+                           value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out,
+                           d_value, d_log_std, partials, counter);
+    return ver::launch_status();
+}

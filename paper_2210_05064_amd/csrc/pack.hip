@@ -1,0 +1,386 @@
+// ver_pack_minibatch: VER minibatch creation and the packed-sequence layout.
+//
+// Paper: section 2.2 "Learning mini-batch creation" and "Batching computation
+// for learning" (figure 2B/2C).  The exact rule (sequence discovery, keyed
+// random order, cut into equal step counts with splitting, longest-first
+// order) is stated with the entry point's declaration.
+//
+// Two kernels per call:
+//   pack_index_kernel  one workgroup of 1024 threads builds every integer
+//                      output.  All of it is O(S) byte reads plus work on the
+//                      K sequences / n_seq pieces, far below a microsecond of
+//                      HBM time, so one CU with LDS-staged prefix sums and
+//                      wave ballots beats a multi-launch device-wide version.
+//   pack_gather_kernel one wave per packed row: resolves the row's flat step
+//                      (binary search in t_off) and copies the row's fields
+//                      with 16-byte accesses.  This is the HBM-bound part:
+//                      2*4*D bytes per row (6*D with bf16 output) + small fields.
+#include "common.h"
+
+namespace ver {
+namespace {
+
+constexpr int IDX_THREADS = 1024;
+constexpr int IDX_WAVES = IDX_THREADS / VER_WAVE;
+
+struct PackWs {
+    uint8_t* flags;       // [S] bit0 sequence start, bit1 episode start
+    int32_t* sf;          // [S] first step of sequence id
+    int32_t* sl;          // [S] length of sequence id
+    uint32_t* skey;       // [S] sort key of sequence id
+    int32_t* order;       // [S] sequence id at random-order position r
+    int32_t* sstart;      // [S+1] stream position where position r starts
+    int32_t* pf;          // [M] pieces in stream order: first step
+    int32_t* plen;        // [M] length
+    uint8_t* peps;        // [M] episode start
+};
+
+// Inclusive scan over the workgroup; returns this thread's inclusive value and
+// the workgroup total through *total.  s_w needs IDX_WAVES + 1 ints.
+__device__ __forceinline__ int block_scan_incl(int v, int* s_w, int* total) {
+    const int lane = threadIdx.x & (VER_WAVE - 1), wave = threadIdx.x / VER_WAVE;
+#pragma unroll
+    for (int d = 1; d < VER_WAVE; d <<= 1) {
+        int up = __shfl_up(v, d, VER_WAVE);
+        if (lane >= d) v += up;
+    }
+    __syncthreads();  // protect s_w from the previous use
+    if (lane == VER_WAVE - 1) s_w[wave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int w = 0; w < IDX_WAVES; ++w) {
+            int t = s_w[w];
+            s_w[w] = run;
+            run += t;
+        }
+        s_w[IDX_WAVES] = run;
+    }
+    __syncthreads();
+    *total = s_w[IDX_WAVES];
+    return v + s_w[wave];
+}
+
+__global__ __launch_bounds__(IDX_THREADS) void pack_index_kernel(
+    const uint8_t* __restrict__ dones, const int32_t* __restrict__ env_off,
+    const uint8_t* __restrict__ env_started_episode, const uint32_t* __restrict__ seq_key,
+    int N, int S, int B, int b, PackWs ws, int32_t* __restrict__ info, int32_t* __restrict__ seq_first,
+    int32_t* __restrict__ seq_len, uint8_t* __restrict__ seq_eps, int32_t* __restrict__ batch_sizes,
+    int32_t* __restrict__ t_off) {
+    __shared__ int s_w[IDX_WAVES + 1];
+    __shared__ int s_cnt[IDX_WAVES + 1];
+    __shared__ uint32_t s_key[IDX_THREADS];
+    __shared__ int s_len[IDX_THREADS];
+    __shared__ int s_misc[4];
+    const int tid = threadIdx.x;
+    const int lane = tid & (VER_WAVE - 1), wave = tid / VER_WAVE;
+    const int M = S / B;
+    const int lo = b * M, hi = lo + M;
+
+    // 1. start flags: the step after an episode end ...
+    for (int k = tid; k < S; k += IDX_THREADS) ws.flags[k] = (k > 0 && dones[k - 1]) ? 3 : 0;
+    __syncthreads();
+    // ... and the first step of every non-empty stretch (whose episode flag comes from the caller)
+    for (int i = tid; i < N; i += IDX_THREADS) {
+        const int k = env_off[i];
+        if (env_off[i + 1] > k)
+            ws.flags[k] = 1 | ((env_started_episode && env_started_episode[i]) ? 2 : 0);
+    }
+    __syncthreads();
+
+    // 2. compaction: each wave owns a contiguous chunk of steps; count with ballots, then place.
+    const int chunk = ((S + IDX_WAVES - 1) / IDX_WAVES + VER_WAVE - 1) / VER_WAVE * VER_WAVE;
+    const int c_lo = min(S, wave * chunk), c_hi = min(S, c_lo + chunk);
+    int cnt = 0;
+    for (int k0 = c_lo; k0 < c_hi; k0 += VER_WAVE) {
+        const int k = k0 + lane;
+        const bool st = k < c_hi && (ws.flags[k] & 1);
+        cnt += __popcll(__ballot(st));
+    }
+    if (lane == 0) s_cnt[wave] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int w = 0; w < IDX_WAVES; ++w) {
+            int t = s_cnt[w];
+            s_cnt[w] = run;
+            run += t;
+        }
+        s_cnt[IDX_WAVES] = run;
+    }
+    __syncthreads();
+    const int K = s_cnt[IDX_WAVES];
+    int base = s_cnt[wave];
+    for (int k0 = c_lo; k0 < c_hi; k0 += VER_WAVE) {
+        const int k = k0 + lane;
+        const bool st = k < c_hi && (ws.flags[k] & 1);
+        const unsigned long long mask = __ballot(st);
+        if (st) {
+            const int id = base + __popcll(mask & ((1ull << lane) - 1ull));
+            ws.sf[id] = k;
+            ws.skey[id] = seq_key[k];
+        }
+        base += __popcll(mask);
+    }
+    __syncthreads();
+    for (int s = tid; s < K; s += IDX_THREADS) ws.sl[s] = ((s + 1 < K) ? ws.sf[s + 1] : S) - ws.sf[s];
+
+    // 3. random order: rank of (key, id) by counting, keys tiled through LDS.
+    for (int s0 = 0; s0 < K; s0 += IDX_THREADS) {
+        const int s = s0 + tid;
+        const uint32_t my = (s < K) ? ws.skey[s] : 0u;
+        int rank = 0;
+        for (int q0 = 0; q0 < K; q0 += IDX_THREADS) {
+            __syncthreads();
+            if (q0 + tid < K) s_key[tid] = ws.skey[q0 + tid];
+            __syncthreads();
+            const int n = min(IDX_THREADS, K - q0);
+            if (s < K)
+                for (int q = 0; q < n; ++q) {
+                    const uint32_t other = s_key[q];
+                    rank += (other < my || (other == my && q0 + q < s)) ? 1 : 0;
+                }
+        }
+        if (s < K) ws.order[rank] = s;
+    }
+    __syncthreads();
+
+    // 4. stream positions: exclusive prefix sum of the lengths in random order, staged in LDS.
+    int run = 0;
+    for (int r0 = 0; r0 < K; r0 += IDX_THREADS) {
+        const int r = r0 + tid;
+        const int len = (r < K) ? ws.sl[ws.order[r]] : 0;
+        int total;
+        const int incl = block_scan_incl(len, s_w, &total);
+        if (r < K) ws.sstart[r] = run + incl - len;
+        run += total;
+    }
+    if (tid == 0) ws.sstart[K] = run;  // == S
+    __syncthreads();
+
+    // 5. pieces of minibatch b, in stream order.
+    int before = 0, inside = 0;  // sequences ending at or before lo; sequences overlapping [lo, hi)
+    for (int r = tid; r < K; r += IDX_THREADS) {
+        const int st = ws.sstart[r], en = ws.sstart[r + 1];
+        before += (en <= lo) ? 1 : 0;
+        inside += (st < hi && en > lo) ? 1 : 0;
+    }
+    int r_lo, n_seq;
+    block_scan_incl(before, s_w, &r_lo);
+    block_scan_incl(inside, s_w, &n_seq);
+    for (int j = tid; j < n_seq; j += IDX_THREADS) {
+        const int r = r_lo + j;
+        const int s = ws.order[r];
+        const int st = ws.sstart[r], en = ws.sstart[r + 1];
+        const int c0 = max(st, lo), c1 = min(en, hi);
+        ws.pf[j] = ws.sf[s] + (c0 - st);
+        ws.plen[j] = c1 - c0;
+        ws.peps[j] = (c0 == st) ? ((ws.flags[ws.sf[s]] >> 1) & 1) : 0;
+    }
+    __syncthreads();
+
+    // 6. longest first, ties in stream order: rank by counting, lengths tiled through LDS.
+    for (int j0 = 0; j0 < n_seq; j0 += IDX_THREADS) {
+        const int j = j0 + tid;
+        const int my = (j < n_seq) ? ws.plen[j] : 0;
+        int rank = 0;
+        for (int q0 = 0; q0 < n_seq; q0 += IDX_THREADS) {
+            __syncthreads();
+            if (q0 + tid < n_seq) s_len[tid] = ws.plen[q0 + tid];
+            __syncthreads();
+            const int n = min(IDX_THREADS, n_seq - q0);
+            if (j < n_seq)
+                for (int q = 0; q < n; ++q) {
+                    const int other = s_len[q];
+                    rank += (other > my || (other == my && q0 + q < j)) ? 1 : 0;
+                }
+        }
+        if (j < n_seq) {
+            seq_first[rank] = ws.pf[j];
+            seq_len[rank] = my;
+            seq_eps[rank] = ws.peps[j];
+        }
+    }
+    __syncthreads();
+    const int t_max = n_seq > 0 ? seq_len[0] : 0;
+
+    // 7. rows per timestep and their offsets.
+    run = 0;
+    for (int t0 = 0; t0 <= M; t0 += IDX_THREADS) {
+        const int t = t0 + tid;
+        int bs = 0;
+        if (t < t_max) {
+            // pieces are sorted by length descending: count those with length > t
+            int a = 0, z = n_seq;  // invariant: seq_len[a-1] > t (or a == 0), seq_len[z] <= t (or z == n_seq)
+            while (a < z) {
+                const int mid = (a + z) >> 1;
+                if (seq_len[mid] > t) a = mid + 1; else z = mid;
+            }
+            bs = a;
+        }
+        int total;
+        const int incl = block_scan_incl(bs, s_w, &total);
+        if (t < M) batch_sizes[t] = bs;
+        if (t <= M) t_off[t] = run + incl - bs;
+        run += total;
+    }
+    if (tid == 0) {
+        info[0] = n_seq;
+        info[1] = t_max;
+        info[2] = K;
+        info[3] = 0;
+    }
+    (void)s_misc;
+}
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ unsigned short f32_to_bf16_rne(float f) {
+    unsigned int u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+
+constexpr int GATHER_THREADS = 256;
+constexpr int GATHER_WAVES = GATHER_THREADS / VER_WAVE;
+
+struct GatherArgs {
+    const int32_t* info;
+    const int32_t* seq_first;
+    const uint8_t* seq_eps;
+    const int32_t* t_off;
+    int32_t* gather_idx;
+    int M, S;
+    const float* obs; int D; void* obs_packed; int obs_bf16;
+    const uint8_t* actions; int act_bytes; uint8_t* actions_packed;
+    const float* logp_old; const float* adv; const float* ret;
+    float* logp_old_packed; float* adv_packed; float* ret_packed;
+    const float* rnn_h; const float* rnn_c; int n_layers, H, seq_cap;
+    float* h0; float* c0;
+};
+
+__global__ __launch_bounds__(GATHER_THREADS) void pack_gather_kernel(GatherArgs g) {
+    const int lane = threadIdx.x & (VER_WAVE - 1);
+    const int p = blockIdx.x * GATHER_WAVES + threadIdx.x / VER_WAVE;  // one wave per packed row
+    if (p >= g.M) return;
+    const int n_seq = g.info[0], t_max = g.info[1];
+    // timestep of row p: t_off[t] <= p < t_off[t+1]
+    int a = 0, z = t_max;  // invariant: t_off[a] <= p < t_off[z]
+    while (z - a > 1) {
+        const int mid = (a + z) >> 1;
+        if (g.t_off[mid] <= p) a = mid; else z = mid;
+    }
+    const int t = a, j = p - g.t_off[a];
+    const int src = g.seq_first[j] + t;
+    if (lane == 0) g.gather_idx[p] = src;
+
+    if (g.obs && g.obs_packed) {
+        const float* in = g.obs + (size_t)src * g.D;
+        if ((g.D & 3) == 0) {
+            const f32x4* in4 = reinterpret_cast<const f32x4*>(in);
+            if (g.obs_bf16) {
+                u16x4* out4 = reinterpret_cast<u16x4*>(static_cast<unsigned short*>(g.obs_packed) + (size_t)p * g.D);
+                for (int i = lane; i < g.D / 4; i += VER_WAVE) {
+                    const f32x4 v = __builtin_nontemporal_load(in4 + i);
+                    u16x4 o;
+                    o.x = f32_to_bf16_rne(v.x); o.y = f32_to_bf16_rne(v.y);
+                    o.z = f32_to_bf16_rne(v.z); o.w = f32_to_bf16_rne(v.w);
+                    out4[i] = o;
+                }
+            } else {
+                f32x4* out4 = reinterpret_cast<f32x4*>(static_cast<float*>(g.obs_packed) + (size_t)p * g.D);
+                for (int i = lane; i < g.D / 4; i += VER_WAVE) out4[i] = __builtin_nontemporal_load(in4 + i);
+            }
+        } else {
+            for (int i = lane; i < g.D; i += VER_WAVE) {
+                if (g.obs_bf16) static_cast<unsigned short*>(g.obs_packed)[(size_t)p * g.D + i] = f32_to_bf16_rne(in[i]);
+                else static_cast<float*>(g.obs_packed)[(size_t)p * g.D + i] = in[i];
+            }
+        }
+    }
+    if (g.actions && g.actions_packed) {
+        const uint8_t* in = g.actions + (size_t)src * g.act_bytes;
+        uint8_t* out = g.actions_packed + (size_t)p * g.act_bytes;
+        if ((g.act_bytes & 3) == 0) {
+            for (int i = lane; i < g.act_bytes / 4; i += VER_WAVE)
+                reinterpret_cast<int32_t*>(out)[i] = reinterpret_cast<const int32_t*>(in)[i];
+        } else {
+            for (int i = lane; i < g.act_bytes; i += VER_WAVE) out[i] = in[i];
+        }
+    }
+    if (lane == 0) {
+        if (g.logp_old && g.logp_old_packed) g.logp_old_packed[p] = g.logp_old[src];
+        if (g.adv && g.adv_packed) g.adv_packed[p] = g.adv[src];
+        if (g.ret && g.ret_packed) g.ret_packed[p] = g.ret[src];
+    }
+    // rows of timestep 0 are the pieces' first steps: fetch their initial recurrent state
+    if (t == 0 && j < n_seq && j < g.seq_cap) {
+        const bool zero = g.seq_eps[j] != 0;
+        for (int l = 0; l < g.n_layers; ++l) {
+            const size_t in_off = ((size_t)l * g.S + src) * g.H, out_off = ((size_t)l * g.seq_cap + j) * g.H;
+            if (g.rnn_h && g.h0)
+                for (int i = lane; i < g.H; i += VER_WAVE) g.h0[out_off + i] = zero ? 0.f : g.rnn_h[in_off + i];
+            if (g.rnn_c && g.c0)
+                for (int i = lane; i < g.H; i += VER_WAVE) g.c0[out_off + i] = zero ? 0.f : g.rnn_c[in_off + i];
+        }
+    }
+}
+
+inline size_t pack_ws_layout(int S, int M, void* base, PackWs* ws) {
+    Carver cv(base);
+    uint8_t* flags = cv.take<uint8_t>((size_t)S);
+    int32_t* sf = cv.take<int32_t>((size_t)S);
+    int32_t* sl = cv.take<int32_t>((size_t)S);
+    uint32_t* skey = cv.take<uint32_t>((size_t)S);
+    int32_t* order = cv.take<int32_t>((size_t)S);
+    int32_t* sstart = cv.take<int32_t>((size_t)S + 1);
+    int32_t* pf = cv.take<int32_t>((size_t)M);
+    int32_t* plen = cv.take<int32_t>((size_t)M);
+    uint8_t* peps = cv.take<uint8_t>((size_t)M);
+    if (ws) *ws = PackWs{flags, sf, sl, skey, order, sstart, pf, plen, peps};
+    return cv.used;
+}
+
+}  // namespace
+}  // namespace ver
+
+extern "C" size_t ver_pack_workspace_bytes(int32_t N, int32_t S, int32_t B) {
+    if (N < 0 || S <= 0 || B <= 0) return 0;
+    return ver::pack_ws_layout(S, S / B, nullptr, nullptr);
+}
+
+extern "C" int ver_pack_minibatch(const ver_pack_args* a, void* stream) {
+    if (!a) return VER_EINVAL;
+    if (a->N <= 0 || a->S <= 0 || a->B <= 0 || a->b < 0 || a->b >= a->B || a->S % a->B != 0) return VER_EINVAL;
+    if (!a->dones || !a->env_off || !a->seq_key || !a->info || !a->seq_first || !a->seq_len ||
+        !a->seq_is_ep_start || !a->batch_sizes || !a->t_off || !a->gather_idx)
+        return VER_EINVAL;
+    if (a->obs && a->obs_packed && a->D <= 0) return VER_EINVAL;
+    if (a->actions && a->actions_packed && a->act_bytes <= 0) return VER_EINVAL;
+    const bool states = (a->rnn_h && a->h0) || (a->rnn_c && a->c0);
+    if (states && (a->n_layers <= 0 || a->H <= 0 || a->seq_cap <= 0)) return VER_EINVAL;
+    if (!a->workspace || a->workspace_bytes < ver_pack_workspace_bytes(a->N, a->S, a->B)) return VER_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int M = a->S / a->B;
+    ver::PackWs ws;
+    ver::pack_ws_layout(a->S, M, a->workspace, &ws);
+    hipLaunchKernelGGL(ver::pack_index_kernel, dim3(1), dim3(ver::IDX_THREADS), 0, s, a->dones, a->env_off,
+                       a->env_started_episode, a->seq_key, a->N, a->S, a->B, a->b, ws, a->info, a->seq_first,
+                       a->seq_len, a->seq_is_ep_start, a->batch_sizes, a->t_off);
+    if (hipGetLastError() != hipSuccess) return VER_EHIP;
+    ver::GatherArgs g;
+    g.info = a->info; g.seq_first = a->seq_first; g.seq_eps = a->seq_is_ep_start; g.t_off = a->t_off;
+    g.gather_idx = a->gather_idx; g.M = M; g.S = a->S;
+    g.obs = a->obs; g.D = a->D; g.obs_packed = a->obs_packed; g.obs_bf16 = a->obs_packed_bf16;
+    g.actions = static_cast<const uint8_t*>(a->actions); g.act_bytes = a->act_bytes;
+    g.actions_packed = static_cast<uint8_t*>(a->actions_packed);
+    g.logp_old = a->logp_old; g.adv = a->adv; g.ret = a->ret;
+    g.logp_old_packed = a->logp_old_packed; g.adv_packed = a->adv_packed; g.ret_packed = a->ret_packed;
+    g.rnn_h = a->rnn_h; g.rnn_c = a->rnn_c; g.n_layers = states ? a->n_layers : 0; g.H = a->H;
+    g.seq_cap = a->seq_cap; g.h0 = a->h0; g.c0 = a->c0;
+    const int blocks = (M + ver::GATHER_WAVES - 1) / ver::GATHER_WAVES;
+    hipLaunchKernelGGL(ver::pack_gather_kernel, dim3(blocks), dim3(ver::GATHER_THREADS), 0, s, g);
+    return ver::launch_status();
+}
