@@ -1,8 +1,398 @@
-// placeholder until the LSTM kernels land
-#include "common.h"
-extern "C" size_t ver_lstm_workspace_bytes(const ver_lstm_cfg*, int32_t) { return 0; }
-extern "C" int ver_lstm_fwd(const ver_lstm_cfg*, const void*, int32_t, const int32_t*, const int32_t*, const int32_t*,
-                 const float*, const float*, int32_t, const float* const*, float*, float*, void*, size_t, void*) { return VER_EUNSUPPORTED; }
-extern "C" int ver_lstm_bwd(const ver_lstm_cfg*, const void*, int32_t, const int32_t*, const int32_t*, const int32_t*,
-                 const float*, const float*, int32_t, const float* const*, const float*, const float*,
-                 float* const*, float*, void*, size_t, void*) { return VER_EUNSUPPORTED; }
+// ver_lstm_fwd / ver_lstm_bwd: multi-layer LSTM actor-critic over a packed
+// minibatch and back-propagation through time.
+//
+// Paper: section 4 "Architecture" (embedding + state vector -> 2-layer LSTM ->
+// action distribution and value), sequences for BPTT from section 2.2.
+//
+// Per layer the work splits into what has no time dependence and what has:
+//   time-batched (one MFMA GEMM over all M rows):  W_ih x_t + b  (forward),
+//       dx = W_ih^T dz, dW_ih = dz^T x, dW_hh = dz^T h_{t-1}     (backward)
+//   sequential (persistent kernel, W_hh resident in LDS): h_{t-1} W_hh^T + gates
+//       (forward), dz_t and W_hh dz_t (backward) - see lstm_rec.h.
+// Internally the 4H gate rows are interleaved (row = unit*4 + gate); user-facing
+// weights and gradients keep the gate-major order i,f,g,o of the declaration.
+#include "lstm_rec.h"
+
+namespace ver {
+namespace {
+
+// ---------------------------------------------------------------- weight preparation
+// dst[q][d] = W[(q%4)*H + q/4][d], optionally also dstT[d][q]; q = unit*4 + gate.
+template <typename E>
+__global__ void prep_matrix_kernel(const float* __restrict__ W, int H, int cols, E* __restrict__ dst,
+                                   E* __restrict__ dstT) {
+    const size_t n = (size_t)4 * H * cols;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const int q = (int)(i / cols), d = (int)(i % cols);
+        const float v = W[((size_t)(q & 3) * H + (q >> 2)) * cols + d];
+        dst[i] = cvt_elem<E>(v);
+    }
+    if (dstT)
+        for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+            const int d = (int)(i / (4 * H)), q = (int)(i % (4 * H));
+            dstT[i] = cvt_elem<E>(W[((size_t)(q & 3) * H + (q >> 2)) * cols + d]);
+        }
+}
+
+__global__ void prep_bias_kernel(const float* __restrict__ b_ih, const float* __restrict__ b_hh, int H,
+                                 float* __restrict__ dst) {
+    const int q = blockIdx.x * blockDim.x + threadIdx.x;
+    if (q < 4 * H) {
+        const int src = (q & 3) * H + (q >> 2);
+        dst[q] = b_ih[src] + b_hh[src];
+    }
+}
+
+// ---------------------------------------------------------------- heads
+__device__ __forceinline__ float wave_sum_all(float v) {
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, VER_WAVE);
+    return v;
+}
+
+// head_out[p][a] = W_a[a] . h[p] + b_a[a];  value[p] = w_v . h[p] + b_v.  One wave per row.
+__global__ __launch_bounds__(256) void heads_fwd_kernel(const float* __restrict__ h, int M, int H, int A,
+                                                        const float* __restrict__ W_a, const float* __restrict__ b_a,
+                                                        const float* __restrict__ w_v, const float* __restrict__ b_v,
+                                                        float* __restrict__ head_out, float* __restrict__ value) {
+    const int lane = threadIdx.x & 63;
+    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (p >= M) return;
+    const float* hp = h + (size_t)p * H;
+    for (int a = 0; a <= A; ++a) {
+        const float* w = (a < A) ? W_a + (size_t)a * H : w_v;
+        float s = 0.f;
+        for (int j = lane; j < H; j += 64) s += hp[j] * w[j];
+        s = wave_sum_all(s);
+        if (lane == 0) {
+            if (a < A) head_out[(size_t)p * A + a] = s + b_a[a];
+            else value[p] = s + b_v[0];
+        }
+    }
+}
+
+// dh[p][j] = sum_a d_u[p][a] W_a[a][j] + d_v[p] w_v[j]; also packs DU[p][0..A] = (d_u[p], d_v[p]).
+__global__ __launch_bounds__(256) void heads_bwd_dh_kernel(const float* __restrict__ d_u, const float* __restrict__ d_v,
+                                                           int M, int H, int A, const float* __restrict__ W_a,
+                                                           const float* __restrict__ w_v, float* __restrict__ dh) {
+    const int lane = threadIdx.x & 63;
+    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (p >= M) return;
+    const float dv = d_v[p];
+    for (int j = lane; j < H; j += 64) {
+        float s = dv * w_v[j];
+        for (int a = 0; a < A; ++a) s += d_u[(size_t)p * A + a] * W_a[(size_t)a * H + j];
+        dh[(size_t)p * H + j] = s;
+    }
+}
+
+// Partial sums over a block of rows: part[rb][a][j] = sum_{p in block rb} du(p,a) * h[p][j], a = 0..A (A = value head).
+constexpr int HW_ROWS = 256;  // rows per row block
+__global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* __restrict__ d_u,
+                                                                  const float* __restrict__ d_v,
+                                                                  const float* __restrict__ h, int M, int H, int A,
+                                                                  float* __restrict__ part) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int rb = blockIdx.y;
+    const int p_lo = rb * HW_ROWS, p_hi = min(M, p_lo + HW_ROWS);
+    if (j >= H) return;
+    for (int a0 = 0; a0 <= A; a0 += 4) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int p = p_lo; p < p_hi; ++p) {
+            const float hv = h[(size_t)p * H + j];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int a = a0 + e;
+                const float g = (a < A) ? d_u[(size_t)p * A + a] : (a == A ? d_v[p] : 0.f);
+                acc[e] += g * hv;
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (a0 + e <= A) part[((size_t)rb * (A + 1) + a0 + e) * H + j] = acc[e];
+    }
+}
+
+__global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __restrict__ part, int n_rb, int H, int A,
+                                                                float* __restrict__ dW_a, float* __restrict__ dw_v) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int a = blockIdx.y;
+    if (j >= H) return;
+    float s = 0.f;
+    for (int rb = 0; rb < n_rb; ++rb) s += part[((size_t)rb * (A + 1) + a) * H + j];
+    if (a < A) dW_a[(size_t)a * H + j] = s; else dw_v[j] = s;
+}
+
+// Column sums of a row-major [rows, cols] matrix in two deterministic stages.
+constexpr int CS_ROWS = 128;
+template <typename E>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const E* __restrict__ X, int rows, int cols, int ld,
+                                                             float* __restrict__ part) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    const int rb = blockIdx.y;
+    if (c >= cols) return;
+    const int r_hi = min(rows, (rb + 1) * CS_ROWS);
+    float s = 0.f;
+    for (int r = rb * CS_ROWS; r < r_hi; ++r) s += cvt_elem<float>(X[(size_t)r * ld + c]);
+    part[(size_t)rb * cols + c] = s;
+}
+// out[perm(c)] (and out2) = sum over row blocks; unperm_h > 0 maps interleaved column c to (c%4)*H + c/4.
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int n_rb, int cols,
+                                                           int unperm_h, float* __restrict__ out,
+                                                           float* __restrict__ out2) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= cols) return;
+    float s = 0.f;
+    for (int rb = 0; rb < n_rb; ++rb) s += part[(size_t)rb * cols + c];
+    const int dst = unperm_h > 0 ? (c & 3) * unperm_h + (c >> 2) : c;
+    out[dst] = s;
+    if (out2) out2[dst] = s;
+}
+
+// ---------------------------------------------------------------- workspace
+struct LayerWs {
+    void* wih;    // [4H, D_l]  operand type, interleaved rows
+    void* wihT;   // [D_l, 4H]
+    void* whh;    // [4H, H]
+    void* whhT;   // [H, 4H]
+    float* bias;  // [4H]
+    float* gates; // [M, 4H]
+    float* c;     // [M, H]
+    float* hout;  // [M, H]
+    void* hprev;  // [M, H] operand type
+};
+struct LstmWs {
+    int* err;          // word 0 of the workspace
+    int* flags;        // [256]
+    LayerWs layer[8];
+    void* dz;          // [M, 4H] operand type
+    float* dh[2];      // [M, H] ping-pong: gradient arriving at a layer's h
+    float* dh_state;   // [M, H]
+    float* dc_state;   // [M, H]
+    float* part;       // partial sums of the two-stage reductions
+    float* db_head;    // [A+1] scratch for bias sums
+    size_t bytes;
+};
+
+inline size_t part_floats(const ver_lstm_cfg& c, int M) {
+    const size_t rb_heads = (size_t)(M + HW_ROWS - 1) / HW_ROWS;
+    const size_t rb_cs = (size_t)(M + CS_ROWS - 1) / CS_ROWS;
+    const size_t a = rb_heads * (c.act_dim + 1) * c.hidden;
+    const size_t b = rb_cs * 4 * c.hidden;
+    const size_t d = rb_cs * (c.act_dim + 1);
+    size_t m = a > b ? a : b;
+    return m > d ? m : d;
+}
+
+inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws) {
+    const size_t es = c.compute ? 2 : 4;
+    const size_t H = c.hidden, Mz = (size_t)M;
+    Carver cv(base);
+    int* head = cv.take<int>(64);
+    ws->err = head;
+    ws->flags = cv.take<int>(256);
+    for (int l = 0; l < c.n_layers; ++l) {
+        const size_t D = l == 0 ? c.input_dim : H;
+        LayerWs& L = ws->layer[l];
+        L.wih = cv.take<char>(4 * H * D * es);
+        L.wihT = cv.take<char>(4 * H * D * es);
+        L.whh = cv.take<char>(4 * H * H * es);
+        L.whhT = cv.take<char>(4 * H * H * es);
+        L.bias = cv.take<float>(4 * H);
+        L.gates = cv.take<float>(Mz * 4 * H);
+        L.c = cv.take<float>(Mz * H);
+        L.hout = cv.take<float>(Mz * H);
+        L.hprev = cv.take<char>(Mz * H * es);
+    }
+    ws->dz = cv.take<char>(Mz * 4 * H * es);
+    ws->dh[0] = cv.take<float>(Mz * H);
+    ws->dh[1] = cv.take<float>(Mz * H);
+    ws->dh_state = cv.take<float>(Mz * H);
+    ws->dc_state = cv.take<float>(Mz * H);
+    ws->part = cv.take<float>(part_floats(c, M));
+    ws->db_head = cv.take<float>(64);
+    ws->bytes = cv.used;
+}
+
+inline int check_cfg(const ver_lstm_cfg* c, int M) {
+    if (!c || M <= 0) return VER_EINVAL;
+    if (c->compute != 0 && c->compute != 1) return VER_EINVAL;
+    if (c->x_bf16 && !c->compute) return VER_EINVAL;
+    if (c->n_layers < 1 || c->n_layers > 8 || c->act_dim < 1 || c->act_dim > 63) return VER_EUNSUPPORTED;
+    if (c->hidden < 64 || c->hidden % 64 != 0 || c->input_dim < 4 || c->input_dim % 4 != 0) return VER_EUNSUPPORTED;
+    // the backward kernel keeps a [16, 4H] slice of W_hh in the 160 KB LDS of a CU
+    if (c->hidden > (c->compute ? 1024 : 512)) return VER_EUNSUPPORTED;
+    return VER_OK;
+}
+
+template <typename K>
+inline bool set_lds(K kernel, size_t bytes) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)bytes) == hipSuccess;
+}
+
+template <int MODE>
+int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, const int32_t* batch_sizes,
+            const int32_t* t_off, const float* h0, const float* c0, int seq_cap, const float* const* w,
+            float* head_out, float* value, LstmWs& ws, hipStream_t s) {
+    typedef typename RecGeom<MODE>::E E;
+    constexpr int MT = MODE == MODE_BF16 ? 4 : 1, KS = MODE == MODE_BF16 ? 1 : 4;
+    const int H = c.hidden, A = c.act_dim;
+    fill_words(ws.err, 1, 0, s);
+    for (int l = 0; l < c.n_layers; ++l) {
+        const int D = l == 0 ? c.input_dim : H;
+        LayerWs& L = ws.layer[l];
+        const float* W_ih = w[4 * l], *W_hh = w[4 * l + 1], *b_ih = w[4 * l + 2], *b_hh = w[4 * l + 3];
+        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, W_ih, H, D, static_cast<E*>(L.wih),
+                           static_cast<E*>(L.wihT));
+        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, W_hh, H, H, static_cast<E*>(L.whh),
+                           static_cast<E*>(L.whhT));
+        hipLaunchKernelGGL(prep_bias_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, b_ih, b_hh, H, L.bias);
+        // time-batched input projection: gates[M, 4H] = x W_ih^T + (b_ih + b_hh), interleaved columns
+        if (l == 0) {
+            if (c.x_bf16)
+                gemm_launch<MODE, bf16_t, E, false>(static_cast<const bf16_t*>(x), D, static_cast<const E*>(L.wih), D,
+                                                    L.gates, 4 * H, M, 4 * H, D, L.bias, 0, s);
+            else
+                gemm_launch<MODE, float, E, false>(static_cast<const float*>(x), D, static_cast<const E*>(L.wih), D,
+                                                   L.gates, 4 * H, M, 4 * H, D, L.bias, 0, s);
+        } else {
+            gemm_launch<MODE, float, E, false>(ws.layer[l - 1].hout, H, static_cast<const E*>(L.wih), H, L.gates,
+                                               4 * H, M, 4 * H, H, L.bias, 0, s);
+        }
+        // sequential part
+        fill_words(ws.flags, 256, 0, s);
+        RecFwdArgs ra;
+        ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
+        ra.gates = L.gates; ra.c = L.c; ra.hout = L.hout; ra.hprev = L.hprev; ra.whh = L.whh;
+        ra.h0 = h0 ? h0 + (size_t)l * seq_cap * H : nullptr;
+        ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
+        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err;
+        const size_t lds = (size_t)16 * MT * (H + RecGeom<MODE>::PAD) * sizeof(E) + (size_t)KS * MT * 64 * 16;
+        if (!set_lds(lstm_rec_fwd_kernel<MODE, MT, KS>, lds)) return VER_EHIP;
+        hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT, KS>), dim3(H / (4 * MT)), dim3(REC_THREADS), lds, s, ra);
+    }
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 3) / 4), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
+                       w[4 * c.n_layers], w[4 * c.n_layers + 1], w[4 * c.n_layers + 2], w[4 * c.n_layers + 3],
+                       head_out, value);
+    return launch_status();
+}
+
+template <int MODE>
+int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, const int32_t* batch_sizes,
+            const int32_t* t_off, const float* c0, int seq_cap, const float* const* w, const float* d_u,
+            const float* d_v, float* const* gw, float* d_x, LstmWs& ws, hipStream_t s) {
+    typedef typename RecGeom<MODE>::E E;
+    const int H = c.hidden, A = c.act_dim, nl = c.n_layers;
+    const float* h_top = ws.layer[nl - 1].hout;
+    // heads
+    hipLaunchKernelGGL(heads_bwd_dh_kernel, dim3((M + 3) / 4), dim3(256), 0, s, d_u, d_v, M, H, A, w[4 * nl],
+                       w[4 * nl + 2], ws.dh[0]);
+    const int rb_h = (M + HW_ROWS - 1) / HW_ROWS;
+    hipLaunchKernelGGL(heads_wgrad_partial_kernel, dim3((H + 255) / 256, rb_h), dim3(256), 0, s, d_u, d_v, h_top, M, H,
+                       A, ws.part);
+    hipLaunchKernelGGL(heads_wgrad_final_kernel, dim3((H + 255) / 256, A + 1), dim3(256), 0, s, ws.part, rb_h, H, A,
+                       gw[4 * nl], gw[4 * nl + 2]);
+    const int rb_c = (M + CS_ROWS - 1) / CS_ROWS;
+    hipLaunchKernelGGL(colsum_partial_kernel<float>, dim3((A + 255) / 256, rb_c), dim3(256), 0, s, d_u, M, A, A,
+                       ws.part);
+    hipLaunchKernelGGL(colsum_final_kernel, dim3((A + 255) / 256), dim3(256), 0, s, ws.part, rb_c, A, 0, gw[4 * nl + 1],
+                       (float*)nullptr);
+    hipLaunchKernelGGL(colsum_partial_kernel<float>, dim3(1, rb_c), dim3(256), 0, s, d_v, M, 1, 1, ws.part);
+    hipLaunchKernelGGL(colsum_final_kernel, dim3(1), dim3(256), 0, s, ws.part, rb_c, 1, 0, gw[4 * nl + 3],
+                       (float*)nullptr);
+
+    int cur = 0;  // ws.dh[cur] holds the gradient arriving at the current layer's h
+    for (int l = nl - 1; l >= 0; --l) {
+        const int D = l == 0 ? c.input_dim : H;
+        LayerWs& L = ws.layer[l];
+        fill_words(ws.flags, 256, 0, s);
+        RecBwdArgs ra;
+        ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
+        ra.gates = L.gates; ra.c = L.c; ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
+        ra.dh_above = ws.dh[cur]; ra.dz = ws.dz; ra.whhT = L.whhT;
+        ra.dh_state = ws.dh_state; ra.dc_state = ws.dc_state;
+        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err;
+        const size_t lds = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E) + (size_t)4 * 64 * 16;
+        if (!set_lds(lstm_rec_bwd_kernel<MODE>, lds)) return VER_EHIP;
+        hipLaunchKernelGGL(lstm_rec_bwd_kernel<MODE>, dim3(H / 16), dim3(REC_THREADS), lds, s, ra);
+
+        const E* dz = static_cast<const E*>(ws.dz);
+        // gradient w.r.t. the layer input: dx[M, D] = dz[M, 4H] . W_ih[4H, D]
+        float* dx = l > 0 ? ws.dh[cur ^ 1] : d_x;
+        if (dx)
+            gemm_launch<MODE, E, E, false>(dz, 4 * H, static_cast<const E*>(L.wihT), 4 * H, dx, D, M, D, 4 * H,
+                                           nullptr, 0, s);
+        // dW_ih[4H, D] = dz^T x ; dW_hh[4H, H] = dz^T h_{t-1}; stored gate-major
+        if (l > 0)
+            gemm_launch<MODE, E, float, true>(dz, 4 * H, ws.layer[l - 1].hout, H, gw[4 * l], D, 4 * H, D, M, nullptr, H, s);
+        else if (c.x_bf16)
+            gemm_launch<MODE, E, bf16_t, true>(dz, 4 * H, static_cast<const bf16_t*>(x), D, gw[4 * l], D, 4 * H, D, M,
+                                               nullptr, H, s);
+        else
+            gemm_launch<MODE, E, float, true>(dz, 4 * H, static_cast<const float*>(x), D, gw[4 * l], D, 4 * H, D, M,
+                                              nullptr, H, s);
+        gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(L.hprev), H, gw[4 * l + 1], H, 4 * H, H, M,
+                                      nullptr, H, s);
+        // db_ih = db_hh = column sums of dz
+        hipLaunchKernelGGL(colsum_partial_kernel<E>, dim3((4 * H + 255) / 256, rb_c), dim3(256), 0, s, dz, M, 4 * H,
+                           4 * H, ws.part);
+        hipLaunchKernelGGL(colsum_final_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, ws.part, rb_c, 4 * H, H,
+                           gw[4 * l + 2], gw[4 * l + 3]);
+        cur ^= 1;
+    }
+    return launch_status();
+}
+
+}  // namespace
+}  // namespace ver
+
+extern "C" size_t ver_lstm_workspace_bytes(const ver_lstm_cfg* cfg, int32_t M) {
+    if (ver::check_cfg(cfg, M) != VER_OK) return 0;
+    ver::LstmWs ws;
+    ver::lstm_ws_layout(*cfg, M, nullptr, &ws);
+    return ws.bytes;
+}
+
+extern "C" int ver_lstm_fwd(const ver_lstm_cfg* cfg, const void* x_packed, int32_t M, const int32_t* info,
+                            const int32_t* batch_sizes, const int32_t* t_off, const float* h0, const float* c0,
+                            int32_t seq_cap, const float* const* weights, float* head_out, float* value,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    const int st = ver::check_cfg(cfg, M);
+    if (st != VER_OK) return st;
+    if (!x_packed || !info || !batch_sizes || !t_off || !weights || !head_out || !value) return VER_EINVAL;
+    if ((h0 || c0) && seq_cap <= 0) return VER_EINVAL;
+    for (int i = 0; i < 4 * cfg->n_layers + 4; ++i)
+        if (!weights[i]) return VER_EINVAL;
+    if (!workspace || workspace_bytes < ver_lstm_workspace_bytes(cfg, M)) return VER_EWORKSPACE;
+    ver::LstmWs ws;
+    ver::lstm_ws_layout(*cfg, M, workspace, &ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return cfg->compute ? ver::run_fwd<ver::MODE_BF16>(*cfg, x_packed, M, info, batch_sizes, t_off, h0, c0, seq_cap,
+                                                       weights, head_out, value, ws, s)
+                        : ver::run_fwd<ver::MODE_F32>(*cfg, x_packed, M, info, batch_sizes, t_off, h0, c0, seq_cap,
+                                                      weights, head_out, value, ws, s);
+}
+
+extern "C" int ver_lstm_bwd(const ver_lstm_cfg* cfg, const void* x_packed, int32_t M, const int32_t* info,
+                            const int32_t* batch_sizes, const int32_t* t_off, const float* h0, const float* c0,
+                            int32_t seq_cap, const float* const* weights, const float* d_head_out,
+                            const float* d_value, float* const* weight_grads, float* d_x, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    (void)h0;  // h_{t-1} of every row, including the initial state, was saved by the forward pass
+    const int st = ver::check_cfg(cfg, M);
+    if (st != VER_OK) return st;
+    if (!x_packed || !info || !batch_sizes || !t_off || !weights || !d_head_out || !d_value || !weight_grads)
+        return VER_EINVAL;
+    if (c0 && seq_cap <= 0) return VER_EINVAL;
+    for (int i = 0; i < 4 * cfg->n_layers + 4; ++i)
+        if (!weights[i] || !weight_grads[i]) return VER_EINVAL;
+    if (!workspace || workspace_bytes < ver_lstm_workspace_bytes(cfg, M)) return VER_EWORKSPACE;
+    ver::LstmWs ws;
+    ver::lstm_ws_layout(*cfg, M, workspace, &ws);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return cfg->compute ? ver::run_bwd<ver::MODE_BF16>(*cfg, x_packed, M, info, batch_sizes, t_off, c0, seq_cap,
+                                                       weights, d_head_out, d_value, weight_grads, d_x, ws, s)
+                        : ver::run_bwd<ver::MODE_F32>(*cfg, x_packed, M, info, batch_sizes, t_off, c0, seq_cap,
+                                                      weights, d_head_out, d_value, weight_grads, d_x, ws, s);
+}

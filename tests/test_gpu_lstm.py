@@ -1,0 +1,138 @@
+"""ver_lstm_fwd / ver_lstm_bwd against the CPU oracle (unpacked, per piece,
+fp64).  fp32 path: every element within 1e-4 of max(|ref|, rms(ref)).
+bf16-operand path: 2e-2 relative per tensor in the 2-norm plus an elementwise
+sanity bound (see tests/util.py)."""
+import numpy as np
+import pytest
+
+from oracle import lstm as olstm, pack as opack
+from paper_2210_05064_amd import workloads as wl
+from tests.gpu_util import LstmRun, grads_to_list, GRAD_NAMES
+from tests.util import assert_close, assert_close_bf16, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_run(ro, w, meta, h0, c0, d_u, d_v):
+    W = olstm.weights_f64(ro["weights"])
+    fwd = olstm.minibatch_forward(ro["obs"], meta["seq_first"], meta["seq_len"], W, h0, c0)
+    u = olstm.to_packed([f[0] for f in fwd], meta["t_off"])
+    v = olstm.to_packed([f[1] for f in fwd], meta["t_off"])
+    grads = olstm.zero_grads(W)
+    du_p = olstm.from_packed(d_u, meta["t_off"], meta["seq_len"])
+    dv_p = olstm.from_packed(d_v, meta["t_off"], meta["seq_len"])
+    dx = [olstm.piece_backward(du_p[j], dv_p[j], W, fwd[j][2], grads) for j in range(meta["n_seq"])]
+    return u, v, grads, olstm.to_packed(dx, meta["t_off"])
+
+
+def case(ver, w, seed, b=0, compute=0, x_bf16=False, states=True, bias_scale=0.2):
+    ro = wl.make_rollout(w, seed=seed, bias_scale=bias_scale)
+    B = w.minibatches
+    meta = opack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][0], B, b, ro["env_started_episode"])
+    h0 = c0 = None
+    if states:
+        h0 = opack.initial_states(ro["rnn_h"], meta["seq_first"], meta["seq_is_ep_start"])
+        c0 = opack.initial_states(ro["rnn_c"], meta["seq_first"], meta["seq_is_ep_start"])
+    rng = np.random.default_rng(seed + 1)
+    M = meta["M"]
+    d_u = (rng.standard_normal((M, w.act_dim)) / M).astype(np.float32)
+    d_v = (rng.standard_normal(M) / M).astype(np.float32)
+    x_packed = opack.gather_rows(ro["obs"], meta["gather_idx"])
+    run = LstmRun(ver, w, ro["weights"], x_packed, meta, h0, c0, compute, x_bf16)
+    u, v = run.forward()
+    grads, d_x = run.backward(d_u, d_v)
+    r_u, r_v, r_grads, r_dx = oracle_run(ro, w, meta, h0, c0, d_u, d_v)
+    close = (lambda a, r, n: assert_close(a, r, 1e-4, n)) if compute == 0 else assert_close_bf16
+    close(u, r_u, "head_out")
+    close(v, r_v, "value")
+    close(d_x, r_dx, "d_x")
+    names = [f"layer{l}.{n}" for l in range(w.n_layers) for n in GRAD_NAMES] + ["W_a", "b_a", "w_v", "b_v"]
+    for name, g, r in zip(names, grads, grads_to_list(r_grads)):
+        close(g, r, name)
+    return run, meta
+
+
+SMALL = dict(budget=640, n_envs=12, hidden=128, input_dim=36, p_done=0.02, minibatches=2)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
+@pytest.mark.parametrize("b", [0, 1])
+def test_two_layers_ragged(ver, compute, b):
+    """Several MFMA tiles in every dimension, ragged tail of single pieces,
+    initial states, both minibatches (the second opens with a split piece)."""
+    case(ver, wl.scaled(wl.WORKLOADS["manip"], **SMALL), seed=21, b=b, compute=compute)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
+def test_tiny_workload(ver, compute):
+    case(ver, wl.WORKLOADS["tiny"], seed=3, compute=compute)
+
+
+def test_categorical_no_initial_state_bf16_input(ver):
+    case(ver, wl.scaled(wl.WORKLOADS["nav"], budget=512, n_envs=8, hidden=64, input_dim=20, p_done=0.05),
+         seed=5, compute=1, x_bf16=True, states=False)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
+def test_many_short_pieces(ver, compute):
+    """More pieces than one MFMA tile holds (n_seq > 16) and T_max small."""
+    case(ver, wl.scaled(wl.WORKLOADS["nav"], budget=600, n_envs=40, hidden=64, input_dim=12, p_done=0.2,
+                        minibatches=1, speed_sigma=0.3), seed=6, compute=compute)
+
+
+def test_single_long_piece(ver):
+    """One environment owns the minibatch: batch size 1 at every timestep."""
+    case(ver, wl.scaled(wl.WORKLOADS["nav"], budget=300, n_envs=1, hidden=64, input_dim=8, p_done=0.0,
+                        minibatches=1), seed=7)
+
+
+def test_three_layers_wide_input(ver):
+    case(ver, wl.scaled(wl.WORKLOADS["manip"], budget=256, n_envs=6, hidden=192, input_dim=260, n_layers=3,
+                        p_done=0.03, minibatches=1), seed=8)
+
+
+def test_packing_order_invariance_on_device(ver):
+    """Another random order of the same sequences (B = 1): identical weight gradients up to rounding."""
+    w = wl.scaled(wl.WORKLOADS["manip"], budget=400, n_envs=10, hidden=64, input_dim=16, p_done=0.03,
+                  minibatches=1, epochs=2)
+    ro = wl.make_rollout(w, seed=9, bias_scale=0.2)
+    rng = np.random.default_rng(1)
+    du_flat = (rng.standard_normal((ro["S"], w.act_dim)) / ro["S"]).astype(np.float32)
+    dv_flat = (rng.standard_normal(ro["S"]) / ro["S"]).astype(np.float32)
+    outs = []
+    for e in range(2):
+        meta = opack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][e], 1, 0)
+        g = meta["gather_idx"]
+        run = LstmRun(ver, w, ro["weights"], ro["obs"][g], meta)
+        u, v = run.forward()
+        grads, _ = run.backward(du_flat[g], dv_flat[g])
+        flat_u = np.zeros_like(u)
+        flat_u[g] = u
+        outs.append((flat_u, grads))
+    assert rel_err(outs[0][0], outs[1][0]) < 1e-5
+    for a, b in zip(outs[0][1], outs[1][1]):
+        assert rel_err(a, b) < 1e-4
+
+
+def test_bitwise_reproducible(ver):
+    w = wl.scaled(wl.WORKLOADS["manip"], **SMALL)
+    ro = wl.make_rollout(w, seed=4)
+    meta = opack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][0], 2, 0)
+    rng = np.random.default_rng(0)
+    d_u = rng.standard_normal((meta["M"], w.act_dim)).astype(np.float32)
+    d_v = rng.standard_normal(meta["M"]).astype(np.float32)
+    res = []
+    for _ in range(2):
+        run = LstmRun(ver, w, ro["weights"], ro["obs"][meta["gather_idx"]], meta, compute=1)
+        u, v = run.forward()
+        grads, dx = run.backward(d_u, d_v)
+        res.append([u, v, dx] + grads)
+    assert all(np.array_equal(a, b) for a, b in zip(*res))
+
+
+def test_unsupported_shapes(ver):
+    for kw in (dict(hidden=96), dict(hidden=1024), dict(input_dim=6), dict(n_layers=9)):
+        c = dict(n_layers=1, input_dim=8, hidden=64, act_dim=4)
+        c.update(kw)
+        cfg = ver.lstm_cfg(c["n_layers"], c["input_dim"], c["hidden"], c["act_dim"], 0, 0)
+        assert ver.ver_lstm_workspace_bytes(cfg, 16) == 0

@@ -18,3 +18,24 @@ def rel_err(x, ref):
 def assert_close(x, ref, tol, what=""):
     e = rel_err(x, ref)
     assert e <= tol, f"{what}: relative error {e:.3e} > {tol:.1e}"
+
+
+def l2_rel_err(x, ref):
+    """||x - ref||_2 / ||ref||_2 over a tensor."""
+    x = np.asarray(x, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert x.shape == ref.shape, (x.shape, ref.shape)
+    den = np.linalg.norm(ref)
+    return float(np.linalg.norm(x - ref) / (den if den > 0 else 1.0))
+
+
+def assert_close_bf16(x, ref, what=""):
+    """Bar for the bf16-operand LSTM path: 2e-2 relative per tensor, taken in
+    the 2-norm (each bf16 operand carries a relative rounding error of up to
+    2^-9, and the largest of millions of such elementwise errors is an
+    extreme-value statistic, not a measure of the arithmetic), plus an
+    elementwise sanity bound of 1e-1 on the error relative to
+    max(|ref|, rms(ref))."""
+    e2, em = l2_rel_err(x, ref), rel_err(x, ref)
+    assert e2 <= 2e-2, f"{what}: relative 2-norm error {e2:.3e} > 2.0e-02"
+    assert em <= 1e-1, f"{what}: elementwise relative error {em:.3e} > 1.0e-01"
