@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the VER learner step on one MI355X.
+
+A "step" is one full PPO update over one synthetic ragged rollout: ver_gae
+once, then epochs x minibatches x (ver_pack_minibatch, ver_lstm_fwd,
+ver_ppo_loss, ver_lstm_bwd).  All inputs are resident in HBM before the timed
+region.  Prints ONE JSON line: learner env-steps/s, the roofline position of
+the dominant kernel (timed with HIP events inside the library during the timed
+region) and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--workload max|large|manip|nav|tiny] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
+
+
+def collection_logp(ro, compute, x_bf16):
+    """Log-probability the current weights give every stored action, evaluated
+    over whole sequences on the GPU (input preparation, untimed), plus the
+    workload's seeded noise: this is the rollout's logp_old."""
+    import torch
+    from paper_2210_05064_amd.learner import Learner
+    w = ro["workload"]
+    full = Learner(ro, compute=compute, x_bf16=x_bf16, minibatches=1)
+    full.pack(0, 0)
+    full.forward()
+    torch.cuda.synchronize()
+    u = full.head_out
+    if w.dist == 0:
+        logp = torch.log_softmax(u, dim=1).gather(1, full.act_packed.long().view(-1, 1)).squeeze(1)
+    else:
+        ls = full.log_std
+        z = (full.act_packed - u) * torch.exp(-ls)
+        logp = (-0.5 * z * z - ls - 0.5 * float(np.log(2 * np.pi))).sum(1)
+    flat = torch.empty(ro["S"], device="cuda")
+    flat[full.gather_idx.long()] = logp
+    flat += torch.from_numpy(ro["logp_noise"]).cuda()
+    torch.cuda.synchronize()
+    del full
+    torch.cuda.empty_cache()
+    return flat
+
+
+def cpu_baseline(ro, budget_s=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload:
+    GAE over the whole buffer, one minibatch's packing and loss in full, and the
+    LSTM forward/backward over as many of that minibatch's pieces (shortest
+    first) as fit the time budget, scaled to the whole update by step count."""
+    from oracle import gae as ogae, lstm as olstm, pack as opack, ppo_loss as oloss
+    w = ro["workload"]
+    S, B, E = ro["S"], w.minibatches, w.epochs
+    t0 = time.perf_counter()
+    adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
+    t_gae = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    meta = opack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][0], B, 0, ro["env_started_episode"])
+    x_rows = opack.gather_rows(ro["obs"], meta["gather_idx"])
+    t_pack = time.perf_counter() - t0
+    M = meta["M"]
+    W = olstm.weights_f64(ro["weights"])
+    rng = np.random.default_rng(0)
+    grads = olstm.zero_grads(W)
+    steps = 0
+    t0 = time.perf_counter()
+    for j in range(meta["n_seq"] - 1, -1, -1):          # shortest pieces first
+        f0, n = int(meta["seq_first"][j]), int(meta["seq_len"][j])
+        u, v, saved = olstm.piece_forward(ro["obs"][f0:f0 + n], W)
+        olstm.piece_backward(rng.standard_normal(u.shape) / M, rng.standard_normal(n) / M, W, saved, grads)
+        steps += n
+        if time.perf_counter() - t0 > budget_s:
+            break
+    t_lstm = (time.perf_counter() - t0) * M / steps
+    t0 = time.perf_counter()
+    u = rng.standard_normal((M, w.act_dim))
+    acts = opack.gather_rows(ro["actions"], meta["gather_idx"])
+    oloss.ppo_loss(w.dist, u, rng.standard_normal(M), W["log_std"], acts, rng.standard_normal(M),
+                   opack.gather_rows(adv, meta["gather_idx"]), opack.gather_rows(ret, meta["gather_idx"]),
+                   w.clip, w.value_coef, w.entropy_coef)
+    t_loss = time.perf_counter() - t0
+    t_update = t_gae + E * B * (t_pack + t_lstm + t_loss)
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {
+        "value": S / t_update, "unit": "env-steps/s", "cores": int(cores), "kind": "oracle",
+        "sample": (f"GAE on all {S} steps ({t_gae:.2f}s); packing ({t_pack:.2f}s) and loss ({t_loss:.2f}s) of one "
+                   f"minibatch of {M} rows in full; LSTM fwd+bwd on {steps} steps of that minibatch's shortest "
+                   f"pieces, scaled to {M} rows ({t_lstm:.1f}s); update = GAE + {E}x{B} minibatches"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="max")
+    ap.add_argument("--seed", type=int, default=4000)
+    ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle LSTM work (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the learner step of ONE GPU; runs on several GPUs are not part of this build "
+              "(the path would shard by data parallelism with one gradient all-reduce per minibatch)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2210_05064_amd import binding as ver, workloads as wl
+    from paper_2210_05064_amd.learner import Learner
+    if not torch.cuda.is_available():
+        print("no GPU visible: the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+
+    w = wl.WORKLOADS[args.workload]
+    ro = wl.make_rollout(w, seed=args.seed)
+    learner = Learner(ro)
+    learner.logp_old.copy_(collection_logp(ro, learner.compute, learner.x_bf16))
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        learner.update()
+    torch.cuda.synchronize()
+    if learner.lstm_timed_out():
+        print("device-side wait timed out during warm-up", file=sys.stderr)
+        sys.exit(4)
+
+    rec_mask = (1 << ver.PROF_CLASSES.index("lstm_rec_fwd")) | (1 << ver.PROF_CLASSES.index("lstm_rec_bwd"))
+    ver.ver_profile_enable(rec_mask)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        learner.update()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = ver.ver_profile_read()
+    ver.ver_profile_enable(0)
+    scalars = learner.scalars.cpu().numpy().tolist()
+    t_max = int(learner.info[1].item())
+
+    # every kernel class once more, for the breakdown (untimed)
+    ver.ver_profile_enable((1 << len(ver.PROF_CLASSES)) - 1)
+    learner.update()
+    torch.cuda.synchronize()
+    full = ver.ver_profile_read()
+    ver.ver_profile_enable(0)
+
+    S, M, H = learner.S, learner.M, w.hidden
+    ms_per_step = 1e3 * elapsed / args.steps
+    dom = max(("lstm_rec_fwd", "lstm_rec_bwd"), key=lambda k: prof[k][0])
+    dom_ms, dom_n = prof[dom]
+    flops_per_launch = 8.0 * H * H * M      # 2 * (4H x H) * rows, one layer, all timesteps of a minibatch
+    achieved = flops_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
+    dtype = "bf16" if learner.compute else "f32"
+    out = {
+        "metric": "learner env-steps/sec per PPO update (1 MI355X)",
+        "value": S / (elapsed / args.steps), "unit": "env-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": w.name, "n_envs": w.n_envs, "rollout_steps": S, "input_dim": w.input_dim,
+                   "lstm": f"{w.n_layers}x{w.hidden}", "policy": "categorical" if w.dist == 0 else "gaussian",
+                   "act_dim": w.act_dim, "epochs": w.epochs, "minibatches": w.minibatches,
+                   "rows_per_minibatch": M, "seed": args.seed},
+        "step_passes_per_sec": S * w.epochs / (elapsed / args.steps),
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_TFLOPS[dtype],
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS[dtype], "traffic": None,
+                     "avg_launch_ms": dom_ms / dom_n, "launches": dom_n, "flops_per_launch": flops_per_launch,
+                     "last_minibatch_T_max": t_max},
+        "kernel_ms_per_update": {k: round(v[0], 4) for k, v in full.items()},
+        "kernel_launches_per_update": {k: v[1] for k, v in full.items()},
+        "loss_scalars_last_minibatch": dict(zip(["total", "policy", "value", "entropy", "approx_kl", "clip_frac"],
+                                                scalars)),
+    }
+    if args.cpu_budget > 0:
+        out["cpu_baseline"] = cpu_baseline(ro, args.cpu_budget)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -194,8 +194,10 @@ int ver_pack_minibatch(const ver_pack_args* args /* host */, void* stream);
  * called with the same cfg, M, metadata, x_packed, h0/c0, weights and
  * workspace as the forward call it differentiates.
  *
- * Errors: VER_EUNSUPPORTED unless hidden is a multiple of 64, 64 <= hidden
- * <= 2048, input_dim a multiple of 4, 1 <= n_layers <= 8, 1 <= act_dim <= 63.
+ * Errors: VER_EUNSUPPORTED unless hidden is a multiple of 64 with
+ * 64 <= hidden <= 1024 (compute = 1) or <= 512 (compute = 0) - the backward
+ * kernel keeps a [16, 4*hidden] slice of W_hh in one CU's 160 KB of LDS -,
+ * input_dim a multiple of 4, 1 <= n_layers <= 8, 1 <= act_dim <= 63.
  * workspace word 0 (int32) is non-zero after the stream has drained if a
  * device-side wait timed out (should never happen; results are then
  * undefined).  Outputs are deterministic.
@@ -264,6 +266,33 @@ int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M,
                  const float* ret, const float* is_weight,
                  float* scalars, float* d_head_out, float* d_value, float* d_log_std,
                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Kernel timing for benchmarks (measurement plumbing, not part of the method).
+ * While enabled, the library brackets the kernels of the selected classes with
+ * HIP events on the stream of the call.  ver_profile_read waits for the
+ * recorded events, adds the elapsed time and launch count of every class into
+ * total_ms / launches (host arrays of VER_PROF_COUNT entries, overwritten) and
+ * forgets the events.  mask: bit i enables class i.  Not thread safe.
+ */
+enum {
+    VER_PROF_GAE = 0,
+    VER_PROF_PACK_INDEX = 1,
+    VER_PROF_PACK_GATHER = 2,
+    VER_PROF_LSTM_PREP = 3,
+    VER_PROF_LSTM_GEMM_FWD = 4,
+    VER_PROF_LSTM_REC_FWD = 5,
+    VER_PROF_HEADS_FWD = 6,
+    VER_PROF_LOSS = 7,
+    VER_PROF_HEADS_BWD = 8,
+    VER_PROF_LSTM_REC_BWD = 9,
+    VER_PROF_LSTM_GEMM_DX = 10,
+    VER_PROF_LSTM_GEMM_DW = 11,
+    VER_PROF_LSTM_DBIAS = 12,
+    VER_PROF_COUNT = 13
+};
+int ver_profile_enable(uint32_t mask);
+int ver_profile_read(double* total_ms, int64_t* launches);
 
 #ifdef __cplusplus
 }

@@ -72,6 +72,14 @@ lib.ver_ppo_loss.argtypes = [C.POINTER(PpoCfg), _i32, _vp, _vp, _vp, _vp, _vp, _
                              _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 
 
+lib.ver_profile_enable.restype = C.c_int
+lib.ver_profile_enable.argtypes = [C.c_uint32]
+lib.ver_profile_read.restype = C.c_int
+lib.ver_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+PROF_CLASSES = ["gae", "pack_index", "pack_gather", "lstm_prep", "lstm_gemm_fwd", "lstm_rec_fwd", "heads_fwd",
+                "ppo_loss", "heads_bwd", "lstm_rec_bwd", "lstm_gemm_dx", "lstm_gemm_dw", "lstm_dbias"]
+
+
 class VerError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
@@ -177,6 +185,18 @@ def ver_ppo_loss(cfg, M, head_out, value, log_std, actions_packed, logp_old, adv
     _check(lib.ver_ppo_loss(C.byref(cfg), M, _ptr(head_out), _ptr(value), _ptr(log_std), _ptr(actions_packed),
                             _ptr(logp_old), _ptr(adv), _ptr(ret), _ptr(is_weight), _ptr(scalars),
                             _ptr(d_head_out), _ptr(d_value), _ptr(d_log_std), p, n, _stream()))
+
+
+def ver_profile_enable(mask: int) -> None:
+    _check(lib.ver_profile_enable(mask))
+
+
+def ver_profile_read() -> dict:
+    """{class name: (total milliseconds, launches)} since the last read."""
+    n = len(PROF_CLASSES)
+    ms, cnt = (C.c_double * n)(), (C.c_int64 * n)()
+    _check(lib.ver_profile_read(ms, cnt))
+    return {name: (ms[i], cnt[i]) for i, name in enumerate(PROF_CLASSES)}
 
 
 def workspace(n_bytes: int) -> torch.Tensor:

@@ -61,4 +61,13 @@ __device__ __forceinline__ int segment_of(const int32_t* __restrict__ off, int n
 __global__ void fill_words_kernel(int32_t* p, size_t n, int32_t v);
 void fill_words(int32_t* p, size_t n, int32_t v, hipStream_t s);
 
+// Optional event bracketing of kernel classes (see ver_profile_enable).
+extern uint32_t g_prof_mask;
+void prof_mark(int cls, bool begin, hipStream_t s);
+struct ProfScope {
+    int cls; hipStream_t s; bool on;
+    ProfScope(int c, hipStream_t st) : cls(c), s(st), on((g_prof_mask >> c) & 1u) { if (on) prof_mark(cls, true, s); }
+    ~ProfScope() { if (on) prof_mark(cls, false, s); }
+};
+
 }  // namespace ver

@@ -232,6 +232,7 @@ extern "C" int ver_gae(const float* rewards, const float* values, const uint8_t*
     ws.inc = cv.take<double>(tiles);
     // ticket, error and flags must start at zero: head block + flag block are adjacent
     ver::fill_words(reinterpret_cast<int32_t*>(head), 64 + ver::align_up((size_t)tiles * 4, 256) / 4, 0, s);
+    ver::ProfScope prof(VER_PROF_GAE, s);
     hipLaunchKernelGGL(ver::gae_kernel, dim3(tiles), dim3(ver::GAE_THREADS), 0, s, rewards, values, dones,
                        last_values, env_off, N, S, gamma, lambda, adv, ret, ws);
     return ver::launch_status();

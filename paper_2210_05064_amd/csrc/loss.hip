@@ -212,6 +212,7 @@ extern "C" int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M, const float* head
     float* partials = cv.take<float>((size_t)ver::loss_blocks(M) * (ver::LOSS_SCALARS + cfg->act_dim));
     ver::fill_words(counter, 1, 0, s);
     const int blocks = ver::loss_blocks(M);
+    ver::ProfScope prof(VER_PROF_LOSS, s);
     if (cfg->dist == 0)
         hipLaunchKernelGGL(ver::ppo_loss_kernel<0>, dim3(blocks), dim3(ver::LOSS_THREADS), 0, s, *cfg, M, head_out,
                            value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out,

@@ -243,12 +243,17 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         const int D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws.layer[l];
         const float* W_ih = w[4 * l], *W_hh = w[4 * l + 1], *b_ih = w[4 * l + 2], *b_hh = w[4 * l + 3];
+        {
+        ProfScope prof(VER_PROF_LSTM_PREP, s);
         hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, W_ih, H, D, static_cast<E*>(L.wih),
                            static_cast<E*>(L.wihT));
         hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, W_hh, H, H, static_cast<E*>(L.whh),
                            static_cast<E*>(L.whhT));
         hipLaunchKernelGGL(prep_bias_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, b_ih, b_hh, H, L.bias);
+        }
         // time-batched input projection: gates[M, 4H] = x W_ih^T + (b_ih + b_hh), interleaved columns
+        {
+        ProfScope prof(VER_PROF_LSTM_GEMM_FWD, s);
         if (l == 0) {
             if (c.x_bf16)
                 gemm_launch<MODE, bf16_t, E, false>(static_cast<const bf16_t*>(x), D, static_cast<const E*>(L.wih), D,
@@ -260,6 +265,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
             gemm_launch<MODE, float, E, false>(ws.layer[l - 1].hout, H, static_cast<const E*>(L.wih), H, L.gates,
                                                4 * H, M, 4 * H, H, L.bias, 0, s);
         }
+        }
         // sequential part
         fill_words(ws.flags, 256, 0, s);
         RecFwdArgs ra;
@@ -270,8 +276,12 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err;
         const size_t lds = (size_t)16 * MT * (H + RecGeom<MODE>::PAD) * sizeof(E) + (size_t)KS * MT * 64 * 16;
         if (!set_lds(lstm_rec_fwd_kernel<MODE, MT, KS>, lds)) return VER_EHIP;
+        {
+        ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
         hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT, KS>), dim3(H / (4 * MT)), dim3(REC_THREADS), lds, s, ra);
+        }
     }
+    ProfScope prof(VER_PROF_HEADS_FWD, s);
     hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 3) / 4), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
                        w[4 * c.n_layers], w[4 * c.n_layers + 1], w[4 * c.n_layers + 2], w[4 * c.n_layers + 3],
                        head_out, value);
@@ -285,7 +295,10 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     typedef typename RecGeom<MODE>::E E;
     const int H = c.hidden, A = c.act_dim, nl = c.n_layers;
     const float* h_top = ws.layer[nl - 1].hout;
+    const int rb_c = (M + CS_ROWS - 1) / CS_ROWS;
     // heads
+    {
+    ProfScope prof(VER_PROF_HEADS_BWD, s);
     hipLaunchKernelGGL(heads_bwd_dh_kernel, dim3((M + 3) / 4), dim3(256), 0, s, d_u, d_v, M, H, A, w[4 * nl],
                        w[4 * nl + 2], ws.dh[0]);
     const int rb_h = (M + HW_ROWS - 1) / HW_ROWS;
@@ -293,7 +306,6 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
                        A, ws.part);
     hipLaunchKernelGGL(heads_wgrad_final_kernel, dim3((H + 255) / 256, A + 1), dim3(256), 0, s, ws.part, rb_h, H, A,
                        gw[4 * nl], gw[4 * nl + 2]);
-    const int rb_c = (M + CS_ROWS - 1) / CS_ROWS;
     hipLaunchKernelGGL(colsum_partial_kernel<float>, dim3((A + 255) / 256, rb_c), dim3(256), 0, s, d_u, M, A, A,
                        ws.part);
     hipLaunchKernelGGL(colsum_final_kernel, dim3((A + 255) / 256), dim3(256), 0, s, ws.part, rb_c, A, 0, gw[4 * nl + 1],
@@ -301,6 +313,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     hipLaunchKernelGGL(colsum_partial_kernel<float>, dim3(1, rb_c), dim3(256), 0, s, d_v, M, 1, 1, ws.part);
     hipLaunchKernelGGL(colsum_final_kernel, dim3(1), dim3(256), 0, s, ws.part, rb_c, 1, 0, gw[4 * nl + 3],
                        (float*)nullptr);
+    }
 
     int cur = 0;  // ws.dh[cur] holds the gradient arriving at the current layer's h
     for (int l = nl - 1; l >= 0; --l) {
@@ -315,15 +328,22 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err;
         const size_t lds = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E) + (size_t)4 * 64 * 16;
         if (!set_lds(lstm_rec_bwd_kernel<MODE>, lds)) return VER_EHIP;
+        {
+        ProfScope prof(VER_PROF_LSTM_REC_BWD, s);
         hipLaunchKernelGGL(lstm_rec_bwd_kernel<MODE>, dim3(H / 16), dim3(REC_THREADS), lds, s, ra);
+        }
 
         const E* dz = static_cast<const E*>(ws.dz);
         // gradient w.r.t. the layer input: dx[M, D] = dz[M, 4H] . W_ih[4H, D]
         float* dx = l > 0 ? ws.dh[cur ^ 1] : d_x;
-        if (dx)
+        if (dx) {
+            ProfScope prof(VER_PROF_LSTM_GEMM_DX, s);
             gemm_launch<MODE, E, E, false>(dz, 4 * H, static_cast<const E*>(L.wihT), 4 * H, dx, D, M, D, 4 * H,
                                            nullptr, 0, s);
+        }
         // dW_ih[4H, D] = dz^T x ; dW_hh[4H, H] = dz^T h_{t-1}; stored gate-major
+        {
+        ProfScope prof(VER_PROF_LSTM_GEMM_DW, s);
         if (l > 0)
             gemm_launch<MODE, E, float, true>(dz, 4 * H, ws.layer[l - 1].hout, H, gw[4 * l], D, 4 * H, D, M, nullptr, H, s);
         else if (c.x_bf16)
@@ -334,11 +354,15 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
                                               nullptr, H, s);
         gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(L.hprev), H, gw[4 * l + 1], H, 4 * H, H, M,
                                       nullptr, H, s);
+        }
         // db_ih = db_hh = column sums of dz
+        {
+        ProfScope prof(VER_PROF_LSTM_DBIAS, s);
         hipLaunchKernelGGL(colsum_partial_kernel<E>, dim3((4 * H + 255) / 256, rb_c), dim3(256), 0, s, dz, M, 4 * H,
                            4 * H, ws.part);
         hipLaunchKernelGGL(colsum_final_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, ws.part, rb_c, 4 * H, H,
                            gw[4 * l + 2], gw[4 * l + 3]);
+        }
         cur ^= 1;
     }
     return launch_status();

@@ -366,9 +366,12 @@ extern "C" int ver_pack_minibatch(const ver_pack_args* a, void* stream) {
     const int M = a->S / a->B;
     ver::PackWs ws;
     ver::pack_ws_layout(a->S, M, a->workspace, &ws);
+    {
+    ver::ProfScope prof(VER_PROF_PACK_INDEX, s);
     hipLaunchKernelGGL(ver::pack_index_kernel, dim3(1), dim3(ver::IDX_THREADS), 0, s, a->dones, a->env_off,
                        a->env_started_episode, a->seq_key, a->N, a->S, a->B, a->b, ws, a->info, a->seq_first,
                        a->seq_len, a->seq_is_ep_start, a->batch_sizes, a->t_off);
+    }
     if (hipGetLastError() != hipSuccess) return VER_EHIP;
     ver::GatherArgs g;
     g.info = a->info; g.seq_first = a->seq_first; g.seq_eps = a->seq_is_ep_start; g.t_off = a->t_off;
@@ -381,6 +384,7 @@ extern "C" int ver_pack_minibatch(const ver_pack_args* a, void* stream) {
     g.rnn_h = a->rnn_h; g.rnn_c = a->rnn_c; g.n_layers = states ? a->n_layers : 0; g.H = a->H;
     g.seq_cap = a->seq_cap; g.h0 = a->h0; g.c0 = a->c0;
     const int blocks = (M + ver::GATHER_WAVES - 1) / ver::GATHER_WAVES;
+    ver::ProfScope prof(VER_PROF_PACK_GATHER, s);
     hipLaunchKernelGGL(ver::pack_gather_kernel, dim3(blocks), dim3(ver::GATHER_THREADS), 0, s, g);
     return ver::launch_status();
 }

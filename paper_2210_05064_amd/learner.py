@@ -1,0 +1,138 @@
+"""One PPO update of the VER learner as a sequence of C-ABI calls.
+
+Buffer management and argument marshalling only: every step of the update
+(advantages, minibatch packing, LSTM forward, PPO loss, LSTM backward) runs in
+the HIP library.  Used by the benchmark, the smoke check and the end-to-end
+tests.  Nothing here synchronises the stream.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as ver
+from .workloads import Workload
+
+
+def _dev(a: np.ndarray) -> torch.Tensor:
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint32:
+        a = a.view(np.int32)
+    return torch.from_numpy(a).cuda()
+
+
+class Learner:
+    """Device-resident rollout + weights + every scratch buffer of one update."""
+
+    def __init__(self, rollout: dict, *, compute: int | None = None, x_bf16: bool | None = None,
+                 want_dx: bool = False, minibatches: int | None = None):
+        w: Workload = rollout["workload"]
+        self.w = w
+        self.S, self.N = rollout["S"], rollout["N"]
+        self.B = minibatches or w.minibatches
+        self.M = self.S // self.B
+        self.compute = int(w.bf16) if compute is None else compute
+        self.x_bf16 = bool(self.compute) if x_bf16 is None else x_bf16
+        S, M, H, nl, A, D = self.S, self.M, w.hidden, w.n_layers, w.act_dim, w.input_dim
+        f32 = dict(dtype=torch.float32, device="cuda")
+        i32 = dict(dtype=torch.int32, device="cuda")
+        # rollout buffer
+        self.rewards, self.values = _dev(rollout["rewards"]), _dev(rollout["values"])
+        self.dones, self.last_values = _dev(rollout["dones"]), _dev(rollout["last_values"])
+        self.env_off = _dev(rollout["env_off"])
+        self.env_started = _dev(rollout["env_started_episode"])
+        self.obs, self.actions = _dev(rollout["obs"]), _dev(rollout["actions"])
+        self.seq_key = _dev(rollout["seq_key"])
+        self.rnn_h = _dev(rollout["rnn_h"]) if "rnn_h" in rollout else None
+        self.rnn_c = _dev(rollout["rnn_c"]) if "rnn_c" in rollout else None
+        self.logp_old = torch.zeros(S, **f32)
+        self.adv, self.ret = torch.empty(S, **f32), torch.empty(S, **f32)
+        # weights, gradients
+        wt = rollout["weights"]
+        flat = []
+        for lw in wt["layers"]:
+            flat += [lw["W_ih"], lw["W_hh"], lw["b_ih"], lw["b_hh"]]
+        flat += [wt["W_a"], wt["b_a"], wt["w_v"], wt["b_v"]]
+        self.weights = [_dev(np.asarray(a, np.float32)) for a in flat]
+        self.grads = [torch.empty_like(t) for t in self.weights]
+        self.log_std = _dev(np.asarray(wt["log_std"], np.float32))
+        self.d_log_std = torch.empty(A, **f32)
+        # packed minibatch
+        self.info = torch.zeros(4, **i32)
+        self.seq_first, self.seq_len = torch.empty(M, **i32), torch.empty(M, **i32)
+        self.seq_eps = torch.empty(M, dtype=torch.uint8, device="cuda")
+        self.batch_sizes, self.t_off = torch.empty(M, **i32), torch.empty(M + 1, **i32)
+        self.gather_idx = torch.empty(M, **i32)
+        self.x_packed = torch.empty((M, D), dtype=torch.bfloat16 if self.x_bf16 else torch.float32, device="cuda")
+        self.act_packed = torch.empty((M,) + tuple(self.actions.shape[1:]), dtype=self.actions.dtype, device="cuda")
+        self.logp_old_p, self.adv_p, self.ret_p = (torch.empty(M, **f32) for _ in range(3))
+        self.seq_cap = M
+        self.h0 = torch.empty((nl, M, H), **f32) if self.rnn_h is not None else None
+        self.c0 = torch.empty((nl, M, H), **f32) if self.rnn_c is not None else None
+        # network outputs, loss
+        self.head_out, self.value = torch.empty((M, A), **f32), torch.empty(M, **f32)
+        self.d_head, self.d_value = torch.empty((M, A), **f32), torch.empty(M, **f32)
+        self.d_x = torch.empty((M, D), **f32) if want_dx else None
+        self.scalars = torch.zeros(6, **f32)
+        # configuration structs and workspaces
+        self.lstm_cfg = ver.lstm_cfg(nl, D, H, A, self.compute, int(self.x_bf16))
+        self.ppo_cfg = ver.ppo_cfg(w.clip, w.value_coef, w.entropy_coef, w.dist, A)
+        self.ws_gae = ver.workspace(ver.ver_gae_workspace_bytes(S))
+        self.ws_pack = ver.workspace(ver.ver_pack_workspace_bytes(self.N, S, self.B))
+        n = ver.ver_lstm_workspace_bytes(self.lstm_cfg, M)
+        if n == 0:
+            raise ver.VerError(-3)
+        self.ws_lstm = ver.workspace(n)
+        self.ws_loss = ver.workspace(ver.ver_ppo_loss_workspace_bytes(M, A))
+        self.act_bytes = int(self.actions[0].numel() * self.actions.element_size())
+
+    # -- the five entry points, in the order of the learning phase ----------------
+    def gae(self):
+        ver.ver_gae(self.rewards, self.values, self.dones, self.last_values, self.env_off, self.N, self.S,
+                    self.w.gamma, self.w.lam, self.adv, self.ret, self.ws_gae)
+
+    def pack(self, epoch: int, b: int):
+        ver.ver_pack_minibatch(
+            dones=self.dones, env_off=self.env_off, env_started_episode=self.env_started,
+            seq_key=self.seq_key[epoch], N=self.N, S=self.S, B=self.B, b=b,
+            info=self.info, seq_first=self.seq_first, seq_len=self.seq_len, seq_is_ep_start=self.seq_eps,
+            batch_sizes=self.batch_sizes, t_off=self.t_off, gather_idx=self.gather_idx,
+            obs=self.obs, D=self.w.input_dim, obs_packed=self.x_packed, obs_packed_bf16=int(self.x_bf16),
+            actions=self.actions, act_bytes=self.act_bytes, actions_packed=self.act_packed,
+            logp_old=self.logp_old, adv=self.adv, ret=self.ret,
+            logp_old_packed=self.logp_old_p, adv_packed=self.adv_p, ret_packed=self.ret_p,
+            rnn_h=self.rnn_h, rnn_c=self.rnn_c, n_layers=self.w.n_layers, H=self.w.hidden,
+            seq_cap=self.seq_cap, h0=self.h0, c0=self.c0, workspace=self.ws_pack)
+
+    def forward(self):
+        ver.ver_lstm_fwd(self.lstm_cfg, self.x_packed, self.M, self.info, self.batch_sizes, self.t_off,
+                         self.h0, self.c0, self.seq_cap, self.weights, self.head_out, self.value, self.ws_lstm)
+
+    def loss(self):
+        ver.ver_ppo_loss(self.ppo_cfg, self.M, self.head_out, self.value,
+                         self.log_std if self.w.dist == 1 else None, self.act_packed, self.logp_old_p,
+                         self.adv_p, self.ret_p, None, self.scalars, self.d_head, self.d_value,
+                         self.d_log_std if self.w.dist == 1 else None, self.ws_loss)
+
+    def backward(self):
+        ver.ver_lstm_bwd(self.lstm_cfg, self.x_packed, self.M, self.info, self.batch_sizes, self.t_off,
+                         self.h0, self.c0, self.seq_cap, self.weights, self.d_head, self.d_value, self.grads,
+                         self.d_x, self.ws_lstm)
+
+    def minibatch(self, epoch: int, b: int):
+        self.pack(epoch, b)
+        self.forward()
+        self.loss()
+        self.backward()
+
+    def update(self, on_minibatch=None):
+        """One PPO update: advantages once, then epochs x minibatches."""
+        self.gae()
+        for e in range(self.w.epochs):
+            for b in range(self.B):
+                self.minibatch(e, b)
+                if on_minibatch is not None:
+                    on_minibatch(e, b)
+
+    def lstm_timed_out(self) -> bool:
+        return bool(self.ws_lstm[0].item() != 0)
