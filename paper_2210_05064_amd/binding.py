@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libver.so")
+LIB_PATH = os.environ.get("VER_LIB", os.path.join(_HERE, "libver.so"))
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2210_05064_amd.build` "
                       "(or __graft_entry__.build()) first; there is no CPU fallback")

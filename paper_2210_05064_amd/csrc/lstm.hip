@@ -164,6 +164,7 @@ struct LayerWs {
 struct LstmWs {
     int* err;          // word 0 of the workspace
     int* flags;        // [256]
+    long long* prof;   // [32] phase counters of the recurrent kernels (forward 0..15, backward 16..31)
     LayerWs layer[8];
     void* dz;          // [M, 4H] operand type
     float* dh[2];      // [M, H] ping-pong: gradient arriving at a layer's h
@@ -191,6 +192,7 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     int* head = cv.take<int>(64);
     ws->err = head;
     ws->flags = cv.take<int>(256);
+    ws->prof = cv.take<long long>(32);
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws->layer[l];
@@ -220,9 +222,16 @@ inline int check_cfg(const ver_lstm_cfg* c, int M) {
     if (c->x_bf16 && !c->compute) return VER_EINVAL;
     if (c->n_layers < 1 || c->n_layers > 8 || c->act_dim < 1 || c->act_dim > 63) return VER_EUNSUPPORTED;
     if (c->hidden < 64 || c->hidden % 64 != 0 || c->input_dim < 4 || c->input_dim % 4 != 0) return VER_EUNSUPPORTED;
-    // the backward kernel keeps a [16, 4H] slice of W_hh in the 160 KB LDS of a CU
+    // a wave keeps its [16, H] share of W_hh in 128 registers; a 16-row tile of dz ([16, 4H]) must fit in LDS
     if (c->hidden > (c->compute ? 1024 : 512)) return VER_EUNSUPPORTED;
     return VER_OK;
+}
+
+// How many 16-row tiles of exchanged rows fit in a CU's 160 KB of LDS next to the reduction buffer.
+inline int rec_tiles(size_t tile_bytes, size_t red_bytes) {
+    const size_t budget = 160 * 1024 - red_bytes;
+    int n = (int)(budget / tile_bytes);
+    return n < 1 ? 1 : (n > REC_NTC ? REC_NTC : n);
 }
 
 template <typename K>
@@ -273,12 +282,24 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.gates = L.gates; ra.c = L.c; ra.hout = L.hout; ra.hprev = L.hprev; ra.whh = L.whh;
         ra.h0 = h0 ? h0 + (size_t)l * seq_cap * H : nullptr;
         ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
-        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err;
-        const size_t lds = (size_t)16 * MT * (H + RecGeom<MODE>::PAD) * sizeof(E) + (size_t)KS * MT * 64 * 16;
-        if (!set_lds(lstm_rec_fwd_kernel<MODE, MT, KS>, lds)) return VER_EHIP;
+        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err; ra.prof = ws.prof;
+        const size_t red = (size_t)KS * MT * REC_NTC * 64 * 16;
+        const size_t tile = (size_t)16 * (H + RecGeom<MODE>::PAD) * sizeof(E);
+        ra.ntc = rec_tiles(tile, red);
+        const size_t lds = ra.ntc * tile + red;
         {
         ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
-        hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT, KS>), dim3(H / (4 * MT)), dim3(REC_THREADS), lds, s, ra);
+        const int ni = (H / KS) / RecGeom<MODE>::KBLK;
+        bool ok = true;
+#define VER_FWD_CASE(N) case N: ok = set_lds(lstm_rec_fwd_kernel<MODE, MT, KS, N>, lds); \
+            if (ok) hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT, KS, N>), dim3(H / (4 * MT)), dim3(REC_THREADS), lds, s, ra); break;
+        switch (ni) {
+            VER_FWD_CASE(1) VER_FWD_CASE(2) VER_FWD_CASE(4) VER_FWD_CASE(8) VER_FWD_CASE(16) VER_FWD_CASE(32)
+            default: ok = set_lds(lstm_rec_fwd_kernel<MODE, MT, KS, 0>, lds);
+                if (ok) hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT, KS, 0>), dim3(H / (4 * MT)), dim3(REC_THREADS), lds, s, ra);
+        }
+#undef VER_FWD_CASE
+        if (!ok) return VER_EHIP;
         }
     }
     ProfScope prof(VER_PROF_HEADS_FWD, s);
@@ -325,12 +346,24 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.gates = L.gates; ra.c = L.c; ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
         ra.dh_above = ws.dh[cur]; ra.dz = ws.dz; ra.whhT = L.whhT;
         ra.dh_state = ws.dh_state; ra.dc_state = ws.dc_state;
-        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err;
-        const size_t lds = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E) + (size_t)4 * 64 * 16;
-        if (!set_lds(lstm_rec_bwd_kernel<MODE>, lds)) return VER_EHIP;
+        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err; ra.prof = ws.prof + 16;
+        const size_t red = (size_t)4 * REC_NTC * 64 * 16;
+        const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
+        ra.ntc = rec_tiles(tile, red);
+        const size_t lds = ra.ntc * tile + red;
         {
         ProfScope prof(VER_PROF_LSTM_REC_BWD, s);
-        hipLaunchKernelGGL(lstm_rec_bwd_kernel<MODE>, dim3(H / 16), dim3(REC_THREADS), lds, s, ra);
+        const int ni = H / RecGeom<MODE>::KBLK;
+        bool ok = true;
+#define VER_BWD_CASE(N) case N: ok = set_lds(lstm_rec_bwd_kernel<MODE, N>, lds); \
+            if (ok) hipLaunchKernelGGL((lstm_rec_bwd_kernel<MODE, N>), dim3(H / 16), dim3(REC_THREADS), lds, s, ra); break;
+        switch (ni) {
+            VER_BWD_CASE(2) VER_BWD_CASE(4) VER_BWD_CASE(8) VER_BWD_CASE(16) VER_BWD_CASE(32)
+            default: ok = set_lds(lstm_rec_bwd_kernel<MODE, 0>, lds);
+                if (ok) hipLaunchKernelGGL((lstm_rec_bwd_kernel<MODE, 0>), dim3(H / 16), dim3(REC_THREADS), lds, s, ra);
+        }
+#undef VER_BWD_CASE
+        if (!ok) return VER_EHIP;
         }
 
         const E* dz = static_cast<const E*>(ws.dz);
