@@ -150,6 +150,10 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------- workspace
+// Tagged-word exchange area: 2 slots x rows x words per row, sized for the widest case (8 rows of H <= 1024
+// floats forward, 2 rows of 4H bf16 backward: both 8192 words per slot).
+constexpr size_t LL_WORDS = 2 * 8192;
+
 struct LayerWs {
     void* wih;    // [4H, D_l]  operand type, interleaved rows
     void* wihT;   // [D_l, 4H]
@@ -163,7 +167,8 @@ struct LayerWs {
 };
 struct LstmWs {
     int* err;          // word 0 of the workspace
-    int* flags;        // [256]
+    int* flags;        // [256], directly followed by
+    unsigned long long* ll;  // [LL_WORDS] tagged-word exchange area of the recurrent kernels (cleared with the flags)
     long long* prof;   // [32] phase counters of the recurrent kernels (forward 0..15, backward 16..31)
     LayerWs layer[8];
     void* dz;          // [M, 4H] operand type
@@ -192,6 +197,7 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     int* head = cv.take<int>(64);
     ws->err = head;
     ws->flags = cv.take<int>(256);
+    ws->ll = cv.take<unsigned long long>(LL_WORDS);
     ws->prof = cv.take<long long>(32);
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t D = l == 0 ? c.input_dim : H;
@@ -232,6 +238,16 @@ inline int rec_tiles(size_t tile_bytes, size_t red_bytes) {
     const size_t budget = 160 * 1024 - red_bytes;
     int n = (int)(budget / tile_bytes);
     return n < 1 ? 1 : (n > REC_NTC ? REC_NTC : n);
+}
+
+// Tagged words per exchanged row, and how many rows a poll may cover: a thread fetches at most REC_LL_UNITS
+// 16-byte units per poll and a slot holds LL_WORDS / 2 words.
+template <typename E> inline int ll_words_host(int row_elems) { return row_elems * (int)sizeof(E) / 4; }
+inline int ll_rows_for(int words_per_row) {
+    int rows = REC_LL_UNITS * REC_THREADS * 2 / words_per_row;
+    const int cap = (int)(LL_WORDS / 2) / words_per_row;
+    if (rows > cap) rows = cap;
+    return rows > 8 ? 8 : rows;
 }
 
 template <typename K>
@@ -276,13 +292,15 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         }
         }
         // sequential part
-        fill_words(ws.flags, 256, 0, s);
+        fill_words(ws.flags, 256 + 2 * LL_WORDS, 0, s);   // flags and the tagged-word area behind them
         RecFwdArgs ra;
         ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
         ra.gates = L.gates; ra.c = L.c; ra.hout = L.hout; ra.hprev = L.hprev; ra.whh = L.whh;
         ra.h0 = h0 ? h0 + (size_t)l * seq_cap * H : nullptr;
         ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
         ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err; ra.prof = ws.prof;
+        ra.ll = ws.ll;
+        ra.ll_rows = ll_rows_for(ll_words_host<E>(H));
         const size_t red = (size_t)KS * MT * REC_NTC * 64 * 16;
         const size_t tile = (size_t)16 * (H + RecGeom<MODE>::PAD) * sizeof(E);
         ra.ntc = rec_tiles(tile, red);
@@ -340,13 +358,15 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     for (int l = nl - 1; l >= 0; --l) {
         const int D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws.layer[l];
-        fill_words(ws.flags, 256, 0, s);
+        fill_words(ws.flags, 256 + 2 * LL_WORDS, 0, s);
         RecBwdArgs ra;
         ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
         ra.gates = L.gates; ra.c = L.c; ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
         ra.dh_above = ws.dh[cur]; ra.dz = ws.dz; ra.whhT = L.whhT;
         ra.dh_state = ws.dh_state; ra.dc_state = ws.dc_state;
         ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err; ra.prof = ws.prof + 16;
+        ra.ll = ws.ll;
+        ra.ll_rows = ll_rows_for(ll_words_host<E>(4 * H));
         const size_t red = (size_t)4 * REC_NTC * 64 * 16;
         const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
         ra.ntc = rec_tiles(tile, red);

@@ -137,6 +137,8 @@ struct RecFwdArgs {
     const float* c0;
     int H, seq_cap;
     int ntc;            // 16-row tiles of staged rows that fit in LDS (1..REC_NTC)
+    int ll_rows;        // timesteps with at most this many alive pieces use the low-latency exchange
+    u64_t* ll;          // [2][ll_rows][words per row] tagged words, zero before the launch
     int* flags;
     int* err;
     long long* prof;    // [16] phase cycle counters (only read by builds with VER_REC_PROF)
@@ -170,6 +172,78 @@ __device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, 
             while (c >= vec_per_row) { c -= vec_per_row; ++r; }
         }
     }
+}
+
+// ---- Low-latency exchange for timesteps with few alive pieces -------------------------------------
+// With a handful of rows, a timestep is pure synchronisation latency.  For those steps every 4 bytes of an
+// exchanged row travel in an 8-byte word {data, tag}: the tag (the timestep counter) makes the word
+// self-validating, so the writer neither waits for its stores to complete nor raises a flag, and readers
+// poll the data itself with coherent loads.  One memory round trip per timestep instead of three.
+// Two slots (timestep parity) suffice: a workgroup can only write slot s+2 after it has read every
+// workgroup's words of step s+1, which they wrote after they had finished reading slot s.
+constexpr int REC_LL_UNITS = 8;   // 16-byte units (two words) a thread fetches per poll at most
+
+// LL words per exchanged row of row_elems elements (4 data bytes per word).
+template <typename E> __device__ __forceinline__ int ll_words(int row_elems) { return row_elems * (int)sizeof(E) / 4; }
+
+// Polls `rows` rows of the slot until every word carries `tag`, then unpacks the data into LDS rows of
+// `stride` elements.  rows * words_per_row / 2 <= REC_LL_UNITS * REC_THREADS.  Bounded.
+template <typename E>
+__device__ __forceinline__ void ll_stage(const u64_t* slot, int rows, int row_elems, unsigned tag, E* lds, int stride,
+                                         int* err) {
+    constexpr int EPW = 4 / sizeof(E);          // elements per word
+    constexpr int AUX_SC1 = 16;
+    const int upr = ll_words<E>(row_elems) / 2;  // 16-byte units per row
+    const int units = rows * upr;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<u64_t*>(slot), 0, units * 16, 0x00020000);
+    u32x4_t d[REC_LL_UNITS];
+    long long spins = 0;
+    for (;;) {
+        bool ready = true;
+#pragma unroll
+        for (int i = 0; i < REC_LL_UNITS; ++i)
+            d[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (threadIdx.x + i * REC_THREADS) * 16, 0, AUX_SC1);
+#pragma unroll
+        for (int i = 0; i < REC_LL_UNITS; ++i)
+            if ((int)threadIdx.x + i * REC_THREADS < units) ready = ready && d[i].y == tag && d[i].w == tag;
+        if (ready) break;
+        if (++spins > REC_SPIN_LIMIT || ld_agent(err) != 0) {
+            st_agent(err, 1);
+            break;
+        }
+    }
+    __syncthreads();  // every wave is past the previous timestep's reads of the staging rows
+#pragma unroll
+    for (int i = 0; i < REC_LL_UNITS; ++i) {
+        const int u = threadIdx.x + i * REC_THREADS;
+        if (u < units) {
+            const int r = u / upr, cu = u - r * upr;
+            *reinterpret_cast<u64_t*>(lds + r * stride + cu * 2 * EPW) = (u64_t)d[i].x | ((u64_t)d[i].z << 32);
+        }
+    }
+    __syncthreads();
+}
+
+// Writes 4 consecutive elements of row `row` (starting at element `col`, a multiple of 4) as tagged words.
+template <typename E>
+__device__ __forceinline__ void ll_store4(u64_t* slot, int row, int row_elems, int col, unsigned tag, float a, float b,
+                                          float c, float d);
+template <>
+__device__ __forceinline__ void ll_store4<bf16_t>(u64_t* slot, int row, int row_elems, int col, unsigned tag, float a,
+                                                  float b, float c, float d) {
+    const u32x4_t v = {(unsigned)to_bf16(a) | ((unsigned)to_bf16(b) << 16), tag,
+                       (unsigned)to_bf16(c) | ((unsigned)to_bf16(d) << 16), tag};
+    u64_t* p = slot + (size_t)row * (row_elems / 2) + col / 2;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(p, 0, 16, 0x00020000);
+    __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, 0, 0, 16);
+}
+template <>
+__device__ __forceinline__ void ll_store4<float>(u64_t* slot, int row, int row_elems, int col, unsigned tag, float a,
+                                                 float b, float c, float d) {
+    u64_t* p = slot + (size_t)row * row_elems + col;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(p, 0, 32, 0x00020000);
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{__float_as_uint(a), tag, __float_as_uint(b), tag}, rsrc, 0, 0, 16);
+    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{__float_as_uint(c), tag, __float_as_uint(d), tag}, rsrc, 16, 0, 16);
 }
 
 // acc[q] += W(16 x k-range) * B_q(k-range x 16) for NT staged tiles; W blocks come from registers, B from LDS.
@@ -282,13 +356,21 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
                                                                   (size_t)(j0 + mt * 4 + lk) * 4);
             }
         }
-        rec_wait(a.flags, G, t + 1, a.err);
+        const bool in_ll = t > 0 && bs <= a.ll_rows;                // how h_{t-1} reaches this timestep
+        const bool out_ll = bs_next > 0 && bs_next <= a.ll_rows;   // how h_t leaves it
+        const int ll_row_words = ll_words<E>(H);
+        u64_t* ll_out = a.ll + (size_t)((t + 1) & 1) * a.ll_rows * ll_row_words;
+        if (!in_ll) rec_wait(a.flags, G, t + 1, a.err);
         REC_PROF_MARK(0);
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
-            if (c0 > 0) __syncthreads();  // the previous chunk's rows have been consumed
-            stage_rows<E>(hprev + (size_t)(base + c0) * H, rows, H, sB, stride);
-            __syncthreads();
+            if (in_ll) {
+                ll_stage<E>(a.ll + (size_t)(t & 1) * a.ll_rows * ll_row_words, rows, H, (unsigned)t, sB, stride, a.err);
+            } else {
+                if (c0 > 0) __syncthreads();  // the previous chunk's rows have been consumed
+                stage_rows<E>(hprev + (size_t)(base + c0) * H, rows, H, sB, stride);
+                __syncthreads();
+            }
             REC_PROF_MARK(1);
             f32x4_t acc[REC_NTC];
 #pragma unroll
@@ -342,14 +424,16 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
                         // the 4 lanes with equal lr hold units mt*4 .. mt*4+3 of piece n: one coherent store
                         const float h1 = __shfl(hn, lr + 16, VER_WAVE), h2 = __shfl(hn, lr + 32, VER_WAVE),
                                     h3 = __shfl(hn, lr + 48, VER_WAVE);
-                        if (lk == 0 && n < bs_next)
+                        if (lk == 0 && n < bs_next) {
                             st_xchg_4<E>(hprev + ((size_t)base_next + n) * H + j0 + mt * 4, hn, h1, h2, h3);
+                            if (out_ll) ll_store4<E>(ll_out, n, H, j0 + mt * 4, (unsigned)(t + 1), hn, h1, h2, h3);
+                        }
                     }
                 }
             }
         }
         REC_PROF_MARK(3);
-        rec_publish(a.flags, t + 2);
+        if (!out_ll && t + 1 < T) rec_publish(a.flags, t + 2);
         REC_PROF_MARK(4);
 #ifdef VER_REC_PROF
         if (threadIdx.x == 0 && blockIdx.x == 0) prof_out[15] += 1;
@@ -371,6 +455,8 @@ struct RecBwdArgs {
     float* dc_state;        // [n_cap, H]
     int H, seq_cap;
     int ntc;
+    int ll_rows;
+    u64_t* ll;          // [2][ll_rows][words per dz row]
     int* flags;
     int* err;
     long long* prof;
@@ -435,6 +521,8 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
         const int bs = a.batch_sizes[t], base = a.t_off[t];
         const int bs_next = (t + 1 < T) ? a.batch_sizes[t + 1] : 0;
         const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
+        const bool use_ll = bs <= a.ll_rows;   // few alive pieces: exchange dz_t through tagged words
+        u64_t* ll_slot = a.ll + (size_t)((T - t) & 1) * a.ll_rows * ll_words<E>(K);
         // A. gate gradients of this workgroup's 16 units for every alive piece
         for (int i = tid; i < bs * UH; i += REC_THREADS) {
             const int n = i / UH, j = j0 + (i % UH);
@@ -445,8 +533,10 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
             const float dh = sv.dh_above + (carried ? a.dh_state[(size_t)n * H + j] : 0.f);
             const float tc = tanhf_(sv.c);
             const float dc = (carried ? a.dc_state[(size_t)n * H + j] : 0.f) + dh * go * (1.f - tc * tc);
-            st_xchg_4<E>(static_cast<E*>(a.dz) + p * K + (size_t)j * 4, dc * gg * gi * (1.f - gi),
-                         dc * sv.c_prev * gf * (1.f - gf), dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
+            const float dzi = dc * gg * gi * (1.f - gi), dzf = dc * sv.c_prev * gf * (1.f - gf),
+                        dzg = dc * gi * (1.f - gg * gg), dzo = dh * tc * go * (1.f - go);
+            st_xchg_4<E>(static_cast<E*>(a.dz) + p * K + (size_t)j * 4, dzi, dzf, dzg, dzo);
+            if (use_ll && t > 0) ll_store4<E>(ll_slot, n, K, j * 4, (unsigned)(T - t), dzi, dzf, dzg, dzo);
             a.dc_state[(size_t)n * H + j] = dc * gf;
         }
         if (t == 0) break;  // nothing is carried before the first timestep
@@ -456,16 +546,22 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
                 pre = load_saved(a, t - 1, base_p, (t > 1) ? a.t_off[t - 2] : 0, tid / UH, j0 + (tid % UH), H);
         }
         REC_PROF_MARK(8);
-        rec_publish(a.flags, T - t);
-        REC_PROF_MARK(9);
-        rec_wait(a.flags, G, T - t, a.err);
+        if (!use_ll) {
+            rec_publish(a.flags, T - t);
+            REC_PROF_MARK(9);
+            rec_wait(a.flags, G, T - t, a.err);
+        }
         REC_PROF_MARK(10);
         // B. dh carried to t-1: dh[n][k] = sum_q dz[n][q] * W_hh[q][k] for this workgroup's 16 columns k
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
-            if (c0 > 0) __syncthreads();
-            stage_rows<E>(dzr + (size_t)(base + c0) * K, rows, K, sB, stride);
-            __syncthreads();
+            if (use_ll) {
+                ll_stage<E>(ll_slot, rows, K, (unsigned)(T - t), sB, stride, a.err);
+            } else {
+                if (c0 > 0) __syncthreads();
+                stage_rows<E>(dzr + (size_t)(base + c0) * K, rows, K, sB, stride);
+                __syncthreads();
+            }
             REC_PROF_MARK(11);
             f32x4_t acc[REC_NTC];
 #pragma unroll
