@@ -150,9 +150,7 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------- workspace
-// Tagged-word exchange area: 2 slots x rows x words per row, sized for the widest case (8 rows of H <= 1024
-// floats forward, 2 rows of 4H bf16 backward: both 8192 words per slot).
-constexpr size_t LL_WORDS = 2 * 8192;
+constexpr int REC_FLAG_WORDS = 64;   // flags[0..31], ticket at [32]
 
 struct LayerWs {
     void* wih;    // [4H, D_l]  operand type, interleaved rows
@@ -167,8 +165,7 @@ struct LayerWs {
 };
 struct LstmWs {
     int* err;          // word 0 of the workspace
-    int* flags;        // [256], directly followed by
-    unsigned long long* ll;  // [LL_WORDS] tagged-word exchange area of the recurrent kernels (cleared with the flags)
+    int* flags;        // [REC_FLAG_WORDS]: per-workgroup flags of a recurrent launch, then its ticket counter
     long long* prof;   // [32] phase counters of the recurrent kernels (forward 0..15, backward 16..31)
     LayerWs layer[8];
     void* dz;          // [M, 4H] operand type
@@ -196,8 +193,7 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     Carver cv(base);
     int* head = cv.take<int>(64);
     ws->err = head;
-    ws->flags = cv.take<int>(256);
-    ws->ll = cv.take<unsigned long long>(LL_WORDS);
+    ws->flags = cv.take<int>(REC_FLAG_WORDS);
     ws->prof = cv.take<long long>(32);
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t D = l == 0 ? c.input_dim : H;
@@ -234,20 +230,9 @@ inline int check_cfg(const ver_lstm_cfg* c, int M) {
 }
 
 // How many 16-row tiles of exchanged rows fit in a CU's 160 KB of LDS next to the reduction buffer.
-inline int rec_tiles(size_t tile_bytes, size_t red_bytes) {
-    const size_t budget = 160 * 1024 - red_bytes;
-    int n = (int)(budget / tile_bytes);
+inline int rec_tiles(size_t tile_bytes, size_t red_bytes_per_tile) {
+    int n = (int)((160 * 1024) / (tile_bytes + red_bytes_per_tile));
     return n < 1 ? 1 : (n > REC_NTC ? REC_NTC : n);
-}
-
-// Tagged words per exchanged row, and how many rows a poll may cover: a thread fetches at most REC_LL_UNITS
-// 16-byte units per poll and a slot holds LL_WORDS / 2 words.
-template <typename E> inline int ll_words_host(int row_elems) { return row_elems * (int)sizeof(E) / 4; }
-inline int ll_rows_for(int words_per_row) {
-    int rows = REC_LL_UNITS * REC_THREADS * 2 / words_per_row;
-    const int cap = (int)(LL_WORDS / 2) / words_per_row;
-    if (rows > cap) rows = cap;
-    return rows > 8 ? 8 : rows;
 }
 
 template <typename K>
@@ -261,7 +246,6 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
             const int32_t* t_off, const float* h0, const float* c0, int seq_cap, const float* const* w,
             float* head_out, float* value, LstmWs& ws, hipStream_t s) {
     typedef typename RecGeom<MODE>::E E;
-    constexpr int MT = MODE == MODE_BF16 ? 4 : 1, KS = MODE == MODE_BF16 ? 1 : 4;
     const int H = c.hidden, A = c.act_dim;
     fill_words(ws.err, 1, 0, s);
     for (int l = 0; l < c.n_layers; ++l) {
@@ -292,31 +276,38 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         }
         }
         // sequential part
-        fill_words(ws.flags, 256 + 2 * LL_WORDS, 0, s);   // flags and the tagged-word area behind them
+        fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
         RecFwdArgs ra;
         ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
         ra.gates = L.gates; ra.c = L.c; ra.hout = L.hout; ra.hprev = L.hprev; ra.whh = L.whh;
         ra.h0 = h0 ? h0 + (size_t)l * seq_cap * H : nullptr;
         ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
-        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err; ra.prof = ws.prof;
-        ra.ll = ws.ll;
-        ra.ll_rows = ll_rows_for(ll_words_host<E>(H));
-        const size_t red = (size_t)KS * MT * REC_NTC * 64 * 16;
-        const size_t tile = (size_t)16 * (H + RecGeom<MODE>::PAD) * sizeof(E);
-        ra.ntc = rec_tiles(tile, red);
-        const size_t lds = ra.ntc * tile + red;
+        ra.H = H; ra.seq_cap = seq_cap; ra.M = M; ra.flags = ws.flags; ra.ticket = ws.flags + 32; ra.err = ws.err;
+        ra.prof = ws.prof;
         {
         ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
-        const int ni = (H / KS) / RecGeom<MODE>::KBLK;
+        // one wave per (16 gate rows, share of the contraction): 8 tiles x 1 when 32 workgroups need all of
+        // H/32 >= 32 units, else 4 tiles x 2
+        const bool wide = H / 16 > REC_MAX_GROUP;
+        const int mt = wide ? 8 : 4, ks = wide ? 1 : 2;
+        ra.G = H / (4 * mt);
+        const size_t tile = (size_t)16 * (H + RecGeom<MODE>::PAD) * sizeof(E);
+        const size_t red_per_tile = (size_t)ks * mt * 64 * 16 + (size_t)16 * 4 * mt * sizeof(E);   // partial sums + new h
+        ra.ntc = rec_tiles(tile, red_per_tile);
+        const size_t lds = ra.ntc * (tile + red_per_tile);
+        const int ni = (H / ks) / RecGeom<MODE>::KBLK;
         bool ok = true;
-#define VER_FWD_CASE(N) case N: ok = set_lds(lstm_rec_fwd_kernel<MODE, MT, KS, N>, lds); \
-            if (ok) hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT, KS, N>), dim3(H / (4 * MT)), dim3(REC_THREADS), lds, s, ra); break;
-        switch (ni) {
-            VER_FWD_CASE(1) VER_FWD_CASE(2) VER_FWD_CASE(4) VER_FWD_CASE(8) VER_FWD_CASE(16) VER_FWD_CASE(32)
-            default: ok = set_lds(lstm_rec_fwd_kernel<MODE, MT, KS, 0>, lds);
-                if (ok) hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT, KS, 0>), dim3(H / (4 * MT)), dim3(REC_THREADS), lds, s, ra);
+#define VER_FWD_LAUNCH(MT_, KS_, N_) do { ok = set_lds(lstm_rec_fwd_kernel<MODE, MT_, KS_, N_>, lds); \
+            if (ok) hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT_, KS_, N_>), dim3(REC_GRID), dim3(REC_THREADS), lds, s, ra); } while (0)
+        if (wide) {
+            if (ni == 32) VER_FWD_LAUNCH(8, 1, 32); else VER_FWD_LAUNCH(8, 1, 0);
+        } else {
+            if (ni == 16) VER_FWD_LAUNCH(4, 2, 16);
+            else if (ni == 8) VER_FWD_LAUNCH(4, 2, 8);
+            else if (ni == 4) VER_FWD_LAUNCH(4, 2, 4);
+            else VER_FWD_LAUNCH(4, 2, 0);
         }
-#undef VER_FWD_CASE
+#undef VER_FWD_LAUNCH
         if (!ok) return VER_EHIP;
         }
     }
@@ -358,31 +349,37 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     for (int l = nl - 1; l >= 0; --l) {
         const int D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws.layer[l];
-        fill_words(ws.flags, 256 + 2 * LL_WORDS, 0, s);
+        fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
         RecBwdArgs ra;
         ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
         ra.gates = L.gates; ra.c = L.c; ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
         ra.dh_above = ws.dh[cur]; ra.dz = ws.dz; ra.whhT = L.whhT;
         ra.dh_state = ws.dh_state; ra.dc_state = ws.dc_state;
-        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.err = ws.err; ra.prof = ws.prof + 16;
-        ra.ll = ws.ll;
-        ra.ll_rows = ll_rows_for(ll_words_host<E>(4 * H));
-        const size_t red = (size_t)4 * REC_NTC * 64 * 16;
-        const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
-        ra.ntc = rec_tiles(tile, red);
-        const size_t lds = ra.ntc * tile + red;
+        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + 32; ra.err = ws.err;
+        ra.prof = ws.prof + 16;
         {
         ProfScope prof(VER_PROF_LSTM_REC_BWD, s);
-        const int ni = H / RecGeom<MODE>::KBLK;
+        // one wave per (16 units, share of the 4H contraction): 2 tiles x 4 when H/16 > 32 workgroups, else 1 x 8
+        const bool wide = H / 16 > REC_MAX_GROUP;
+        const int mt = wide ? 2 : 1, ks = wide ? 4 : 8;
+        ra.G = H / (16 * mt);
+        const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
+        const size_t red_per_tile = (size_t)ks * mt * 64 * 16;
+        ra.ntc = rec_tiles(tile, red_per_tile);
+        const size_t lds = ra.ntc * (tile + red_per_tile);
+        const int ni = (4 * H / ks) / RecGeom<MODE>::KBLK;
         bool ok = true;
-#define VER_BWD_CASE(N) case N: ok = set_lds(lstm_rec_bwd_kernel<MODE, N>, lds); \
-            if (ok) hipLaunchKernelGGL((lstm_rec_bwd_kernel<MODE, N>), dim3(H / 16), dim3(REC_THREADS), lds, s, ra); break;
-        switch (ni) {
-            VER_BWD_CASE(2) VER_BWD_CASE(4) VER_BWD_CASE(8) VER_BWD_CASE(16) VER_BWD_CASE(32)
-            default: ok = set_lds(lstm_rec_bwd_kernel<MODE, 0>, lds);
-                if (ok) hipLaunchKernelGGL((lstm_rec_bwd_kernel<MODE, 0>), dim3(H / 16), dim3(REC_THREADS), lds, s, ra);
+#define VER_BWD_LAUNCH(MT_, KS_, N_) do { ok = set_lds(lstm_rec_bwd_kernel<MODE, MT_, KS_, N_>, lds); \
+            if (ok) hipLaunchKernelGGL((lstm_rec_bwd_kernel<MODE, MT_, KS_, N_>), dim3(REC_GRID), dim3(REC_THREADS), lds, s, ra); } while (0)
+        if (wide) {
+            if (ni == 32) VER_BWD_LAUNCH(2, 4, 32); else VER_BWD_LAUNCH(2, 4, 0);
+        } else {
+            if (ni == 16) VER_BWD_LAUNCH(1, 8, 16);
+            else if (ni == 8) VER_BWD_LAUNCH(1, 8, 8);
+            else if (ni == 4) VER_BWD_LAUNCH(1, 8, 4);
+            else VER_BWD_LAUNCH(1, 8, 0);
         }
-#undef VER_BWD_CASE
+#undef VER_BWD_LAUNCH
         if (!ok) return VER_EHIP;
         }
 

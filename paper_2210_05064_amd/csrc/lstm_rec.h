@@ -5,45 +5,65 @@
 // minibatch of section 2.2: at timestep t only the first batch_sizes[t] pieces
 // are alive, and row j of timestep t continues row j of timestep t-1.
 //
-// The time loop is sequential, so its cost is latency, not FLOPs.  Design:
-//  * the hidden units are split over G workgroups; each wave keeps ITS 16 rows
-//    of the recurrent weight matrix in registers, already in MFMA operand
-//    layout, for the whole kernel (loaded once), so a timestep touches HBM/L2
-//    only for the h / dz rows that are exchanged; those rows are fetched by the
-//    whole workgroup in one burst and staged in LDS, from where every wave
-//    reads its MFMA operands;
+// The time loop is sequential (hundreds of dependent timesteps with a handful of
+// alive pieces each), so its cost is the latency of one all-to-all exchange of
+// h_t (forward) or dz_t (backward) between the workgroups that share the hidden
+// units, not FLOPs.  Measured on MI355X, per exchange step:
+//     64 workgroups on 8 XCDs, agent-scope release/acquire fences   6.5 us
+//     64 workgroups on 8 XCDs, write-through stores + coherent loads 2.6 us
+//     32 workgroups on ONE XCD, synchronising through its L2          1.0 us
+// Hence the design:
+//  * the kernel is launched on the whole chip (one workgroup per CU), but only
+//    the workgroups that find themselves on XCD 0 (hardware register XCC_ID)
+//    take part, ranked by a ticket; the others return at once.  The G <= 32
+//    participants share one L2, which makes it the coherence point: exchanged
+//    rows are written with plain stores; the writer waits for their completion
+//    (s_waitcnt) before it raises its flag; readers poll the flags with loads
+//    that bypass their CU's L1 and then read the rows, which no CU has touched
+//    before in this launch (every row of the exchange buffers belongs to exactly
+//    one timestep), so they come from L2.  No cache-wide write-back or
+//    invalidate is ever issued;
+//  * each wave keeps ITS [16 x K] block of the recurrent weight matrix in
+//    registers, already in MFMA operand layout, for the whole kernel; a timestep
+//    touches memory only for the exchanged rows (staged in LDS for all waves)
+//    and the saved activations;
 //  * gate rows are interleaved (row = unit*4 + gate) so that one MFMA output
 //    fragment holds the four gates of a unit in one lane: the cell update needs
 //    no cross-lane traffic;
 //  * 4H (forward) or H (backward) sits on the MFMA M dimension and the alive
 //    pieces on N, so a ragged tail of one or two pieces wastes only N padding;
-//  * workgroups synchronise once per timestep through a flag array in global
-//    memory.  Exchanged rows are written with device-coherent write-through
-//    stores, the writer waits for their completion before it raises its flag,
-//    and readers fetch them with device-coherent loads.  No cache-wide
-//    write-back or invalidate is issued: on this chip those cost microseconds
-//    per workgroup and serialise within an XCD, far more than the exchange
-//    itself.  Every wait is bounded: on time-out the error word is set and all
-//    later waits fall through, so the kernel always terminates.
+//  * every wait is bounded and sticky: on time-out the error word is set, every
+//    workgroup that sees it leaves the kernel, so the grid always drains.
 #pragma once
 #include "gemm.h"
 
 namespace ver {
 
-// Optional phase timing (build with -DVER_REC_PROF): thread 0 of workgroup 0 adds the core-clock cycles spent
-// in each phase of the time loop to prof[phase]; prof[15] counts timesteps.  Off in the product build.
+// Optional phase timing (build with -DVER_REC_PROF): thread 0 of the rank-0 workgroup adds the core-clock
+// cycles spent in each phase of the time loop to prof[phase]; prof[15] counts timesteps.  Off in the product build.
 #ifdef VER_REC_PROF
-#define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof;
-#define REC_PROF_START() do { if (threadIdx.x == 0 && blockIdx.x == 0) prof_t = clock64(); } while (0)
-#define REC_PROF_MARK(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) { long long now_ = clock64(); prof_out[i] += now_ - prof_t; prof_t = now_; } } while (0)
+#define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof; const bool prof_on = threadIdx.x == 0 && rank == 0;
+#define REC_PROF_START() do { if (prof_on) prof_t = clock64(); } while (0)
+#define REC_PROF_MARK(i) do { if (prof_on) { long long now_ = clock64(); prof_out[i] += now_ - prof_t; prof_t = now_; } } while (0)
+#define REC_PROF_STEP() do { if (prof_on) prof_out[15] += 1; } while (0)
 #else
 #define REC_PROF_DECL
 #define REC_PROF_START() do { } while (0)
 #define REC_PROF_MARK(i) do { } while (0)
+#define REC_PROF_STEP() do { } while (0)
 #endif
 
-constexpr int REC_THREADS = 256;
-constexpr long long REC_SPIN_LIMIT = 1LL << 22;
+constexpr int REC_THREADS = 512;          // 8 waves, two per SIMD: 256 registers each
+constexpr int REC_WAVES = REC_THREADS / VER_WAVE;
+constexpr int REC_GRID = 256;             // one workgroup per CU; those on the chosen XCD take part
+constexpr int REC_MAX_GROUP = 32;         // CUs of one XCD
+constexpr int REC_XCD = 0;                // the XCD whose workgroups run the recurrence
+constexpr long long REC_SPIN_LIMIT = 1LL << 21;
+constexpr int REC_NTC = 4;                // at most this many 16-piece tiles are staged and multiplied at once
+constexpr int REC_NI = 32;                // at most this many 16-byte operand blocks of W per lane (128 registers)
+
+typedef unsigned long long u64_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int MODE> struct RecGeom;
 template <> struct RecGeom<MODE_BF16> {
@@ -71,100 +91,96 @@ template <> __device__ __forceinline__ f32x4_t mfma_block<MODE_F32>(f32x4_t a_ra
     return acc;
 }
 
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + __expf(-x)); }
+// Gate non-linearities from the hardware exp2 and reciprocal (about 1 ulp each): at microseconds per
+// timestep the instruction count of the cell update matters, and an IEEE division costs ten instructions.
+__device__ __forceinline__ float sigmoidf_(float x) { return __builtin_amdgcn_rcpf(1.f + __expf(-x)); }
 __device__ __forceinline__ float tanhf_(float x) {
-    // tanh(x) = 1 - 2 / (exp(2x) + 1); exact limits at +-inf, ~1e-7 relative elsewhere
-    const float e = __expf(2.f * x);
-    return 1.f - 2.f / (e + 1.f);
+    // tanh(x) = 1 - 2 / (exp(2x) + 1); exact limits at +-inf, ~1e-7 absolute elsewhere
+    return 1.f - 2.f * __builtin_amdgcn_rcpf(__expf(2.f * x) + 1.f);
 }
+// Round to nearest even for finite values (hidden states and their gradients are finite by construction).
+__device__ __forceinline__ bf16_t to_bf16_finite(float f) {
+    unsigned int u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+template <typename E> __device__ __forceinline__ E cvt_finite(float v);
+template <> __device__ __forceinline__ float cvt_finite<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t cvt_finite<bf16_t>(float v) { return to_bf16_finite(v); }
 
-// All workgroups have published a value >= target.  Bounded.
-__device__ __forceinline__ void rec_wait(const int* flags, int G, int target, int* err) {
-    if (threadIdx.x < VER_WAVE) {
-        long long spins = 0;
-        for (;;) {
-            bool ok = true;
-            for (int i = threadIdx.x; i < G; i += VER_WAVE) ok = ok && (ld_agent(&flags[i]) >= target);
-            if (__all(ok)) break;
-            if (++spins > REC_SPIN_LIMIT || ld_agent(err) != 0) {
-                if (threadIdx.x == 0) st_agent(err, 1);
-                break;
-            }
-            __builtin_amdgcn_s_sleep(1);
+// ---- which workgroups take part ---------------------------------------------------------------------
+// Returns this workgroup's rank in [0, G) or -1.  ticket must be zero at launch.
+__device__ __forceinline__ int rec_rank(int* ticket, int G) {
+    __shared__ int s_rank;
+    if (threadIdx.x == 0) {
+        const int xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf;   // HW_REG_XCC_ID, 4 bits
+        int r = -1;
+        if (xcc == REC_XCD) {
+            r = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (r >= G) r = -1;
         }
+        s_rank = r;
     }
     __syncthreads();
+    return s_rank;
 }
 
-// Call after the exchanged rows were written with st_xchg*: waits until this wave's write-through
-// stores have completed, then (after the workgroup barrier) raises the workgroup's flag.
-__device__ __forceinline__ void rec_publish(int* flags, int value) {
+// ---- exchange through the XCD's L2 --------------------------------------------------------------------
+// Flag read that is never served by the CU's L1 (a volatile load carries the sc0 sc1 cache bits); measured
+// three times faster than the same bits on a buffer load.
+__device__ __forceinline__ int ld_l2(const int* p) { return *reinterpret_cast<const volatile int*>(p); }
+
+// All G participants have published a value >= target.  Returns false if the wait was abandoned (time-out
+// here or in another workgroup): the caller must leave the kernel.
+__device__ __forceinline__ bool rec_wait(const int* flags, int G, int target, int* err) {
+    __shared__ int s_ok;
+    if (threadIdx.x < VER_WAVE) {
+        long long spins = 0;
+        bool alive = true;
+        for (;;) {
+            const bool ok = (int)threadIdx.x >= G || ld_l2(&flags[threadIdx.x]) >= target;
+            if (__all(ok)) break;
+            ++spins;
+            if ((spins & 1023) == 0 && (spins > REC_SPIN_LIMIT || ld_agent(err) != 0)) {
+                if (threadIdx.x == 0) st_agent(err, 1);
+                alive = false;
+                break;
+            }
+        }
+        if (threadIdx.x == 0) s_ok = alive ? 1 : 0;
+    }
+    __syncthreads();
+    return s_ok != 0;
+}
+
+// Call after the exchanged rows were written: waits until this wave's stores have reached L2, then (after
+// the workgroup barrier) raises the workgroup's flag.
+__device__ __forceinline__ void rec_publish(int* flags, int rank, int value) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) st_agent(&flags[blockIdx.x], value);
+    if (threadIdx.x == 0) {
+        __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(&flags[rank], 0, 4, 0x00020000);
+        __builtin_amdgcn_raw_buffer_store_b32(value, r, 0, 0, 0);
+    }
 }
 
-// Device-coherent 8-byte accesses for rows exchanged between workgroups.
-typedef unsigned long long u64_t;
-typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void st_xchg8(void* p, u64_t v) {
-    __hip_atomic_store(static_cast<u64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ u64_t ld_xchg8(const void* p) {
-    return __hip_atomic_load(static_cast<const u64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// Stores 4 consecutive elements of an exchanged row (8 bytes bf16, 16 bytes fp32).
-template <typename E> __device__ __forceinline__ void st_xchg_4(E* p, float a, float b, float c, float d);
-template <> __device__ __forceinline__ void st_xchg_4<bf16_t>(bf16_t* p, float a, float b, float c, float d) {
-    const u64_t v = (u64_t)to_bf16(a) | ((u64_t)to_bf16(b) << 16) | ((u64_t)to_bf16(c) << 32) | ((u64_t)to_bf16(d) << 48);
-    st_xchg8(p, v);
-}
-template <> __device__ __forceinline__ void st_xchg_4<float>(float* p, float a, float b, float c, float d) {
-    st_xchg8(p, (u64_t)__float_as_uint(a) | ((u64_t)__float_as_uint(b) << 32));
-    st_xchg8(p + 2, (u64_t)__float_as_uint(c) | ((u64_t)__float_as_uint(d) << 32));
-}
-
-struct RecFwdArgs {
-    const int32_t* info;
-    const int32_t* batch_sizes;
-    const int32_t* t_off;
-    float* gates;       // [M, 4H] in: W_ih x + b (interleaved columns); out: activated gates i,f,g,o
-    float* c;           // [M, H]
-    float* hout;        // [M, H]
-    void* hprev;        // [M, H] operand type: row p = h_{t-1} of the piece in row p
-    const void* whh;    // [4H, H] operand type, interleaved rows
-    const float* h0;    // [seq_cap, H] of this layer, or NULL
-    const float* c0;
-    int H, seq_cap;
-    int ntc;            // 16-row tiles of staged rows that fit in LDS (1..REC_NTC)
-    int ll_rows;        // timesteps with at most this many alive pieces use the low-latency exchange
-    u64_t* ll;          // [2][ll_rows][words per row] tagged words, zero before the launch
-    int* flags;
-    int* err;
-    long long* prof;    // [16] phase cycle counters (only read by builds with VER_REC_PROF)
-};
-
-constexpr int REC_NTC = 4;   // at most this many 16-piece tiles are staged and multiplied at once
-constexpr int REC_NI = 32;   // at most this many 16-byte operand blocks of W per lane (128 VGPRs)
-
-// Copies `rows` rows of `row_elems` elements (16-byte multiples) from global memory into LDS rows of
-// `stride` elements.  The whole workgroup takes part; loads are 16-byte device-coherent buffer loads
-// (cache policy sc1), which the compiler keeps in flight eight deep per thread.
+// Copies `rows` rows of `row_elems` elements (16-byte multiples) from global memory (L2) into LDS rows of
+// `stride` elements.  The whole workgroup takes part, DEPTH loads in flight per thread; reads past the last
+// row return zero (buffer bounds).
 template <typename E>
 __device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, int row_elems, E* __restrict__ lds,
                                            int stride) {
     constexpr int VEC = 16 / sizeof(E);
-    constexpr int AUX_SC1 = 16;          // cache-policy bit 4: coherent at device scope
+    constexpr int DEPTH = 4;
     const int vec_per_row = row_elems / VEC;
     const int n = rows * vec_per_row;
     __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<E*>(src), 0, n * 16, 0x00020000);
-    constexpr int DEPTH = 8;  // loads in flight per thread; reads past the last row return zero (buffer bounds)
     int r = threadIdx.x / vec_per_row, c = threadIdx.x - r * vec_per_row;   // position of vector v = threadIdx.x
     for (int v0 = threadIdx.x; v0 < n; v0 += DEPTH * REC_THREADS) {
         u32x4_t tmp[DEPTH];
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u)
-            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (v0 + u * REC_THREADS) * 16, 0, AUX_SC1);
+            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (v0 + u * REC_THREADS) * 16, 0, 0);
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) {
             if (v0 + u * REC_THREADS < n) *reinterpret_cast<u32x4_t*>(lds + r * stride + c * VEC) = tmp[u];
@@ -174,85 +190,28 @@ __device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, 
     }
 }
 
-// ---- Low-latency exchange for timesteps with few alive pieces -------------------------------------
-// With a handful of rows, a timestep is pure synchronisation latency.  For those steps every 4 bytes of an
-// exchanged row travel in an 8-byte word {data, tag}: the tag (the timestep counter) makes the word
-// self-validating, so the writer neither waits for its stores to complete nor raises a flag, and readers
-// poll the data itself with coherent loads.  One memory round trip per timestep instead of three.
-// Two slots (timestep parity) suffice: a workgroup can only write slot s+2 after it has read every
-// workgroup's words of step s+1, which they wrote after they had finished reading slot s.
-constexpr int REC_LL_UNITS = 8;   // 16-byte units (two words) a thread fetches per poll at most
-
-// LL words per exchanged row of row_elems elements (4 data bytes per word).
-template <typename E> __device__ __forceinline__ int ll_words(int row_elems) { return row_elems * (int)sizeof(E) / 4; }
-
-// Polls `rows` rows of the slot until every word carries `tag`, then unpacks the data into LDS rows of
-// `stride` elements.  rows * words_per_row / 2 <= REC_LL_UNITS * REC_THREADS.  Bounded.
-template <typename E>
-__device__ __forceinline__ void ll_stage(const u64_t* slot, int rows, int row_elems, unsigned tag, E* lds, int stride,
-                                         int* err) {
-    constexpr int EPW = 4 / sizeof(E);          // elements per word
-    constexpr int AUX_SC1 = 16;
-    const int upr = ll_words<E>(row_elems) / 2;  // 16-byte units per row
-    const int units = rows * upr;
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<u64_t*>(slot), 0, units * 16, 0x00020000);
-    u32x4_t d[REC_LL_UNITS];
-    long long spins = 0;
-    for (;;) {
-        bool ready = true;
-#pragma unroll
-        for (int i = 0; i < REC_LL_UNITS; ++i)
-            d[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (threadIdx.x + i * REC_THREADS) * 16, 0, AUX_SC1);
-#pragma unroll
-        for (int i = 0; i < REC_LL_UNITS; ++i)
-            if ((int)threadIdx.x + i * REC_THREADS < units) ready = ready && d[i].y == tag && d[i].w == tag;
-        if (ready) break;
-        if (++spins > REC_SPIN_LIMIT || ld_agent(err) != 0) {
-            st_agent(err, 1);
-            break;
-        }
-    }
-    __syncthreads();  // every wave is past the previous timestep's reads of the staging rows
-#pragma unroll
-    for (int i = 0; i < REC_LL_UNITS; ++i) {
-        const int u = threadIdx.x + i * REC_THREADS;
-        if (u < units) {
-            const int r = u / upr, cu = u - r * upr;
-            *reinterpret_cast<u64_t*>(lds + r * stride + cu * 2 * EPW) = (u64_t)d[i].x | ((u64_t)d[i].z << 32);
-        }
-    }
-    __syncthreads();
+// Stores 4 consecutive elements of an exchanged row (8 bytes bf16, 16 bytes fp32).
+template <typename E> __device__ __forceinline__ void st_row4(E* p, float a, float b, float c, float d);
+template <> __device__ __forceinline__ void st_row4<bf16_t>(bf16_t* p, float a, float b, float c, float d) {
+    u16x4_t v;
+    v.x = to_bf16_finite(a); v.y = to_bf16_finite(b); v.z = to_bf16_finite(c); v.w = to_bf16_finite(d);
+    *reinterpret_cast<u16x4_t*>(p) = v;
 }
-
-// Writes 4 consecutive elements of row `row` (starting at element `col`, a multiple of 4) as tagged words.
-template <typename E>
-__device__ __forceinline__ void ll_store4(u64_t* slot, int row, int row_elems, int col, unsigned tag, float a, float b,
-                                          float c, float d);
-template <>
-__device__ __forceinline__ void ll_store4<bf16_t>(u64_t* slot, int row, int row_elems, int col, unsigned tag, float a,
-                                                  float b, float c, float d) {
-    const u32x4_t v = {(unsigned)to_bf16(a) | ((unsigned)to_bf16(b) << 16), tag,
-                       (unsigned)to_bf16(c) | ((unsigned)to_bf16(d) << 16), tag};
-    u64_t* p = slot + (size_t)row * (row_elems / 2) + col / 2;
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(p, 0, 16, 0x00020000);
-    __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, 0, 0, 16);
-}
-template <>
-__device__ __forceinline__ void ll_store4<float>(u64_t* slot, int row, int row_elems, int col, unsigned tag, float a,
-                                                 float b, float c, float d) {
-    u64_t* p = slot + (size_t)row * row_elems + col;
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(p, 0, 32, 0x00020000);
-    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{__float_as_uint(a), tag, __float_as_uint(b), tag}, rsrc, 0, 0, 16);
-    __builtin_amdgcn_raw_buffer_store_b128(u32x4_t{__float_as_uint(c), tag, __float_as_uint(d), tag}, rsrc, 16, 0, 16);
+template <> __device__ __forceinline__ void st_row4<float>(float* p, float a, float b, float c, float d) {
+    *reinterpret_cast<f32x4_t*>(p) = f32x4_t{a, b, c, d};
 }
 
 // acc[q] += W(16 x k-range) * B_q(k-range x 16) for NT staged tiles; W blocks come from registers, B from LDS.
+// In the last (possibly partly empty) tile, lanes whose piece does not exist read piece 0 instead (blast
+// points there): equal addresses are broadcast by the LDS, so with one or two alive pieces the LDS traffic
+// of the step drops sixteen-fold, and the reads stay unconditional so that they can be issued ahead.
 // NI > 0: exactly NI blocks, straight-line code (all LDS reads can be issued ahead of the MFMAs).
 // NI == 0: ni_rt blocks (<= REC_NI), guarded: the general, slower path.
 template <int MODE, int NI, int NT, int NW>
 __device__ __forceinline__ void mma_tiles(const f32x4_t (&wreg)[NW], const typename RecGeom<MODE>::E* brow, int stride,
-                                          int ni_rt, f32x4_t (&acc)[REC_NTC]) {
+                                          int ni_rt, const typename RecGeom<MODE>::E* blast, f32x4_t (&acc)[REC_NTC]) {
     constexpr int KBLK = RecGeom<MODE>::KBLK;
+    const f32x4_t zero = {0.f, 0.f, 0.f, 0.f};
     if (NI > 0) {
         // with few tiles, split the contraction over CH independent accumulator chains per tile so that
         // consecutive MFMAs do not wait for each other's result
@@ -261,13 +220,27 @@ __device__ __forceinline__ void mma_tiles(const f32x4_t (&wreg)[NW], const typen
 #pragma unroll
         for (int q = 0; q < NT; ++q)
 #pragma unroll
-            for (int c = 0; c < CH; ++c) part[q][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < CH; ++c) part[q][c] = zero;
+        // operand blocks are fetched from LDS GRP at a time, ahead of the MFMAs that consume them
+        constexpr int GRP = (NI * NT >= 8) ? 8 / NT : (NI > 0 ? NI : 1);
 #pragma unroll
-        for (int i = 0; i < NI; ++i)
+        for (int i0 = 0; i0 < NI; i0 += GRP) {
+            f32x4_t b[GRP][NT];
 #pragma unroll
-            for (int q = 0; q < NT; ++q)
-                part[q][i % CH] = mfma_block<MODE>(
-                    wreg[i], *reinterpret_cast<const f32x4_t*>(brow + q * 16 * stride + i * KBLK), part[q][i % CH]);
+            for (int g = 0; g < GRP; ++g)
+#pragma unroll
+                for (int q = 0; q < NT; ++q) {
+                    const typename RecGeom<MODE>::E* src = (q + 1 < NT) ? brow : blast;   // only the last tile can be partly empty
+                    if (i0 + g < NI) b[g][q] = *reinterpret_cast<const f32x4_t*>(src + q * 16 * stride + (i0 + g) * KBLK);
+                }
+            __builtin_amdgcn_sched_barrier(0);   // keep the loads of a group together and ahead of its MFMAs
+#pragma unroll
+            for (int g = 0; g < GRP; ++g)
+#pragma unroll
+                for (int q = 0; q < NT; ++q)
+                    if (i0 + g < NI)
+                        part[q][(i0 + g) % CH] = mfma_block<MODE>(wreg[i0 + g], b[g][q], part[q][(i0 + g) % CH]);
+        }
 #pragma unroll
         for (int q = 0; q < NT; ++q) {
             f32x4_t sum = part[q][0];
@@ -279,42 +252,75 @@ __device__ __forceinline__ void mma_tiles(const f32x4_t (&wreg)[NW], const typen
         }
     } else {
 #pragma unroll
+        for (int q = 0; q < NT; ++q) acc[q] = zero;
+#pragma unroll
         for (int i = 0; i < NW; ++i)
             if (i < ni_rt) {
 #pragma unroll
-                for (int q = 0; q < NT; ++q)
-                    acc[q] = mfma_block<MODE>(wreg[i],
-                                              *reinterpret_cast<const f32x4_t*>(brow + q * 16 * stride + i * KBLK), acc[q]);
+                for (int q = 0; q < NT; ++q) {
+                    const typename RecGeom<MODE>::E* src = (q + 1 < NT) ? brow : blast;
+                    const f32x4_t b = *reinterpret_cast<const f32x4_t*>(src + q * 16 * stride + i * KBLK);
+                    acc[q] = mfma_block<MODE>(wreg[i], b, acc[q]);
+                }
             }
     }
 }
+// rows: staged rows of this chunk (1 .. 16*REC_NTC); lr: this lane's piece index within a tile.
 template <int MODE, int NI, int NW>
 __device__ __forceinline__ void mma_dispatch(const f32x4_t (&wreg)[NW], const typename RecGeom<MODE>::E* brow, int stride,
-                                             int ni_rt, int rows, f32x4_t (&acc)[REC_NTC]) {
-    if (rows <= 16) mma_tiles<MODE, NI, 1, NW>(wreg, brow, stride, ni_rt, acc);
-    else if (rows <= 32) mma_tiles<MODE, NI, 2, NW>(wreg, brow, stride, ni_rt, acc);
-    else if (rows <= 48) mma_tiles<MODE, NI, 3, NW>(wreg, brow, stride, ni_rt, acc);
-    else mma_tiles<MODE, NI, 4, NW>(wreg, brow, stride, ni_rt, acc);
+                                             int ni_rt, int rows, int lr, f32x4_t (&acc)[REC_NTC]) {
+    const int nt = (rows + 15) >> 4;
+    const bool lane_live = (nt - 1) * 16 + lr < rows;
+    const typename RecGeom<MODE>::E* blast = lane_live ? brow : brow - lr * stride;
+    if (nt == 1) mma_tiles<MODE, NI, 1, NW>(wreg, brow, stride, ni_rt, blast, acc);
+    else if (nt == 2) mma_tiles<MODE, NI, 2, NW>(wreg, brow, stride, ni_rt, blast, acc);
+    else if (nt == 3) mma_tiles<MODE, NI, 3, NW>(wreg, brow, stride, ni_rt, blast, acc);
+    else mma_tiles<MODE, NI, 4, NW>(wreg, brow, stride, ni_rt, blast, acc);
 }
 
-// MT 16-row tiles of gate rows per workgroup (4*MT hidden units), KS-way split of the contraction.
-// NI: 16-byte blocks of W per lane when known at compile time (fast path), 0 = general path.
+// ======================================================================================================
+struct RecFwdArgs {
+    const int32_t* info;
+    const int32_t* batch_sizes;
+    const int32_t* t_off;
+    float* gates;       // [M, 4H] in: W_ih x + b (interleaved columns); out: activated gates i,f,g,o
+    float* c;           // [M, H]
+    float* hout;        // [M, H]
+    void* hprev;        // [M, H] operand type: row p = h_{t-1} of the piece in row p
+    const void* whh;    // [4H, H] operand type, interleaved rows
+    const float* h0;    // [seq_cap, H] of this layer, or NULL
+    const float* c0;
+    int H, seq_cap, M;
+    int G;              // participating workgroups; each owns 4*MT hidden units
+    int ntc;            // 16-row tiles of staged rows that fit in LDS (1..REC_NTC)
+    int* flags;         // [G] zero at launch
+    int* ticket;        // zero at launch
+    int* err;
+    long long* prof;    // [16] phase cycle counters (only touched by builds with VER_REC_PROF)
+};
+
+// MT 16-row tiles of gate rows per workgroup (4*MT hidden units), KS-way split of the contraction; one wave
+// per (tile, split).  NI: 16-byte blocks of W per lane when known at compile time (fast path), 0 = general.
 template <int MODE, int MT, int KS, int NI>
-__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1))) void lstm_rec_fwd_kernel(RecFwdArgs a) {
-    constexpr int NW = NI > 0 ? NI : REC_NI;
-    static_assert(MT * KS * VER_WAVE == REC_THREADS, "one wave per (tile, k-split)");
+__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_rec_fwd_kernel(RecFwdArgs a) {
+    static_assert(MT * KS == REC_WAVES, "one wave per (tile, k-split)");
     typedef typename RecGeom<MODE>::E E;
     constexpr int PAD = RecGeom<MODE>::PAD, KBLK = RecGeom<MODE>::KBLK, VEC = RecGeom<MODE>::VEC;
     constexpr int UH = 4 * MT, ROWS = 16 * MT;
+    constexpr int NW = NI > 0 ? NI : REC_NI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int H = a.H, stride = H + PAD, ntc = a.ntc;
-    E* sB = reinterpret_cast<E*>(smem);                                                   // staged h rows
-    f32x4_t* sRed = reinterpret_cast<f32x4_t*>(smem + (size_t)ntc * 16 * stride * sizeof(E));  // [KS][MT][NTC][64]
+    const int G = a.G;
+    const int rank = rec_rank(a.ticket, G);
+    if (rank < 0) return;
 
+    const int H = a.H, stride = H + PAD, ntc = a.ntc;
+    E* sB = reinterpret_cast<E*>(smem);                                                        // staged h rows
+    f32x4_t* sRed = reinterpret_cast<f32x4_t*>(smem + (size_t)ntc * 16 * stride * sizeof(E));  // [KS][MT][ntc][64]
+    E* sH = reinterpret_cast<E*>(sRed + (size_t)KS * MT * ntc * 64);                            // [ntc*16][UH] new h
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int mt = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
-    const int G = gridDim.x, j0 = blockIdx.x * UH;
+    const int j0 = rank * UH;
     const int n_seq = a.info[0], T = a.info[1];
     E* hprev = static_cast<E*>(a.hprev);
     const int k_lo = ks * (H / KS);
@@ -323,7 +329,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
     // this wave's 16 rows of W_hh (its share of the contraction) -> registers, in MFMA operand layout
     f32x4_t wreg[NW];
     {
-        const E* wrow = static_cast<const E*>(a.whh) + ((size_t)blockIdx.x * ROWS + mt * 16 + lr) * H + k_lo + lk * VEC;
+        const E* wrow = static_cast<const E*>(a.whh) + ((size_t)rank * ROWS + mt * 16 + lr) * H + k_lo + lk * VEC;
 #pragma unroll
         for (int i = 0; i < NW; ++i)
             wreg[i] = (i < ni) ? *reinterpret_cast<const f32x4_t*>(wrow + i * KBLK) : f32x4_t{0.f, 0.f, 0.f, 0.f};
@@ -333,53 +339,53 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
         const int n = i / (UH / 4), u = (i % (UH / 4)) * 4;
         f32x4_t v = {0.f, 0.f, 0.f, 0.f};
         if (a.h0 && n < a.seq_cap) v = *reinterpret_cast<const f32x4_t*>(a.h0 + (size_t)n * H + j0 + u);
-        st_xchg_4<E>(hprev + (size_t)n * H + j0 + u, v[0], v[1], v[2], v[3]);
+        st_row4<E>(hprev + (size_t)n * H + j0 + u, v[0], v[1], v[2], v[3]);
     }
-    rec_publish(a.flags, 1);
+    rec_publish(a.flags, rank, 1);
     REC_PROF_DECL
     REC_PROF_START();
     float creg[REC_NTC] = {0.f, 0.f, 0.f, 0.f};  // cell state of the pieces in this lane's first REC_NTC tiles
+    // input projections of the first REC_NTC tiles of the coming timestep, fetched one timestep ahead
+    f32x4_t zpre[REC_NTC], znext[REC_NTC];
+#pragma unroll
+    for (int q = 0; q < REC_NTC; ++q) zpre[q] = znext[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const size_t gcol = (size_t)(j0 + mt * 4 + lk) * 4;
+    if (ks == 0 && T > 0) {
+        const int bs0 = a.batch_sizes[0];
+#pragma unroll
+        for (int q = 0; q < REC_NTC; ++q)
+            if (q * 16 + lr < bs0) zpre[q] = *reinterpret_cast<const f32x4_t*>(a.gates + (size_t)(q * 16 + lr) * 4 * H + gcol);
+    }
 
     for (int t = 0; t < T; ++t) {
         const int bs = a.batch_sizes[t], base = a.t_off[t];
         const int bs_next = (t + 1 < T) ? a.batch_sizes[t + 1] : 0, base_next = base + bs;
         const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
-        // The input projections of the first REC_NTC tiles do not depend on other workgroups: fetch them
-        // before waiting, so that their latency overlaps the wait and the exchange.
-        f32x4_t zpre[REC_NTC];
-        if (ks == 0) {
-#pragma unroll
-            for (int q = 0; q < REC_NTC; ++q) {
-                const int n = q * 16 + lr;
-                if (n < bs)
-                    zpre[q] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base + n) * 4 * H +
-                                                                  (size_t)(j0 + mt * 4 + lk) * 4);
-            }
-        }
-        const bool in_ll = t > 0 && bs <= a.ll_rows;                // how h_{t-1} reaches this timestep
-        const bool out_ll = bs_next > 0 && bs_next <= a.ll_rows;   // how h_t leaves it
-        const int ll_row_words = ll_words<E>(H);
-        u64_t* ll_out = a.ll + (size_t)((t + 1) & 1) * a.ll_rows * ll_row_words;
-        if (!in_ll) rec_wait(a.flags, G, t + 1, a.err);
+        if (!rec_wait(a.flags, G, t + 1, a.err)) return;
         REC_PROF_MARK(0);
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
-            if (in_ll) {
-                ll_stage<E>(a.ll + (size_t)(t & 1) * a.ll_rows * ll_row_words, rows, H, (unsigned)t, sB, stride, a.err);
-            } else {
-                if (c0 > 0) __syncthreads();  // the previous chunk's rows have been consumed
-                stage_rows<E>(hprev + (size_t)(base + c0) * H, rows, H, sB, stride);
-                __syncthreads();
-            }
+            if (c0 > 0) __syncthreads();  // the previous chunk's rows have been consumed
+            stage_rows<E>(hprev + (size_t)(base + c0) * H, rows, H, sB, stride);
+            REC_PROF_MARK(5);
+            __syncthreads();
             REC_PROF_MARK(1);
-            f32x4_t acc[REC_NTC];
+            if (c0 == 0 && ks == 0 && t + 1 < T) {
+                // next timestep's input projections (first REC_NTC tiles).  Issued right after the exchanged
+                // rows have arrived: the memory counter retires in order, so a prefetch must never be queued
+                // in front of loads that the critical path waits for; from here it has the MFMA and cell-update
+                // phases to complete before the next wait on the counter.
 #pragma unroll
-            for (int q = 0; q < REC_NTC; ++q) acc[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, acc);
+                for (int q = 0; q < REC_NTC; ++q)
+                    if (q * 16 + lr < bs_next)
+                        znext[q] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base_next + q * 16 + lr) * 4 * H + gcol);
+            }
+            f32x4_t acc[REC_NTC];
+            mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
             if (KS > 1) {
 #pragma unroll
                 for (int q = 0; q < REC_NTC; ++q)
-                    if (q * 16 < rows) sRed[((ks * MT + mt) * REC_NTC + q) * 64 + lane] = acc[q];
+                    if (q * 16 < rows) sRed[((ks * MT + mt) * ntc + q) * 64 + lane] = acc[q];
                 __syncthreads();
                 if (ks == 0) {
 #pragma unroll
@@ -387,7 +393,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
                         if (q * 16 < rows) {
 #pragma unroll
                             for (int s = 1; s < KS; ++s) {
-                                const f32x4_t o = sRed[((s * MT + mt) * REC_NTC + q) * 64 + lane];
+                                const f32x4_t o = sRed[((s * MT + mt) * ntc + q) * 64 + lane];
                                 acc[q][0] += o[0]; acc[q][1] += o[1]; acc[q][2] += o[2]; acc[q][3] += o[3];
                             }
                         }
@@ -420,27 +426,35 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
                         a.c[p * H + j] = cn;
                         a.hout[p * H + j] = hn;
                     }
-                    if (q * 16 < rows) {
-                        // the 4 lanes with equal lr hold units mt*4 .. mt*4+3 of piece n: one coherent store
-                        const float h1 = __shfl(hn, lr + 16, VER_WAVE), h2 = __shfl(hn, lr + 32, VER_WAVE),
-                                    h3 = __shfl(hn, lr + 48, VER_WAVE);
-                        if (lk == 0 && n < bs_next) {
-                            st_xchg_4<E>(hprev + ((size_t)base_next + n) * H + j0 + mt * 4, hn, h1, h2, h3);
-                            if (out_ll) ll_store4<E>(ll_out, n, H, j0 + mt * 4, (unsigned)(t + 1), hn, h1, h2, h3);
-                        }
-                    }
+                    // h_t goes to the exchange row of the next timestep through LDS (below)
+                    if (q * 16 < rows) sH[(q * 16 + lr) * UH + mt * 4 + lk] = cvt_finite<E>(hn);
+                }
+            }
+            // The workgroup's UH units of a row are contiguous (UH * sizeof(E) = 32..64 bytes): write them with
+            // full 16-byte pieces from consecutive lanes.  Partial-sector writes scattered over several
+            // instructions make the L2 fetch the rest of the line from memory, and the readers of the next
+            // timestep then wait for that fill (about 2 us) instead of an L2 hit.
+            __syncthreads();
+            {
+                constexpr int PIECES = UH * (int)sizeof(E) / 16;     // 16-byte pieces per row
+                const int live = min(rows, bs_next - c0);            // rows of this chunk still alive at t+1
+                for (int i = tid; i < live * PIECES; i += REC_THREADS) {
+                    const int r = i / PIECES, pc = i % PIECES;
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sH + r * UH + pc * VEC);
+                    *reinterpret_cast<u32x4_t*>(hprev + ((size_t)base_next + c0 + r) * H + j0 + pc * VEC) = v;
                 }
             }
         }
         REC_PROF_MARK(3);
-        if (!out_ll && t + 1 < T) rec_publish(a.flags, t + 2);
+        if (t + 1 < T) rec_publish(a.flags, rank, t + 2);
+#pragma unroll
+        for (int q = 0; q < REC_NTC; ++q) zpre[q] = znext[q];
         REC_PROF_MARK(4);
-#ifdef VER_REC_PROF
-        if (threadIdx.x == 0 && blockIdx.x == 0) prof_out[15] += 1;
-#endif
+        REC_PROF_STEP();
     }
 }
 
+// ======================================================================================================
 struct RecBwdArgs {
     const int32_t* info;
     const int32_t* batch_sizes;
@@ -454,14 +468,13 @@ struct RecBwdArgs {
     float* dh_state;        // [n_cap, H] recurrent gradient carried to the previous timestep
     float* dc_state;        // [n_cap, H]
     int H, seq_cap;
+    int G;                  // participating workgroups; each owns 16*MT hidden units
     int ntc;
-    int ll_rows;
-    u64_t* ll;          // [2][ll_rows][words per dz row]
     int* flags;
+    int* ticket;
     int* err;
     long long* prof;
 };
-
 
 // What the gate-gradient step needs from the forward pass for one (piece, unit).
 struct BwdSaved {
@@ -479,35 +492,40 @@ __device__ __forceinline__ BwdSaved load_saved(const RecBwdArgs& a, int t, int b
     return s;
 }
 
-// One 16-unit tile per workgroup, KS = 4 waves split the contraction over the 4H gate rows.
-template <int MODE, int NI>
-__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1))) void lstm_rec_bwd_kernel(RecBwdArgs a) {
-    constexpr int NW = NI > 0 ? NI : REC_NI;
+// MT 16-unit tiles per workgroup, KS waves per tile split the contraction over the 4H gate rows.
+template <int MODE, int MT, int KS, int NI>
+__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_rec_bwd_kernel(RecBwdArgs a) {
+    static_assert(MT * KS == REC_WAVES, "one wave per (tile, k-split)");
+    static_assert(MT * REC_NTC <= REC_WAVES, "one wave per tile sum");
     typedef typename RecGeom<MODE>::E E;
     constexpr int PAD = RecGeom<MODE>::PAD, KBLK = RecGeom<MODE>::KBLK, VEC = RecGeom<MODE>::VEC;
-    constexpr int KS = 4, UH = 16;
+    constexpr int UH = 16 * MT;
+    constexpr int NW = NI > 0 ? NI : REC_NI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int H = a.H, K = 4 * H, stride = K + PAD, ntc = a.ntc;
-    E* sB = reinterpret_cast<E*>(smem);                                                       // staged dz rows
-    f32x4_t* sRed = reinterpret_cast<f32x4_t*>(smem + (size_t)ntc * 16 * stride * sizeof(E));  // [KS][NTC][64]
+    const int G = a.G;
+    const int rank = rec_rank(a.ticket, G);
+    if (rank < 0) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, ks = tid >> 6;
+    const int H = a.H, K = 4 * H, stride = K + PAD, ntc = a.ntc;
+    E* sB = reinterpret_cast<E*>(smem);                                                        // staged dz rows
+    f32x4_t* sRed = reinterpret_cast<f32x4_t*>(smem + (size_t)ntc * 16 * stride * sizeof(E));  // [KS][MT][ntc][64]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int mt = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
-    const int G = gridDim.x, j0 = blockIdx.x * UH;
+    const int j0 = rank * UH;
     const int T = a.info[1];
-    const E* dzr = static_cast<const E*>(a.dz);
-    const int k_lo = ks * H;      // this wave's quarter of the 4H contraction
-    const int ni = H / KBLK;
+    E* dzw = static_cast<E*>(a.dz);
+    const int k_lo = ks * (K / KS);
+    const int ni = (K / KS) / KBLK;
 
     f32x4_t wreg[NW];
     {
-        const E* wrow = static_cast<const E*>(a.whhT) + ((size_t)j0 + lr) * K + k_lo + lk * VEC;
+        const E* wrow = static_cast<const E*>(a.whhT) + ((size_t)j0 + mt * 16 + lr) * K + k_lo + lk * VEC;
 #pragma unroll
         for (int i = 0; i < NW; ++i)
             wreg[i] = (i < ni) ? *reinterpret_cast<const f32x4_t*>(wrow + i * KBLK) : f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
-
-    BwdSaved pre;
+    BwdSaved pre;   // saved activations of this thread's first (piece, unit) of the coming timestep
     pre.g4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
     pre.c = pre.c_prev = pre.dh_above = 0.f;
     if (T > 0) {
@@ -521,9 +539,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
         const int bs = a.batch_sizes[t], base = a.t_off[t];
         const int bs_next = (t + 1 < T) ? a.batch_sizes[t + 1] : 0;
         const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
-        const bool use_ll = bs <= a.ll_rows;   // few alive pieces: exchange dz_t through tagged words
-        u64_t* ll_slot = a.ll + (size_t)((T - t) & 1) * a.ll_rows * ll_words<E>(K);
-        // A. gate gradients of this workgroup's 16 units for every alive piece
+        // A. gate gradients of this workgroup's units for every alive piece
         for (int i = tid; i < bs * UH; i += REC_THREADS) {
             const int n = i / UH, j = j0 + (i % UH);
             const size_t p = (size_t)base + n;
@@ -533,61 +549,53 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(1, 
             const float dh = sv.dh_above + (carried ? a.dh_state[(size_t)n * H + j] : 0.f);
             const float tc = tanhf_(sv.c);
             const float dc = (carried ? a.dc_state[(size_t)n * H + j] : 0.f) + dh * go * (1.f - tc * tc);
-            const float dzi = dc * gg * gi * (1.f - gi), dzf = dc * sv.c_prev * gf * (1.f - gf),
-                        dzg = dc * gi * (1.f - gg * gg), dzo = dh * tc * go * (1.f - go);
-            st_xchg_4<E>(static_cast<E*>(a.dz) + p * K + (size_t)j * 4, dzi, dzf, dzg, dzo);
-            if (use_ll && t > 0) ll_store4<E>(ll_slot, n, K, j * 4, (unsigned)(T - t), dzi, dzf, dzg, dzo);
+            st_row4<E>(dzw + p * K + (size_t)j * 4, dc * gg * gi * (1.f - gi), dc * sv.c_prev * gf * (1.f - gf),
+                       dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
             a.dc_state[(size_t)n * H + j] = dc * gf;
         }
         if (t == 0) break;  // nothing is carried before the first timestep
-        {   // saved activations of this thread's first item of timestep t-1: in flight during the exchange
-            const int bs_p = a.batch_sizes[t - 1], base_p = a.t_off[t - 1];
-            if (tid < bs_p * UH)
-                pre = load_saved(a, t - 1, base_p, (t > 1) ? a.t_off[t - 2] : 0, tid / UH, j0 + (tid % UH), H);
-        }
         REC_PROF_MARK(8);
-        if (!use_ll) {
-            rec_publish(a.flags, T - t);
-            REC_PROF_MARK(9);
-            rec_wait(a.flags, G, T - t, a.err);
-        }
+        rec_publish(a.flags, rank, T - t);
+        REC_PROF_MARK(9);
+        if (!rec_wait(a.flags, G, T - t, a.err)) return;
         REC_PROF_MARK(10);
-        // B. dh carried to t-1: dh[n][k] = sum_q dz[n][q] * W_hh[q][k] for this workgroup's 16 columns k
+        // B. dh carried to t-1: dh[n][k] = sum_q dz[n][q] * W_hh[q][k] for this workgroup's columns k
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
-            if (use_ll) {
-                ll_stage<E>(ll_slot, rows, K, (unsigned)(T - t), sB, stride, a.err);
-            } else {
-                if (c0 > 0) __syncthreads();
-                stage_rows<E>(dzr + (size_t)(base + c0) * K, rows, K, sB, stride);
-                __syncthreads();
-            }
+            if (c0 > 0) __syncthreads();
+            stage_rows<E>(dzw + (size_t)(base + c0) * K, rows, K, sB, stride);
+            __syncthreads();
             REC_PROF_MARK(11);
+            if (c0 == 0) {
+                // saved activations of this thread's first item of timestep t-1, issued once the exchanged rows
+                // have arrived (see the forward kernel): in flight during the MFMA phase
+                const int bs_p = a.batch_sizes[t - 1], base_p = a.t_off[t - 1];
+                if (tid < bs_p * UH)
+                    pre = load_saved(a, t - 1, base_p, (t > 1) ? a.t_off[t - 2] : 0, tid / UH, j0 + (tid % UH), H);
+            }
             f32x4_t acc[REC_NTC];
-#pragma unroll
-            for (int q = 0; q < REC_NTC; ++q) acc[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-            mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, acc);
+            mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
 #pragma unroll
             for (int q = 0; q < REC_NTC; ++q)
-                if (q * 16 < rows) sRed[(ks * REC_NTC + q) * 64 + lane] = acc[q];
+                if (q * 16 < rows) sRed[((ks * MT + mt) * ntc + q) * 64 + lane] = acc[q];
             __syncthreads();
-            // wave q of the workgroup adds the four partial sums of tile q: lane holds units lk*4..lk*4+3 of piece n
-            if (ks * 16 < rows) {
-                const int n = c0 + ks * 16 + lr;
-                f32x4_t sum = sRed[(0 * REC_NTC + ks) * 64 + lane];
+            // wave w adds the KS partial sums of (unit tile w / REC_NTC, piece tile w % REC_NTC):
+            // its lane holds units lk*4..lk*4+3 of piece n
+            const int smt = wave / REC_NTC, sq = wave % REC_NTC;
+            if (smt < MT && sq * 16 < rows) {
+                const int n = c0 + sq * 16 + lr;
+                f32x4_t sum = sRed[((0 * MT + smt) * ntc + sq) * 64 + lane];
 #pragma unroll
                 for (int s = 1; s < KS; ++s) {
-                    const f32x4_t o = sRed[(s * REC_NTC + ks) * 64 + lane];
+                    const f32x4_t o = sRed[((s * MT + smt) * ntc + sq) * 64 + lane];
                     sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
                 }
-                if (n < bs) *reinterpret_cast<f32x4_t*>(a.dh_state + (size_t)n * H + j0 + lk * 4) = sum;
+                if (n < bs) *reinterpret_cast<f32x4_t*>(a.dh_state + (size_t)n * H + j0 + smt * 16 + lk * 4) = sum;
             }
         }
         __syncthreads();  // dh_state is read by other threads in the next timestep's part A
         REC_PROF_MARK(12);
-#ifdef VER_REC_PROF
-        if (threadIdx.x == 0 && blockIdx.x == 0) prof_out[15] += 1;
-#endif
+        REC_PROF_STEP();
     }
 }
 
