@@ -7,11 +7,15 @@
 // contiguous) or, with TRANS, "K-minor" (A(m,k) = A[k*lda + m]: used for the
 // weight gradients, where the contraction runs over the packed rows).  Either
 // way a 128x128 tile of C is built by 4 waves (2x2, 64x64 each) from K-tiles
-// staged in LDS as [row][k] so that every MFMA operand is one aligned LDS read.
+// staged in LDS as [row][k] so that every MFMA operand is one aligned 16-byte
+// LDS read.  K-minor tiles are transposed in registers (4x4 blocks) on the way
+// into LDS.  The global loads of K-tile i+1 are issued before the MFMAs of tile
+// i (register double buffering), and the contraction can be split over
+// gridDim.z with the partial tiles summed in index order by a second kernel, so
+// that small outputs still fill the chip; both keep the result deterministic.
 //   MODE_BF16: operands rounded to bf16 on the way into LDS (or already bf16),
 //              v_mfma_f32_16x16x32_bf16, fp32 accumulate.
 //   MODE_F32 : fp32 operands, v_mfma_f32_16x16x4_f32.
-// Results are deterministic (no split-K, no atomics).
 #pragma once
 #include "common.h"
 
@@ -52,73 +56,117 @@ template <typename TO> __device__ __forceinline__ TO cvt_elem(bf16_t v);
 template <> __device__ __forceinline__ float cvt_elem<float>(bf16_t v) { return from_bf16(v); }
 template <> __device__ __forceinline__ bf16_t cvt_elem<bf16_t>(bf16_t v) { return v; }
 
-// Loads 4 consecutive elements (aligned to 4 elements) as floats or raw bf16.
-template <typename T> struct Vec4;
-template <> struct Vec4<float> {
-    float v[4];
-    __device__ __forceinline__ void load(const float* p) {
-        f32x4_t t = *reinterpret_cast<const f32x4_t*>(p);
-        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    }
-    __device__ __forceinline__ void zero() { v[0] = v[1] = v[2] = v[3] = 0.f; }
-};
-template <> struct Vec4<bf16_t> {
-    bf16_t v[4];
-    __device__ __forceinline__ void load(const bf16_t* p) {
-        u16x4_t t = *reinterpret_cast<const u16x4_t*>(p);
-        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-    }
-    __device__ __forceinline__ void zero() { v[0] = v[1] = v[2] = v[3] = 0; }
-};
+// 4 consecutive elements (aligned to 4 elements) of a source row, converted to the LDS element type.
+template <typename E> struct Quad { E v[4]; };
+template <typename E, typename T> __device__ __forceinline__ Quad<E> load_quad(const T* p);
+template <> __device__ __forceinline__ Quad<float> load_quad<float, float>(const float* p) {
+    const f32x4_t t = *reinterpret_cast<const f32x4_t*>(p);
+    return Quad<float>{{t[0], t[1], t[2], t[3]}};
+}
+template <> __device__ __forceinline__ Quad<bf16_t> load_quad<bf16_t, float>(const float* p) {
+    const f32x4_t t = *reinterpret_cast<const f32x4_t*>(p);
+    return Quad<bf16_t>{{to_bf16(t[0]), to_bf16(t[1]), to_bf16(t[2]), to_bf16(t[3])}};
+}
+template <> __device__ __forceinline__ Quad<bf16_t> load_quad<bf16_t, bf16_t>(const bf16_t* p) {
+    const u16x4_t t = *reinterpret_cast<const u16x4_t*>(p);
+    return Quad<bf16_t>{{t[0], t[1], t[2], t[3]}};
+}
+template <> __device__ __forceinline__ Quad<float> load_quad<float, bf16_t>(const bf16_t* p) {
+    const u16x4_t t = *reinterpret_cast<const u16x4_t*>(p);
+    return Quad<float>{{from_bf16(t[0]), from_bf16(t[1]), from_bf16(t[2]), from_bf16(t[3])}};
+}
+template <typename E> __device__ __forceinline__ Quad<E> zero_quad() {
+    Quad<E> q;
+    q.v[0] = q.v[1] = q.v[2] = q.v[3] = E(0);
+    return q;
+}
+// One aligned store of 4 consecutive LDS elements (8 bytes bf16, 16 bytes fp32).
+__device__ __forceinline__ void store_quad(bf16_t* dst, const Quad<bf16_t>& q) {
+    u16x4_t t;
+    t[0] = q.v[0]; t[1] = q.v[1]; t[2] = q.v[2]; t[3] = q.v[3];
+    *reinterpret_cast<u16x4_t*>(dst) = t;
+}
+__device__ __forceinline__ void store_quad(float* dst, const Quad<float>& q) {
+    *reinterpret_cast<f32x4_t*>(dst) = f32x4_t{q.v[0], q.v[1], q.v[2], q.v[3]};
+}
 
 constexpr int GEMM_BM = 128, GEMM_BN = 128, GEMM_THREADS = 256;
 
 template <int MODE> struct GemmGeom;
-template <> struct GemmGeom<MODE_BF16> { static constexpr int BK = 32, LDS_STRIDE = 40; };
-template <> struct GemmGeom<MODE_F32> { static constexpr int BK = 16, LDS_STRIDE = 20; };
+template <> struct GemmGeom<MODE_BF16> { static constexpr int BK = 64, LDS_STRIDE = 72; };
+template <> struct GemmGeom<MODE_F32> { static constexpr int BK = 32, LDS_STRIDE = 36; };
 
-// Stages one operand tile (128 rows x BK) into LDS as [row][k].
-template <int MODE, typename T, bool TRANS>
-__device__ __forceinline__ void gemm_stage(const T* __restrict__ src, int ld, int row0, int n_rows, int k0, int K,
-                                           typename LdsElem<MODE>::type* __restrict__ lds) {
+// One operand tile (128 rows x BK) on its way from global memory to LDS, held in registers as
+// QUADS 4-element groups per thread.
+template <int MODE> struct TileRegs {
     typedef typename LdsElem<MODE>::type E;
-    constexpr int BK = GemmGeom<MODE>::BK, STRIDE = GemmGeom<MODE>::LDS_STRIDE;
+    static constexpr int QUADS = 128 * GemmGeom<MODE>::BK / 4 / GEMM_THREADS;
+    Quad<E> q[QUADS];
+};
+
+// K-major source: quad c (of BK/4) of row r; 16-byte (fp32) or 8-byte (bf16) coalesced loads.
+// K-minor source: each thread owns 4(k) x 4(rows) blocks, loaded as 4 row-quads and transposed.
+template <int MODE, typename T, bool TRANS>
+__device__ __forceinline__ void tile_load(const T* __restrict__ src, int ld, int row0, int n_rows, int k0, int k_end,
+                                          TileRegs<MODE>& regs) {
+    typedef typename LdsElem<MODE>::type E;
+    constexpr int BK = GemmGeom<MODE>::BK, QUADS = TileRegs<MODE>::QUADS;
     const int tid = threadIdx.x;
     if (!TRANS) {
-        constexpr int CHUNKS = BK / 4;                   // 4-element chunks per row
-        constexpr int ROWS_PER_PASS = GEMM_THREADS / CHUNKS;
-        const int c = tid % CHUNKS, r = tid / CHUNKS;
+        constexpr int CPR = BK / 4;                      // quads per row
+        constexpr int RPP = GEMM_THREADS / CPR;          // rows per pass
+        const int c = tid % CPR, r = tid / CPR;
 #pragma unroll
-        for (int pass = 0; pass < 128 / ROWS_PER_PASS; ++pass) {
-            const int row = r + pass * ROWS_PER_PASS;
-            const int gr = row0 + row, gk = k0 + c * 4;
-            Vec4<T> v;
-            if (gr < n_rows && gk < K) v.load(src + (size_t)gr * ld + gk); else v.zero();
-            E* dst = lds + row * STRIDE + c * 4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) dst[i] = cvt_elem<E>(v.v[i]);
+        for (int i = 0; i < QUADS; ++i) {
+            const int gr = row0 + r + i * RPP, gk = k0 + c * 4;
+            regs.q[i] = (gr < n_rows && gk < k_end) ? load_quad<E, T>(src + (size_t)gr * ld + gk) : zero_quad<E>();
         }
     } else {
-        constexpr int CHUNKS = 128 / 4;                  // 4-row chunks per k
-        constexpr int K_PER_PASS = GEMM_THREADS / CHUNKS;
-        const int c = tid % CHUNKS, kk = tid / CHUNKS;
+        constexpr int MB = 128 / 4;                      // 4-row blocks across the tile
+        constexpr int KPP = GEMM_THREADS / MB;           // 4-k blocks per pass
+        const int mb = tid % MB, kb = tid / MB;
 #pragma unroll
-        for (int pass = 0; pass < BK / K_PER_PASS; ++pass) {
-            const int k = kk + pass * K_PER_PASS;
-            const int gk = k0 + k, gr = row0 + c * 4;
-            Vec4<T> v;
-            if (gk < K && gr < n_rows) v.load(src + (size_t)gk * ld + gr); else v.zero();
+        for (int i = 0; i < QUADS / 4; ++i) {
+            const int gk = k0 + (kb + i * KPP) * 4, gr = row0 + mb * 4;
+            Quad<E> in[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) lds[(c * 4 + i) * STRIDE + k] = cvt_elem<E>(v.v[i]);
+            for (int j = 0; j < 4; ++j)
+                in[j] = (gk + j < k_end && gr < n_rows) ? load_quad<E, T>(src + (size_t)(gk + j) * ld + gr) : zero_quad<E>();
+#pragma unroll
+            for (int m = 0; m < 4; ++m)                  // row gr+m gets k = gk .. gk+3
+#pragma unroll
+                for (int j = 0; j < 4; ++j) regs.q[i * 4 + m].v[j] = in[j].v[m];
         }
     }
 }
 
+template <int MODE, bool TRANS>
+__device__ __forceinline__ void tile_store(const TileRegs<MODE>& regs, typename LdsElem<MODE>::type* __restrict__ lds) {
+    constexpr int BK = GemmGeom<MODE>::BK, STRIDE = GemmGeom<MODE>::LDS_STRIDE, QUADS = TileRegs<MODE>::QUADS;
+    const int tid = threadIdx.x;
+    if (!TRANS) {
+        constexpr int CPR = BK / 4, RPP = GEMM_THREADS / CPR;
+        const int c = tid % CPR, r = tid / CPR;
+#pragma unroll
+        for (int i = 0; i < QUADS; ++i) store_quad(lds + (r + i * RPP) * STRIDE + c * 4, regs.q[i]);
+    } else {
+        constexpr int MB = 128 / 4, KPP = GEMM_THREADS / MB;
+        const int mb = tid % MB, kb = tid / MB;
+#pragma unroll
+        for (int i = 0; i < QUADS / 4; ++i)
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+                store_quad(lds + (mb * 4 + m) * STRIDE + (kb + i * KPP) * 4, regs.q[i * 4 + m]);
+    }
+}
+
 // unperm_h > 0: output row m is stored at row (m % 4) * unperm_h + m / 4 (gate-interleaved -> gate-major).
+// gridDim.z > 1: block z contracts k in [z*k_chunk, (z+1)*k_chunk) and writes its partial tile to
+// C + z*split_stride without bias and without the row permutation (gemm_reduce_kernel applies both).
 template <int MODE, typename TA, typename TB, bool TRANS>
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(
     const TA* __restrict__ A, int lda, const TB* __restrict__ B, int ldb, float* __restrict__ C, int ldc,
-    int Mr, int Nc, int K, const float* __restrict__ bias, int unperm_h) {
+    int Mr, int Nc, int K, const float* __restrict__ bias, int unperm_h, int k_chunk, size_t split_stride) {
     typedef typename LdsElem<MODE>::type E;
     constexpr int BK = GemmGeom<MODE>::BK, STRIDE = GemmGeom<MODE>::LDS_STRIDE;
     __shared__ __attribute__((aligned(16))) E sA[GEMM_BM * STRIDE];
@@ -127,6 +175,9 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     const int m0 = blockIdx.y * GEMM_BM, n0 = blockIdx.x * GEMM_BN;
     const int lr = lane & 15, lk = lane >> 4;
+    const int k_begin = blockIdx.z * k_chunk, k_end = min(K, k_begin + k_chunk);
+    const bool split = gridDim.z > 1;
+    if (split) C += (size_t)blockIdx.z * split_stride;
 
     f32x4_t acc[4][4];
 #pragma unroll
@@ -134,37 +185,53 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = 0; k0 < K; k0 += BK) {
+    TileRegs<MODE> ra, rb;
+    tile_load<MODE, TA, TRANS>(A, lda, m0, Mr, k_begin, k_end, ra);
+    tile_load<MODE, TB, TRANS>(B, ldb, n0, Nc, k_begin, k_end, rb);
+    for (int k0 = k_begin; k0 < k_end; k0 += BK) {
+        tile_store<MODE, TRANS>(ra, sA);
+        tile_store<MODE, TRANS>(rb, sB);
         __syncthreads();
-        gemm_stage<MODE, TA, TRANS>(A, lda, m0, Mr, k0, K, sA);
-        gemm_stage<MODE, TB, TRANS>(B, ldb, n0, Nc, k0, K, sB);
-        __syncthreads();
+        if (k0 + BK < k_end) {   // next K-tile: in flight while this one is multiplied
+            tile_load<MODE, TA, TRANS>(A, lda, m0, Mr, k0 + BK, k_end, ra);
+            tile_load<MODE, TB, TRANS>(B, ldb, n0, Nc, k0 + BK, k_end, rb);
+        }
         if (MODE == MODE_BF16) {
-            u16x8_t a[4], b[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                a[i] = *reinterpret_cast<const u16x8_t*>(reinterpret_cast<const bf16_t*>(sA) + (wm + i * 16 + lr) * STRIDE + lk * 8);
+            for (int ks = 0; ks < BK; ks += 32) {
+                u16x8_t a[4], b[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                b[j] = *reinterpret_cast<const u16x8_t*>(reinterpret_cast<const bf16_t*>(sB) + (wn + j * 16 + lr) * STRIDE + lk * 8);
+                for (int i = 0; i < 4; ++i)
+                    a[i] = *reinterpret_cast<const u16x8_t*>(reinterpret_cast<const bf16_t*>(sA) + (wm + i * 16 + lr) * STRIDE + ks + lk * 8);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16_16x16x32(a[i], b[j], acc[i][j]);
-        } else {
-#pragma unroll
-            for (int ks = 0; ks < BK; ks += 4) {
-                float a[4], b[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) a[i] = reinterpret_cast<const float*>(sA)[(wm + i * 16 + lr) * STRIDE + ks + lk];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) b[j] = reinterpret_cast<const float*>(sB)[(wn + j * 16 + lr) * STRIDE + ks + lk];
+                for (int j = 0; j < 4; ++j)
+                    b[j] = *reinterpret_cast<const u16x8_t*>(reinterpret_cast<const bf16_t*>(sB) + (wn + j * 16 + lr) * STRIDE + ks + lk * 8);
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) acc[i][j] = mfma_f32_16x16x4(a[i], b[j], acc[i][j]);
+                    for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16_16x16x32(a[i], b[j], acc[i][j]);
+            }
+        } else {
+#pragma unroll
+            for (int ks = 0; ks < BK; ks += 16) {
+                // a lane takes 4 consecutive k of its row in one 16-byte read and feeds them to 4 MFMAs; which
+                // k a lane contributes is free as long as A and B agree
+                f32x4_t a[4], b[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    a[i] = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(sA) + (wm + i * 16 + lr) * STRIDE + ks + lk * 4);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    b[j] = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(sB) + (wn + j * 16 + lr) * STRIDE + ks + lk * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[i][j] = mfma_f32_16x16x4(a[i][e], b[j][e], acc[i][j]);
             }
         }
+        __syncthreads();
     }
     // C fragment: element r of lane l is row (l / 16) * 4 + r, column l % 16 of the 16x16 tile.
 #pragma unroll
@@ -173,23 +240,64 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + wn + j * 16 + lr;
             if (n >= Nc) continue;
-            const float bv = bias ? bias[n] : 0.f;
+            const float bv = (bias && !split) ? bias[n] : 0.f;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int m = m0 + wm + i * 16 + lk * 4 + r;
                 if (m >= Mr) continue;
-                const int out_row = unperm_h > 0 ? (m & 3) * unperm_h + (m >> 2) : m;
+                const int out_row = (unperm_h > 0 && !split) ? (m & 3) * unperm_h + (m >> 2) : m;
                 C[(size_t)out_row * ldc + n] = acc[i][j][r] + bv;
             }
         }
 }
 
+// C[perm(m)][n] = sum_z part[z][m][n] (+ bias[n]), z ascending.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restrict__ part, int splits, size_t split_stride,
+                                                          int Mr, int Nc, float* __restrict__ C, int ldc,
+                                                          const float* __restrict__ bias, int unperm_h) {
+    const size_t total = (size_t)Mr * Nc;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int m = (int)(i / Nc), n = (int)(i % Nc);
+        float s = 0.f;
+        for (int z = 0; z < splits; ++z) s += part[(size_t)z * split_stride + i];
+        if (bias) s += bias[n];
+        const int out_row = unperm_h > 0 ? (m & 3) * unperm_h + (m >> 2) : m;
+        C[(size_t)out_row * ldc + n] = s;
+    }
+}
+
+// How many ways to split the contraction so that the grid has a few workgroups per CU.
+inline int gemm_splits(int Mr, int Nc, int K, int BK) {
+    const long tiles = (long)((Mr + GEMM_BM - 1) / GEMM_BM) * ((Nc + GEMM_BN - 1) / GEMM_BN);
+    int s = (int)((768 + tiles - 1) / tiles);
+    const int max_s = K / (4 * BK) > 0 ? K / (4 * BK) : 1;   // at least 4 K-tiles per split
+    if (s > max_s) s = max_s;
+    if (s > 8) s = 8;
+    return s < 1 ? 1 : s;
+}
+inline size_t gemm_part_floats(int Mr, int Nc, int K, int BK) {
+    const int s = gemm_splits(Mr, Nc, K, BK);
+    return s > 1 ? (size_t)s * Mr * Nc : 0;
+}
+
+// part: scratch of gemm_part_floats(...) floats (may be NULL when that is 0 or allow_split is false).
 template <int MODE, typename TA, typename TB, bool TRANS>
 inline void gemm_launch(const TA* A, int lda, const TB* B, int ldb, float* C, int ldc, int Mr, int Nc, int K,
-                        const float* bias, int unperm_h, hipStream_t s) {
-    dim3 grid((Nc + GEMM_BN - 1) / GEMM_BN, (Mr + GEMM_BM - 1) / GEMM_BM);
-    hipLaunchKernelGGL((gemm_kernel<MODE, TA, TB, TRANS>), grid, dim3(GEMM_THREADS), 0, s, A, lda, B, ldb, C, ldc, Mr,
-                       Nc, K, bias, unperm_h);
+                        const float* bias, int unperm_h, float* part, bool allow_split, hipStream_t s) {
+    constexpr int BK = GemmGeom<MODE>::BK;
+    const int splits = (allow_split && part) ? gemm_splits(Mr, Nc, K, BK) : 1;
+    dim3 grid((Nc + GEMM_BN - 1) / GEMM_BN, (Mr + GEMM_BM - 1) / GEMM_BM, splits);
+    if (splits == 1) {
+        hipLaunchKernelGGL((gemm_kernel<MODE, TA, TB, TRANS>), grid, dim3(GEMM_THREADS), 0, s, A, lda, B, ldb, C, ldc, Mr,
+                           Nc, K, bias, unperm_h, K, (size_t)0);
+        return;
+    }
+    const int k_chunk = ((K + splits - 1) / splits + BK - 1) / BK * BK;
+    const size_t stride = (size_t)Mr * Nc;
+    hipLaunchKernelGGL((gemm_kernel<MODE, TA, TB, TRANS>), grid, dim3(GEMM_THREADS), 0, s, A, lda, B, ldb, part, Nc, Mr,
+                       Nc, K, bias, unperm_h, k_chunk, stride);
+    hipLaunchKernelGGL(gemm_reduce_kernel, dim3(1024), dim3(256), 0, s, part, splits, stride, Mr, Nc, C, ldc, bias,
+                       unperm_h);
 }
 
 }  // namespace ver

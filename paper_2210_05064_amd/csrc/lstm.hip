@@ -173,6 +173,7 @@ struct LstmWs {
     float* dh_state;   // [M, H]
     float* dc_state;   // [M, H]
     float* part;       // partial sums of the two-stage reductions
+    float* gemm_part;  // partial tiles of GEMMs whose contraction is split over workgroups
     float* db_head;    // [A+1] scratch for bias sums
     size_t bytes;
 };
@@ -185,6 +186,20 @@ inline size_t part_floats(const ver_lstm_cfg& c, int M) {
     const size_t d = rb_cs * (c.act_dim + 1);
     size_t m = a > b ? a : b;
     return m > d ? m : d;
+}
+
+// Largest split-K scratch any GEMM of the forward or backward pass asks for.
+inline size_t gemm_part_max(const ver_lstm_cfg& c, int M) {
+    const int bk = c.compute ? GemmGeom<MODE_BF16>::BK : GemmGeom<MODE_F32>::BK;
+    const int H = c.hidden;
+    size_t m = 0;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const int D = l == 0 ? c.input_dim : H;
+        const size_t v[4] = {gemm_part_floats(M, 4 * H, D, bk), gemm_part_floats(M, D, 4 * H, bk),
+                             gemm_part_floats(4 * H, D, M, bk), gemm_part_floats(4 * H, H, M, bk)};
+        for (size_t x : v) m = x > m ? x : m;
+    }
+    return m;
 }
 
 inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws) {
@@ -214,6 +229,7 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     ws->dh_state = cv.take<float>(Mz * H);
     ws->dc_state = cv.take<float>(Mz * H);
     ws->part = cv.take<float>(part_floats(c, M));
+    ws->gemm_part = cv.take<float>(gemm_part_max(c, M));
     ws->db_head = cv.take<float>(64);
     ws->bytes = cv.used;
 }
@@ -266,13 +282,13 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         if (l == 0) {
             if (c.x_bf16)
                 gemm_launch<MODE, bf16_t, E, false>(static_cast<const bf16_t*>(x), D, static_cast<const E*>(L.wih), D,
-                                                    L.gates, 4 * H, M, 4 * H, D, L.bias, 0, s);
+                                                    L.gates, 4 * H, M, 4 * H, D, L.bias, 0, ws.gemm_part, true, s);
             else
                 gemm_launch<MODE, float, E, false>(static_cast<const float*>(x), D, static_cast<const E*>(L.wih), D,
-                                                   L.gates, 4 * H, M, 4 * H, D, L.bias, 0, s);
+                                                   L.gates, 4 * H, M, 4 * H, D, L.bias, 0, ws.gemm_part, true, s);
         } else {
             gemm_launch<MODE, float, E, false>(ws.layer[l - 1].hout, H, static_cast<const E*>(L.wih), H, L.gates,
-                                               4 * H, M, 4 * H, H, L.bias, 0, s);
+                                               4 * H, M, 4 * H, H, L.bias, 0, ws.gemm_part, true, s);
         }
         }
         // sequential part
@@ -389,21 +405,21 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         if (dx) {
             ProfScope prof(VER_PROF_LSTM_GEMM_DX, s);
             gemm_launch<MODE, E, E, false>(dz, 4 * H, static_cast<const E*>(L.wihT), 4 * H, dx, D, M, D, 4 * H,
-                                           nullptr, 0, s);
+                                           nullptr, 0, ws.gemm_part, true, s);
         }
         // dW_ih[4H, D] = dz^T x ; dW_hh[4H, H] = dz^T h_{t-1}; stored gate-major
         {
         ProfScope prof(VER_PROF_LSTM_GEMM_DW, s);
         if (l > 0)
-            gemm_launch<MODE, E, float, true>(dz, 4 * H, ws.layer[l - 1].hout, H, gw[4 * l], D, 4 * H, D, M, nullptr, H, s);
+            gemm_launch<MODE, E, float, true>(dz, 4 * H, ws.layer[l - 1].hout, H, gw[4 * l], D, 4 * H, D, M, nullptr, H, ws.gemm_part, true, s);
         else if (c.x_bf16)
             gemm_launch<MODE, E, bf16_t, true>(dz, 4 * H, static_cast<const bf16_t*>(x), D, gw[4 * l], D, 4 * H, D, M,
-                                               nullptr, H, s);
+                                               nullptr, H, ws.gemm_part, true, s);
         else
             gemm_launch<MODE, E, float, true>(dz, 4 * H, static_cast<const float*>(x), D, gw[4 * l], D, 4 * H, D, M,
-                                              nullptr, H, s);
+                                              nullptr, H, ws.gemm_part, true, s);
         gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(L.hprev), H, gw[4 * l + 1], H, 4 * H, H, M,
-                                      nullptr, H, s);
+                                      nullptr, H, ws.gemm_part, true, s);
         }
         // db_ih = db_hh = column sums of dz
         {
