@@ -167,25 +167,33 @@ __device__ __forceinline__ void rec_publish(int* flags, int rank, int value) {
 // Copies `rows` rows of `row_elems` elements (16-byte multiples) from global memory (L2) into LDS rows of
 // `stride` elements.  The whole workgroup takes part, DEPTH loads in flight per thread; reads past the last
 // row return zero (buffer bounds).
+// `rot` rotates the order in which this workgroup walks the vectors: all workgroups fetch the same rows at
+// the same moment, and starting each one at a different place spreads them over the L2 channels.
 template <typename E>
 __device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, int row_elems, E* __restrict__ lds,
-                                           int stride) {
+                                           int stride, int rot) {
     constexpr int VEC = 16 / sizeof(E);
     constexpr int DEPTH = 4;
     const int vec_per_row = row_elems / VEC;
     const int n = rows * vec_per_row;
     __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<E*>(src), 0, n * 16, 0x00020000);
-    int r = threadIdx.x / vec_per_row, c = threadIdx.x - r * vec_per_row;   // position of vector v = threadIdx.x
+    const int shift = (int)(((long long)rot * n) / REC_MAX_GROUP) & ~63;   // whole waves stay contiguous
     for (int v0 = threadIdx.x; v0 < n; v0 += DEPTH * REC_THREADS) {
         u32x4_t tmp[DEPTH];
-#pragma unroll
-        for (int u = 0; u < DEPTH; ++u)
-            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (v0 + u * REC_THREADS) * 16, 0, 0);
+        int vv[DEPTH];
 #pragma unroll
         for (int u = 0; u < DEPTH; ++u) {
-            if (v0 + u * REC_THREADS < n) *reinterpret_cast<u32x4_t*>(lds + r * stride + c * VEC) = tmp[u];
-            c += REC_THREADS;
-            while (c >= vec_per_row) { c -= vec_per_row; ++r; }
+            int v = v0 + u * REC_THREADS + shift;
+            if (v >= n) v -= n;
+            vv[u] = v;
+            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, v * 16, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < DEPTH; ++u) {
+            if (v0 + u * REC_THREADS < n) {
+                const int r = vv[u] / vec_per_row, c = vv[u] - r * vec_per_row;
+                *reinterpret_cast<u32x4_t*>(lds + r * stride + c * VEC) = tmp[u];
+            }
         }
     }
 }
@@ -366,7 +374,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
             if (c0 > 0) __syncthreads();  // the previous chunk's rows have been consumed
-            stage_rows<E>(hprev + (size_t)(base + c0) * H, rows, H, sB, stride);
+            stage_rows<E>(hprev + (size_t)(base + c0) * H, rows, H, sB, stride, rank);
             REC_PROF_MARK(5);
             __syncthreads();
             REC_PROF_MARK(1);
@@ -563,7 +571,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
             if (c0 > 0) __syncthreads();
-            stage_rows<E>(dzw + (size_t)(base + c0) * K, rows, K, sB, stride);
+            stage_rows<E>(dzw + (size_t)(base + c0) * K, rows, K, sB, stride, rank);
             __syncthreads();
             REC_PROF_MARK(11);
             if (c0 == 0) {
