@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 
+# HBM bytes per launch (read + written) of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of
+# this script, scaled by a copy of known size: see profiles/hbm_traffic_max_workload.md.  None where unmeasured.
+MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 393.9e6, ("max", "lstm_rec_fwd"): 447.2e6}
+
 
 def collection_logp(ro, compute, x_bf16):
     """Log-probability the current weights give every stored action, evaluated
@@ -111,6 +115,9 @@ def main():
     ap.add_argument("--workload", default="max")
     ap.add_argument("--seed", type=int, default=4000)
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle LSTM work (0 = skip)")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="only run three device-to-device copies of MIB mebibytes (a kernel of known HBM traffic "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters by) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the learner step of ONE GPU; runs on several GPUs are not part of this build "
@@ -124,6 +131,15 @@ def main():
     if not torch.cuda.is_available():
         print("no GPU visible: the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+
+    if args.copy_calibration > 0:
+        src = torch.ones(args.copy_calibration << 18, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "copy_calibration_bytes_written": src.numel() * 4}))
+        return
 
     w = wl.WORKLOADS[args.workload]
     ro = wl.make_rollout(w, seed=args.seed)
@@ -177,7 +193,8 @@ def main():
                    "rows_per_minibatch": M, "seed": args.seed},
         "step_passes_per_sec": S * w.epochs / (elapsed / args.steps),
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_TFLOPS[dtype],
-                     "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS[dtype], "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS[dtype],
+                     "traffic": MEASURED_TRAFFIC.get((w.name, dom)),
                      "avg_launch_ms": dom_ms / dom_n, "launches": dom_n, "flops_per_launch": flops_per_launch,
                      "last_minibatch_T_max": t_max},
         "kernel_ms_per_update": {k: round(v[0], 4) for k, v in full.items()},
