@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------- workspace
-constexpr int REC_FLAG_WORDS = 64;   // flags[0..31], ticket at [32]
+constexpr int REC_FLAG_WORDS = REC_GROUPS * REC_MAX_GROUP + 64;   // flags[group][32], then one ticket per group
 
 struct LayerWs {
     void* wih;    // [4H, D_l]  operand type, interleaved rows
@@ -165,7 +165,7 @@ struct LayerWs {
 };
 struct LstmWs {
     int* err;          // word 0 of the workspace
-    int* flags;        // [REC_FLAG_WORDS]: per-workgroup flags of a recurrent launch, then its ticket counter
+    int* flags;        // [REC_FLAG_WORDS]: per-workgroup flags of a recurrent launch, then its ticket counters
     long long* prof;   // [32] phase counters of the recurrent kernels (forward 0..15, backward 16..31)
     LayerWs layer[8];
     void* dz;          // [M, 4H] operand type
@@ -298,7 +298,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.gates = L.gates; ra.c = L.c; ra.hout = L.hout; ra.hprev = L.hprev; ra.whh = L.whh;
         ra.h0 = h0 ? h0 + (size_t)l * seq_cap * H : nullptr;
         ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
-        ra.H = H; ra.seq_cap = seq_cap; ra.M = M; ra.flags = ws.flags; ra.ticket = ws.flags + 32; ra.err = ws.err;
+        ra.H = H; ra.seq_cap = seq_cap; ra.M = M; ra.flags = ws.flags; ra.ticket = ws.flags + REC_GROUPS * REC_MAX_GROUP; ra.err = ws.err;
         ra.prof = ws.prof;
         {
         ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
@@ -371,7 +371,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.gates = L.gates; ra.c = L.c; ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
         ra.dh_above = ws.dh[cur]; ra.dz = ws.dz; ra.whhT = L.whhT;
         ra.dh_state = ws.dh_state; ra.dc_state = ws.dc_state;
-        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + 32; ra.err = ws.err;
+        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + REC_GROUPS * REC_MAX_GROUP; ra.err = ws.err;
         ra.prof = ws.prof + 16;
         {
         ProfScope prof(VER_PROF_LSTM_REC_BWD, s);

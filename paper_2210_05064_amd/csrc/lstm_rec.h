@@ -13,20 +13,21 @@
 //     64 workgroups on 8 XCDs, write-through stores + coherent loads 2.6 us
 //     32 workgroups on ONE XCD, synchronising through its L2          1.0 us
 // Hence the design:
-//  * the kernel is launched on the whole chip (one workgroup per CU), but only
-//    the workgroups that find themselves on XCD 0 (hardware register XCC_ID)
-//    take part, ranked by a ticket; the others return at once.  The G <= 32
-//    participants share one L2, which makes it the coherence point: exchanged
-//    rows are written with plain stores; the writer waits for their completion
-//    (s_waitcnt) before it raises its flag; readers poll the flags with loads
-//    that bypass their CU's L1 and then read the rows, which no CU has touched
-//    before in this launch (every row of the exchange buffers belongs to exactly
-//    one timestep), so they come from L2.  No cache-wide write-back or
-//    invalidate is ever issued;
+//  * pieces are independent of each other in the time loop, so they are dealt to the 8 XCDs: the kernel is
+//    launched on the whole chip (one workgroup per CU), the workgroups that find themselves on XCD x
+//    (hardware register XCC_ID) form group x, take ranks from the group's ticket and run the pieces
+//    n = x, x+8, x+16, ... with a full copy of the recurrent weights spread over their registers.  A
+//    group exchanges only its own pieces' rows, and only inside its own L2, which makes that L2 the
+//    coherence point: exchanged rows are written with plain stores; the writer waits for their
+//    completion (s_waitcnt) before it raises its flag; readers poll the flags with loads that bypass
+//    their CU's L1 and then read the rows, which no CU has touched before in this launch (every row of
+//    the exchange buffers belongs to exactly one timestep), so they come from L2.  No cache-wide
+//    write-back or invalidate is ever issued.  Pieces are sorted longest first, so group 0 runs all
+//    T_max timesteps and the others stop earlier;
 //  * each wave keeps ITS [16 x K] block of the recurrent weight matrix in
 //    registers, already in MFMA operand layout, for the whole kernel; a timestep
-//    touches memory only for the exchanged rows (staged in LDS for all waves)
-//    and the saved activations;
+//    touches memory only for the exchanged rows (copied by loads that write LDS directly, for all
+//    waves) and the saved activations;
 //  * gate rows are interleaved (row = unit*4 + gate) so that one MFMA output
 //    fragment holds the four gates of a unit in one lane: the cell update needs
 //    no cross-lane traffic;
@@ -42,7 +43,7 @@ namespace ver {
 // Optional phase timing (build with -DVER_REC_PROF): thread 0 of the rank-0 workgroup adds the core-clock
 // cycles spent in each phase of the time loop to prof[phase]; prof[15] counts timesteps.  Off in the product build.
 #ifdef VER_REC_PROF
-#define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof; const bool prof_on = threadIdx.x == 0 && rank == 0;
+#define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof; const bool prof_on = threadIdx.x == 0 && rank == 0 && grp == 0;
 #define REC_PROF_START() do { if (prof_on) prof_t = clock64(); } while (0)
 #define REC_PROF_MARK(i) do { if (prof_on) { long long now_ = clock64(); prof_out[i] += now_ - prof_t; prof_t = now_; } } while (0)
 #define REC_PROF_STEP() do { if (prof_on) prof_out[15] += 1; } while (0)
@@ -55,9 +56,9 @@ namespace ver {
 
 constexpr int REC_THREADS = 512;          // 8 waves, two per SIMD: 256 registers each
 constexpr int REC_WAVES = REC_THREADS / VER_WAVE;
-constexpr int REC_GRID = 256;             // one workgroup per CU; those on the chosen XCD take part
+constexpr int REC_GRID = 256;             // one workgroup per CU: 32 per XCD, each XCD one group
 constexpr int REC_MAX_GROUP = 32;         // CUs of one XCD
-constexpr int REC_XCD = 0;                // the XCD whose workgroups run the recurrence
+constexpr int REC_GROUPS = 8;             // XCDs: the workgroups of XCD x run the pieces n = x, x+8, x+16, ...
 constexpr long long REC_SPIN_LIMIT = 1LL << 21;
 constexpr int REC_NTC = 4;                // at most this many 16-piece tiles are staged and multiplied at once
 constexpr int REC_NI = 32;                // at most this many 16-byte operand blocks of W per lane (128 registers)
@@ -109,20 +110,36 @@ template <> __device__ __forceinline__ float cvt_finite<float>(float v) { return
 template <> __device__ __forceinline__ bf16_t cvt_finite<bf16_t>(float v) { return to_bf16_finite(v); }
 
 // ---- which workgroups take part ---------------------------------------------------------------------
-// Returns this workgroup's rank in [0, G) or -1.  ticket must be zero at launch.
-__device__ __forceinline__ int rec_rank(int* ticket, int G) {
-    __shared__ int s_rank;
+// The workgroups of one XCD form a group (grp = hardware XCC id) and take ranks from that group's ticket
+// (tickets[REC_GROUPS], zero at launch).  Returns this workgroup's rank in [0, G) or -1.
+__device__ __forceinline__ int rec_rank(int* tickets, int G, int& grp) {
+    __shared__ int s_rank, s_grp;
     if (threadIdx.x == 0) {
         const int xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf;   // HW_REG_XCC_ID, 4 bits
         int r = -1;
-        if (xcc == REC_XCD) {
-            r = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (xcc < REC_GROUPS) {
+            r = __hip_atomic_fetch_add(&tickets[xcc], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             if (r >= G) r = -1;
         }
         s_rank = r;
+        s_grp = xcc;
     }
     __syncthreads();
+    grp = s_grp;
     return s_rank;
+}
+// Pieces of group x alive when `bs` pieces are alive in all: n = x, x + REC_GROUPS, ... < bs.
+__device__ __forceinline__ int grp_count(int bs, int x) { return bs > x ? (bs - x + REC_GROUPS - 1) / REC_GROUPS : 0; }
+// Timesteps at which group x has an alive piece: batch sizes never grow, so that is how many exceed x.
+__device__ __forceinline__ int grp_steps(const int32_t* batch_sizes, int T, int x) {
+    __shared__ int s_T;
+    if (threadIdx.x == 0) s_T = 0;
+    __syncthreads();
+    int cnt = 0;
+    for (int t = threadIdx.x; t < T; t += blockDim.x) cnt += batch_sizes[t] > x ? 1 : 0;
+    if (cnt) atomicAdd(&s_T, cnt);
+    __syncthreads();
+    return s_T;
 }
 
 // ---- exchange through the XCD's L2 --------------------------------------------------------------------
@@ -164,37 +181,34 @@ __device__ __forceinline__ void rec_publish(int* flags, int rank, int value) {
     }
 }
 
-// Copies `rows` rows of `row_elems` elements (16-byte multiples) from global memory (L2) into LDS rows of
-// `stride` elements.  The whole workgroup takes part, DEPTH loads in flight per thread; reads past the last
-// row return zero (buffer bounds).
-// `rot` rotates the order in which this workgroup walks the vectors: all workgroups fetch the same rows at
+// Copies `rows` rows of `row_elems` elements (16-byte multiples), `pitch` elements apart in global memory
+// (L2), into LDS rows of `stride` elements, with loads that write LDS directly (no registers in between, so a wave can have dozens
+// of kilobytes in flight: the copy is bound by the latency of L2, and only the number of bytes in flight
+// shortens it).  One wave instruction moves a segment of up to 1 KB of one row: lane i's 16 bytes land at
+// the instruction's LDS base + 16*i.  Segments are dealt round-robin to the waves.
+// `rot` rotates the order in which this workgroup walks the segments: all workgroups fetch the same rows at
 // the same moment, and starting each one at a different place spreads them over the L2 channels.
+// The caller waits for the loads (s_waitcnt vmcnt(0)) and synchronises the workgroup.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
 template <typename E>
-__device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, int row_elems, E* __restrict__ lds,
-                                           int stride, int rot) {
-    constexpr int VEC = 16 / sizeof(E);
-    constexpr int DEPTH = 4;
-    const int vec_per_row = row_elems / VEC;
-    const int n = rows * vec_per_row;
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<E*>(src), 0, n * 16, 0x00020000);
-    const int shift = (int)(((long long)rot * n) / REC_MAX_GROUP) & ~63;   // whole waves stay contiguous
-    for (int v0 = threadIdx.x; v0 < n; v0 += DEPTH * REC_THREADS) {
-        u32x4_t tmp[DEPTH];
-        int vv[DEPTH];
-#pragma unroll
-        for (int u = 0; u < DEPTH; ++u) {
-            int v = v0 + u * REC_THREADS + shift;
-            if (v >= n) v -= n;
-            vv[u] = v;
-            tmp[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, v * 16, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < DEPTH; ++u) {
-            if (v0 + u * REC_THREADS < n) {
-                const int r = vv[u] / vec_per_row, c = vv[u] - r * vec_per_row;
-                *reinterpret_cast<u32x4_t*>(lds + r * stride + c * VEC) = tmp[u];
-            }
-        }
+__device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, int row_elems, int pitch,
+                                           E* __restrict__ lds, int stride, int rot) {
+    const int row_bytes = row_elems * (int)sizeof(E), pitch_bytes = pitch * (int)sizeof(E);
+    const int nseg = (row_bytes + 1023) >> 10;
+    const int n = rows * nseg;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<E*>(src), 0, (rows - 1) * pitch_bytes + row_bytes,
+                                                                    0x00020000);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int shift = (int)(((long long)rot * n) / REC_MAX_GROUP);
+    unsigned char* lds_b = reinterpret_cast<unsigned char*>(lds);
+    for (int s0 = wave; s0 < n; s0 += REC_WAVES) {
+        int sg = s0 + shift;
+        if (sg >= n) sg -= n;
+        const int r = sg / nseg, part = sg - r * nseg;
+        const int in_row = part * 1024 + lane * 16;
+        if (in_row < row_bytes)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(lds_b + (size_t)r * stride * sizeof(E) + part * 1024), 16,
+                                                     r * pitch_bytes + in_row, 0, 0, 0);
     }
 }
 
@@ -318,8 +332,12 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     constexpr int NW = NI > 0 ? NI : REC_NI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int G = a.G;
-    const int rank = rec_rank(a.ticket, G);
+    int grp;
+    const int rank = rec_rank(a.ticket, G, grp);
     if (rank < 0) return;
+    constexpr int X = REC_GROUPS;
+    const int x = grp;                       // this group's pieces: n = m * X + x, m = 0, 1, ...
+    int* flags = a.flags + x * REC_MAX_GROUP;
 
     const int H = a.H, stride = H + PAD, ntc = a.ntc;
     E* sB = reinterpret_cast<E*>(smem);                                                        // staged h rows
@@ -329,7 +347,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     const int mt = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
     const int j0 = rank * UH;
-    const int n_seq = a.info[0], T = a.info[1];
+    const int n_seq = grp_count(a.info[0], x), T = grp_steps(a.batch_sizes, a.info[1], x);
     E* hprev = static_cast<E*>(a.hprev);
     const int k_lo = ks * (H / KS);
     const int ni = (H / KS) / KBLK;
@@ -344,12 +362,12 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     }
     // initial hidden state of every piece, this workgroup's columns
     for (int i = tid; i < n_seq * (UH / 4); i += REC_THREADS) {
-        const int n = i / (UH / 4), u = (i % (UH / 4)) * 4;
+        const int n = (i / (UH / 4)) * X + x, u = (i % (UH / 4)) * 4;
         f32x4_t v = {0.f, 0.f, 0.f, 0.f};
         if (a.h0 && n < a.seq_cap) v = *reinterpret_cast<const f32x4_t*>(a.h0 + (size_t)n * H + j0 + u);
         st_row4<E>(hprev + (size_t)n * H + j0 + u, v[0], v[1], v[2], v[3]);
     }
-    rec_publish(a.flags, rank, 1);
+    rec_publish(flags, rank, 1);
     REC_PROF_DECL
     REC_PROF_START();
     float creg[REC_NTC] = {0.f, 0.f, 0.f, 0.f};  // cell state of the pieces in this lane's first REC_NTC tiles
@@ -359,22 +377,25 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     for (int q = 0; q < REC_NTC; ++q) zpre[q] = znext[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const size_t gcol = (size_t)(j0 + mt * 4 + lk) * 4;
     if (ks == 0 && T > 0) {
-        const int bs0 = a.batch_sizes[0];
+        const int bs0 = grp_count(a.batch_sizes[0], x);
 #pragma unroll
         for (int q = 0; q < REC_NTC; ++q)
-            if (q * 16 + lr < bs0) zpre[q] = *reinterpret_cast<const f32x4_t*>(a.gates + (size_t)(q * 16 + lr) * 4 * H + gcol);
+            if (q * 16 + lr < bs0)
+                zpre[q] = *reinterpret_cast<const f32x4_t*>(a.gates + (size_t)((q * 16 + lr) * X + x) * 4 * H + gcol);
     }
 
     for (int t = 0; t < T; ++t) {
-        const int bs = a.batch_sizes[t], base = a.t_off[t];
-        const int bs_next = (t + 1 < T) ? a.batch_sizes[t + 1] : 0, base_next = base + bs;
+        // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
+        const int bs_all = a.batch_sizes[t], bs = grp_count(bs_all, x), base = a.t_off[t];
+        const int bs_next = (t + 1 < T) ? grp_count(a.batch_sizes[t + 1], x) : 0, base_next = base + bs_all;
         const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
-        if (!rec_wait(a.flags, G, t + 1, a.err)) return;
+        if (!rec_wait(flags, G, t + 1, a.err)) return;
         REC_PROF_MARK(0);
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
             if (c0 > 0) __syncthreads();  // the previous chunk's rows have been consumed
-            stage_rows<E>(hprev + (size_t)(base + c0) * H, rows, H, sB, stride, rank);
+            stage_rows<E>(hprev + ((size_t)base + (size_t)c0 * X + x) * H, rows, H, X * H, sB, stride, rank);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             REC_PROF_MARK(5);
             __syncthreads();
             REC_PROF_MARK(1);
@@ -386,7 +407,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
                 for (int q = 0; q < REC_NTC; ++q)
                     if (q * 16 + lr < bs_next)
-                        znext[q] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base_next + q * 16 + lr) * 4 * H + gcol);
+                        znext[q] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base_next + (q * 16 + lr) * X + x) * 4 * H + gcol);
             }
             f32x4_t acc[REC_NTC];
             mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
@@ -413,9 +434,9 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
                 const int j = j0 + mt * 4 + lk;
 #pragma unroll
                 for (int q = 0; q < REC_NTC; ++q) {
-                    const int n = c0 + q * 16 + lr;
+                    const int m = c0 + q * 16 + lr, n = m * X + x;
                     float hn = 0.f;
-                    if (q * 16 < rows && n < bs) {
+                    if (q * 16 < rows && m < bs) {
                         const size_t p = (size_t)base + n;
                         f32x4_t* gp = reinterpret_cast<f32x4_t*>(a.gates + p * 4 * H + (size_t)j * 4);
                         const f32x4_t zin = (c0 == 0) ? zpre[q] : *gp;
@@ -449,12 +470,12 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
                 for (int i = tid; i < live * PIECES; i += REC_THREADS) {
                     const int r = i / PIECES, pc = i % PIECES;
                     const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sH + r * UH + pc * VEC);
-                    *reinterpret_cast<u32x4_t*>(hprev + ((size_t)base_next + c0 + r) * H + j0 + pc * VEC) = v;
+                    *reinterpret_cast<u32x4_t*>(hprev + ((size_t)base_next + (size_t)(c0 + r) * X + x) * H + j0 + pc * VEC) = v;
                 }
             }
         }
         REC_PROF_MARK(3);
-        if (t + 1 < T) rec_publish(a.flags, rank, t + 2);
+        if (t + 1 < T) rec_publish(flags, rank, t + 2);
 #pragma unroll
         for (int q = 0; q < REC_NTC; ++q) zpre[q] = znext[q];
         REC_PROF_MARK(4);
@@ -511,8 +532,12 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     constexpr int NW = NI > 0 ? NI : REC_NI;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int G = a.G;
-    const int rank = rec_rank(a.ticket, G);
+    int grp;
+    const int rank = rec_rank(a.ticket, G, grp);
     if (rank < 0) return;
+    constexpr int X = REC_GROUPS;
+    const int x = grp;                       // this group's pieces: n = m * X + x, m = 0, 1, ...
+    int* flags = a.flags + x * REC_MAX_GROUP;
 
     const int H = a.H, K = 4 * H, stride = K + PAD, ntc = a.ntc;
     E* sB = reinterpret_cast<E*>(smem);                                                        // staged dz rows
@@ -521,7 +546,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     const int mt = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
     const int j0 = rank * UH;
-    const int T = a.info[1];
+    const int T = grp_steps(a.batch_sizes, a.info[1], x);
     E* dzw = static_cast<E*>(a.dz);
     const int k_lo = ks * (K / KS);
     const int ni = (K / KS) / KBLK;
@@ -537,23 +562,24 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     pre.g4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
     pre.c = pre.c_prev = pre.dh_above = 0.f;
     if (T > 0) {
-        const int bs_l = a.batch_sizes[T - 1], base_l = a.t_off[T - 1];
+        const int bs_l = grp_count(a.batch_sizes[T - 1], x), base_l = a.t_off[T - 1];
         if (tid < bs_l * UH)
-            pre = load_saved(a, T - 1, base_l, (T > 1) ? a.t_off[T - 2] : 0, tid / UH, j0 + (tid % UH), H);
+            pre = load_saved(a, T - 1, base_l, (T > 1) ? a.t_off[T - 2] : 0, (tid / UH) * X + x, j0 + (tid % UH), H);
     }
     REC_PROF_DECL
     REC_PROF_START();
     for (int t = T - 1; t >= 0; --t) {
-        const int bs = a.batch_sizes[t], base = a.t_off[t];
-        const int bs_next = (t + 1 < T) ? a.batch_sizes[t + 1] : 0;
+        // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
+        const int bs = grp_count(a.batch_sizes[t], x), base = a.t_off[t];
+        const int bs_next = (t + 1 < T) ? grp_count(a.batch_sizes[t + 1], x) : 0;
         const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
         // A. gate gradients of this workgroup's units for every alive piece
         for (int i = tid; i < bs * UH; i += REC_THREADS) {
-            const int n = i / UH, j = j0 + (i % UH);
+            const int m = i / UH, n = m * X + x, j = j0 + (i % UH);
             const size_t p = (size_t)base + n;
             const BwdSaved sv = (i == tid) ? pre : load_saved(a, t, base, base_prev, n, j, H);
             const float gi = sv.g4[0], gf = sv.g4[1], gg = sv.g4[2], go = sv.g4[3];
-            const bool carried = n < bs_next;  // the piece is still alive at t+1
+            const bool carried = m < bs_next;  // the piece is still alive at t+1
             const float dh = sv.dh_above + (carried ? a.dh_state[(size_t)n * H + j] : 0.f);
             const float tc = tanhf_(sv.c);
             const float dc = (carried ? a.dc_state[(size_t)n * H + j] : 0.f) + dh * go * (1.f - tc * tc);
@@ -563,23 +589,24 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         }
         if (t == 0) break;  // nothing is carried before the first timestep
         REC_PROF_MARK(8);
-        rec_publish(a.flags, rank, T - t);
+        rec_publish(flags, rank, T - t);
         REC_PROF_MARK(9);
-        if (!rec_wait(a.flags, G, T - t, a.err)) return;
+        if (!rec_wait(flags, G, T - t, a.err)) return;
         REC_PROF_MARK(10);
         // B. dh carried to t-1: dh[n][k] = sum_q dz[n][q] * W_hh[q][k] for this workgroup's columns k
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
             if (c0 > 0) __syncthreads();
-            stage_rows<E>(dzw + (size_t)(base + c0) * K, rows, K, sB, stride, rank);
+            stage_rows<E>(dzw + ((size_t)base + (size_t)c0 * X + x) * K, rows, K, X * K, sB, stride, rank);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             REC_PROF_MARK(11);
             if (c0 == 0) {
                 // saved activations of this thread's first item of timestep t-1, issued once the exchanged rows
                 // have arrived (see the forward kernel): in flight during the MFMA phase
-                const int bs_p = a.batch_sizes[t - 1], base_p = a.t_off[t - 1];
+                const int bs_p = grp_count(a.batch_sizes[t - 1], x), base_p = a.t_off[t - 1];
                 if (tid < bs_p * UH)
-                    pre = load_saved(a, t - 1, base_p, (t > 1) ? a.t_off[t - 2] : 0, tid / UH, j0 + (tid % UH), H);
+                    pre = load_saved(a, t - 1, base_p, (t > 1) ? a.t_off[t - 2] : 0, (tid / UH) * X + x, j0 + (tid % UH), H);
             }
             f32x4_t acc[REC_NTC];
             mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
@@ -591,14 +618,14 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
             // its lane holds units lk*4..lk*4+3 of piece n
             const int smt = wave / REC_NTC, sq = wave % REC_NTC;
             if (smt < MT && sq * 16 < rows) {
-                const int n = c0 + sq * 16 + lr;
+                const int m = c0 + sq * 16 + lr, n = m * X + x;
                 f32x4_t sum = sRed[((0 * MT + smt) * ntc + sq) * 64 + lane];
 #pragma unroll
                 for (int s = 1; s < KS; ++s) {
                     const f32x4_t o = sRed[((s * MT + smt) * ntc + sq) * 64 + lane];
                     sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
                 }
-                if (n < bs) *reinterpret_cast<f32x4_t*>(a.dh_state + (size_t)n * H + j0 + smt * 16 + lk * 4) = sum;
+                if (m < bs) *reinterpret_cast<f32x4_t*>(a.dh_state + (size_t)n * H + j0 + smt * 16 + lk * 4) = sum;
             }
         }
         __syncthreads();  // dh_state is read by other threads in the next timestep's part A
