@@ -302,26 +302,34 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.prof = ws.prof;
         {
         ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
-        // one wave per (16 gate rows, share of the contraction): 8 tiles x 1 when 32 workgroups need all of
-        // H/32 >= 32 units, else 4 tiles x 2
+        // 8 waves = row groups x shares of the contraction (TPW tiles of 16 gate rows per wave): a workgroup owns
+        // 8 tiles (32 units) when 32 workgroups need all of H/32 units each, else 4 tiles (16 units)
         const bool wide = H / 16 > REC_MAX_GROUP;
-        const int mt = wide ? 8 : 4, ks = wide ? 1 : 2;
+        const bool quarter = MODE == MODE_F32 || H % 128 == 0;   // a quarter of H is a whole number of operand blocks
+        const int ks = quarter ? 4 : 2;
+        const int mt = wide ? 8 : 4;
         ra.G = H / (4 * mt);
         const size_t tile = (size_t)16 * (H + RecGeom<MODE>::PAD) * sizeof(E);
         const size_t red_per_tile = (size_t)ks * mt * 64 * 16 + (size_t)16 * 4 * mt * sizeof(E);   // partial sums + new h
         ra.ntc = rec_tiles(tile, red_per_tile);
         const size_t lds = ra.ntc * (tile + red_per_tile);
-        const int ni = (H / ks) / RecGeom<MODE>::KBLK;
+        const int nb = (H / ks) / RecGeom<MODE>::KBLK;
         bool ok = true;
-#define VER_FWD_LAUNCH(MT_, KS_, N_) do { ok = set_lds(lstm_rec_fwd_kernel<MODE, MT_, KS_, N_>, lds); \
-            if (ok) hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, MT_, KS_, N_>), dim3(REC_GRID), dim3(REC_THREADS), lds, s, ra); } while (0)
-        if (wide) {
-            if (ni == 32) VER_FWD_LAUNCH(8, 1, 32); else VER_FWD_LAUNCH(8, 1, 0);
+#define VER_FWD_LAUNCH(TPW_, KS_, NBW_, ST_) do { ok = set_lds(lstm_rec_fwd_kernel<MODE, TPW_, KS_, NBW_, ST_>, lds); \
+            if (ok) hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, TPW_, KS_, NBW_, ST_>), dim3(REC_GRID), dim3(REC_THREADS), lds, s, ra); } while (0)
+        if constexpr (MODE == MODE_BF16) {
+            if (wide) {
+                if (!quarter) VER_FWD_LAUNCH(2, 2, 16, false);
+                else if (nb == 8) VER_FWD_LAUNCH(4, 4, 8, true);
+                else VER_FWD_LAUNCH(4, 4, 8, false);
+            } else {
+                if (!quarter) VER_FWD_LAUNCH(1, 2, 8, false);
+                else if (nb == 4) VER_FWD_LAUNCH(2, 4, 4, true);
+                else VER_FWD_LAUNCH(2, 4, 4, false);
+            }
         } else {
-            if (ni == 16) VER_FWD_LAUNCH(4, 2, 16);
-            else if (ni == 8) VER_FWD_LAUNCH(4, 2, 8);
-            else if (ni == 4) VER_FWD_LAUNCH(4, 2, 4);
-            else VER_FWD_LAUNCH(4, 2, 0);
+            if (nb == 8) VER_FWD_LAUNCH(2, 4, 8, true);
+            else VER_FWD_LAUNCH(2, 4, 8, false);
         }
 #undef VER_FWD_LAUNCH
         if (!ok) return VER_EHIP;

@@ -300,6 +300,59 @@ __device__ __forceinline__ void mma_dispatch(const f32x4_t (&wreg)[NW], const ty
     else mma_tiles<MODE, NI, 4, NW>(wreg, brow, stride, ni_rt, blast, acc);
 }
 
+// ---- the product of one timestep (forward kernel) ---------------------------------------------------------
+// A wave holds TPW 16-row tiles of the weight matrix over its share of the contraction, NBW 16-byte operand
+// blocks per tile (wreg[tile * NBW + block]).  For one tile of 16 pieces it reads the matching blocks of the
+// staged rows from LDS once, multiplies them with all its tiles, and leaves its partial sums in LDS for the
+// wave that owns the tile in the epilogue.  Sharing the contraction between waves is what keeps the number of
+// LDS reads down: with one or two alive pieces the step is bound by LDS instructions, not by the MFMAs.
+// (Operand blocks loaded straight from the exchanged rows in L2 were measured slower than staging: a load
+// instruction costs the same whether 4 or 64 of its lanes carry data.)
+constexpr int REC_PRE = 2;   // piece tiles whose per-step inputs are prefetched one timestep ahead
+
+// Register slot i of a wave holds operand block blk_of(i) of its share, for the weights and for the rows
+// alike: the rotation `rot` (different in every workgroup) keeps the workgroups of a group, which all read the
+// same rows at the same moment, from asking L2 for the same line at the same time.
+template <int NBW, bool STATIC>
+__device__ __forceinline__ int blk_of(int i, int rot, int nb) {
+    const int v = i + rot;
+    if (STATIC) return v % NBW;
+    return v >= nb ? v - nb : v;
+}
+template <int MODE, int NBW, bool STATIC>
+__device__ __forceinline__ void load_b_lds(const typename RecGeom<MODE>::E* p, int nb, int rot, f32x4_t (&b)[NBW]) {
+#pragma unroll
+    for (int i = 0; i < NBW; ++i)
+        if (STATIC || i < nb) b[i] = *reinterpret_cast<const f32x4_t*>(p + blk_of<NBW, STATIC>(i, rot, nb) * RecGeom<MODE>::KBLK);
+}
+template <int MODE, int TPW, int NBW, bool STATIC>
+__device__ __forceinline__ void mma_step(const f32x4_t (&wreg)[TPW * NBW], const f32x4_t (&b)[NBW], int nb,
+                                         f32x4_t (&acc)[TPW]) {
+    // with a single tile, two accumulator chains so that consecutive MFMAs do not wait for each other
+    constexpr int CH = TPW == 1 ? 2 : 1;
+    f32x4_t part[TPW][CH];
+#pragma unroll
+    for (int tt = 0; tt < TPW; ++tt)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) part[tt][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < NBW; ++i)
+        if (STATIC || i < nb) {
+#pragma unroll
+            for (int tt = 0; tt < TPW; ++tt)
+                part[tt][i % CH] = mfma_block<MODE>(wreg[tt * NBW + i], b[i], part[tt][i % CH]);
+        }
+#pragma unroll
+    for (int tt = 0; tt < TPW; ++tt) {
+        f32x4_t sum = part[tt][0];
+#pragma unroll
+        for (int c = 1; c < CH; ++c) {
+            sum[0] += part[tt][c][0]; sum[1] += part[tt][c][1]; sum[2] += part[tt][c][2]; sum[3] += part[tt][c][3];
+        }
+        acc[tt] = sum;
+    }
+}
+
 // ======================================================================================================
 struct RecFwdArgs {
     const int32_t* info;
@@ -313,23 +366,24 @@ struct RecFwdArgs {
     const float* h0;    // [seq_cap, H] of this layer, or NULL
     const float* c0;
     int H, seq_cap, M;
-    int G;              // participating workgroups; each owns 4*MT hidden units
+    int G;              // workgroups per group; each owns 4*MT hidden units
     int ntc;            // 16-row tiles of staged rows that fit in LDS (1..REC_NTC)
-    int* flags;         // [G] zero at launch
-    int* ticket;        // zero at launch
+    int* flags;         // [REC_GROUPS][REC_MAX_GROUP] zero at launch
+    int* ticket;        // [REC_GROUPS] zero at launch
     int* err;
     long long* prof;    // [16] phase cycle counters (only touched by builds with VER_REC_PROF)
 };
 
-// MT 16-row tiles of gate rows per workgroup (4*MT hidden units), KS-way split of the contraction; one wave
-// per (tile, split).  NI: 16-byte blocks of W per lane when known at compile time (fast path), 0 = general.
-template <int MODE, int MT, int KS, int NI>
+// Waves are (row group rg, contraction share ks): REC_WAVES = RG * KS; a wave multiplies TPW tiles of 16 gate
+// rows over 1/KS of the contraction; the workgroup owns MT = RG*TPW tiles = 4*MT hidden units.  In the
+// epilogue wave w adds the KS partial sums of tile w and updates the cells of its 4 units.
+// NBW: capacity in operand blocks per tile and wave; STATIC: exactly NBW blocks (straight-line code).
+template <int MODE, int TPW, int KS, int NBW, bool STATIC>
 __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_rec_fwd_kernel(RecFwdArgs a) {
-    static_assert(MT * KS == REC_WAVES, "one wave per (tile, k-split)");
     typedef typename RecGeom<MODE>::E E;
     constexpr int PAD = RecGeom<MODE>::PAD, KBLK = RecGeom<MODE>::KBLK, VEC = RecGeom<MODE>::VEC;
-    constexpr int UH = 4 * MT, ROWS = 16 * MT;
-    constexpr int NW = NI > 0 ? NI : REC_NI;
+    constexpr int RG = REC_WAVES / KS, MT = RG * TPW, UH = 4 * MT, ROWS = 16 * MT;
+    static_assert(RG * KS == REC_WAVES && MT <= REC_WAVES, "wave roles");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int G = a.G;
     int grp;
@@ -344,21 +398,24 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     f32x4_t* sRed = reinterpret_cast<f32x4_t*>(smem + (size_t)ntc * 16 * stride * sizeof(E));  // [KS][MT][ntc][64]
     E* sH = reinterpret_cast<E*>(sRed + (size_t)KS * MT * ntc * 64);                            // [ntc*16][UH] new h
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int mt = wave / KS, ks = wave % KS;
+    const int rg = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
     const int j0 = rank * UH;
     const int n_seq = grp_count(a.info[0], x), T = grp_steps(a.batch_sizes, a.info[1], x);
     E* hprev = static_cast<E*>(a.hprev);
-    const int k_lo = ks * (H / KS);
-    const int ni = (H / KS) / KBLK;
+    const int k_lo = ((ks + rank) % KS) * (H / KS);   // which share a wave takes rotates with the rank, too
+    const int nb = (H / KS) / KBLK;
+    const int rot = (rank / KS) % nb;
 
-    // this wave's 16 rows of W_hh (its share of the contraction) -> registers, in MFMA operand layout
-    f32x4_t wreg[NW];
-    {
-        const E* wrow = static_cast<const E*>(a.whh) + ((size_t)rank * ROWS + mt * 16 + lr) * H + k_lo + lk * VEC;
+    // this wave's rows of W_hh (its share of the contraction) -> registers, in MFMA operand layout
+    f32x4_t wreg[TPW * NBW];
 #pragma unroll
-        for (int i = 0; i < NW; ++i)
-            wreg[i] = (i < ni) ? *reinterpret_cast<const f32x4_t*>(wrow + i * KBLK) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int tt = 0; tt < TPW; ++tt) {
+        const E* wrow = static_cast<const E*>(a.whh) + ((size_t)rank * ROWS + (rg * TPW + tt) * 16 + lr) * H + k_lo + lk * VEC;
+#pragma unroll
+        for (int i = 0; i < NBW; ++i)
+            wreg[tt * NBW + i] = (STATIC || i < nb) ? *reinterpret_cast<const f32x4_t*>(wrow + blk_of<NBW, STATIC>(i, rot, nb) * KBLK)
+                                                    : f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
     // initial hidden state of every piece, this workgroup's columns
     for (int i = tid; i < n_seq * (UH / 4); i += REC_THREADS) {
@@ -370,16 +427,22 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     rec_publish(flags, rank, 1);
     REC_PROF_DECL
     REC_PROF_START();
-    float creg[REC_NTC] = {0.f, 0.f, 0.f, 0.f};  // cell state of the pieces in this lane's first REC_NTC tiles
-    // input projections of the first REC_NTC tiles of the coming timestep, fetched one timestep ahead
-    f32x4_t zpre[REC_NTC], znext[REC_NTC];
+    // epilogue role: wave `wave` owns row tile `wave` (units j0 + wave*4 .. +3); its lane holds the four gates of
+    // unit wave*4 + lk for piece lr of a piece tile
+    const bool has_tile = wave < MT;
+    const int je = j0 + wave * 4 + lk;
+    const size_t gcol = (size_t)je * 4;
+    float creg[REC_PRE];     // cell state of the pieces in this lane's first REC_PRE tiles
+    f32x4_t zpre[REC_PRE], znext[REC_PRE];   // their input projections, fetched one timestep ahead
 #pragma unroll
-    for (int q = 0; q < REC_NTC; ++q) zpre[q] = znext[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const size_t gcol = (size_t)(j0 + mt * 4 + lk) * 4;
-    if (ks == 0 && T > 0) {
+    for (int q = 0; q < REC_PRE; ++q) {
+        creg[q] = 0.f;
+        zpre[q] = znext[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+    if (has_tile && T > 0) {
         const int bs0 = grp_count(a.batch_sizes[0], x);
 #pragma unroll
-        for (int q = 0; q < REC_NTC; ++q)
+        for (int q = 0; q < REC_PRE; ++q)
             if (q * 16 + lr < bs0)
                 zpre[q] = *reinterpret_cast<const f32x4_t*>(a.gates + (size_t)((q * 16 + lr) * X + x) * 4 * H + gcol);
     }
@@ -392,71 +455,68 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         if (!rec_wait(flags, G, t + 1, a.err)) return;
         REC_PROF_MARK(0);
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
-            const int rows = min(bs - c0, 16 * ntc);
+            const int rows = min(bs - c0, 16 * ntc), nt = (rows + 15) >> 4;
             if (c0 > 0) __syncthreads();  // the previous chunk's rows have been consumed
             stage_rows<E>(hprev + ((size_t)base + (size_t)c0 * X + x) * H, rows, H, X * H, sB, stride, rank);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            REC_PROF_MARK(5);
             __syncthreads();
             REC_PROF_MARK(1);
-            if (c0 == 0 && ks == 0 && t + 1 < T) {
-                // next timestep's input projections (first REC_NTC tiles).  Issued right after the exchanged
-                // rows have arrived: the memory counter retires in order, so a prefetch must never be queued
-                // in front of loads that the critical path waits for; from here it has the MFMA and cell-update
-                // phases to complete before the next wait on the counter.
+#pragma unroll 1
+            for (int q = 0; q < nt; ++q) {
+                f32x4_t b[NBW];
+                // dead lanes of the last tile read its first row: equal addresses are broadcast by the LDS
+                const int r = q * 16 + ((q * 16 + lr < rows) ? lr : 0);
+                load_b_lds<MODE, NBW, STATIC>(sB + r * stride + k_lo + lk * VEC, nb, rot, b);
+                f32x4_t acc[TPW];
+                mma_step<MODE, TPW, NBW, STATIC>(wreg, b, nb, acc);
 #pragma unroll
-                for (int q = 0; q < REC_NTC; ++q)
-                    if (q * 16 + lr < bs_next)
-                        znext[q] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base_next + (q * 16 + lr) * X + x) * 4 * H + gcol);
-            }
-            f32x4_t acc[REC_NTC];
-            mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
-            if (KS > 1) {
+                for (int tt = 0; tt < TPW; ++tt) sRed[((ks * MT + rg * TPW + tt) * ntc + q) * 64 + lane] = acc[tt];
+                if (q == 0 && c0 == 0 && has_tile && t + 1 < T) {
+                    // next timestep's input projections.  Issued after the product: the memory counter retires in
+                    // order, so every wait on an operand load would also wait for a prefetch issued before or
+                    // between them (and the compiler must assume the worst about loads under a condition).
 #pragma unroll
-                for (int q = 0; q < REC_NTC; ++q)
-                    if (q * 16 < rows) sRed[((ks * MT + mt) * ntc + q) * 64 + lane] = acc[q];
-                __syncthreads();
-                if (ks == 0) {
-#pragma unroll
-                    for (int q = 0; q < REC_NTC; ++q)
-                        if (q * 16 < rows) {
-#pragma unroll
-                            for (int s = 1; s < KS; ++s) {
-                                const f32x4_t o = sRed[((s * MT + mt) * ntc + q) * 64 + lane];
-                                acc[q][0] += o[0]; acc[q][1] += o[1]; acc[q][2] += o[2]; acc[q][3] += o[3];
-                            }
-                        }
+                    for (int qq = 0; qq < REC_PRE; ++qq)
+                        if (qq * 16 + lr < bs_next)
+                            znext[qq] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base_next + (qq * 16 + lr) * X + x) * 4 * H + gcol);
                 }
             }
+            __syncthreads();
             REC_PROF_MARK(2);
-            // lane holds the 4 gate pre-activations of unit (mt*4 + lk) for piece c0 + q*16 + lr
-            if (ks == 0) {
-                const int j = j0 + mt * 4 + lk;
+            if (has_tile) {
 #pragma unroll
                 for (int q = 0; q < REC_NTC; ++q) {
+                    if (q >= nt) break;
+                    f32x4_t z = sRed[((0 * MT + wave) * ntc + q) * 64 + lane];
+#pragma unroll
+                    for (int sp = 1; sp < KS; ++sp) {
+                        const f32x4_t o = sRed[((sp * MT + wave) * ntc + q) * 64 + lane];
+                        z[0] += o[0]; z[1] += o[1]; z[2] += o[2]; z[3] += o[3];
+                    }
                     const int m = c0 + q * 16 + lr, n = m * X + x;
+                    const bool in_regs = c0 == 0 && q < REC_PRE;
                     float hn = 0.f;
-                    if (q * 16 < rows && m < bs) {
+                    if (m < bs) {
                         const size_t p = (size_t)base + n;
-                        f32x4_t* gp = reinterpret_cast<f32x4_t*>(a.gates + p * 4 * H + (size_t)j * 4);
-                        const f32x4_t zin = (c0 == 0) ? zpre[q] : *gp;
-                        const float gi = sigmoidf_(acc[q][0] + zin[0]);
-                        const float gf = sigmoidf_(acc[q][1] + zin[1]);
-                        const float gg = tanhf_(acc[q][2] + zin[2]);
-                        const float go = sigmoidf_(acc[q][3] + zin[3]);
+                        f32x4_t* gp = reinterpret_cast<f32x4_t*>(a.gates + p * 4 * H + gcol);
+                        const f32x4_t zin = in_regs ? zpre[q < REC_PRE ? q : 0] : *gp;
+                        const float gi = sigmoidf_(z[0] + zin[0]);
+                        const float gf = sigmoidf_(z[1] + zin[1]);
+                        const float gg = tanhf_(z[2] + zin[2]);
+                        const float go = sigmoidf_(z[3] + zin[3]);
                         float c_prev;
-                        if (t == 0) c_prev = (a.c0 && n < a.seq_cap) ? a.c0[(size_t)n * H + j] : 0.f;
-                        else if (c0 == 0) c_prev = creg[q];   // this lane computed it one timestep ago
-                        else c_prev = a.c[((size_t)base_prev + n) * H + j];
+                        if (t == 0) c_prev = (a.c0 && n < a.seq_cap) ? a.c0[(size_t)n * H + je] : 0.f;
+                        else if (in_regs) c_prev = creg[q < REC_PRE ? q : 0];   // this lane computed it one timestep ago
+                        else c_prev = a.c[((size_t)base_prev + n) * H + je];
                         const float cn = gf * c_prev + gi * gg;
-                        if (c0 == 0) creg[q] = cn;
+                        if (in_regs) creg[q < REC_PRE ? q : 0] = cn;
                         hn = go * tanhf_(cn);
                         *gp = f32x4_t{gi, gf, gg, go};
-                        a.c[p * H + j] = cn;
-                        a.hout[p * H + j] = hn;
+                        a.c[p * H + je] = cn;
+                        a.hout[p * H + je] = hn;
                     }
                     // h_t goes to the exchange row of the next timestep through LDS (below)
-                    if (q * 16 < rows) sH[(q * 16 + lr) * UH + mt * 4 + lk] = cvt_finite<E>(hn);
+                    sH[(q * 16 + lr) * UH + wave * 4 + lk] = cvt_finite<E>(hn);
                 }
             }
             // The workgroup's UH units of a row are contiguous (UH * sizeof(E) = 32..64 bytes): write them with
@@ -477,7 +537,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         REC_PROF_MARK(3);
         if (t + 1 < T) rec_publish(flags, rank, t + 2);
 #pragma unroll
-        for (int q = 0; q < REC_NTC; ++q) zpre[q] = znext[q];
+        for (int q = 0; q < REC_PRE; ++q) zpre[q] = znext[q];
         REC_PROF_MARK(4);
         REC_PROF_STEP();
     }
