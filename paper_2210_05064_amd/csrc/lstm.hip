@@ -388,7 +388,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         const int mt = wide ? 2 : 1, ks = wide ? 4 : 8;
         ra.G = H / (16 * mt);
         const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
-        const size_t red_per_tile = (size_t)ks * mt * 64 * 16;
+        const size_t red_per_tile = (size_t)ks * mt * 64 * 16 + (size_t)16 * 16 * mt * sizeof(float);   // partial sums + carried dh
         ra.ntc = rec_tiles(tile, red_per_tile);
         const size_t lds = ra.ntc * (tile + red_per_tile);
         const int ni = (4 * H / ks) / RecGeom<MODE>::KBLK;

@@ -109,6 +109,11 @@ template <typename E> __device__ __forceinline__ E cvt_finite(float v);
 template <> __device__ __forceinline__ float cvt_finite<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t cvt_finite<bf16_t>(float v) { return to_bf16_finite(v); }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
+// load and store of the wave, which would put the latency of each prefetch on the critical path of the
+// timestep; the time loops wait for global memory explicitly where a step needs it.
+__device__ __forceinline__ void bar_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // ---- which workgroups take part ---------------------------------------------------------------------
 // The workgroups of one XCD form a group (grp = hardware XCC id) and take ranks from that group's ticket
 // (tickets[REC_GROUPS], zero at launch).  Returns this workgroup's rank in [0, G) or -1.
@@ -157,6 +162,9 @@ __device__ __forceinline__ bool rec_wait(const int* flags, int G, int target, in
         for (;;) {
             const bool ok = (int)threadIdx.x >= G || ld_l2(&flags[threadIdx.x]) >= target;
             if (__all(ok)) break;
+#ifdef VER_REC_SLEEP
+            __builtin_amdgcn_s_sleep(VER_REC_SLEEP);
+#endif
             ++spins;
             if ((spins & 1023) == 0 && (spins > REC_SPIN_LIMIT || ld_agent(err) != 0)) {
                 if (threadIdx.x == 0) st_agent(err, 1);
@@ -166,7 +174,7 @@ __device__ __forceinline__ bool rec_wait(const int* flags, int G, int target, in
         }
         if (threadIdx.x == 0) s_ok = alive ? 1 : 0;
     }
-    __syncthreads();
+    bar_lds();
     return s_ok != 0;
 }
 
@@ -174,7 +182,7 @@ __device__ __forceinline__ bool rec_wait(const int* flags, int G, int target, in
 // the workgroup barrier) raises the workgroup's flag.
 __device__ __forceinline__ void rec_publish(int* flags, int rank, int value) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    bar_lds();
     if (threadIdx.x == 0) {
         __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(&flags[rank], 0, 4, 0x00020000);
         __builtin_amdgcn_raw_buffer_store_b32(value, r, 0, 0, 0);
@@ -456,10 +464,20 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         REC_PROF_MARK(0);
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc), nt = (rows + 15) >> 4;
-            if (c0 > 0) __syncthreads();  // the previous chunk's rows have been consumed
+            if (c0 > 0) bar_lds();  // the previous chunk's rows have been consumed
             stage_rows<E>(hprev + ((size_t)base + (size_t)c0 * X + x) * H, rows, H, X * H, sB, stride, rank);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+            bar_lds();
+            if (c0 == 0 && has_tile && t + 1 < T) {
+                // next timestep's input projections.  Issued right after the exchanged rows have arrived: the
+                // memory counter retires in order, so a prefetch must never be queued in front of loads that
+                // the critical path waits for; from here nothing waits for global memory until the flag is
+                // raised at the end of the step.
+#pragma unroll
+                for (int qq = 0; qq < REC_PRE; ++qq)
+                    if (qq * 16 + lr < bs_next)
+                        znext[qq] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base_next + (qq * 16 + lr) * X + x) * 4 * H + gcol);
+            }
             REC_PROF_MARK(1);
 #pragma unroll 1
             for (int q = 0; q < nt; ++q) {
@@ -471,17 +489,8 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
                 mma_step<MODE, TPW, NBW, STATIC>(wreg, b, nb, acc);
 #pragma unroll
                 for (int tt = 0; tt < TPW; ++tt) sRed[((ks * MT + rg * TPW + tt) * ntc + q) * 64 + lane] = acc[tt];
-                if (q == 0 && c0 == 0 && has_tile && t + 1 < T) {
-                    // next timestep's input projections.  Issued after the product: the memory counter retires in
-                    // order, so every wait on an operand load would also wait for a prefetch issued before or
-                    // between them (and the compiler must assume the worst about loads under a condition).
-#pragma unroll
-                    for (int qq = 0; qq < REC_PRE; ++qq)
-                        if (qq * 16 + lr < bs_next)
-                            znext[qq] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base_next + (qq * 16 + lr) * X + x) * 4 * H + gcol);
-                }
             }
-            __syncthreads();
+            bar_lds();
             REC_PROF_MARK(2);
             if (has_tile) {
 #pragma unroll
@@ -523,7 +532,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
             // full 16-byte pieces from consecutive lanes.  Partial-sector writes scattered over several
             // instructions make the L2 fetch the rest of the line from memory, and the readers of the next
             // timestep then wait for that fill (about 2 us) instead of an L2 hit.
-            __syncthreads();
+            bar_lds();
             {
                 constexpr int PIECES = UH * (int)sizeof(E) / 16;     // 16-byte pieces per row
                 const int live = min(rows, bs_next - c0);            // rows of this chunk still alive at t+1
@@ -602,6 +611,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     const int H = a.H, K = 4 * H, stride = K + PAD, ntc = a.ntc;
     E* sB = reinterpret_cast<E*>(smem);                                                        // staged dz rows
     f32x4_t* sRed = reinterpret_cast<f32x4_t*>(smem + (size_t)ntc * 16 * stride * sizeof(E));  // [KS][MT][ntc][64]
+    float* sDh = reinterpret_cast<float*>(sRed + (size_t)KS * MT * ntc * 64);   // [ntc*16][UH] dh carried to the previous timestep
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int mt = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
@@ -621,6 +631,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     BwdSaved pre;   // saved activations of this thread's first (piece, unit) of the coming timestep
     pre.g4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
     pre.c = pre.c_prev = pre.dh_above = 0.f;
+    float dcreg = 0.f;   // cell-state gradient of that (piece, unit), carried from timestep to timestep
     if (T > 0) {
         const int bs_l = grp_count(a.batch_sizes[T - 1], x), base_l = a.t_off[T - 1];
         if (tid < bs_l * UH)
@@ -637,15 +648,22 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         for (int i = tid; i < bs * UH; i += REC_THREADS) {
             const int m = i / UH, n = m * X + x, j = j0 + (i % UH);
             const size_t p = (size_t)base + n;
-            const BwdSaved sv = (i == tid) ? pre : load_saved(a, t, base, base_prev, n, j, H);
+            const bool first = i == tid;
+            const BwdSaved sv = first ? pre : load_saved(a, t, base, base_prev, n, j, H);
             const float gi = sv.g4[0], gf = sv.g4[1], gg = sv.g4[2], go = sv.g4[3];
             const bool carried = m < bs_next;  // the piece is still alive at t+1
-            const float dh = sv.dh_above + (carried ? a.dh_state[(size_t)n * H + j] : 0.f);
+            float dh = sv.dh_above, dc = 0.f;
+            if (carried) {
+                // the pieces of the first chunk hand dh over in LDS, a thread's first item keeps dc in a register
+                dh += (m < 16 * ntc) ? sDh[m * UH + (i % UH)] : a.dh_state[(size_t)n * H + j];
+                dc = first ? dcreg : a.dc_state[(size_t)n * H + j];
+            }
             const float tc = tanhf_(sv.c);
-            const float dc = (carried ? a.dc_state[(size_t)n * H + j] : 0.f) + dh * go * (1.f - tc * tc);
+            dc += dh * go * (1.f - tc * tc);
             st_row4<E>(dzw + p * K + (size_t)j * 4, dc * gg * gi * (1.f - gi), dc * sv.c_prev * gf * (1.f - gf),
                        dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
-            a.dc_state[(size_t)n * H + j] = dc * gf;
+            if (first) dcreg = dc * gf;
+            else a.dc_state[(size_t)n * H + j] = dc * gf;
         }
         if (t == 0) break;  // nothing is carried before the first timestep
         REC_PROF_MARK(8);
@@ -656,10 +674,10 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         // B. dh carried to t-1: dh[n][k] = sum_q dz[n][q] * W_hh[q][k] for this workgroup's columns k
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
-            if (c0 > 0) __syncthreads();
+            if (c0 > 0) bar_lds();
             stage_rows<E>(dzw + ((size_t)base + (size_t)c0 * X + x) * K, rows, K, X * K, sB, stride, rank);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
+            bar_lds();
             REC_PROF_MARK(11);
             if (c0 == 0) {
                 // saved activations of this thread's first item of timestep t-1, issued once the exchanged rows
@@ -673,7 +691,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
 #pragma unroll
             for (int q = 0; q < REC_NTC; ++q)
                 if (q * 16 < rows) sRed[((ks * MT + mt) * ntc + q) * 64 + lane] = acc[q];
-            __syncthreads();
+            bar_lds();
             // wave w adds the KS partial sums of (unit tile w / REC_NTC, piece tile w % REC_NTC):
             // its lane holds units lk*4..lk*4+3 of piece n
             const int smt = wave / REC_NTC, sq = wave % REC_NTC;
@@ -685,10 +703,16 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
                     const f32x4_t o = sRed[((s * MT + smt) * ntc + sq) * 64 + lane];
                     sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
                 }
-                if (m < bs) *reinterpret_cast<f32x4_t*>(a.dh_state + (size_t)n * H + j0 + smt * 16 + lk * 4) = sum;
+                if (m < bs) {
+                    if (c0 == 0) *reinterpret_cast<f32x4_t*>(sDh + (sq * 16 + lr) * UH + smt * 16 + lk * 4) = sum;
+                    else *reinterpret_cast<f32x4_t*>(a.dh_state + (size_t)n * H + j0 + smt * 16 + lk * 4) = sum;
+                }
             }
         }
-        __syncthreads();  // dh_state is read by other threads in the next timestep's part A
+        // dh is read by other threads in the next timestep's part A: from LDS, or (pieces beyond the first chunk)
+        // from global memory, whose stores must have completed
+        if (bs > 16 * ntc) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        bar_lds();
         REC_PROF_MARK(12);
         REC_PROF_STEP();
     }
