@@ -27,7 +27,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 
 # HBM bytes per launch (read + written) of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of
 # this script, scaled by a copy of known size: see profiles/hbm_traffic_max_workload.md.  None where unmeasured.
-MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 393.9e6, ("max", "lstm_rec_fwd"): 447.2e6}
+MEASURED_TRAFFIC = {}
 
 
 def collection_logp(ro, compute, x_bf16):
@@ -178,7 +178,9 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     dom = max(("lstm_rec_fwd", "lstm_rec_bwd"), key=lambda k: prof[k][0])
     dom_ms, dom_n = prof[dom]
-    flops_per_launch = 8.0 * H * H * M      # 2 * (4H x H) * rows, one layer, all timesteps of a minibatch
+    # recurrent product of one layer over all timesteps of a minibatch: 2 * (4H x H) * rows.  With two layers one
+    # launch runs both time loops and the projection between them (the same number of FLOPs again).
+    flops_per_launch = 8.0 * H * H * M * (3 if w.n_layers == 2 else 1)
     achieved = flops_per_launch / (dom_ms / dom_n * 1e-3) / 1e12
     dtype = "bf16" if learner.compute else "f32"
     out = {

@@ -11,7 +11,7 @@
 //       (forward), dz_t and W_hh dz_t (backward) - see lstm_rec.h.
 // Internally the 4H gate rows are interleaved (row = unit*4 + gate); user-facing
 // weights and gradients keep the gate-major order i,f,g,o of the declaration.
-#include "lstm_rec.h"
+#include "lstm_pipe.h"
 
 namespace ver {
 namespace {
@@ -168,7 +168,9 @@ struct LstmWs {
     int* flags;        // [REC_FLAG_WORDS]: per-workgroup flags of a recurrent launch, then its ticket counters
     long long* prof;   // [32] phase counters of the recurrent kernels (forward 0..15, backward 16..31)
     LayerWs layer[8];
-    void* dz;          // [M, 4H] operand type
+    void* dz[2];       // [M, 4H] operand type; the second one only when two layers share a launch
+    int* pipe;         // hand-over words of a two-layer launch: progress[8], queue at [8], done[] from [16]
+    int pipe_words;
     float* dh[2];      // [M, H] ping-pong: gradient arriving at a layer's h
     float* dh_state;   // [M, H]
     float* dc_state;   // [M, H]
@@ -223,11 +225,14 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
         L.hout = cv.take<float>(Mz * H);
         L.hprev = cv.take<char>(Mz * H * es);
     }
-    ws->dz = cv.take<char>(Mz * 4 * H * es);
+    ws->dz[0] = cv.take<char>(Mz * 4 * H * es);
+    ws->dz[1] = c.n_layers == 2 ? cv.take<char>(Mz * 4 * H * es) : ws->dz[0];
+    ws->pipe_words = 16 + M / PIPE_CT + 2;
+    ws->pipe = cv.take<int>(ws->pipe_words);
     ws->dh[0] = cv.take<float>(Mz * H);
     ws->dh[1] = cv.take<float>(Mz * H);
-    ws->dh_state = cv.take<float>(Mz * H);
-    ws->dc_state = cv.take<float>(Mz * H);
+    ws->dh_state = cv.take<float>(2 * Mz * H);
+    ws->dc_state = cv.take<float>(2 * Mz * H);
     ws->part = cv.take<float>(part_floats(c, M));
     ws->gemm_part = cv.take<float>(gemm_part_max(c, M));
     ws->db_head = cv.take<float>(64);
@@ -257,27 +262,57 @@ inline bool set_lds(K kernel, size_t bytes) {
                                (int)bytes) == hipSuccess;
 }
 
+// LDS of a worker of a two-layer launch: one 128 x BK and one 256 x BK operand tile.
+template <int MODE>
+inline size_t pipe_worker_lds() {
+    return (size_t)(PIPE_BM + PIPE_BN) * GemmGeom<MODE>::LDS_STRIDE * sizeof(typename LdsElem<MODE>::type);
+}
+inline void pipe_link(const ver_lstm_cfg& c, int M, int N, LstmWs& ws, hipStream_t s, PipeLink* pl) {
+    fill_words(ws.pipe, ws.pipe_words, 0, s);
+    pl->progress = ws.pipe;
+    pl->done = ws.pipe + 16;
+    pl->tiles_n = (N + PIPE_BN - 1) / PIPE_BN;
+    pl->T_all = 0;   // filled in on the device from info[1]
+    pl->M = M;
+    (void)c;
+}
+
 template <int MODE>
 int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, const int32_t* batch_sizes,
             const int32_t* t_off, const float* h0, const float* c0, int seq_cap, const float* const* w,
             float* head_out, float* value, LstmWs& ws, hipStream_t s) {
     typedef typename RecGeom<MODE>::E E;
     const int H = c.hidden, A = c.act_dim;
+    const bool pipelined = c.n_layers == 2;   // both time loops in one launch
     fill_words(ws.err, 1, 0, s);
-    for (int l = 0; l < c.n_layers; ++l) {
+
+    // 8 waves = row groups x shares of the contraction (TPW tiles of 16 gate rows per wave): a workgroup owns
+    // 8 tiles (32 units) when 32 workgroups need all of H/32 units each, else 4 tiles (16 units)
+    const bool wide = H / 16 > REC_MAX_GROUP;
+    const bool quarter = MODE == MODE_F32 || H % 128 == 0;   // a quarter of H is a whole number of operand blocks
+    const int ks = quarter ? 4 : 2;
+    const int mt = wide ? 8 : 4;
+    const size_t tile = (size_t)16 * (H + RecGeom<MODE>::PAD) * sizeof(E);
+    const size_t red_per_tile = (size_t)ks * mt * 64 * 16 + (size_t)16 * 4 * mt * sizeof(E);   // partial sums + new h
+    const int ntc = rec_tiles(tile, red_per_tile);
+    size_t lds = ntc * (tile + red_per_tile);
+    if (pipelined && pipe_worker_lds<MODE>() > lds) lds = pipe_worker_lds<MODE>();
+    const int nb = (H / ks) / RecGeom<MODE>::KBLK;
+
+    auto prep = [&](int l) {
         const int D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws.layer[l];
-        const float* W_ih = w[4 * l], *W_hh = w[4 * l + 1], *b_ih = w[4 * l + 2], *b_hh = w[4 * l + 3];
-        {
         ProfScope prof(VER_PROF_LSTM_PREP, s);
-        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, W_ih, H, D, static_cast<E*>(L.wih),
+        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, w[4 * l], H, D, static_cast<E*>(L.wih),
                            static_cast<E*>(L.wihT));
-        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, W_hh, H, H, static_cast<E*>(L.whh),
+        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, w[4 * l + 1], H, H, static_cast<E*>(L.whh),
                            static_cast<E*>(L.whhT));
-        hipLaunchKernelGGL(prep_bias_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, b_ih, b_hh, H, L.bias);
-        }
-        // time-batched input projection: gates[M, 4H] = x W_ih^T + (b_ih + b_hh), interleaved columns
-        {
+        hipLaunchKernelGGL(prep_bias_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, w[4 * l + 2], w[4 * l + 3], H, L.bias);
+    };
+    // time-batched input projection: gates[M, 4H] = x W_ih^T + (b_ih + b_hh), interleaved columns
+    auto project = [&](int l) {
+        const int D = l == 0 ? c.input_dim : H;
+        LayerWs& L = ws.layer[l];
         ProfScope prof(VER_PROF_LSTM_GEMM_FWD, s);
         if (l == 0) {
             if (c.x_bf16)
@@ -290,51 +325,66 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
             gemm_launch<MODE, float, E, false>(ws.layer[l - 1].hout, H, static_cast<const E*>(L.wih), H, L.gates,
                                                4 * H, M, 4 * H, H, L.bias, 0, ws.gemm_part, true, s);
         }
-        }
-        // sequential part
-        fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
+    };
+    auto rec_args = [&](int l) {
+        LayerWs& L = ws.layer[l];
         RecFwdArgs ra;
         ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
         ra.gates = L.gates; ra.c = L.c; ra.hout = L.hout; ra.hprev = L.hprev; ra.whh = L.whh;
         ra.h0 = h0 ? h0 + (size_t)l * seq_cap * H : nullptr;
         ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
-        ra.H = H; ra.seq_cap = seq_cap; ra.M = M; ra.flags = ws.flags; ra.ticket = ws.flags + REC_GROUPS * REC_MAX_GROUP; ra.err = ws.err;
-        ra.prof = ws.prof;
-        {
+        ra.H = H; ra.seq_cap = seq_cap; ra.M = M; ra.flags = ws.flags; ra.ticket = ws.flags + REC_GROUPS * REC_MAX_GROUP;
+        ra.err = ws.err; ra.prof = ws.prof;
+        ra.G = H / (4 * mt); ra.ntc = ntc;
+        return ra;
+    };
+    bool ok = true;
+#define VER_FWD_LAUNCH(KERNEL, ARGS, TPW_, KS_, NBW_, ST_) do { ok = set_lds(KERNEL<MODE, TPW_, KS_, NBW_, ST_>, lds); \
+        if (ok) hipLaunchKernelGGL((KERNEL<MODE, TPW_, KS_, NBW_, ST_>), dim3(REC_GRID), dim3(REC_THREADS), lds, s, ARGS); } while (0)
+#define VER_FWD_DISPATCH(KERNEL, ARGS) do { \
+        if constexpr (MODE == MODE_BF16) { \
+            if (wide) { \
+                if (!quarter) VER_FWD_LAUNCH(KERNEL, ARGS, 2, 2, 16, false); \
+                else if (nb == 8) VER_FWD_LAUNCH(KERNEL, ARGS, 4, 4, 8, true); \
+                else VER_FWD_LAUNCH(KERNEL, ARGS, 4, 4, 8, false); \
+            } else { \
+                if (!quarter) VER_FWD_LAUNCH(KERNEL, ARGS, 1, 2, 8, false); \
+                else if (nb == 4) VER_FWD_LAUNCH(KERNEL, ARGS, 2, 4, 4, true); \
+                else VER_FWD_LAUNCH(KERNEL, ARGS, 2, 4, 4, false); \
+            } \
+        } else { \
+            if (nb == 8) VER_FWD_LAUNCH(KERNEL, ARGS, 2, 4, 8, true); \
+            else VER_FWD_LAUNCH(KERNEL, ARGS, 2, 4, 8, false); \
+        } } while (0)
+
+    if (pipelined) {
+        prep(0);
+        prep(1);
+        project(0);
+        fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
+        PipeFwdArgs pa;
+        pa.l0 = rec_args(0);
+        pa.l1 = rec_args(1);
+        pipe_link(c, M, 4 * H, ws, s, &pa.link);
+        pa.work.A = ws.layer[0].hout; pa.work.B = ws.layer[1].wih; pa.work.C = ws.layer[1].gates;
+        pa.work.bias = ws.layer[1].bias; pa.work.K = H; pa.work.N = 4 * H;
+        pa.work.batch_sizes = batch_sizes; pa.work.t_off = t_off; pa.work.queue = ws.pipe + 8; pa.work.err = ws.err;
         ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
-        // 8 waves = row groups x shares of the contraction (TPW tiles of 16 gate rows per wave): a workgroup owns
-        // 8 tiles (32 units) when 32 workgroups need all of H/32 units each, else 4 tiles (16 units)
-        const bool wide = H / 16 > REC_MAX_GROUP;
-        const bool quarter = MODE == MODE_F32 || H % 128 == 0;   // a quarter of H is a whole number of operand blocks
-        const int ks = quarter ? 4 : 2;
-        const int mt = wide ? 8 : 4;
-        ra.G = H / (4 * mt);
-        const size_t tile = (size_t)16 * (H + RecGeom<MODE>::PAD) * sizeof(E);
-        const size_t red_per_tile = (size_t)ks * mt * 64 * 16 + (size_t)16 * 4 * mt * sizeof(E);   // partial sums + new h
-        ra.ntc = rec_tiles(tile, red_per_tile);
-        const size_t lds = ra.ntc * (tile + red_per_tile);
-        const int nb = (H / ks) / RecGeom<MODE>::KBLK;
-        bool ok = true;
-#define VER_FWD_LAUNCH(TPW_, KS_, NBW_, ST_) do { ok = set_lds(lstm_rec_fwd_kernel<MODE, TPW_, KS_, NBW_, ST_>, lds); \
-            if (ok) hipLaunchKernelGGL((lstm_rec_fwd_kernel<MODE, TPW_, KS_, NBW_, ST_>), dim3(REC_GRID), dim3(REC_THREADS), lds, s, ra); } while (0)
-        if constexpr (MODE == MODE_BF16) {
-            if (wide) {
-                if (!quarter) VER_FWD_LAUNCH(2, 2, 16, false);
-                else if (nb == 8) VER_FWD_LAUNCH(4, 4, 8, true);
-                else VER_FWD_LAUNCH(4, 4, 8, false);
-            } else {
-                if (!quarter) VER_FWD_LAUNCH(1, 2, 8, false);
-                else if (nb == 4) VER_FWD_LAUNCH(2, 4, 4, true);
-                else VER_FWD_LAUNCH(2, 4, 4, false);
-            }
-        } else {
-            if (nb == 8) VER_FWD_LAUNCH(2, 4, 8, true);
-            else VER_FWD_LAUNCH(2, 4, 8, false);
-        }
-#undef VER_FWD_LAUNCH
+        VER_FWD_DISPATCH(lstm_pipe_fwd_kernel, pa);
         if (!ok) return VER_EHIP;
+    } else {
+        for (int l = 0; l < c.n_layers; ++l) {
+            prep(l);
+            project(l);
+            fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
+            RecFwdArgs ra = rec_args(l);
+            ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
+            VER_FWD_DISPATCH(lstm_rec_fwd_kernel, ra);
+            if (!ok) return VER_EHIP;
         }
     }
+#undef VER_FWD_DISPATCH
+#undef VER_FWD_LAUNCH
     ProfScope prof(VER_PROF_HEADS_FWD, s);
     hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 3) / 4), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
                        w[4 * c.n_layers], w[4 * c.n_layers + 1], w[4 * c.n_layers + 2], w[4 * c.n_layers + 3],
@@ -369,47 +419,51 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
                        (float*)nullptr);
     }
 
-    int cur = 0;  // ws.dh[cur] holds the gradient arriving at the current layer's h
-    for (int l = nl - 1; l >= 0; --l) {
-        const int D = l == 0 ? c.input_dim : H;
+    // one wave per (16 units, share of the 4H contraction): 2 tiles x 4 when H/16 > 32 workgroups, else 1 x 8
+    const bool pipelined = nl == 2;   // both time loops in one launch
+    const bool wide = H / 16 > REC_MAX_GROUP;
+    const int mt = wide ? 2 : 1, ks = wide ? 4 : 8;
+    const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
+    const size_t red_per_tile = (size_t)ks * mt * 64 * 16 + (size_t)16 * 16 * mt * sizeof(float);   // partial sums + carried dh
+    const int ntc = rec_tiles(tile, red_per_tile);
+    size_t lds = ntc * (tile + red_per_tile);
+    if (pipelined && pipe_worker_lds<MODE>() > lds) lds = pipe_worker_lds<MODE>();
+    const int ni = (4 * H / ks) / RecGeom<MODE>::KBLK;
+
+    // ws.dh[l == nl-1 ? 0 : 1 ...]: gradient arriving at layer l's h; dz_of(l): its gate gradients
+    auto dz_of = [&](int l) { return pipelined ? ws.dz[l] : ws.dz[0]; };
+    auto rec_args = [&](int l, const float* dh_above) {
         LayerWs& L = ws.layer[l];
-        fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
         RecBwdArgs ra;
         ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
         ra.gates = L.gates; ra.c = L.c; ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
-        ra.dh_above = ws.dh[cur]; ra.dz = ws.dz; ra.whhT = L.whhT;
-        ra.dh_state = ws.dh_state; ra.dc_state = ws.dc_state;
-        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + REC_GROUPS * REC_MAX_GROUP; ra.err = ws.err;
-        ra.prof = ws.prof + 16;
-        {
-        ProfScope prof(VER_PROF_LSTM_REC_BWD, s);
-        // one wave per (16 units, share of the 4H contraction): 2 tiles x 4 when H/16 > 32 workgroups, else 1 x 8
-        const bool wide = H / 16 > REC_MAX_GROUP;
-        const int mt = wide ? 2 : 1, ks = wide ? 4 : 8;
-        ra.G = H / (16 * mt);
-        const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
-        const size_t red_per_tile = (size_t)ks * mt * 64 * 16 + (size_t)16 * 16 * mt * sizeof(float);   // partial sums + carried dh
-        ra.ntc = rec_tiles(tile, red_per_tile);
-        const size_t lds = ra.ntc * (tile + red_per_tile);
-        const int ni = (4 * H / ks) / RecGeom<MODE>::KBLK;
-        bool ok = true;
-#define VER_BWD_LAUNCH(MT_, KS_, N_) do { ok = set_lds(lstm_rec_bwd_kernel<MODE, MT_, KS_, N_>, lds); \
-            if (ok) hipLaunchKernelGGL((lstm_rec_bwd_kernel<MODE, MT_, KS_, N_>), dim3(REC_GRID), dim3(REC_THREADS), lds, s, ra); } while (0)
-        if (wide) {
-            if (ni == 32) VER_BWD_LAUNCH(2, 4, 32); else VER_BWD_LAUNCH(2, 4, 0);
-        } else {
-            if (ni == 16) VER_BWD_LAUNCH(1, 8, 16);
-            else if (ni == 8) VER_BWD_LAUNCH(1, 8, 8);
-            else if (ni == 4) VER_BWD_LAUNCH(1, 8, 4);
-            else VER_BWD_LAUNCH(1, 8, 0);
-        }
-#undef VER_BWD_LAUNCH
-        if (!ok) return VER_EHIP;
-        }
-
-        const E* dz = static_cast<const E*>(ws.dz);
+        ra.dh_above = dh_above; ra.dz = dz_of(l); ra.whhT = L.whhT;
+        // the two layers of a shared launch carry their state in separate halves of the scratch
+        ra.dh_state = ws.dh_state + (pipelined ? (size_t)l * M * H : 0);
+        ra.dc_state = ws.dc_state + (pipelined ? (size_t)l * M * H : 0);
+        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + REC_GROUPS * REC_MAX_GROUP;
+        ra.err = ws.err; ra.prof = ws.prof + 16;
+        ra.G = H / (16 * mt); ra.ntc = ntc;
+        return ra;
+    };
+    bool ok = true;
+#define VER_BWD_LAUNCH(KERNEL, ARGS, MT_, KS_, N_) do { ok = set_lds(KERNEL<MODE, MT_, KS_, N_>, lds); \
+        if (ok) hipLaunchKernelGGL((KERNEL<MODE, MT_, KS_, N_>), dim3(REC_GRID), dim3(REC_THREADS), lds, s, ARGS); } while (0)
+#define VER_BWD_DISPATCH(KERNEL, ARGS) do { \
+        if (wide) { \
+            if (ni == 32) VER_BWD_LAUNCH(KERNEL, ARGS, 2, 4, 32); else VER_BWD_LAUNCH(KERNEL, ARGS, 2, 4, 0); \
+        } else { \
+            if (ni == 16) VER_BWD_LAUNCH(KERNEL, ARGS, 1, 8, 16); \
+            else if (ni == 8) VER_BWD_LAUNCH(KERNEL, ARGS, 1, 8, 8); \
+            else if (ni == 4) VER_BWD_LAUNCH(KERNEL, ARGS, 1, 8, 4); \
+            else VER_BWD_LAUNCH(KERNEL, ARGS, 1, 8, 0); \
+        } } while (0)
+    // everything of layer l that is not the time loop: dx (optional), dW_ih, dW_hh, db
+    auto layer_grads = [&](int l, float* dx) {
+        const int D = l == 0 ? c.input_dim : H;
+        LayerWs& L = ws.layer[l];
+        const E* dz = static_cast<const E*>(dz_of(l));
         // gradient w.r.t. the layer input: dx[M, D] = dz[M, 4H] . W_ih[4H, D]
-        float* dx = l > 0 ? ws.dh[cur ^ 1] : d_x;
         if (dx) {
             ProfScope prof(VER_PROF_LSTM_GEMM_DX, s);
             gemm_launch<MODE, E, E, false>(dz, 4 * H, static_cast<const E*>(L.wihT), 4 * H, dx, D, M, D, 4 * H,
@@ -437,8 +491,40 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         hipLaunchKernelGGL(colsum_final_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, ws.part, rb_c, 4 * H, H,
                            gw[4 * l + 2], gw[4 * l + 3]);
         }
-        cur ^= 1;
+    };
+
+    if (pipelined) {
+        fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
+        PipeBwdArgs pa;
+        pa.l1 = rec_args(1, ws.dh[0]);
+        pa.l0 = rec_args(0, ws.dh[1]);
+        pipe_link(c, M, H, ws, s, &pa.link);
+        pa.work.A = ws.dz[1]; pa.work.B = ws.layer[1].wihT; pa.work.C = ws.dh[1]; pa.work.bias = nullptr;
+        pa.work.K = 4 * H; pa.work.N = H;
+        pa.work.batch_sizes = batch_sizes; pa.work.t_off = t_off; pa.work.queue = ws.pipe + 8; pa.work.err = ws.err;
+        {
+        ProfScope prof(VER_PROF_LSTM_REC_BWD, s);
+        VER_BWD_DISPATCH(lstm_pipe_bwd_kernel, pa);
+        if (!ok) return VER_EHIP;
+        }
+        layer_grads(1, nullptr);
+        layer_grads(0, d_x);
+    } else {
+        int cur = 0;  // ws.dh[cur] holds the gradient arriving at the current layer's h
+        for (int l = nl - 1; l >= 0; --l) {
+            fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
+            RecBwdArgs ra = rec_args(l, ws.dh[cur]);
+            {
+            ProfScope prof(VER_PROF_LSTM_REC_BWD, s);
+            VER_BWD_DISPATCH(lstm_rec_bwd_kernel, ra);
+            if (!ok) return VER_EHIP;
+            }
+            layer_grads(l, l > 0 ? ws.dh[cur ^ 1] : d_x);
+            cur ^= 1;
+        }
     }
+#undef VER_BWD_DISPATCH
+#undef VER_BWD_LAUNCH
     return launch_status();
 }
 

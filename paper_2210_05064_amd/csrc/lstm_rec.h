@@ -43,7 +43,7 @@ namespace ver {
 // Optional phase timing (build with -DVER_REC_PROF): thread 0 of the rank-0 workgroup adds the core-clock
 // cycles spent in each phase of the time loop to prof[phase]; prof[15] counts timesteps.  Off in the product build.
 #ifdef VER_REC_PROF
-#define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof; const bool prof_on = threadIdx.x == 0 && rank == 0 && grp == 0;
+#define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof; const bool prof_on = threadIdx.x == 0 && rank == 0 && x == 0;
 #define REC_PROF_START() do { if (prof_on) prof_t = clock64(); } while (0)
 #define REC_PROF_MARK(i) do { if (prof_on) { long long now_ = clock64(); prof_out[i] += now_ - prof_t; prof_t = now_; } } while (0)
 #define REC_PROF_STEP() do { if (prof_on) prof_out[15] += 1; } while (0)
@@ -133,8 +133,8 @@ __device__ __forceinline__ int rec_rank(int* tickets, int G, int& grp) {
     grp = s_grp;
     return s_rank;
 }
-// Pieces of group x alive when `bs` pieces are alive in all: n = x, x + REC_GROUPS, ... < bs.
-__device__ __forceinline__ int grp_count(int bs, int x) { return bs > x ? (bs - x + REC_GROUPS - 1) / REC_GROUPS : 0; }
+// Pieces of group x (of X groups) alive when `bs` pieces are alive in all: n = x, x + X, ... < bs.
+__device__ __forceinline__ int grp_count(int bs, int x, int X) { return bs > x ? (bs - x + X - 1) / X : 0; }
 // Timesteps at which group x has an alive piece: batch sizes never grow, so that is how many exceed x.
 __device__ __forceinline__ int grp_steps(const int32_t* batch_sizes, int T, int x) {
     __shared__ int s_T;
@@ -308,6 +308,71 @@ __device__ __forceinline__ void mma_dispatch(const f32x4_t (&wreg)[NW], const ty
     else mma_tiles<MODE, NI, 4, NW>(wreg, brow, stride, ni_rt, blast, acc);
 }
 
+// ---- two layers in one launch ---------------------------------------------------------------------------
+// With two layers, both time loops run in the same launch on different XCDs: the groups of the first
+// ("producer") layer in time order publish how far they are; workgroups on the remaining XCDs ("workers")
+// turn each finished chunk of PIPE_CT timesteps into the second layer's input (a GEMM tile at a time,
+// gemm_pipe.h); the groups of the second ("consumer") layer wait for the chunk that holds their next timestep.
+// Everything that crosses XCDs is written through to memory (the L2s of different XCDs are not coherent),
+// completed (s_waitcnt) before it is announced, and announced/read with agent-scope atomics.
+constexpr int PIPE_CT = 8;           // timesteps per chunk
+constexpr int PIPE_BM = 128;         // rows per GEMM tile
+constexpr int PIPE_BN = 256;         // columns per GEMM tile
+enum { PIPE_NONE = 0, PIPE_PRODUCER = 1, PIPE_CONSUMER = 2 };
+struct PipeLink {
+    int* progress;   // [producer groups] timesteps whose rows are complete in memory
+    int* done;       // [chunks] GEMM tiles finished per chunk
+    int tiles_n;     // column tiles per row tile of the GEMM
+    int T_all;       // timesteps of the minibatch
+    int M;           // rows of the minibatch
+};
+// Rows of the chunk of timesteps [c*PIPE_CT, (c+1)*PIPE_CT) and the GEMM tiles that cover them.
+__device__ __forceinline__ int pipe_chunk_row0(const int32_t* t_off, int c) { return t_off[c * PIPE_CT]; }
+__device__ __forceinline__ int pipe_chunk_rows(const int32_t* t_off, int T_all, int c) {
+    const int t1 = min((c + 1) * PIPE_CT, T_all);
+    return t_off[t1] - t_off[c * PIPE_CT];
+}
+__device__ __forceinline__ int pipe_chunk_tiles(const int32_t* t_off, const PipeLink& pl, int c) {
+    return (pipe_chunk_rows(t_off, pl.T_all, c) + PIPE_BM - 1) / PIPE_BM * pl.tiles_n;
+}
+// Consumer: blocks until the workers have finished chunk c.  False if the wait was abandoned.
+__device__ __forceinline__ bool pipe_wait_chunk(const int32_t* t_off, const PipeLink& pl, int c, int* err) {
+    __shared__ int s_ok2;
+    if (threadIdx.x == 0) {
+        const int need = pipe_chunk_tiles(t_off, pl, c);
+        long long spins = 0;
+        bool alive = true;
+        while (ld_agent(&pl.done[c]) < need) {
+            ++spins;
+            if ((spins & 255) == 0 && (spins > REC_SPIN_LIMIT || ld_agent(err) != 0)) {
+                st_agent(err, 1);
+                alive = false;
+                break;
+            }
+        }
+        s_ok2 = alive ? 1 : 0;
+    }
+    bar_lds();
+    return s_ok2 != 0;
+}
+// Stores that are written through to memory (visible to the other XCDs once complete).  rs: buffer resource
+// (wave-uniform) of the rows of one timestep; off: this lane's byte offset in it.
+__device__ __forceinline__ void st_through(__amdgpu_buffer_rsrc_t rs, int off, float v) {
+    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, off, 0, 17);
+}
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+template <typename E> __device__ __forceinline__ void st_row4_through(__amdgpu_buffer_rsrc_t rs, int off, float a, float b, float c, float d);
+template <> __device__ __forceinline__ void st_row4_through<bf16_t>(__amdgpu_buffer_rsrc_t rs, int off, float a, float b, float c, float d) {
+    u32x2_t v;
+    v.x = (unsigned)to_bf16_finite(a) | ((unsigned)to_bf16_finite(b) << 16);
+    v.y = (unsigned)to_bf16_finite(c) | ((unsigned)to_bf16_finite(d) << 16);
+    __builtin_amdgcn_raw_buffer_store_b64(v, rs, off, 0, 17);
+}
+template <> __device__ __forceinline__ void st_row4_through<float>(__amdgpu_buffer_rsrc_t rs, int off, float a, float b, float c, float d) {
+    u32x4_t v = {__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
+    __builtin_amdgcn_raw_buffer_store_b128(v, rs, off, 0, 17);
+}
+
 // ---- the product of one timestep (forward kernel) ---------------------------------------------------------
 // A wave holds TPW 16-row tiles of the weight matrix over its share of the contraction, NBW 16-byte operand
 // blocks per tile (wreg[tile * NBW + block]).  For one tile of 16 pieces it reads the matching blocks of the
@@ -386,20 +451,16 @@ struct RecFwdArgs {
 // rows over 1/KS of the contraction; the workgroup owns MT = RG*TPW tiles = 4*MT hidden units.  In the
 // epilogue wave w adds the KS partial sums of tile w and updates the cells of its 4 units.
 // NBW: capacity in operand blocks per tile and wave; STATIC: exactly NBW blocks (straight-line code).
-template <int MODE, int TPW, int KS, int NBW, bool STATIC>
-__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_rec_fwd_kernel(RecFwdArgs a) {
+// rank: this workgroup's rank in its group; the group runs the pieces n = m * X + x, m = 0, 1, ...; flags: the
+// group's flag words.  PIPE: alone, or producer / consumer of a two-layer launch (pl).
+template <int MODE, int TPW, int KS, int NBW, bool STATIC, int PIPE>
+__device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int x, int X, int* flags, const PipeLink& pl,
+                                             unsigned char* smem) {
     typedef typename RecGeom<MODE>::E E;
     constexpr int PAD = RecGeom<MODE>::PAD, KBLK = RecGeom<MODE>::KBLK, VEC = RecGeom<MODE>::VEC;
     constexpr int RG = REC_WAVES / KS, MT = RG * TPW, UH = 4 * MT, ROWS = 16 * MT;
     static_assert(RG * KS == REC_WAVES && MT <= REC_WAVES, "wave roles");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int G = a.G;
-    int grp;
-    const int rank = rec_rank(a.ticket, G, grp);
-    if (rank < 0) return;
-    constexpr int X = REC_GROUPS;
-    const int x = grp;                       // this group's pieces: n = m * X + x, m = 0, 1, ...
-    int* flags = a.flags + x * REC_MAX_GROUP;
 
     const int H = a.H, stride = H + PAD, ntc = a.ntc;
     E* sB = reinterpret_cast<E*>(smem);                                                        // staged h rows
@@ -409,7 +470,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     const int rg = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
     const int j0 = rank * UH;
-    const int n_seq = grp_count(a.info[0], x), T = grp_steps(a.batch_sizes, a.info[1], x);
+    const int n_seq = grp_count(a.info[0], x, X), T = grp_steps(a.batch_sizes, a.info[1], x);
     E* hprev = static_cast<E*>(a.hprev);
     const int k_lo = ((ks + rank) % KS) * (H / KS);   // which share a wave takes rotates with the rank, too
     const int nb = (H / KS) / KBLK;
@@ -447,8 +508,9 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         creg[q] = 0.f;
         zpre[q] = znext[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
+    if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(a.t_off, pl, 0, a.err)) return;
     if (has_tile && T > 0) {
-        const int bs0 = grp_count(a.batch_sizes[0], x);
+        const int bs0 = grp_count(a.batch_sizes[0], x, X);
 #pragma unroll
         for (int q = 0; q < REC_PRE; ++q)
             if (q * 16 + lr < bs0)
@@ -457,10 +519,15 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
 
     for (int t = 0; t < T; ++t) {
         // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
-        const int bs_all = a.batch_sizes[t], bs = grp_count(bs_all, x), base = a.t_off[t];
-        const int bs_next = (t + 1 < T) ? grp_count(a.batch_sizes[t + 1], x) : 0, base_next = base + bs_all;
+        const int bs_all = a.batch_sizes[t], bs = grp_count(bs_all, x, X), base = a.t_off[t];
+        const int bs_next = (t + 1 < T) ? grp_count(a.batch_sizes[t + 1], x, X) : 0, base_next = base + bs_all;
         const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
+        if (PIPE == PIPE_CONSUMER && t + 1 < T && (t + 1) % PIPE_CT == 0 &&
+            !pipe_wait_chunk(a.t_off, pl, (t + 1) / PIPE_CT, a.err)) return;
+        __amdgpu_buffer_rsrc_t rs_hout = __builtin_amdgcn_make_buffer_rsrc(a.hout + (size_t)base * H, 0, bs_all * H * 4, 0x00020000);
         if (!rec_wait(flags, G, t + 1, a.err)) return;
+        // every workgroup of the group has raised its flag for timestep t-1, i.e. completed that step's stores
+        if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0 && t > 0) st_agent(&pl.progress[x], t);
         REC_PROF_MARK(0);
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc), nt = (rows + 15) >> 4;
@@ -522,7 +589,8 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
                         hn = go * tanhf_(cn);
                         *gp = f32x4_t{gi, gf, gg, go};
                         a.c[p * H + je] = cn;
-                        a.hout[p * H + je] = hn;
+                        if (PIPE == PIPE_PRODUCER) st_through(rs_hout, (n * H + je) * 4, hn);   // read by the workers on other XCDs
+                        else a.hout[p * H + je] = hn;
                     }
                     // h_t goes to the exchange row of the next timestep through LDS (below)
                     sH[(q * 16 + lr) * UH + wave * 4 + lk] = cvt_finite<E>(hn);
@@ -544,12 +612,26 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
             }
         }
         REC_PROF_MARK(3);
-        if (t + 1 < T) rec_publish(flags, rank, t + 2);
+        if (t + 1 < T || PIPE == PIPE_PRODUCER) rec_publish(flags, rank, t + 2);
 #pragma unroll
         for (int q = 0; q < REC_PRE; ++q) zpre[q] = znext[q];
         REC_PROF_MARK(4);
         REC_PROF_STEP();
     }
+    if (PIPE == PIPE_PRODUCER && rank == 0) {   // the last timestep is complete once every flag says so
+        if (T > 0 && !rec_wait(flags, G, T + 1, a.err)) return;
+        if (tid == 0) st_agent(&pl.progress[x], T);
+    }
+}
+
+template <int MODE, int TPW, int KS, int NBW, bool STATIC>
+__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_rec_fwd_kernel(RecFwdArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int grp;
+    const int rank = rec_rank(a.ticket, a.G, grp);
+    if (rank < 0) return;
+    PipeLink none = {};
+    rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_NONE>(a, rank, grp, REC_GROUPS, a.flags + grp * REC_MAX_GROUP, none, smem);
 }
 
 // ======================================================================================================
@@ -591,22 +673,16 @@ __device__ __forceinline__ BwdSaved load_saved(const RecBwdArgs& a, int t, int b
 }
 
 // MT 16-unit tiles per workgroup, KS waves per tile split the contraction over the 4H gate rows.
-template <int MODE, int MT, int KS, int NI>
-__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_rec_bwd_kernel(RecBwdArgs a) {
+template <int MODE, int MT, int KS, int NI, int PIPE>
+__device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int x, int X, int* flags, const PipeLink& pl,
+                                             unsigned char* smem) {
     static_assert(MT * KS == REC_WAVES, "one wave per (tile, k-split)");
     static_assert(MT * REC_NTC <= REC_WAVES, "one wave per tile sum");
     typedef typename RecGeom<MODE>::E E;
     constexpr int PAD = RecGeom<MODE>::PAD, KBLK = RecGeom<MODE>::KBLK, VEC = RecGeom<MODE>::VEC;
     constexpr int UH = 16 * MT;
     constexpr int NW = NI > 0 ? NI : REC_NI;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int G = a.G;
-    int grp;
-    const int rank = rec_rank(a.ticket, G, grp);
-    if (rank < 0) return;
-    constexpr int X = REC_GROUPS;
-    const int x = grp;                       // this group's pieces: n = m * X + x, m = 0, 1, ...
-    int* flags = a.flags + x * REC_MAX_GROUP;
 
     const int H = a.H, K = 4 * H, stride = K + PAD, ntc = a.ntc;
     E* sB = reinterpret_cast<E*>(smem);                                                        // staged dz rows
@@ -632,8 +708,9 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     pre.g4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
     pre.c = pre.c_prev = pre.dh_above = 0.f;
     float dcreg = 0.f;   // cell-state gradient of that (piece, unit), carried from timestep to timestep
+    if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(a.t_off, pl, (T - 1) / PIPE_CT, a.err)) return;
     if (T > 0) {
-        const int bs_l = grp_count(a.batch_sizes[T - 1], x), base_l = a.t_off[T - 1];
+        const int bs_l = grp_count(a.batch_sizes[T - 1], x, X), base_l = a.t_off[T - 1];
         if (tid < bs_l * UH)
             pre = load_saved(a, T - 1, base_l, (T > 1) ? a.t_off[T - 2] : 0, (tid / UH) * X + x, j0 + (tid % UH), H);
     }
@@ -641,9 +718,11 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     REC_PROF_START();
     for (int t = T - 1; t >= 0; --t) {
         // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
-        const int bs = grp_count(a.batch_sizes[t], x), base = a.t_off[t];
-        const int bs_next = (t + 1 < T) ? grp_count(a.batch_sizes[t + 1], x) : 0;
+        const int bs = grp_count(a.batch_sizes[t], x, X), base = a.t_off[t];
+        const int bs_next = (t + 1 < T) ? grp_count(a.batch_sizes[t + 1], x, X) : 0;
         const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
+        __amdgpu_buffer_rsrc_t rs_dz = __builtin_amdgcn_make_buffer_rsrc(dzw + (size_t)base * K, 0,
+                                                                         a.batch_sizes[t] * K * (int)sizeof(E), 0x00020000);
         // A. gate gradients of this workgroup's units for every alive piece
         for (int i = tid; i < bs * UH; i += REC_THREADS) {
             const int m = i / UH, n = m * X + x, j = j0 + (i % UH);
@@ -660,16 +739,24 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
             }
             const float tc = tanhf_(sv.c);
             dc += dh * go * (1.f - tc * tc);
-            st_row4<E>(dzw + p * K + (size_t)j * 4, dc * gg * gi * (1.f - gi), dc * sv.c_prev * gf * (1.f - gf),
-                       dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
+            if (PIPE == PIPE_PRODUCER)   // also read by the workers on other XCDs
+                st_row4_through<E>(rs_dz, (n * K + j * 4) * (int)sizeof(E), dc * gg * gi * (1.f - gi), dc * sv.c_prev * gf * (1.f - gf),
+                                   dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
+            else
+                st_row4<E>(dzw + p * K + (size_t)j * 4, dc * gg * gi * (1.f - gi), dc * sv.c_prev * gf * (1.f - gf),
+                           dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
             if (first) dcreg = dc * gf;
             else a.dc_state[(size_t)n * H + j] = dc * gf;
         }
-        if (t == 0) break;  // nothing is carried before the first timestep
+        if (t == 0 && PIPE != PIPE_PRODUCER) break;  // nothing is carried before the first timestep
         REC_PROF_MARK(8);
         rec_publish(flags, rank, T - t);
         REC_PROF_MARK(9);
+        if (t == 0 && rank != 0) break;
         if (!rec_wait(flags, G, T - t, a.err)) return;
+        // every workgroup of the group has completed the dz rows of timesteps >= t
+        if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0) st_agent(&pl.progress[x], T - t);
+        if (t == 0) break;
         REC_PROF_MARK(10);
         // B. dh carried to t-1: dh[n][k] = sum_q dz[n][q] * W_hh[q][k] for this workgroup's columns k
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
@@ -679,10 +766,12 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             bar_lds();
             REC_PROF_MARK(11);
+            if (PIPE == PIPE_CONSUMER && c0 == 0 && t % PIPE_CT == 0 && !pipe_wait_chunk(a.t_off, pl, (t - 1) / PIPE_CT, a.err))
+                return;
             if (c0 == 0) {
                 // saved activations of this thread's first item of timestep t-1, issued once the exchanged rows
                 // have arrived (see the forward kernel): in flight during the MFMA phase
-                const int bs_p = grp_count(a.batch_sizes[t - 1], x), base_p = a.t_off[t - 1];
+                const int bs_p = grp_count(a.batch_sizes[t - 1], x, X), base_p = a.t_off[t - 1];
                 if (tid < bs_p * UH)
                     pre = load_saved(a, t - 1, base_p, (t > 1) ? a.t_off[t - 2] : 0, (tid / UH) * X + x, j0 + (tid % UH), H);
             }
@@ -716,6 +805,16 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         REC_PROF_MARK(12);
         REC_PROF_STEP();
     }
+}
+
+template <int MODE, int MT, int KS, int NI>
+__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_rec_bwd_kernel(RecBwdArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    int grp;
+    const int rank = rec_rank(a.ticket, a.G, grp);
+    if (rank < 0) return;
+    PipeLink none = {};
+    rec_bwd_body<MODE, MT, KS, NI, PIPE_NONE>(a, rank, grp, REC_GROUPS, a.flags + grp * REC_MAX_GROUP, none, smem);
 }
 
 }  // namespace ver
