@@ -201,6 +201,14 @@ int ver_pack_minibatch(const ver_pack_args* args /* host */, void* stream);
  * workspace word 0 (int32) is non-zero after the stream has drained if a
  * device-side wait timed out (should never happen; results are then
  * undefined).  Outputs are deterministic.
+ *
+ * The time loops run as persistent kernels that need the whole GPU (one
+ * workgroup on every CU at the same time, cooperating per XCD): kernels of
+ * other streams or processes that hold CUs for long can make their bounded
+ * waits time out.  Networks of two layers run both layers' time loops in one
+ * launch; the environment variable VER_LSTM_SEQUENTIAL=1 (read at every call)
+ * makes them run layer by layer like any other depth - a diagnostic switch,
+ * results agree up to the order of fp32 additions.
  */
 typedef struct {
     int32_t n_layers;

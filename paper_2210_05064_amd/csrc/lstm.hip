@@ -11,6 +11,8 @@
 //       (forward), dz_t and W_hh dz_t (backward) - see lstm_rec.h.
 // Internally the 4H gate rows are interleaved (row = unit*4 + gate); user-facing
 // weights and gradients keep the gate-major order i,f,g,o of the declaration.
+#include <cstdlib>
+
 #include "lstm_pipe.h"
 
 namespace ver {
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------- workspace
-constexpr int REC_FLAG_WORDS = REC_GROUPS * REC_MAX_GROUP + 64;   // flags[group][32], then one ticket per group
+constexpr int REC_FLAG_WORDS = 8 * REC_MAX_GROUP + 64;   // flags[group][32], then one ticket per group
 
 struct LayerWs {
     void* wih;    // [4H, D_l]  operand type, interleaved rows
@@ -162,11 +164,12 @@ struct LayerWs {
     float* c;     // [M, H]
     float* hout;  // [M, H]
     void* hprev;  // [M, H] operand type
+    void* hcopy;  // [M, H] operand type: h_t, for the workers of a two-layer launch
 };
 struct LstmWs {
     int* err;          // word 0 of the workspace
     int* flags;        // [REC_FLAG_WORDS]: per-workgroup flags of a recurrent launch, then its ticket counters
-    long long* prof;   // [32] phase counters of the recurrent kernels (forward 0..15, backward 16..31)
+    long long* prof;   // [64] phase counters of the recurrent kernels (forward 0..15, backward 16..31; +32: consumer layer)
     LayerWs layer[8];
     void* dz[2];       // [M, 4H] operand type; the second one only when two layers share a launch
     int* pipe;         // hand-over words of a two-layer launch: progress[8], queue at [8], done[] from [16]
@@ -211,7 +214,7 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     int* head = cv.take<int>(64);
     ws->err = head;
     ws->flags = cv.take<int>(REC_FLAG_WORDS);
-    ws->prof = cv.take<long long>(32);
+    ws->prof = cv.take<long long>(80);
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws->layer[l];
@@ -224,6 +227,7 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
         L.c = cv.take<float>(Mz * H);
         L.hout = cv.take<float>(Mz * H);
         L.hprev = cv.take<char>(Mz * H * es);
+        L.hcopy = (c.n_layers == 2 && l == 0) ? cv.take<char>(Mz * H * es) : nullptr;
     }
     ws->dz[0] = cv.take<char>(Mz * 4 * H * es);
     ws->dz[1] = c.n_layers == 2 ? cv.take<char>(Mz * 4 * H * es) : ws->dz[0];
@@ -262,9 +266,17 @@ inline bool set_lds(K kernel, size_t bytes) {
                                (int)bytes) == hipSuccess;
 }
 
+// Diagnostic switch: with VER_LSTM_SEQUENTIAL=1 in the environment two-layer networks run one launch per layer,
+// like any other depth (used by the tests to check both paths against each other and by timing comparisons).
+inline bool sequential_layers() {
+    const char* v = getenv("VER_LSTM_SEQUENTIAL");
+    return v && v[0] == '1';
+}
+
 // LDS of a worker of a two-layer launch: one 128 x BK and one 256 x BK operand tile.
 template <int MODE>
 inline size_t pipe_worker_lds() {
+    if (MODE == MODE_BF16) return (size_t)PIPE_STAGES * PIPE_STAGE_BYTES;
     return (size_t)(PIPE_BM + PIPE_BN) * GemmGeom<MODE>::LDS_STRIDE * sizeof(typename LdsElem<MODE>::type);
 }
 inline void pipe_link(const ver_lstm_cfg& c, int M, int N, LstmWs& ws, hipStream_t s, PipeLink* pl) {
@@ -283,7 +295,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
             float* head_out, float* value, LstmWs& ws, hipStream_t s) {
     typedef typename RecGeom<MODE>::E E;
     const int H = c.hidden, A = c.act_dim;
-    const bool pipelined = c.n_layers == 2;   // both time loops in one launch
+    const bool pipelined = c.n_layers == 2 && !sequential_layers();   // both time loops in one launch
     fill_words(ws.err, 1, 0, s);
 
     // 8 waves = row groups x shares of the contraction (TPW tiles of 16 gate rows per wave): a workgroup owns
@@ -330,11 +342,11 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         LayerWs& L = ws.layer[l];
         RecFwdArgs ra;
         ra.info = info; ra.batch_sizes = batch_sizes; ra.t_off = t_off;
-        ra.gates = L.gates; ra.c = L.c; ra.hout = L.hout; ra.hprev = L.hprev; ra.whh = L.whh;
+        ra.gates = L.gates; ra.c = L.c; ra.hout = L.hout; ra.hprev = L.hprev; ra.hcopy = L.hcopy; ra.whh = L.whh;
         ra.h0 = h0 ? h0 + (size_t)l * seq_cap * H : nullptr;
         ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
-        ra.H = H; ra.seq_cap = seq_cap; ra.M = M; ra.flags = ws.flags; ra.ticket = ws.flags + REC_GROUPS * REC_MAX_GROUP;
-        ra.err = ws.err; ra.prof = ws.prof;
+        ra.H = H; ra.seq_cap = seq_cap; ra.M = M; ra.flags = ws.flags; ra.ticket = ws.flags + 8 * REC_MAX_GROUP;
+        ra.err = ws.err; ra.prof = ws.prof + (pipelined && l == 1 ? 32 : 0);
         ra.G = H / (4 * mt); ra.ntc = ntc;
         return ra;
     };
@@ -366,7 +378,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         pa.l0 = rec_args(0);
         pa.l1 = rec_args(1);
         pipe_link(c, M, 4 * H, ws, s, &pa.link);
-        pa.work.A = ws.layer[0].hout; pa.work.B = ws.layer[1].wih; pa.work.C = ws.layer[1].gates;
+        pa.work.A = ws.layer[0].hcopy; pa.work.B = ws.layer[1].wih; pa.work.C = ws.layer[1].gates;
         pa.work.bias = ws.layer[1].bias; pa.work.K = H; pa.work.N = 4 * H;
         pa.work.batch_sizes = batch_sizes; pa.work.t_off = t_off; pa.work.queue = ws.pipe + 8; pa.work.err = ws.err;
         ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
@@ -420,7 +432,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     }
 
     // one wave per (16 units, share of the 4H contraction): 2 tiles x 4 when H/16 > 32 workgroups, else 1 x 8
-    const bool pipelined = nl == 2;   // both time loops in one launch
+    const bool pipelined = nl == 2 && !sequential_layers();   // both time loops in one launch
     const bool wide = H / 16 > REC_MAX_GROUP;
     const int mt = wide ? 2 : 1, ks = wide ? 4 : 8;
     const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
@@ -441,8 +453,8 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         // the two layers of a shared launch carry their state in separate halves of the scratch
         ra.dh_state = ws.dh_state + (pipelined ? (size_t)l * M * H : 0);
         ra.dc_state = ws.dc_state + (pipelined ? (size_t)l * M * H : 0);
-        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + REC_GROUPS * REC_MAX_GROUP;
-        ra.err = ws.err; ra.prof = ws.prof + 16;
+        ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + 8 * REC_MAX_GROUP;
+        ra.err = ws.err; ra.prof = ws.prof + 16 + (pipelined && l == 0 ? 32 : 0);
         ra.G = H / (16 * mt); ra.ntc = ntc;
         return ra;
     };

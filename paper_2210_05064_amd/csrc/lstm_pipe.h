@@ -23,9 +23,10 @@
 namespace ver {
 
 constexpr int PIPE_GROUPS = 3;       // groups (XCDs) per layer
+constexpr int PIPE_XCDS = 8;         // XCDs of the chip: those beyond the two layers' groups are workers
 
 struct PipeWork {
-    const void* A;      // producer rows [M, K]: fp32 (forward: h) or operand type (backward: dz)
+    const void* A;      // producer rows [M, K], operand type (forward: h, backward: dz)
     const void* B;      // [N, K] operand type, K contiguous
     float* C;           // [M, N]
     const float* bias;  // [N] or NULL
@@ -40,11 +41,6 @@ template <typename E, typename T> __device__ __forceinline__ Quad<E> load_quad_c
 template <> __device__ __forceinline__ Quad<float> load_quad_coh<float, float>(__amdgpu_buffer_rsrc_t r, int byte_off) {
     const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 17);
     return Quad<float>{{__uint_as_float(t[0]), __uint_as_float(t[1]), __uint_as_float(t[2]), __uint_as_float(t[3])}};
-}
-template <> __device__ __forceinline__ Quad<bf16_t> load_quad_coh<bf16_t, float>(__amdgpu_buffer_rsrc_t r, int byte_off) {
-    const u32x4_t t = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 17);
-    return Quad<bf16_t>{{to_bf16(__uint_as_float(t[0])), to_bf16(__uint_as_float(t[1])), to_bf16(__uint_as_float(t[2])),
-                         to_bf16(__uint_as_float(t[3]))}};
 }
 template <> __device__ __forceinline__ Quad<bf16_t> load_quad_coh<bf16_t, bf16_t>(__amdgpu_buffer_rsrc_t r, int byte_off) {
     const u32x2_t t = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, 17);
@@ -149,10 +145,107 @@ __device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, int row0, int 
         }
 }
 
+// The same tile for bf16 operands on both sides, built for a workgroup that has the CU to itself: K-tiles of
+// 64 go from global memory straight into LDS (three stages, two K-tiles in flight while one is multiplied,
+// one barrier per K-tile, no registers or LDS stores in between).  An LDS row is the 128 bytes of a tile row,
+// as 8 chunks of 16 bytes; chunk position p of row r holds chunk p ^ ((r >> 1) & 7), which makes the 16-byte
+// MFMA operand reads of 16 consecutive rows hit all banks once.  A load instruction fills 8 rows (lane -> row
+// lane / 8, position lane % 8), so the swizzle is applied on the global side.
+constexpr int PIPE_STAGES = 3;
+constexpr int PIPE_STAGE_BYTES = (PIPE_BM + PIPE_BN) * 128;
+__device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, int row_end, int col0, unsigned char* smem) {
+    constexpr int BK = 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = (wave >> 2) * 64, wn = (wave & 3) * 64;
+    const int lr = lane & 15, lk = lane >> 4;
+    const int K = w.K, N = w.N, nk = K / BK;
+    const int ncols = min(N - col0, PIPE_BN);
+    __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(static_cast<const bf16_t*>(w.A)) + (size_t)row0 * K, 0, (row_end - row0) * K * 2, 0x00020000);
+    __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(static_cast<const bf16_t*>(w.B)) + (size_t)col0 * K, 0, ncols * K * 2, 0x00020000);
+    // source offsets of this lane in the 2 (A) + 4 (B) load instructions of this wave per K-tile
+    int voffA[2], voffB[4];
+    const int row_in = lane >> 3, pos = lane & 7;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row = (wave * 2 + j) * 8 + row_in;
+        voffA[j] = row * K * 2 + ((pos ^ ((row >> 1) & 7)) << 4);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int row = (wave * 4 + j) * 8 + row_in;
+        voffB[j] = row * K * 2 + ((pos ^ ((row >> 1) & 7)) << 4);
+    }
+    auto issue = [&](int kt) {
+        unsigned char* st = smem + (kt % PIPE_STAGES) * PIPE_STAGE_BYTES;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)   // producer rows: written by other XCDs during this launch
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)(st + (wave * 2 + j) * 1024), 16, voffA[j], kt * BK * 2, 0, 17);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr_t)(st + PIPE_BM * 128 + (wave * 4 + j) * 1024), 16, voffB[j],
+                                                     kt * BK * 2, 0, 0);
+    };
+    // operand read offsets: row byte offset and swizzle of this lane's row in each 16-row tile
+    int arow[4], asw[4], brow[4], bsw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int ra_ = wm + i * 16 + lr, rb_ = wn + i * 16 + lr;
+        arow[i] = ra_ * 128; asw[i] = (ra_ >> 1) & 7;
+        brow[i] = PIPE_BM * 128 + rb_ * 128; bsw[i] = (rb_ >> 1) & 7;
+    }
+    f32x4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    issue(0);
+    if (nk > 1) issue(1);
+    for (int kt = 0; kt < nk; ++kt) {
+        // this wave's loads of stage kt have landed (the 6 of stage kt+1 may still be in flight) ...
+        if (kt + 1 < nk) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        bar_lds();   // ... and so have everyone's; everyone has also finished reading stage kt-1
+        if (kt + 2 < nk) issue(kt + 2);   // into the stage that was read in iteration kt-1
+        const unsigned char* st = smem + (kt % PIPE_STAGES) * PIPE_STAGE_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            u16x8_t a[4], b[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                a[i] = *reinterpret_cast<const u16x8_t*>(st + arow[i] + (((ks * 4 + lk) ^ asw[i]) << 4));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                b[j] = *reinterpret_cast<const u16x8_t*>(st + brow[j] + (((ks * 4 + lk) ^ bsw[j]) << 4));
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16_16x16x32(a[i], b[j], acc[i][j]);
+        }
+    }
+    // C fragment: element e of lane l is row (l / 16) * 4 + e, column l % 16 of the 16x16 tile; written through
+    __amdgpu_buffer_rsrc_t rsC = __builtin_amdgcn_make_buffer_rsrc(w.C + (size_t)row0 * N, 0, (row_end - row0) * N * 4, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = col0 + wn + j * 16 + lr;
+            if (n >= N) continue;
+            const float bv = w.bias ? w.bias[n] : 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int lrow = wm + i * 16 + lk * 4 + e;   // rows past the end of the chunk are dropped (buffer bounds)
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][e] + bv), rsC, (lrow * N + n) * 4, 0, 17);
+            }
+        }
+}
+
 // Worker loop.  Items are the tiles of all chunks in the order the consumer needs the chunks (DESCEND: last
 // chunk first); item -> (chunk, row tile, column tile) is found by walking the chunks, which a worker only ever
 // does forwards because the queue hands out increasing items.
-template <int MODE, typename TA, bool DESCEND>
+template <int MODE, bool DESCEND>
 __device__ __forceinline__ void pipe_worker(const PipeWork& w, const PipeLink& pl, unsigned char* smem) {
     __shared__ int s_item[4];    // chunk, local tile, ok
     __shared__ int s_Tg[PIPE_GROUPS];
@@ -199,20 +292,24 @@ __device__ __forceinline__ void pipe_worker(const PipeWork& w, const PipeLink& p
         if (!ok) return;
         const int row0 = pipe_chunk_row0(w.t_off, c), rows = pipe_chunk_rows(w.t_off, T_all, c);
         const int rt = local / pl.tiles_n, ct = local % pl.tiles_n;
-        pipe_gemm_tile<MODE, TA>(w, row0 + rt * PIPE_BM, min(row0 + rows, row0 + (rt + 1) * PIPE_BM), ct * PIPE_BN, smem);
+        if constexpr (MODE == MODE_BF16)
+            pipe_gemm_tile_dma(w, row0 + rt * PIPE_BM, min(row0 + rows, row0 + (rt + 1) * PIPE_BM), ct * PIPE_BN, smem);
+        else
+            pipe_gemm_tile<MODE, typename LdsElem<MODE>::type>(w, row0 + rt * PIPE_BM, min(row0 + rows, row0 + (rt + 1) * PIPE_BM),
+                                                                ct * PIPE_BN, smem);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         bar_lds();
         if (threadIdx.x == 0) __hip_atomic_fetch_add(&pl.done[c], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
-// This workgroup's XCD and its ticket there (tickets[REC_GROUPS], zero at launch).
+// This workgroup's XCD and its ticket there (tickets[PIPE_XCDS], zero at launch).
 __device__ __forceinline__ int xcc_ticket(int* tickets, int& xcc) {
     __shared__ int s_t, s_x;
     if (threadIdx.x == 0) {
         const int id = __builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf;   // HW_REG_XCC_ID, 4 bits
         s_x = id;
-        s_t = id < REC_GROUPS ? __hip_atomic_fetch_add(&tickets[id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : REC_MAX_GROUP;
+        s_t = id < PIPE_XCDS ? __hip_atomic_fetch_add(&tickets[id], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : REC_MAX_GROUP;
     }
     __syncthreads();
     xcc = s_x;
@@ -231,6 +328,11 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     const int rank = xcc_ticket(p.l0.ticket, xcc);
     PipeLink link = p.link;
     link.T_all = p.l0.info[1];
+#ifdef VER_REC_PROF
+    const bool stamp = threadIdx.x == 0 && rank == 0 && (xcc == 0 || xcc == PIPE_GROUPS || xcc == 2 * PIPE_GROUPS);
+    long long* tl = p.l0.prof + 64 + (xcc == 0 ? 0 : (xcc == PIPE_GROUPS ? 2 : 4));
+    if (stamp) tl[0] = wall_clock64();
+#endif
     if (xcc < PIPE_GROUPS) {
         if (rank < p.l0.G)
             rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_PRODUCER>(p.l0, rank, xcc, PIPE_GROUPS, p.l0.flags + xcc * REC_MAX_GROUP,
@@ -239,9 +341,12 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         if (rank < p.l1.G)
             rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_CONSUMER>(p.l1, rank, xcc - PIPE_GROUPS, PIPE_GROUPS,
                                                                     p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
-    } else if (xcc < REC_GROUPS) {
-        pipe_worker<MODE, float, false>(p.work, link, smem);
+    } else if (xcc < PIPE_XCDS) {
+        pipe_worker<MODE, false>(p.work, link, smem);
     }
+#ifdef VER_REC_PROF
+    if (stamp) tl[1] = wall_clock64();
+#endif
 }
 
 struct PipeBwdArgs {
@@ -264,8 +369,8 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         if (rank < p.l0.G)
             rec_bwd_body<MODE, MT, KS, NI, PIPE_CONSUMER>(p.l0, rank, xcc - PIPE_GROUPS, PIPE_GROUPS,
                                                           p.l0.flags + xcc * REC_MAX_GROUP, link, smem);
-    } else if (xcc < REC_GROUPS) {
-        pipe_worker<MODE, E, true>(p.work, link, smem);
+    } else if (xcc < PIPE_XCDS) {
+        pipe_worker<MODE, true>(p.work, link, smem);
     }
 }
 

@@ -58,7 +58,10 @@ constexpr int REC_THREADS = 512;          // 8 waves, two per SIMD: 256 register
 constexpr int REC_WAVES = REC_THREADS / VER_WAVE;
 constexpr int REC_GRID = 256;             // one workgroup per CU: 32 per XCD, each XCD one group
 constexpr int REC_MAX_GROUP = 32;         // CUs of one XCD
-constexpr int REC_GROUPS = 8;             // XCDs: the workgroups of XCD x run the pieces n = x, x+8, x+16, ...
+#ifndef VER_REC_GROUPS
+#define VER_REC_GROUPS 8
+#endif
+constexpr int REC_GROUPS = VER_REC_GROUPS;   // XCDs in use: the workgroups of XCD x run the pieces n = x, x+8, x+16, ...
 constexpr long long REC_SPIN_LIMIT = 1LL << 21;
 constexpr int REC_NTC = 4;                // at most this many 16-piece tiles are staged and multiplied at once
 constexpr int REC_NI = 32;                // at most this many 16-byte operand blocks of W per lane (128 registers)
@@ -154,25 +157,28 @@ __device__ __forceinline__ int ld_l2(const int* p) { return *reinterpret_cast<co
 
 // All G participants have published a value >= target.  Returns false if the wait was abandoned (time-out
 // here or in another workgroup): the caller must leave the kernel.
-__device__ __forceinline__ bool rec_wait(const int* flags, int G, int target, int* err) {
+// poll_wave: the wave that polls.  A volatile load waits for everything the wave has in flight, so a caller
+// that leaves stores in flight across the wait names a wave that rarely has any.
+__device__ __forceinline__ bool rec_wait(const int* flags, int G, int target, int* err, int poll_wave = 0) {
     __shared__ int s_ok;
-    if (threadIdx.x < VER_WAVE) {
+    if ((int)(threadIdx.x >> 6) == poll_wave) {
+        const int pl = threadIdx.x & 63;
         long long spins = 0;
         bool alive = true;
         for (;;) {
-            const bool ok = (int)threadIdx.x >= G || ld_l2(&flags[threadIdx.x]) >= target;
+            const bool ok = pl >= G || ld_l2(&flags[pl]) >= target;
             if (__all(ok)) break;
 #ifdef VER_REC_SLEEP
             __builtin_amdgcn_s_sleep(VER_REC_SLEEP);
 #endif
             ++spins;
             if ((spins & 1023) == 0 && (spins > REC_SPIN_LIMIT || ld_agent(err) != 0)) {
-                if (threadIdx.x == 0) st_agent(err, 1);
+                if (pl == 0) st_agent(err, 1);
                 alive = false;
                 break;
             }
         }
-        if (threadIdx.x == 0) s_ok = alive ? 1 : 0;
+        if (pl == 0) s_ok = alive ? 1 : 0;
     }
     bar_lds();
     return s_ok != 0;
@@ -435,6 +441,7 @@ struct RecFwdArgs {
     float* c;           // [M, H]
     float* hout;        // [M, H]
     void* hprev;        // [M, H] operand type: row p = h_{t-1} of the piece in row p
+    void* hcopy;        // [M, H] operand type: row p = h_t, written through for the workers (producer layer only)
     const void* whh;    // [4H, H] operand type, interleaved rows
     const float* h0;    // [seq_cap, H] of this layer, or NULL
     const float* c0;
@@ -517,14 +524,20 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                 zpre[q] = *reinterpret_cast<const f32x4_t*>(a.gates + (size_t)((q * 16 + lr) * X + x) * 4 * H + gcol);
     }
 
+    // batch sizes of timesteps t, t+1 (and t+2, fetched a step ahead: a scalar load that misses costs about half
+    // a microsecond, which would otherwise sit at the top of every step); row offsets follow by addition
+    int bs_a = T > 0 ? a.batch_sizes[0] : 0, bs_b = T > 1 ? a.batch_sizes[1] : 0;
+    int base = 0, base_prev = 0;
     for (int t = 0; t < T; ++t) {
+        const int bs_c = (t + 2 < T) ? a.batch_sizes[t + 2] : 0;
         // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
-        const int bs_all = a.batch_sizes[t], bs = grp_count(bs_all, x, X), base = a.t_off[t];
-        const int bs_next = (t + 1 < T) ? grp_count(a.batch_sizes[t + 1], x, X) : 0, base_next = base + bs_all;
-        const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
+        const int bs_all = bs_a, bs = grp_count(bs_all, x, X);
+        const int bs_next = (t + 1 < T) ? grp_count(bs_b, x, X) : 0, base_next = base + bs_all;
         if (PIPE == PIPE_CONSUMER && t + 1 < T && (t + 1) % PIPE_CT == 0 &&
             !pipe_wait_chunk(a.t_off, pl, (t + 1) / PIPE_CT, a.err)) return;
-        __amdgpu_buffer_rsrc_t rs_hout = __builtin_amdgcn_make_buffer_rsrc(a.hout + (size_t)base * H, 0, bs_all * H * 4, 0x00020000);
+        REC_PROF_MARK(6);
+        __amdgpu_buffer_rsrc_t rs_hcopy = __builtin_amdgcn_make_buffer_rsrc(static_cast<E*>(a.hcopy) + (size_t)base * H, 0,
+                                                                            PIPE == PIPE_PRODUCER ? bs_all * H * (int)sizeof(E) : 0, 0x00020000);
         if (!rec_wait(flags, G, t + 1, a.err)) return;
         // every workgroup of the group has raised its flag for timestep t-1, i.e. completed that step's stores
         if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0 && t > 0) st_agent(&pl.progress[x], t);
@@ -589,8 +602,7 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                         hn = go * tanhf_(cn);
                         *gp = f32x4_t{gi, gf, gg, go};
                         a.c[p * H + je] = cn;
-                        if (PIPE == PIPE_PRODUCER) st_through(rs_hout, (n * H + je) * 4, hn);   // read by the workers on other XCDs
-                        else a.hout[p * H + je] = hn;
+                        a.hout[p * H + je] = hn;
                     }
                     // h_t goes to the exchange row of the next timestep through LDS (below)
                     sH[(q * 16 + lr) * UH + wave * 4 + lk] = cvt_finite<E>(hn);
@@ -609,12 +621,24 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                     const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sH + r * UH + pc * VEC);
                     *reinterpret_cast<u32x4_t*>(hprev + ((size_t)base_next + (size_t)(c0 + r) * X + x) * H + j0 + pc * VEC) = v;
                 }
+                if (PIPE == PIPE_PRODUCER) {
+                    // h_t of every row of the chunk in operand type, written through: input of the workers' GEMM
+                    for (int i = tid; i < min(rows, bs - c0) * PIECES; i += REC_THREADS) {
+                        const int r = i / PIECES, pc = i % PIECES;
+                        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sH + r * UH + pc * VEC);
+                        __builtin_amdgcn_raw_buffer_store_b128(v, rs_hcopy, (((c0 + r) * X + x) * H + j0 + pc * VEC) * (int)sizeof(E), 0, 17);
+                    }
+                }
             }
         }
         REC_PROF_MARK(3);
         if (t + 1 < T || PIPE == PIPE_PRODUCER) rec_publish(flags, rank, t + 2);
 #pragma unroll
         for (int q = 0; q < REC_PRE; ++q) zpre[q] = znext[q];
+        base_prev = base;
+        base = base_next;
+        bs_a = bs_b;
+        bs_b = bs_c;
         REC_PROF_MARK(4);
         REC_PROF_STEP();
     }
@@ -709,20 +733,26 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
     pre.c = pre.c_prev = pre.dh_above = 0.f;
     float dcreg = 0.f;   // cell-state gradient of that (piece, unit), carried from timestep to timestep
     if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(a.t_off, pl, (T - 1) / PIPE_CT, a.err)) return;
+    // batch sizes of timesteps t+1, t, t-1, t-2 (t-3 is fetched a step ahead, see the forward kernel); row offsets
+    // follow by subtraction
+    int bs_up = 0, bs_t = T > 0 ? a.batch_sizes[T - 1] : 0, bs_m1 = T > 1 ? a.batch_sizes[T - 2] : 0,
+        bs_m2 = T > 2 ? a.batch_sizes[T - 3] : 0;
+    int base = T > 0 ? a.t_off[T - 1] : 0;
     if (T > 0) {
-        const int bs_l = grp_count(a.batch_sizes[T - 1], x, X), base_l = a.t_off[T - 1];
+        const int bs_l = grp_count(bs_t, x, X);
         if (tid < bs_l * UH)
-            pre = load_saved(a, T - 1, base_l, (T > 1) ? a.t_off[T - 2] : 0, (tid / UH) * X + x, j0 + (tid % UH), H);
+            pre = load_saved(a, T - 1, base, base - bs_m1, (tid / UH) * X + x, j0 + (tid % UH), H);
     }
     REC_PROF_DECL
     REC_PROF_START();
     for (int t = T - 1; t >= 0; --t) {
         // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
-        const int bs = grp_count(a.batch_sizes[t], x, X), base = a.t_off[t];
-        const int bs_next = (t + 1 < T) ? grp_count(a.batch_sizes[t + 1], x, X) : 0;
-        const int base_prev = (t > 0) ? a.t_off[t - 1] : 0;
+        const int bs_m3 = t > 2 ? a.batch_sizes[t - 3] : 0;
+        const int bs = grp_count(bs_t, x, X);
+        const int bs_next = (t + 1 < T) ? grp_count(bs_up, x, X) : 0;
+        const int base_prev = base - bs_m1;     // rows of timestep t-1 (unused when t == 0)
         __amdgpu_buffer_rsrc_t rs_dz = __builtin_amdgcn_make_buffer_rsrc(dzw + (size_t)base * K, 0,
-                                                                         a.batch_sizes[t] * K * (int)sizeof(E), 0x00020000);
+                                                                         bs_t * K * (int)sizeof(E), 0x00020000);
         // A. gate gradients of this workgroup's units for every alive piece
         for (int i = tid; i < bs * UH; i += REC_THREADS) {
             const int m = i / UH, n = m * X + x, j = j0 + (i % UH);
@@ -768,12 +798,13 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
             REC_PROF_MARK(11);
             if (PIPE == PIPE_CONSUMER && c0 == 0 && t % PIPE_CT == 0 && !pipe_wait_chunk(a.t_off, pl, (t - 1) / PIPE_CT, a.err))
                 return;
+            REC_PROF_MARK(13);
             if (c0 == 0) {
                 // saved activations of this thread's first item of timestep t-1, issued once the exchanged rows
                 // have arrived (see the forward kernel): in flight during the MFMA phase
-                const int bs_p = grp_count(a.batch_sizes[t - 1], x, X), base_p = a.t_off[t - 1];
+                const int bs_p = grp_count(bs_m1, x, X);
                 if (tid < bs_p * UH)
-                    pre = load_saved(a, t - 1, base_p, (t > 1) ? a.t_off[t - 2] : 0, (tid / UH) * X + x, j0 + (tid % UH), H);
+                    pre = load_saved(a, t - 1, base_prev, base_prev - bs_m2, (tid / UH) * X + x, j0 + (tid % UH), H);
             }
             f32x4_t acc[REC_NTC];
             mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
@@ -802,6 +833,11 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
         // from global memory, whose stores must have completed
         if (bs > 16 * ntc) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         bar_lds();
+        base = base_prev;
+        bs_up = bs_t;
+        bs_t = bs_m1;
+        bs_m1 = bs_m2;
+        bs_m2 = bs_m3;
         REC_PROF_MARK(12);
         REC_PROF_STEP();
     }

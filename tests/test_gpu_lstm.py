@@ -64,6 +64,38 @@ def test_two_layers_ragged(ver, compute, b):
 
 
 @pytest.mark.parametrize("compute", [0, 1])
+def test_two_layers_one_launch_per_layer(ver, compute, monkeypatch):
+    """Two-layer networks normally run both time loops in one launch; the layer-by-layer path (every other
+    depth) is checked against the oracle on the same case through the library's diagnostic switch."""
+    monkeypatch.setenv("VER_LSTM_SEQUENTIAL", "1")
+    case(ver, wl.scaled(wl.WORKLOADS["manip"], **SMALL), seed=21, b=1, compute=compute)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
+def test_two_layer_launch_matches_layer_by_layer(ver, compute, monkeypatch):
+    """Same inputs through both paths: they differ only in the order of fp32 additions in the projection
+    between the layers."""
+    w = wl.scaled(wl.WORKLOADS["manip"], budget=1500, n_envs=70, hidden=128, input_dim=36, p_done=0.03, minibatches=1)
+    ro = wl.make_rollout(w, seed=31, bias_scale=0.2)
+    meta = opack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][0], 1, 0, ro["env_started_episode"])
+    h0 = opack.initial_states(ro["rnn_h"], meta["seq_first"], meta["seq_is_ep_start"])
+    c0 = opack.initial_states(ro["rnn_c"], meta["seq_first"], meta["seq_is_ep_start"])
+    rng = np.random.default_rng(2)
+    d_u = (rng.standard_normal((meta["M"], w.act_dim)) / meta["M"]).astype(np.float32)
+    d_v = (rng.standard_normal(meta["M"]) / meta["M"]).astype(np.float32)
+    res = []
+    for sequential in ("0", "1"):
+        monkeypatch.setenv("VER_LSTM_SEQUENTIAL", sequential)
+        run = LstmRun(ver, w, ro["weights"], opack.gather_rows(ro["obs"], meta["gather_idx"]), meta, h0, c0, compute)
+        u, v = run.forward()
+        grads, dx = run.backward(d_u, d_v)
+        res.append([u, v, dx] + grads)
+    for a, b in zip(*res):
+        # bf16 operands: a last-bit difference in fp32 can flip the rounding of an operand (2^-9 relative)
+        assert rel_err(a, b) < (1e-5 if compute == 0 else 1e-2)
+
+
+@pytest.mark.parametrize("compute", [0, 1])
 def test_tiny_workload(ver, compute):
     case(ver, wl.WORKLOADS["tiny"], seed=3, compute=compute)
 
