@@ -52,44 +52,72 @@ __device__ __forceinline__ float wave_sum_all(float v) {
     return v;
 }
 
-// head_out[p][a] = W_a[a] . h[p] + b_a[a];  value[p] = w_v . h[p] + b_v.  One wave per row.
+// head_out[p][a] = W_a[a] . h[p] + b_a[a];  value[p] = w_v . h[p] + b_v.  One wave per HF_ROWS rows: the rows stay
+// in registers for all heads (H <= 1024) and a head weight is read once for all of them.
+constexpr int HF_ROWS = 4;
 __global__ __launch_bounds__(256) void heads_fwd_kernel(const float* __restrict__ h, int M, int H, int A,
                                                         const float* __restrict__ W_a, const float* __restrict__ b_a,
                                                         const float* __restrict__ w_v, const float* __restrict__ b_v,
                                                         float* __restrict__ head_out, float* __restrict__ value) {
     const int lane = threadIdx.x & 63;
-    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (p >= M) return;
-    const float* hp = h + (size_t)p * H;
+    const int p0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * HF_ROWS;
+    if (p0 >= M) return;
+    float hv[HF_ROWS][16];
+#pragma unroll
+    for (int r = 0; r < HF_ROWS; ++r)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            hv[r][i] = (p0 + r < M && lane + i * 64 < H) ? h[(size_t)(p0 + r) * H + lane + i * 64] : 0.f;
     for (int a = 0; a <= A; ++a) {
         const float* w = (a < A) ? W_a + (size_t)a * H : w_v;
-        float s = 0.f;
-        for (int j = lane; j < H; j += 64) s += hp[j] * w[j];
-        s = wave_sum_all(s);
-        if (lane == 0) {
-            if (a < A) head_out[(size_t)p * A + a] = s + b_a[a];
-            else value[p] = s + b_v[0];
+        float s[HF_ROWS];
+#pragma unroll
+        for (int r = 0; r < HF_ROWS; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (lane + i * 64 < H) {
+                const float wv = w[lane + i * 64];
+#pragma unroll
+                for (int r = 0; r < HF_ROWS; ++r) s[r] += hv[r][i] * wv;
+            }
+#pragma unroll
+        for (int r = 0; r < HF_ROWS; ++r) {
+            const float t = wave_sum_all(s[r]);
+            if (lane == 0 && p0 + r < M) {
+                if (a < A) head_out[(size_t)(p0 + r) * A + a] = t + b_a[a];
+                else value[p0 + r] = t + b_v[0];
+            }
         }
     }
 }
 
-// dh[p][j] = sum_a d_u[p][a] W_a[a][j] + d_v[p] w_v[j]; also packs DU[p][0..A] = (d_u[p], d_v[p]).
+// dh[p][j] = sum_a d_u[p][a] W_a[a][j] + d_v[p] w_v[j].  A thread owns column j for a block of HB_ROWS rows, so a
+// head weight is read once per block instead of once per row (the loss gradients are wave-uniform scalars).
+constexpr int HB_ROWS = 16;
 __global__ __launch_bounds__(256) void heads_bwd_dh_kernel(const float* __restrict__ d_u, const float* __restrict__ d_v,
                                                            int M, int H, int A, const float* __restrict__ W_a,
                                                            const float* __restrict__ w_v, float* __restrict__ dh) {
-    const int lane = threadIdx.x & 63;
-    const int p = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (p >= M) return;
-    const float dv = d_v[p];
-    for (int j = lane; j < H; j += 64) {
-        float s = dv * w_v[j];
-        for (int a = 0; a < A; ++a) s += d_u[(size_t)p * A + a] * W_a[(size_t)a * H + j];
-        dh[(size_t)p * H + j] = s;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int p0 = blockIdx.y * HB_ROWS;
+    if (j >= H) return;
+    float s[HB_ROWS];
+    const float wv = w_v[j];
+#pragma unroll
+    for (int r = 0; r < HB_ROWS; ++r) s[r] = (p0 + r < M) ? d_v[p0 + r] * wv : 0.f;
+    for (int a = 0; a < A; ++a) {
+        const float w = W_a[(size_t)a * H + j];
+#pragma unroll
+        for (int r = 0; r < HB_ROWS; ++r)
+            if (p0 + r < M) s[r] += d_u[(size_t)(p0 + r) * A + a] * w;
     }
+#pragma unroll
+    for (int r = 0; r < HB_ROWS; ++r)
+        if (p0 + r < M) dh[(size_t)(p0 + r) * H + j] = s[r];
 }
 
 // Partial sums over a block of rows: part[rb][a][j] = sum_{p in block rb} du(p,a) * h[p][j], a = 0..A (A = value head).
-constexpr int HW_ROWS = 256;  // rows per row block
+// h is read once per 16 heads; the loss gradients are wave-uniform scalars.
+constexpr int HW_ROWS = 32;  // rows per row block
 __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* __restrict__ d_u,
                                                                   const float* __restrict__ d_v,
                                                                   const float* __restrict__ h, int M, int H, int A,
@@ -98,19 +126,27 @@ __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* _
     const int rb = blockIdx.y;
     const int p_lo = rb * HW_ROWS, p_hi = min(M, p_lo + HW_ROWS);
     if (j >= H) return;
-    for (int a0 = 0; a0 <= A; a0 += 4) {
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int p = p_lo; p < p_hi; ++p) {
-            const float hv = h[(size_t)p * H + j];
+    for (int a0 = 0; a0 <= A; a0 += 16) {
+        float acc[16];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int a = a0 + e;
-                const float g = (a < A) ? d_u[(size_t)p * A + a] : (a == A ? d_v[p] : 0.f);
-                acc[e] += g * hv;
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        for (int p = p_lo; p < p_hi; p += 4) {
+            float hv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) hv[u] = (p + u < p_hi) ? h[(size_t)(p + u) * H + j] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (p + u >= p_hi) continue;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int a = a0 + e;
+                    const float g = (a < A) ? d_u[(size_t)(p + u) * A + a] : (a == A ? d_v[p + u] : 0.f);
+                    acc[e] += g * hv[u];
+                }
             }
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
+        for (int e = 0; e < 16; ++e)
             if (a0 + e <= A) part[((size_t)rb * (A + 1) + a0 + e) * H + j] = acc[e];
     }
 }
@@ -125,18 +161,45 @@ __global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __r
     if (a < A) dW_a[(size_t)a * H + j] = s; else dw_v[j] = s;
 }
 
-// Column sums of a row-major [rows, cols] matrix in two deterministic stages.
-constexpr int CS_ROWS = 128;
+// Column sums of a row-major [rows, cols] matrix in two deterministic stages.  When the shape allows it a block
+// covers 256 columns x CS_ROWS rows: a thread sums 4 adjacent columns (one 8- or 16-byte load per row) over a
+// quarter of the rows, and the four quarters are added in LDS in a fixed order.
+constexpr int CS_ROWS = 256;
 template <typename E>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const E* __restrict__ X, int rows, int cols, int ld,
                                                              float* __restrict__ part) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
+    __shared__ float red[4][256];
     const int rb = blockIdx.y;
-    if (c >= cols) return;
-    const int r_hi = min(rows, (rb + 1) * CS_ROWS);
-    float s = 0.f;
-    for (int r = rb * CS_ROWS; r < r_hi; ++r) s += cvt_elem<float>(X[(size_t)r * ld + c]);
-    part[(size_t)rb * cols + c] = s;
+    const int r_lo = rb * CS_ROWS, r_hi = min(rows, r_lo + CS_ROWS);
+    if (cols % 4 == 0 && ld % 4 == 0) {
+        const int cq = threadIdx.x & 63, slice = threadIdx.x >> 6;
+        const int c = blockIdx.x * 256 + cq * 4;
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
+        if (c < cols) {
+            for (int r = r_lo + slice * (CS_ROWS / 4); r < min(r_hi, r_lo + (slice + 1) * (CS_ROWS / 4)); r += 4) {
+                Quad<float> q[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    q[u] = (r + u < r_hi) ? load_quad<float, E>(X + (size_t)(r + u) * ld + c) : zero_quad<float>();
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) s[e] += q[u].v[e];
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[slice][cq * 4 + e] = s[e];
+        __syncthreads();
+        const int cc = blockIdx.x * 256 + threadIdx.x;
+        if (cc < cols)
+            part[(size_t)rb * cols + cc] = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+    } else {
+        for (int c = blockIdx.x * 256 + threadIdx.x; c < min(cols, (int)(blockIdx.x + 1) * 256); c += 256) {
+            float s = 0.f;
+            for (int r = r_lo; r < r_hi; ++r) s += cvt_elem<float>(X[(size_t)r * ld + c]);
+            part[(size_t)rb * cols + c] = s;
+        }
+    }
 }
 // out[perm(c)] (and out2) = sum over row blocks; unperm_h > 0 maps interleaved column c to (c%4)*H + c/4.
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int n_rb, int cols,
@@ -398,7 +461,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
 #undef VER_FWD_DISPATCH
 #undef VER_FWD_LAUNCH
     ProfScope prof(VER_PROF_HEADS_FWD, s);
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 3) / 4), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 4 * HF_ROWS - 1) / (4 * HF_ROWS)), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
                        w[4 * c.n_layers], w[4 * c.n_layers + 1], w[4 * c.n_layers + 2], w[4 * c.n_layers + 3],
                        head_out, value);
     return launch_status();
@@ -415,7 +478,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     // heads
     {
     ProfScope prof(VER_PROF_HEADS_BWD, s);
-    hipLaunchKernelGGL(heads_bwd_dh_kernel, dim3((M + 3) / 4), dim3(256), 0, s, d_u, d_v, M, H, A, w[4 * nl],
+    hipLaunchKernelGGL(heads_bwd_dh_kernel, dim3((H + 255) / 256, (M + HB_ROWS - 1) / HB_ROWS), dim3(256), 0, s, d_u, d_v, M, H, A, w[4 * nl],
                        w[4 * nl + 2], ws.dh[0]);
     const int rb_h = (M + HW_ROWS - 1) / HW_ROWS;
     hipLaunchKernelGGL(heads_wgrad_partial_kernel, dim3((H + 255) / 256, rb_h), dim3(256), 0, s, d_u, d_v, h_top, M, H,
