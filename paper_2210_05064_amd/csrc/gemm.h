@@ -90,7 +90,28 @@ __device__ __forceinline__ void store_quad(float* dst, const Quad<float>& q) {
     *reinterpret_cast<f32x4_t*>(dst) = f32x4_t{q.v[0], q.v[1], q.v[2], q.v[3]};
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
+// load and store of the wave, which would put the latency of each prefetch on the critical path; code that
+// uses it waits for global memory explicitly where it needs it.
+__device__ __forceinline__ void bar_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
 constexpr int GEMM_BM = 128, GEMM_BN = 128, GEMM_THREADS = 256;
+
+// Which tile a workgroup computes.  Workgroups are dealt to the 8 XCDs round-robin in launch order and every
+// XCD has its own L2, so the workgroups of one XCD are given a compact block of the tile grid (a band of
+// row tiles with all its column tiles and K-splits): the operand tiles they share are then fetched from HBM
+// once per XCD instead of once per workgroup.  bx: column tile, by: row tile, bz: K-split.
+__device__ __forceinline__ void gemm_tile_of_block(int& bx, int& by, int& bz) {
+    const int gx = gridDim.x, gy = gridDim.y, gz = gridDim.z;
+    const int total = gx * gy * gz;
+    int id = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+    if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
+    by = id / (gx * gz);
+    const int rem = id - by * (gx * gz);
+    bz = rem / gx;
+    bx = rem - bz * gx;
+}
 
 template <int MODE> struct GemmGeom;
 template <> struct GemmGeom<MODE_BF16> { static constexpr int BK = 64, LDS_STRIDE = 72; };
@@ -173,11 +194,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_kernel(
     __shared__ __attribute__((aligned(16))) E sB[GEMM_BN * STRIDE];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-    const int m0 = blockIdx.y * GEMM_BM, n0 = blockIdx.x * GEMM_BN;
+    int bx, by, bz;
+    gemm_tile_of_block(bx, by, bz);
+    const int m0 = by * GEMM_BM, n0 = bx * GEMM_BN;
     const int lr = lane & 15, lk = lane >> 4;
-    const int k_begin = blockIdx.z * k_chunk, k_end = min(K, k_begin + k_chunk);
+    const int k_begin = bz * k_chunk, k_end = min(K, k_begin + k_chunk);
     const bool split = gridDim.z > 1;
-    if (split) C += (size_t)blockIdx.z * split_stride;
+    if (split) C += (size_t)bz * split_stride;
 
     f32x4_t acc[4][4];
 #pragma unroll
@@ -266,6 +289,119 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
     }
 }
 
+// ---- K-minor bf16 operands through LDS-direct loads --------------------------------------------------------
+// C[m][n] = sum_k A[k*lda + m] * B[k*ldb + n] (weight gradients: the contraction runs over the packed rows).
+// Tiles of 32 k-rows go from global memory straight into LDS, four stages deep (three tiles in flight while
+// one is multiplied, one barrier per tile); the MFMA operands are read with the transposing LDS load
+// (ds_read_b64_tr_b16): in every group of 16 lanes, lane i supplies the address of 4 consecutive elements of
+// row k = i/4 (columns 4*(i%4)..+3 of a 16-column tile) and receives, for column i, the 4 values of rows
+// 0..3 - measured layout: result[j] of lane l = element l%4 of source lane l/4 + 4j.
+// An LDS row holds the 128 columns of one k as 16 chunks of 16 bytes; chunk position p of row k holds chunk
+// p ^ swz(k), swz(k) = 2*(k&3) | 8*((k>>3)&1), so that the 32 lanes served together (rows k..k+3 and k+8..k+11,
+// two chunks each) touch every bank once.  A load instruction fills 4 rows (lane -> row lane/16, position
+// lane%16): the swizzle is applied on the global side.
+constexpr int TN_BK = 32, TN_STAGES = 4, TN_STAGE_BYTES = 2 * TN_BK * 256;
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int tn_swz(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
+
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_kernel(
+    const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb, float* __restrict__ C, int ldc,
+    int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride) {
+    __shared__ __attribute__((aligned(16))) unsigned char smem[TN_STAGES * TN_STAGE_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    int bx, by, bz;
+    gemm_tile_of_block(bx, by, bz);
+    const int m0 = by * GEMM_BM, n0 = bx * GEMM_BN;
+    const int lr = lane & 15, lk = lane >> 4;
+    const int k_begin = bz * k_chunk, k_end = min(K, k_begin + k_chunk);
+    const int nk = (k_end - k_begin + TN_BK - 1) / TN_BK;
+    const bool split = gridDim.z > 1;
+    if (split) C += (size_t)bz * split_stride;
+    // rows beyond K read zero (buffer bounds); columns beyond the matrix only feed outputs that are not stored
+    __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, (int)min((size_t)K * lda * 2, (size_t)0x7fffffff), 0x00020000);
+    __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, (int)min((size_t)K * ldb * 2, (size_t)0x7fffffff), 0x00020000);
+    // this lane's part of the 2 + 2 load instructions of its wave per stage
+    int voffA[2], voffB[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int k = (wave * 2 + j) * 4 + (lane >> 4), c = (lane & 15) ^ tn_swz(k);
+        voffA[j] = k * lda * 2 + m0 * 2 + c * 16;
+        voffB[j] = k * ldb * 2 + n0 * 2 + c * 16;
+    }
+    auto issue = [&](int kt) {
+        unsigned char* st = smem + (kt % TN_STAGES) * TN_STAGE_BYTES;
+        const int k0 = k_begin + kt * TN_BK;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            // the row goes into the per-lane offset: only that one is checked against the buffer bounds
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)(st + (wave * 2 + j) * 1024), 16, voffA[j] + k0 * lda * 2, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr_t)(st + TN_BK * 256 + (wave * 2 + j) * 1024), 16,
+                                                     voffB[j] + k0 * ldb * 2, 0, 0, 0);
+        }
+    };
+    // operand read offsets: source row k = lk*8 + lr/4 (+4 for the second half), columns tile*16 + 4*(lr%4)..+3
+    int offA[4][2], offB[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = lk * 8 + (lr >> 2) + 4 * h;
+            const int colA = wm + i * 16 + 4 * (lr & 3), colB = wn + i * 16 + 4 * (lr & 3);
+            offA[i][h] = k * 256 + ((((colA * 2) >> 4) ^ tn_swz(k)) << 4) + ((colA * 2) & 8);
+            offB[i][h] = TN_BK * 256 + k * 256 + ((((colB * 2) >> 4) ^ tn_swz(k)) << 4) + ((colB * 2) & 8);
+        }
+    f32x4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    for (int kt = 0; kt < TN_STAGES - 1 && kt < nk; ++kt) issue(kt);
+    for (int kt = 0; kt < nk; ++kt) {
+        // this wave's 4 loads of stage kt have landed; up to two younger stages (8 loads) may be in flight
+        const int younger = min(nk - 1 - kt, TN_STAGES - 2);
+        if (younger >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (younger == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        bar_lds();   // everyone's loads of stage kt have landed, and everyone is done reading stage kt-1
+        if (kt + TN_STAGES - 1 < nk) issue(kt + TN_STAGES - 1);
+        const unsigned char* st = smem + (kt % TN_STAGES) * TN_STAGE_BYTES;
+        u16x8_t a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offA[i][0]));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offA[i][1]));
+            a[i] = u16x8_t{(bf16_t)lo[0], (bf16_t)lo[1], (bf16_t)lo[2], (bf16_t)lo[3], (bf16_t)hi[0], (bf16_t)hi[1], (bf16_t)hi[2], (bf16_t)hi[3]};
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offB[j][0]));
+            const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offB[j][1]));
+            b[j] = u16x8_t{(bf16_t)lo[0], (bf16_t)lo[1], (bf16_t)lo[2], (bf16_t)lo[3], (bf16_t)hi[0], (bf16_t)hi[1], (bf16_t)hi[2], (bf16_t)hi[3]};
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16_16x16x32(a[i], b[j], acc[i][j]);
+    }
+    // C fragment: element r of lane l is row (l / 16) * 4 + r, column l % 16 of the 16x16 tile.
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + wn + j * 16 + lr;
+            if (n >= Nc) continue;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = m0 + wm + i * 16 + lk * 4 + r;
+                if (m >= Mr) continue;
+                const int out_row = (unperm_h > 0 && !split) ? (m & 3) * unperm_h + (m >> 2) : m;
+                C[(size_t)out_row * ldc + n] = acc[i][j][r];
+            }
+        }
+}
+
 // How many ways to split the contraction so that the grid has a few workgroups per CU.
 inline int gemm_splits(int Mr, int Nc, int K, int BK) {
     const long tiles = (long)((Mr + GEMM_BM - 1) / GEMM_BM) * ((Nc + GEMM_BN - 1) / GEMM_BN);
@@ -287,6 +423,20 @@ inline void gemm_launch(const TA* A, int lda, const TB* B, int ldb, float* C, in
     constexpr int BK = GemmGeom<MODE>::BK;
     const int splits = (allow_split && part) ? gemm_splits(Mr, Nc, K, BK) : 1;
     dim3 grid((Nc + GEMM_BN - 1) / GEMM_BN, (Mr + GEMM_BM - 1) / GEMM_BM, splits);
+    if constexpr (TRANS && MODE == MODE_BF16 && sizeof(TA) == 2 && sizeof(TB) == 2) {
+        // both operands bf16 and K-minor: the LDS-direct kernel (bias is never used with these shapes)
+        if (!bias && lda % 2 == 0 && ldb % 2 == 0 && (size_t)K * lda * 2 < 0x7fffffff && (size_t)K * ldb * 2 < 0x7fffffff) {
+            const int k_chunk = splits == 1 ? K : ((K + splits - 1) / splits + BK - 1) / BK * BK;
+            const size_t stride = (size_t)Mr * Nc;
+            hipLaunchKernelGGL(gemm_tn_dma_kernel, grid, dim3(GEMM_THREADS), 0, s, reinterpret_cast<const bf16_t*>(A), lda,
+                               reinterpret_cast<const bf16_t*>(B), ldb, splits == 1 ? C : part, splits == 1 ? ldc : Nc, Mr, Nc, K,
+                               unperm_h, k_chunk, stride);
+            if (splits > 1)
+                hipLaunchKernelGGL(gemm_reduce_kernel, dim3(1024), dim3(256), 0, s, part, splits, stride, Mr, Nc, C, ldc, bias,
+                                   unperm_h);
+            return;
+        }
+    }
     if (splits == 1) {
         hipLaunchKernelGGL((gemm_kernel<MODE, TA, TB, TRANS>), grid, dim3(GEMM_THREADS), 0, s, A, lda, B, ldb, C, ldc, Mr,
                            Nc, K, bias, unperm_h, K, (size_t)0);

@@ -157,7 +157,15 @@ __global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __r
     const int a = blockIdx.y;
     if (j >= H) return;
     float s = 0.f;
-    for (int rb = 0; rb < n_rb; ++rb) s += part[((size_t)rb * (A + 1) + a) * H + j];
+    int rb = 0;
+    for (; rb + 8 <= n_rb; rb += 8) {   // 8 loads in flight, added in index order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = part[((size_t)(rb + u) * (A + 1) + a) * H + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; rb < n_rb; ++rb) s += part[((size_t)rb * (A + 1) + a) * H + j];
     if (a < A) dW_a[(size_t)a * H + j] = s; else dw_v[j] = s;
 }
 
@@ -208,7 +216,15 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restri
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= cols) return;
     float s = 0.f;
-    for (int rb = 0; rb < n_rb; ++rb) s += part[(size_t)rb * cols + c];
+    int rb = 0;
+    for (; rb + 8 <= n_rb; rb += 8) {   // 8 loads in flight, added in index order
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = part[(size_t)(rb + u) * cols + c];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; rb < n_rb; ++rb) s += part[(size_t)rb * cols + c];
     const int dst = unperm_h > 0 ? (c & 3) * unperm_h + (c >> 2) : c;
     out[dst] = s;
     if (out2) out2[dst] = s;
@@ -547,7 +563,10 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         // dW_ih[4H, D] = dz^T x ; dW_hh[4H, H] = dz^T h_{t-1}; stored gate-major
         {
         ProfScope prof(VER_PROF_LSTM_GEMM_DW, s);
-        if (l > 0)
+        if (l > 0 && pipelined && ws.layer[l - 1].hcopy)   // the layer below left its h in operand type
+            gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(ws.layer[l - 1].hcopy), H, gw[4 * l], D, 4 * H, D, M,
+                                          nullptr, H, ws.gemm_part, true, s);
+        else if (l > 0)
             gemm_launch<MODE, E, float, true>(dz, 4 * H, ws.layer[l - 1].hout, H, gw[4 * l], D, 4 * H, D, M, nullptr, H, ws.gemm_part, true, s);
         else if (c.x_bf16)
             gemm_launch<MODE, E, bf16_t, true>(dz, 4 * H, static_cast<const bf16_t*>(x), D, gw[4 * l], D, 4 * H, D, M,

@@ -112,11 +112,6 @@ template <typename E> __device__ __forceinline__ E cvt_finite(float v);
 template <> __device__ __forceinline__ float cvt_finite<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t cvt_finite<bf16_t>(float v) { return to_bf16_finite(v); }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
-// load and store of the wave, which would put the latency of each prefetch on the critical path of the
-// timestep; the time loops wait for global memory explicitly where a step needs it.
-__device__ __forceinline__ void bar_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
-
 // ---- which workgroups take part ---------------------------------------------------------------------
 // The workgroups of one XCD form a group (grp = hardware XCC id) and take ranks from that group's ticket
 // (tickets[REC_GROUPS], zero at launch).  Returns this workgroup's rank in [0, G) or -1.
@@ -203,7 +198,6 @@ __device__ __forceinline__ void rec_publish(int* flags, int rank, int value) {
 // `rot` rotates the order in which this workgroup walks the segments: all workgroups fetch the same rows at
 // the same moment, and starting each one at a different place spreads them over the L2 channels.
 // The caller waits for the loads (s_waitcnt vmcnt(0)) and synchronises the workgroup.
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
 template <typename E>
 __device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, int row_elems, int pitch,
                                            E* __restrict__ lds, int stride, int rot) {
