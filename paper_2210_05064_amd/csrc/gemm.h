@@ -301,6 +301,10 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
 // two chunks each) touch every bank once.  A load instruction fills 4 rows (lane -> row lane/16, position
 // lane%16): the swizzle is applied on the global side.
 constexpr int TN_BK = 32, TN_STAGES = 4, TN_STAGE_BYTES = 2 * TN_BK * 256;
+#ifndef VER_TN_TARGET_WGS
+#define VER_TN_TARGET_WGS 512
+#endif
+constexpr int TN_TARGET_WGS = VER_TN_TARGET_WGS;
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ int tn_swz(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
 
@@ -426,6 +430,15 @@ inline void gemm_launch(const TA* A, int lda, const TB* B, int ldb, float* C, in
     if constexpr (TRANS && MODE == MODE_BF16 && sizeof(TA) == 2 && sizeof(TB) == 2) {
         // both operands bf16 and K-minor: the LDS-direct kernel (bias is never used with these shapes)
         if (!bias && lda % 2 == 0 && ldb % 2 == 0 && (size_t)K * lda * 2 < 0x7fffffff && (size_t)K * ldb * 2 < 0x7fffffff) {
+            // two workgroups fit on a CU: aim at one full round of 512
+            const int tiles = grid.x * grid.y;
+            int sp = (allow_split && part) ? (TN_TARGET_WGS + tiles / 2) / tiles : 1;
+            const int max_sp = K / (8 * TN_BK) > 0 ? K / (8 * TN_BK) : 1;
+            sp = sp < 1 ? 1 : (sp > 8 ? 8 : sp);
+            if (sp > max_sp) sp = max_sp;
+            if (sp > gemm_splits(Mr, Nc, K, BK)) sp = gemm_splits(Mr, Nc, K, BK);   // the scratch is sized for that many
+            grid.z = sp;
+            const int splits = sp;
             const int k_chunk = splits == 1 ? K : ((K + splits - 1) / splits + BK - 1) / BK * BK;
             const size_t stride = (size_t)Mr * Nc;
             hipLaunchKernelGGL(gemm_tn_dma_kernel, grid, dim3(GEMM_THREADS), 0, s, reinterpret_cast<const bf16_t*>(A), lda,
