@@ -25,9 +25,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 
-# HBM bytes per launch (read + written) of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of
-# this script, scaled by a copy of known size: see profiles/hbm_traffic_max_workload.md.  None where unmeasured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch (read + written) of the dominant kernel class (with two layers: the launch that runs both
+# time loops of one direction), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a copy of
+# known size: see profiles/hbm_traffic_max_workload.md.  None where unmeasured.
+MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 1390.6e6, ("max", "lstm_rec_fwd"): 1698.4e6}
 
 
 def collection_logp(ro, compute, x_bf16):

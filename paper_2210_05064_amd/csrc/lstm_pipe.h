@@ -22,7 +22,12 @@
 
 namespace ver {
 
-constexpr int PIPE_GROUPS = 3;       // groups (XCDs) per layer
+#ifndef VER_PIPE_P
+#define VER_PIPE_P 3
+#define VER_PIPE_C 3
+#endif
+constexpr int PIPE_GROUPS = VER_PIPE_P;   // groups (XCDs) of the producer layer
+constexpr int PIPE_GROUPS_C = VER_PIPE_C; // groups (XCDs) of the consumer layer
 constexpr int PIPE_XCDS = 8;         // XCDs of the chip: those beyond the two layers' groups are workers
 
 struct PipeWork {
@@ -332,7 +337,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     PipeLink link = p.link;
     link.T_all = p.l0.info[1];
 #ifdef VER_REC_PROF
-    const bool stamp = threadIdx.x == 0 && rank == 0 && (xcc == 0 || xcc == PIPE_GROUPS || xcc == 2 * PIPE_GROUPS);
+    const bool stamp = threadIdx.x == 0 && rank == 0 && (xcc == 0 || xcc == PIPE_GROUPS || xcc == PIPE_GROUPS + PIPE_GROUPS_C);
     long long* tl = p.l0.prof + 64 + (xcc == 0 ? 0 : (xcc == PIPE_GROUPS ? 2 : 4));
     if (stamp) tl[0] = wall_clock64();
 #endif
@@ -340,12 +345,12 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         if (rank < p.l0.G)
             rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_PRODUCER>(p.l0, rank, xcc, PIPE_GROUPS, p.l0.flags + xcc * REC_MAX_GROUP,
                                                                     link, smem);
-    } else if (xcc < 2 * PIPE_GROUPS) {
+    } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C) {
 #ifdef VER_TIMING_NO_CONSUMER
         return;
 #endif
         if (rank < p.l1.G)
-            rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_CONSUMER>(p.l1, rank, xcc - PIPE_GROUPS, PIPE_GROUPS,
+            rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_CONSUMER>(p.l1, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C,
                                                                     p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
     } else if (xcc < PIPE_XCDS) {
         pipe_worker<MODE, false>(p.work, link, smem);
@@ -371,9 +376,9 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     if (xcc < PIPE_GROUPS) {
         if (rank < p.l1.G)
             rec_bwd_body<MODE, MT, KS, NI, PIPE_PRODUCER>(p.l1, rank, xcc, PIPE_GROUPS, p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
-    } else if (xcc < 2 * PIPE_GROUPS) {
+    } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C) {
         if (rank < p.l0.G)
-            rec_bwd_body<MODE, MT, KS, NI, PIPE_CONSUMER>(p.l0, rank, xcc - PIPE_GROUPS, PIPE_GROUPS,
+            rec_bwd_body<MODE, MT, KS, NI, PIPE_CONSUMER>(p.l0, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C,
                                                           p.l0.flags + xcc * REC_MAX_GROUP, link, smem);
     } else if (xcc < PIPE_XCDS) {
         pipe_worker<MODE, true>(p.work, link, smem);
