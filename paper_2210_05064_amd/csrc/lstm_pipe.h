@@ -252,9 +252,6 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, 
 // does forwards because the queue hands out increasing items.
 template <int MODE, bool DESCEND>
 __device__ __forceinline__ void pipe_worker(const PipeWork& w, const PipeLink& pl, unsigned char* smem) {
-#ifdef VER_TIMING_NO_WORKERS
-    return;
-#endif
     __shared__ int s_item[4];    // chunk, local tile, ok
     __shared__ int s_Tg[PIPE_GROUPS];
     const int T_all = pl.T_all;
@@ -346,9 +343,6 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
             rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_PRODUCER>(p.l0, rank, xcc, PIPE_GROUPS, p.l0.flags + xcc * REC_MAX_GROUP,
                                                                     link, smem);
     } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C) {
-#ifdef VER_TIMING_NO_CONSUMER
-        return;
-#endif
         if (rank < p.l1.G)
             rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_CONSUMER>(p.l1, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C,
                                                                     p.l1.flags + xcc * REC_MAX_GROUP, link, smem);

@@ -163,9 +163,6 @@ __device__ __forceinline__ bool rec_wait(const int* flags, int G, int target, in
         for (;;) {
             const bool ok = pl >= G || ld_l2(&flags[pl]) >= target;
             if (__all(ok)) break;
-#ifdef VER_REC_SLEEP
-            __builtin_amdgcn_s_sleep(VER_REC_SLEEP);
-#endif
             ++spins;
             if ((spins & 1023) == 0 && (spins > REC_SPIN_LIMIT || ld_agent(err) != 0)) {
                 if (pl == 0) st_agent(err, 1);
@@ -337,9 +334,6 @@ __device__ __forceinline__ int pipe_chunk_tiles(const int32_t* t_off, const Pipe
 }
 // Consumer: blocks until the workers have finished chunk c.  False if the wait was abandoned.
 __device__ __forceinline__ bool pipe_wait_chunk(const int32_t* t_off, const PipeLink& pl, int c, int* err) {
-#ifdef VER_TIMING_NO_SYNC
-    return true;
-#endif
     __shared__ int s_ok2;
     if (threadIdx.x == 0) {
         const int need = pipe_chunk_tiles(t_off, pl, c);
@@ -618,7 +612,6 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                     const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sH + r * UH + pc * VEC);
                     *reinterpret_cast<u32x4_t*>(hprev + ((size_t)base_next + (size_t)(c0 + r) * X + x) * H + j0 + pc * VEC) = v;
                 }
-#ifndef VER_TIMING_NO_COPY
                 if (PIPE == PIPE_PRODUCER) {
                     // h_t of every row of the chunk in operand type, written through: input of the workers' GEMM
                     for (int i = tid; i < min(rows, bs - c0) * PIECES; i += REC_THREADS) {
@@ -627,7 +620,6 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                         __builtin_amdgcn_raw_buffer_store_b128(v, rs_hcopy, (((c0 + r) * X + x) * H + j0 + pc * VEC) * (int)sizeof(E), 0, 17);
                     }
                 }
-#endif
             }
         }
         REC_PROF_MARK(3);
