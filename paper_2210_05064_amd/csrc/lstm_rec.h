@@ -312,7 +312,10 @@ __device__ __forceinline__ void mma_dispatch(const f32x4_t (&wreg)[NW], const ty
 // gemm_pipe.h); the groups of the second ("consumer") layer wait for the chunk that holds their next timestep.
 // Everything that crosses XCDs is written through to memory (the L2s of different XCDs are not coherent),
 // completed (s_waitcnt) before it is announced, and announced/read with agent-scope atomics.
-constexpr int PIPE_CT = 8;           // timesteps per chunk
+#ifndef VER_PIPE_CT
+#define VER_PIPE_CT 4
+#endif
+constexpr int PIPE_CT = VER_PIPE_CT;   // timesteps per chunk
 constexpr int PIPE_BM = 128;         // rows per GEMM tile
 constexpr int PIPE_BN = 256;         // columns per GEMM tile
 enum { PIPE_NONE = 0, PIPE_PRODUCER = 1, PIPE_CONSUMER = 2 };
