@@ -99,18 +99,26 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 constexpr int GEMM_BM = 128, GEMM_BN = 128, GEMM_THREADS = 256;
 
 // Which tile a workgroup computes.  Workgroups are dealt to the 8 XCDs round-robin in launch order and every
-// XCD has its own L2, so the workgroups of one XCD are given a compact block of the tile grid (a band of
-// row tiles with all its column tiles and K-splits): the operand tiles they share are then fetched from HBM
-// once per XCD instead of once per workgroup.  bx: column tile, by: row tile, bz: K-split.
+// XCD has its own 4 MB L2, so the workgroups of one XCD are given a band of row tiles (with all its column tiles
+// and K-splits), and inside the band the ~64 workgroups that are resident at a time form an 8 x 8 block of
+// tiles: the operand tiles they share are then fetched from HBM once per block instead of once per workgroup.
+// bx: column tile, by: row tile, bz: K-split.
 __device__ __forceinline__ void gemm_tile_of_block(int& bx, int& by, int& bz) {
     const int gx = gridDim.x, gy = gridDim.y, gz = gridDim.z;
-    const int total = gx * gy * gz;
-    int id = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
-    if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
-    by = id / (gx * gz);
-    const int rem = id - by * (gx * gz);
-    bz = rem / gx;
-    bx = rem - bz * gx;
+    const int id = blockIdx.x + gx * (blockIdx.y + gy * blockIdx.z);
+    if (gy % 8 != 0) {   // no even bands: launch order as it is
+        bx = blockIdx.x; by = blockIdx.y; bz = blockIdx.z;
+        return;
+    }
+    const int R = gy / 8;                       // row tiles of a band
+    const int xcd = id % 8, slot = id / 8;      // slot: 0 .. R*gx*gz - 1 in launch order on this XCD
+    bz = slot / (R * gx);
+    const int rem = slot - bz * (R * gx);
+    const int Rb = R % 8 == 0 ? 8 : R, Cb = gx % 8 == 0 ? 8 : gx;   // block of tiles that is resident together
+    const int blk = rem / (Rb * Cb), in = rem - blk * (Rb * Cb);
+    const int blocks_x = gx / Cb;
+    by = xcd * R + (blk / blocks_x) * Rb + in / Cb;
+    bx = (blk % blocks_x) * Cb + in % Cb;
 }
 
 template <int MODE> struct GemmGeom;

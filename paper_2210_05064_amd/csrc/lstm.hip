@@ -19,21 +19,28 @@ namespace ver {
 namespace {
 
 // ---------------------------------------------------------------- weight preparation
-// dst[q][d] = W[(q%4)*H + q/4][d], optionally also dstT[d][q]; q = unit*4 + gate.
+// dst[q][d] = W[(q%4)*H + q/4][d] and dstT[d][q]; q = unit*4 + gate.  A block moves a 64 x 64 tile through LDS so
+// that the reads of W and both writes are contiguous along their fastest index.
 template <typename E>
-__global__ void prep_matrix_kernel(const float* __restrict__ W, int H, int cols, E* __restrict__ dst,
-                                   E* __restrict__ dstT) {
-    const size_t n = (size_t)4 * H * cols;
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        const int q = (int)(i / cols), d = (int)(i % cols);
-        const float v = W[((size_t)(q & 3) * H + (q >> 2)) * cols + d];
-        dst[i] = cvt_elem<E>(v);
-    }
-    if (dstT)
-        for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-            const int d = (int)(i / (4 * H)), q = (int)(i % (4 * H));
-            dstT[i] = cvt_elem<E>(W[((size_t)(q & 3) * H + (q >> 2)) * cols + d]);
+__global__ __launch_bounds__(256) void prep_matrix_kernel(const float* __restrict__ W, int H, int cols, E* __restrict__ dst,
+                                                          E* __restrict__ dstT) {
+    __shared__ float tile[64][65];
+    const int q0 = blockIdx.y * 64, d0 = blockIdx.x * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const int q = q0 + r, d = d0 + tx;
+        float v = 0.f;
+        if (d < cols) {   // 4H is a multiple of 64: q is always a valid row
+            v = W[((size_t)(q & 3) * H + (q >> 2)) * cols + d];
+            dst[(size_t)q * cols + d] = cvt_elem<E>(v);
         }
+        tile[r][tx] = v;
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const int d = d0 + r, q = q0 + tx;
+        if (d < cols) dstT[(size_t)d * 4 * H + q] = cvt_elem<E>(tile[tx][r]);
+    }
 }
 
 __global__ void prep_bias_kernel(const float* __restrict__ b_ih, const float* __restrict__ b_hh, int H,
@@ -52,40 +59,40 @@ __device__ __forceinline__ float wave_sum_all(float v) {
     return v;
 }
 
-// head_out[p][a] = W_a[a] . h[p] + b_a[a];  value[p] = w_v . h[p] + b_v.  One wave per HF_ROWS rows: the rows stay
-// in registers for all heads (H <= 1024) and a head weight is read once for all of them.
-constexpr int HF_ROWS = 4;
+// head_out[p][a] = W_a[a] . h[p] + b_a[a];  value[p] = w_v . h[p] + b_v: a skinny fp32 GEMM (at most 64 columns)
+// bound by reading h once.  One wave per 16 rows, fp32 MFMA 16x16x4 with the heads (action outputs, then the
+// value) on the N dimension, 16 at a time.
 __global__ __launch_bounds__(256) void heads_fwd_kernel(const float* __restrict__ h, int M, int H, int A,
                                                         const float* __restrict__ W_a, const float* __restrict__ b_a,
                                                         const float* __restrict__ w_v, const float* __restrict__ b_v,
                                                         float* __restrict__ head_out, float* __restrict__ value) {
-    const int lane = threadIdx.x & 63;
-    const int p0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * HF_ROWS;
+    const int lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4;
+    const int p0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 16;
     if (p0 >= M) return;
-    float hv[HF_ROWS][16];
+    const bool row_ok = p0 + lr < M;
+    const float* hrow = h + (size_t)(row_ok ? p0 + lr : p0) * H + lk * 4;
+    for (int ht = 0; ht * 16 <= A; ++ht) {
+        const int hd = ht * 16 + lr;   // this lane's head as B operand
+        const float* wrow = (hd < A ? W_a + (size_t)hd * H : w_v) + lk * 4;
+        const bool head_ok = hd <= A;
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        for (int k0 = 0; k0 < H; k0 += 16) {
+            f32x4_t av = *reinterpret_cast<const f32x4_t*>(hrow + k0);
+            f32x4_t wv = *reinterpret_cast<const f32x4_t*>(wrow + k0);
+            if (!row_ok) av = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            if (!head_ok) wv = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int r = 0; r < HF_ROWS; ++r)
+            for (int e = 0; e < 4; ++e) acc = mfma_f32_16x16x4(av[e], wv[e], acc);
+        }
+        // element r of the lane: row lk*4 + r, head ht*16 + lr
+        if (head_ok) {
+            const float bias = hd < A ? b_a[hd] : b_v[0];
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            hv[r][i] = (p0 + r < M && lane + i * 64 < H) ? h[(size_t)(p0 + r) * H + lane + i * 64] : 0.f;
-    for (int a = 0; a <= A; ++a) {
-        const float* w = (a < A) ? W_a + (size_t)a * H : w_v;
-        float s[HF_ROWS];
-#pragma unroll
-        for (int r = 0; r < HF_ROWS; ++r) s[r] = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i)
-            if (lane + i * 64 < H) {
-                const float wv = w[lane + i * 64];
-#pragma unroll
-                for (int r = 0; r < HF_ROWS; ++r) s[r] += hv[r][i] * wv;
-            }
-#pragma unroll
-        for (int r = 0; r < HF_ROWS; ++r) {
-            const float t = wave_sum_all(s[r]);
-            if (lane == 0 && p0 + r < M) {
-                if (a < A) head_out[(size_t)(p0 + r) * A + a] = t + b_a[a];
-                else value[p0 + r] = t + b_v[0];
+            for (int r = 0; r < 4; ++r) {
+                const int p = p0 + lk * 4 + r;
+                if (p >= M) continue;
+                if (hd < A) head_out[(size_t)p * A + hd] = acc[r] + bias;
+                else value[p] = acc[r] + bias;
             }
         }
     }
@@ -394,10 +401,10 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         const int D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws.layer[l];
         ProfScope prof(VER_PROF_LSTM_PREP, s);
-        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, w[4 * l], H, D, static_cast<E*>(L.wih),
-                           static_cast<E*>(L.wihT));
-        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3(1024), dim3(256), 0, s, w[4 * l + 1], H, H, static_cast<E*>(L.whh),
-                           static_cast<E*>(L.whhT));
+        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3((D + 63) / 64, 4 * H / 64), dim3(256), 0, s, w[4 * l], H, D,
+                           static_cast<E*>(L.wih), static_cast<E*>(L.wihT));
+        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3((H + 63) / 64, 4 * H / 64), dim3(256), 0, s, w[4 * l + 1], H, H,
+                           static_cast<E*>(L.whh), static_cast<E*>(L.whhT));
         hipLaunchKernelGGL(prep_bias_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, w[4 * l + 2], w[4 * l + 3], H, L.bias);
     };
     // time-batched input projection: gates[M, 4H] = x W_ih^T + (b_ih + b_hh), interleaved columns
@@ -477,7 +484,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
 #undef VER_FWD_DISPATCH
 #undef VER_FWD_LAUNCH
     ProfScope prof(VER_PROF_HEADS_FWD, s);
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 4 * HF_ROWS - 1) / (4 * HF_ROWS)), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 63) / 64), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
                        w[4 * c.n_layers], w[4 * c.n_layers + 1], w[4 * c.n_layers + 2], w[4 * c.n_layers + 3],
                        head_out, value);
     return launch_status();
