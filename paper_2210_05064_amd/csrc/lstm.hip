@@ -158,6 +158,25 @@ __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* _
     }
 }
 
+// Bias gradients of the heads: db_a[a] = sum_p d_u[p][a], db_v = sum_p d_v[p].  One block per head; a thread
+// adds a strided share of the rows, the block adds the shares in a fixed tree (deterministic).
+__global__ __launch_bounds__(256) void heads_bias_grad_kernel(const float* __restrict__ d_u, const float* __restrict__ d_v,
+                                                              int M, int A, float* __restrict__ db_a, float* __restrict__ db_v) {
+    __shared__ float red[256];
+    const int a = blockIdx.x;
+    float s = 0.f;
+    for (int p = threadIdx.x; p < M; p += 256) s += (a < A) ? d_u[(size_t)p * A + a] : d_v[p];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        if (a < A) db_a[a] = red[0]; else db_v[0] = red[0];
+    }
+}
+
 __global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __restrict__ part, int n_rb, int H, int A,
                                                                 float* __restrict__ dW_a, float* __restrict__ dw_v) {
     const int j = blockIdx.x * 256 + threadIdx.x;
@@ -508,13 +527,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
                        A, ws.part);
     hipLaunchKernelGGL(heads_wgrad_final_kernel, dim3((H + 255) / 256, A + 1), dim3(256), 0, s, ws.part, rb_h, H, A,
                        gw[4 * nl], gw[4 * nl + 2]);
-    hipLaunchKernelGGL(colsum_partial_kernel<float>, dim3((A + 255) / 256, rb_c), dim3(256), 0, s, d_u, M, A, A,
-                       ws.part);
-    hipLaunchKernelGGL(colsum_final_kernel, dim3((A + 255) / 256), dim3(256), 0, s, ws.part, rb_c, A, 0, gw[4 * nl + 1],
-                       (float*)nullptr);
-    hipLaunchKernelGGL(colsum_partial_kernel<float>, dim3(1, rb_c), dim3(256), 0, s, d_v, M, 1, 1, ws.part);
-    hipLaunchKernelGGL(colsum_final_kernel, dim3(1), dim3(256), 0, s, ws.part, rb_c, 1, 0, gw[4 * nl + 3],
-                       (float*)nullptr);
+    hipLaunchKernelGGL(heads_bias_grad_kernel, dim3(A + 1), dim3(256), 0, s, d_u, d_v, M, A, gw[4 * nl + 1], gw[4 * nl + 3]);
     }
 
     // one wave per (16 units, share of the 4H contraction): 2 tiles x 4 when H/16 > 32 workgroups, else 1 x 8
