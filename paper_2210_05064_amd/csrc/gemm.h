@@ -308,7 +308,14 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restric
 // p ^ swz(k), swz(k) = 2*(k&3) | 8*((k>>3)&1), so that the 32 lanes served together (rows k..k+3 and k+8..k+11,
 // two chunks each) touch every bank once.  A load instruction fills 4 rows (lane -> row lane/16, position
 // lane%16): the swizzle is applied on the global side.
-constexpr int TN_BK = 32, TN_STAGES = 4, TN_STAGE_BYTES = 2 * TN_BK * 256;
+constexpr int TN_BK = 32;
+// WM: 16-row tiles per wave along m (wave tile 16*WM x 64, workgroup tile 32*WM x 128).  WM = 8 halves the LDS
+// bytes read per MFMA (the limit of the 64 x 64 wave tile) at the price of one stage less in flight.
+template <int WM> struct TnGeom {
+    static constexpr int BM = 32 * WM, ROW_A = BM * 2, STAGE = TN_BK * (ROW_A + 256), STAGES = WM == 8 ? 3 : 4;
+    static constexpr int NA = TN_BK * ROW_A / 1024 / 4;   // A load instructions per wave and stage
+    static constexpr int LDS = STAGES * STAGE;
+};
 #ifndef VER_TN_TARGET_WGS
 #define VER_TN_TARGET_WGS 512
 #endif
@@ -316,15 +323,17 @@ constexpr int TN_TARGET_WGS = VER_TN_TARGET_WGS;
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ int tn_swz(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
 
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_kernel(
+template <int WM>
+__device__ __forceinline__ void gemm_tn_dma_body(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb, float* __restrict__ C, int ldc,
-    int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride) {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[TN_STAGES * TN_STAGE_BYTES];
+    int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride, unsigned char* smem) {
+    typedef TnGeom<WM> G;
+    constexpr int TN_STAGES = G::STAGES, TN_STAGE_BYTES = G::STAGE, ROW_A = G::ROW_A, NA = G::NA;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int wm = (wave >> 1) * 16 * WM, wn = (wave & 1) * 64;
     int bx, by, bz;
     gemm_tile_of_block(bx, by, bz);
-    const int m0 = by * GEMM_BM, n0 = bx * GEMM_BN;
+    const int m0 = by * G::BM, n0 = bx * GEMM_BN;
     const int lr = lane & 15, lk = lane >> 4;
     const int k_begin = bz * k_chunk, k_end = min(K, k_begin + k_chunk);
     const int nk = (k_end - k_begin + TN_BK - 1) / TN_BK;
@@ -333,55 +342,71 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_kernel(
     // rows beyond K read zero (buffer bounds); columns beyond the matrix only feed outputs that are not stored
     __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, (int)min((size_t)K * lda * 2, (size_t)0x7fffffff), 0x00020000);
     __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(B), 0, (int)min((size_t)K * ldb * 2, (size_t)0x7fffffff), 0x00020000);
-    // this lane's part of the 2 + 2 load instructions of its wave per stage
-    int voffA[2], voffB[2];
+    // this lane's part of the NA + 2 load instructions of its wave per stage (an instruction fills 1 KB of LDS:
+    // 1024 / ROW_A rows of A, 4 rows of B)
+    int voffA[NA], voffB[2];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const int k = (wave * NA + j) * (1024 / ROW_A) + lane / (ROW_A / 16), c = (lane % (ROW_A / 16)) ^ tn_swz(k);
+        voffA[j] = k * lda * 2 + m0 * 2 + c * 16;
+    }
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int k = (wave * 2 + j) * 4 + (lane >> 4), c = (lane & 15) ^ tn_swz(k);
-        voffA[j] = k * lda * 2 + m0 * 2 + c * 16;
         voffB[j] = k * ldb * 2 + n0 * 2 + c * 16;
     }
     auto issue = [&](int kt) {
         unsigned char* st = smem + (kt % TN_STAGES) * TN_STAGE_BYTES;
         const int k0 = k_begin + kt * TN_BK;
+        // the row goes into the per-lane offset: only that one is checked against the buffer bounds
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            // the row goes into the per-lane offset: only that one is checked against the buffer bounds
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)(st + (wave * 2 + j) * 1024), 16, voffA[j] + k0 * lda * 2, 0, 0, 0);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr_t)(st + TN_BK * 256 + (wave * 2 + j) * 1024), 16,
+        for (int j = 0; j < NA; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)(st + (wave * NA + j) * 1024), 16, voffA[j] + k0 * lda * 2, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr_t)(st + TN_BK * ROW_A + (wave * 2 + j) * 1024), 16,
                                                      voffB[j] + k0 * ldb * 2, 0, 0, 0);
-        }
     };
     // operand read offsets: source row k = lk*8 + lr/4 (+4 for the second half), columns tile*16 + 4*(lr%4)..+3
-    int offA[4][2], offB[4][2];
+    int offA[WM][2], offB[4][2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int h = 0; h < 2; ++h) {
+        const int k = lk * 8 + (lr >> 2) + 4 * h;
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int k = lk * 8 + (lr >> 2) + 4 * h;
-            const int colA = wm + i * 16 + 4 * (lr & 3), colB = wn + i * 16 + 4 * (lr & 3);
-            offA[i][h] = k * 256 + ((((colA * 2) >> 4) ^ tn_swz(k)) << 4) + ((colA * 2) & 8);
-            offB[i][h] = TN_BK * 256 + k * 256 + ((((colB * 2) >> 4) ^ tn_swz(k)) << 4) + ((colB * 2) & 8);
+        for (int i = 0; i < WM; ++i) {
+            const int colA = wm + i * 16 + 4 * (lr & 3);
+            offA[i][h] = k * ROW_A + ((((colA * 2) >> 4) ^ tn_swz(k)) << 4) + ((colA * 2) & 8);
         }
-    f32x4_t acc[4][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i) {
+            const int colB = wn + i * 16 + 4 * (lr & 3);
+            offB[i][h] = TN_BK * ROW_A + k * 256 + ((((colB * 2) >> 4) ^ tn_swz(k)) << 4) + ((colB * 2) & 8);
+        }
+    }
+    f32x4_t acc[WM][4];
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     for (int kt = 0; kt < TN_STAGES - 1 && kt < nk; ++kt) issue(kt);
     for (int kt = 0; kt < nk; ++kt) {
-        // this wave's 4 loads of stage kt have landed; up to two younger stages (8 loads) may be in flight
+        // this wave's NA + 2 loads of stage kt have landed; up to STAGES - 2 younger stages may be in flight
         const int younger = min(nk - 1 - kt, TN_STAGES - 2);
-        if (younger >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if (younger == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (WM == 8) {
+            if (younger >= 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
+            if (younger >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+            else if (younger == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         bar_lds();   // everyone's loads of stage kt have landed, and everyone is done reading stage kt-1
         if (kt + TN_STAGES - 1 < nk) issue(kt + TN_STAGES - 1);
         const unsigned char* st = smem + (kt % TN_STAGES) * TN_STAGE_BYTES;
-        u16x8_t a[4], b[4];
+        u16x8_t a[WM], b[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < WM; ++i) {
             const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offA[i][0]));
             const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offA[i][1]));
             a[i] = u16x8_t{(bf16_t)lo[0], (bf16_t)lo[1], (bf16_t)lo[2], (bf16_t)lo[3], (bf16_t)hi[0], (bf16_t)hi[1], (bf16_t)hi[2], (bf16_t)hi[3]};
@@ -393,13 +418,13 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_kernel(
             b[j] = u16x8_t{(bf16_t)lo[0], (bf16_t)lo[1], (bf16_t)lo[2], (bf16_t)lo[3], (bf16_t)hi[0], (bf16_t)hi[1], (bf16_t)hi[2], (bf16_t)hi[3]};
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < WM; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16_16x16x32(a[i], b[j], acc[i][j]);
     }
     // C fragment: element r of lane l is row (l / 16) * 4 + r, column l % 16 of the 16x16 tile.
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = n0 + wn + j * 16 + lr;
@@ -412,6 +437,20 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_kernel(
                 C[(size_t)out_row * ldc + n] = acc[i][j][r];
             }
         }
+}
+
+// (plain kernels around the template body: the transposing-load builtin only exists in the device pass)
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_kernel(
+    const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb, float* __restrict__ C, int ldc,
+    int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    gemm_tn_dma_body<4>(A, lda, B, ldb, C, ldc, Mr, Nc, K, unperm_h, k_chunk, split_stride, smem);
+}
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_tall_kernel(
+    const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb, float* __restrict__ C, int ldc,
+    int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    gemm_tn_dma_body<8>(A, lda, B, ldb, C, ldc, Mr, Nc, K, unperm_h, k_chunk, split_stride, smem);
 }
 
 // How many ways to split the contraction so that the grid has a few workgroups per CU.
@@ -439,6 +478,8 @@ inline void gemm_launch(const TA* A, int lda, const TB* B, int ldb, float* C, in
         // both operands bf16 and K-minor: the LDS-direct kernel (bias is never used with these shapes)
         if (!bias && lda % 2 == 0 && ldb % 2 == 0 && (size_t)K * lda * 2 < 0x7fffffff && (size_t)K * ldb * 2 < 0x7fffffff) {
             // two workgroups fit on a CU: aim at one full round of 512
+            const bool tall = Mr % 256 == 0 && Mr >= 2048;   // 256-row tiles when there are enough of them
+            if (tall) grid.y = Mr / 256;
             const int tiles = grid.x * grid.y;
             int sp = (allow_split && part) ? (TN_TARGET_WGS + tiles / 2) / tiles : 1;
             const int max_sp = K / (8 * TN_BK) > 0 ? K / (8 * TN_BK) : 1;
@@ -449,9 +490,19 @@ inline void gemm_launch(const TA* A, int lda, const TB* B, int ldb, float* C, in
             const int splits = sp;
             const int k_chunk = splits == 1 ? K : ((K + splits - 1) / splits + BK - 1) / BK * BK;
             const size_t stride = (size_t)Mr * Nc;
-            hipLaunchKernelGGL(gemm_tn_dma_kernel, grid, dim3(GEMM_THREADS), 0, s, reinterpret_cast<const bf16_t*>(A), lda,
-                               reinterpret_cast<const bf16_t*>(B), ldb, splits == 1 ? C : part, splits == 1 ? ldc : Nc, Mr, Nc, K,
-                               unperm_h, k_chunk, stride);
+            if (tall) {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_dma_tall_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    TnGeom<8>::LDS);
+                hipLaunchKernelGGL(gemm_tn_dma_tall_kernel, grid, dim3(GEMM_THREADS), TnGeom<8>::LDS, s, reinterpret_cast<const bf16_t*>(A),
+                                   lda, reinterpret_cast<const bf16_t*>(B), ldb, splits == 1 ? C : part, splits == 1 ? ldc : Nc, Mr, Nc,
+                                   K, unperm_h, k_chunk, stride);
+            } else {
+                (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_dma_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    TnGeom<4>::LDS);
+                hipLaunchKernelGGL(gemm_tn_dma_kernel, grid, dim3(GEMM_THREADS), TnGeom<4>::LDS, s, reinterpret_cast<const bf16_t*>(A),
+                                   lda, reinterpret_cast<const bf16_t*>(B), ldb, splits == 1 ? C : part, splits == 1 ? ldc : Nc, Mr, Nc,
+                                   K, unperm_h, k_chunk, stride);
+            }
             if (splits > 1)
                 hipLaunchKernelGGL(gemm_reduce_kernel, dim3(1024), dim3(256), 0, s, part, splits, stride, Mr, Nc, C, ldc, bias,
                                    unperm_h);
