@@ -6,8 +6,8 @@
 // loops run side by side, a few timesteps apart, instead of one after the other.
 //
 //   XCD 0..2   time loop of the producer layer (forward: layer 0; backward: layer 1), pieces dealt to 3 groups
-//   XCD 3..5   time loop of the consumer layer, same dealing
-//   XCD 6..7   workers: for every finished chunk of PIPE_CT timesteps, the GEMM that turns the producer's rows
+//   XCD 3..5   time loop of the consumer layer, same dealing (backward: XCD 3..6, 4 groups)
+//   the rest   workers: for every finished chunk of PIPE_CT timesteps, the GEMM that turns the producer's rows
 //              into the consumer's input (forward: gates_1 = h_0 W_ih1^T + b; backward: dh_0 = dz_1 W_ih1),
 //              one 128 x 256 tile at a time from a shared queue, in the order the consumer needs them
 //
@@ -22,12 +22,9 @@
 
 namespace ver {
 
-#ifndef VER_PIPE_P
-#define VER_PIPE_P 3
-#define VER_PIPE_C 3
-#endif
-constexpr int PIPE_GROUPS = VER_PIPE_P;   // groups (XCDs) of the producer layer
-constexpr int PIPE_GROUPS_C = VER_PIPE_C; // groups (XCDs) of the consumer layer
+constexpr int PIPE_GROUPS = 3;        // groups (XCDs) of the producer layer
+constexpr int PIPE_GROUPS_C_FWD = 3;  // groups of the consumer layer, forward: two XCDs of workers
+constexpr int PIPE_GROUPS_C_BWD = 4;  // backward (heavier steps, lighter GEMM): one XCD of workers (measured best)
 constexpr int PIPE_XCDS = 8;         // XCDs of the chip: those beyond the two layers' groups are workers
 
 struct PipeWork {
@@ -334,7 +331,7 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     PipeLink link = p.link;
     link.T_all = p.l0.info[1];
 #ifdef VER_REC_PROF
-    const bool stamp = threadIdx.x == 0 && rank == 0 && (xcc == 0 || xcc == PIPE_GROUPS || xcc == PIPE_GROUPS + PIPE_GROUPS_C);
+    const bool stamp = threadIdx.x == 0 && rank == 0 && (xcc == 0 || xcc == PIPE_GROUPS || xcc == PIPE_GROUPS + PIPE_GROUPS_C_FWD);
     long long* tl = p.l0.prof + 64 + (xcc == 0 ? 0 : (xcc == PIPE_GROUPS ? 2 : 4));
     if (stamp) tl[0] = wall_clock64();
 #endif
@@ -342,9 +339,9 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         if (rank < p.l0.G)
             rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_PRODUCER>(p.l0, rank, xcc, PIPE_GROUPS, p.l0.flags + xcc * REC_MAX_GROUP,
                                                                     link, smem);
-    } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C) {
+    } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C_FWD) {
         if (rank < p.l1.G)
-            rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_CONSUMER>(p.l1, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C,
+            rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_CONSUMER>(p.l1, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C_FWD,
                                                                     p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
     } else if (xcc < PIPE_XCDS) {
         pipe_worker<MODE, false>(p.work, link, smem);
@@ -370,9 +367,9 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     if (xcc < PIPE_GROUPS) {
         if (rank < p.l1.G)
             rec_bwd_body<MODE, MT, KS, NI, PIPE_PRODUCER>(p.l1, rank, xcc, PIPE_GROUPS, p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
-    } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C) {
+    } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C_BWD) {
         if (rank < p.l0.G)
-            rec_bwd_body<MODE, MT, KS, NI, PIPE_CONSUMER>(p.l0, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C,
+            rec_bwd_body<MODE, MT, KS, NI, PIPE_CONSUMER>(p.l0, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C_BWD,
                                                           p.l0.flags + xcc * REC_MAX_GROUP, link, smem);
     } else if (xcc < PIPE_XCDS) {
         pipe_worker<MODE, true>(p.work, link, smem);
