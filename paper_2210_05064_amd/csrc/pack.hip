@@ -61,6 +61,8 @@ __device__ __forceinline__ int block_scan_incl(int v, int* s_w, int* total) {
     return v + s_w[wave];
 }
 
+constexpr int IDX_SL_CACHE = 4096;   // sorted piece lengths kept in LDS for the per-timestep counts
+
 __global__ __launch_bounds__(IDX_THREADS) void pack_index_kernel(
     const uint8_t* __restrict__ dones, const int32_t* __restrict__ env_off,
     const uint8_t* __restrict__ env_started_episode, const uint32_t* __restrict__ seq_key,
@@ -92,10 +94,15 @@ __global__ __launch_bounds__(IDX_THREADS) void pack_index_kernel(
     const int chunk = ((S + IDX_WAVES - 1) / IDX_WAVES + VER_WAVE - 1) / VER_WAVE * VER_WAVE;
     const int c_lo = min(S, wave * chunk), c_hi = min(S, c_lo + chunk);
     int cnt = 0;
-    for (int k0 = c_lo; k0 < c_hi; k0 += VER_WAVE) {
-        const int k = k0 + lane;
-        const bool st = k < c_hi && (ws.flags[k] & 1);
-        cnt += __popcll(__ballot(st));
+    for (int k0 = c_lo; k0 < c_hi; k0 += 8 * VER_WAVE) {   // 8 loads in flight per lane
+        unsigned char f[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + u * VER_WAVE + lane;
+            f[u] = k < c_hi ? ws.flags[k] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cnt += __popcll(__ballot((f[u] & 1) != 0));
     }
     if (lane == 0) s_cnt[wave] = cnt;
     __syncthreads();
@@ -111,16 +118,25 @@ __global__ __launch_bounds__(IDX_THREADS) void pack_index_kernel(
     __syncthreads();
     const int K = s_cnt[IDX_WAVES];
     int base = s_cnt[wave];
-    for (int k0 = c_lo; k0 < c_hi; k0 += VER_WAVE) {
-        const int k = k0 + lane;
-        const bool st = k < c_hi && (ws.flags[k] & 1);
-        const unsigned long long mask = __ballot(st);
-        if (st) {
-            const int id = base + __popcll(mask & ((1ull << lane) - 1ull));
-            ws.sf[id] = k;
-            ws.skey[id] = seq_key[k];
+    for (int k0 = c_lo; k0 < c_hi; k0 += 8 * VER_WAVE) {
+        unsigned char f[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + u * VER_WAVE + lane;
+            f[u] = k < c_hi ? ws.flags[k] : 0;
         }
-        base += __popcll(mask);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + u * VER_WAVE + lane;
+            const bool st = (f[u] & 1) != 0;
+            const unsigned long long mask = __ballot(st);
+            if (st) {
+                const int id = base + __popcll(mask & ((1ull << lane) - 1ull));
+                ws.sf[id] = k;
+                ws.skey[id] = seq_key[k];
+            }
+            base += __popcll(mask);
+        }
     }
     __syncthreads();
     for (int s = tid; s < K; s += IDX_THREADS) ws.sl[s] = ((s + 1 < K) ? ws.sf[s + 1] : S) - ws.sf[s];
@@ -204,9 +220,14 @@ __global__ __launch_bounds__(IDX_THREADS) void pack_index_kernel(
     __syncthreads();
     const int t_max = n_seq > 0 ? seq_len[0] : 0;
 
-    // 7. rows per timestep and their offsets.
+    // 7. rows per timestep and their offsets.  Only the first t_max timesteps have rows: they are counted by a
+    // binary search over the sorted lengths (kept in LDS as far as they fit) and scanned; the rest is filled in.
+    __shared__ int s_sl[IDX_SL_CACHE];
+    for (int j = tid; j < min(n_seq, IDX_SL_CACHE); j += IDX_THREADS) s_sl[j] = seq_len[j];
+    __syncthreads();
     run = 0;
-    for (int t0 = 0; t0 <= M; t0 += IDX_THREADS) {
+    int t_done = 0;
+    for (int t0 = 0; t0 < t_max; t0 += IDX_THREADS) {
         const int t = t0 + tid;
         int bs = 0;
         if (t < t_max) {
@@ -214,7 +235,8 @@ __global__ __launch_bounds__(IDX_THREADS) void pack_index_kernel(
             int a = 0, z = n_seq;  // invariant: seq_len[a-1] > t (or a == 0), seq_len[z] <= t (or z == n_seq)
             while (a < z) {
                 const int mid = (a + z) >> 1;
-                if (seq_len[mid] > t) a = mid + 1; else z = mid;
+                const int len = mid < IDX_SL_CACHE ? s_sl[mid] : seq_len[mid];
+                if (len > t) a = mid + 1; else z = mid;
             }
             bs = a;
         }
@@ -223,6 +245,11 @@ __global__ __launch_bounds__(IDX_THREADS) void pack_index_kernel(
         if (t < M) batch_sizes[t] = bs;
         if (t <= M) t_off[t] = run + incl - bs;
         run += total;
+        t_done = t0 + IDX_THREADS;
+    }
+    for (int t = t_done + tid; t <= M; t += IDX_THREADS) {   // run == M here (or 0 when the minibatch is empty)
+        if (t < M) batch_sizes[t] = 0;
+        t_off[t] = run;
     }
     if (tid == 0) {
         info[0] = n_seq;
