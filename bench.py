@@ -28,7 +28,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 # HBM bytes per launch (read + written) of the dominant kernel class (with two layers: the launch that runs both
 # time loops of one direction), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a copy of
 # known size: see profiles/hbm_traffic_max_workload.md.  None where unmeasured.
-MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 1390.6e6, ("max", "lstm_rec_fwd"): 1698.4e6}
+MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 1785.9e6, ("max", "lstm_rec_fwd"): 2016.2e6}
 
 
 def collection_logp(ro, compute, x_bf16):
@@ -195,7 +195,9 @@ def main():
                    "act_dim": w.act_dim, "epochs": w.epochs, "minibatches": w.minibatches,
                    "rows_per_minibatch": M, "seed": args.seed},
         "step_passes_per_sec": S * w.epochs / (elapsed / args.steps),
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_TFLOPS[dtype],
+        "roofline": {"bound": "mfma", "kernel": dom,
+                     "kernel_symbol": ("lstm_pipe_" if w.n_layers == 2 else "lstm_rec_") + dom[-3:] + "_kernel",
+                     "achieved": achieved, "peak": PEAK_TFLOPS[dtype],
                      "unit": "TFLOP/s", "frac": achieved / PEAK_TFLOPS[dtype],
                      "traffic": MEASURED_TRAFFIC.get((w.name, dom)),
                      "avg_launch_ms": dom_ms / dom_n, "launches": dom_n, "flops_per_launch": flops_per_launch,
