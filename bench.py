@@ -3,7 +3,7 @@
 
 A "step" is one full PPO update over one synthetic ragged rollout: ver_gae
 once, then epochs x minibatches x (ver_pack_minibatch, ver_lstm_fwd,
-ver_ppo_loss, ver_lstm_bwd).  All inputs are resident in HBM before the timed
+ver_ppo_loss, ver_lstm_bwd, ver_adam_step).  All inputs are resident in HBM before the timed
 region.  Prints ONE JSON line: learner env-steps/s, the roofline position of
 the dominant kernel (timed with HIP events inside the library during the timed
 region) and the CPU oracle timed on a bounded sample of the same workload.
@@ -63,7 +63,7 @@ def cpu_baseline(ro, budget_s=15.0):
     GAE over the whole buffer, one minibatch's packing and loss in full, and the
     LSTM forward/backward over as many of that minibatch's pieces (shortest
     first) as fit the time budget, scaled to the whole update by step count."""
-    from oracle import gae as ogae, lstm as olstm, pack as opack, ppo_loss as oloss
+    from oracle import adam as oadam, gae as ogae, lstm as olstm, pack as opack, ppo_loss as oloss
     w = ro["workload"]
     S, B, E = ro["S"], w.minibatches, w.epochs
     t0 = time.perf_counter()
@@ -94,7 +94,12 @@ def cpu_baseline(ro, budget_s=15.0):
                    opack.gather_rows(adv, meta["gather_idx"]), opack.gather_rows(ret, meta["gather_idx"]),
                    w.clip, w.value_coef, w.entropy_coef)
     t_loss = time.perf_counter() - t0
-    t_update = t_gae + E * B * (t_pack + t_lstm + t_loss)
+    flat = [W["layers"][l][k] for l in range(w.n_layers) for k in ("W_ih", "W_hh", "b_ih", "b_hh")] + \
+           [W["W_a"], W["b_a"], W["w_v"], W["b_v"], W["log_std"]]
+    t0 = time.perf_counter()
+    oadam.adam_step(flat, flat, [np.zeros_like(x) for x in flat], [np.zeros_like(x) for x in flat], 1, 2.5e-4)
+    t_adam = time.perf_counter() - t0
+    t_update = t_gae + E * B * (t_pack + t_lstm + t_loss + t_adam)
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -104,7 +109,8 @@ def cpu_baseline(ro, budget_s=15.0):
         "value": S / t_update, "unit": "env-steps/s", "cores": int(cores), "kind": "oracle",
         "sample": (f"GAE on all {S} steps ({t_gae:.2f}s); packing ({t_pack:.2f}s) and loss ({t_loss:.2f}s) of one "
                    f"minibatch of {M} rows in full; LSTM fwd+bwd on {steps} steps of that minibatch's shortest "
-                   f"pieces, scaled to {M} rows ({t_lstm:.1f}s); update = GAE + {E}x{B} minibatches"),
+                   f"pieces, scaled to {M} rows ({t_lstm:.1f}s); Adam step on all weights ({t_adam:.2f}s); "
+                   f"update = GAE + {E}x{B} minibatches"),
     }
 
 
@@ -144,7 +150,8 @@ def main():
 
     w = wl.WORKLOADS[args.workload]
     ro = wl.make_rollout(w, seed=args.seed)
-    learner = Learner(ro)
+    # the optimiser runs inside the update: Adam with the paper's cosine schedule over its 500 M training steps
+    learner = Learner(ro, adam_total_steps=max(1, int(500e6 // ro["S"])) * w.epochs * w.minibatches)
     learner.logp_old.copy_(collection_logp(ro, learner.compute, learner.x_bf16))
     torch.cuda.synchronize()
 

@@ -276,6 +276,46 @@ int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M,
                  void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * ver_adam_step - the optimiser step that follows ver_lstm_bwd.
+ * Paper: section 4 "Training" and the appendix hyper-parameter table: Adam,
+ * initial learning rate 2.5e-4 decayed to zero with a cosine schedule.  The
+ * optimiser is only cited: this is the bias-corrected step of the cited Adam
+ * paper,
+ *   m <- beta1 m + (1-beta1) g,  v <- beta2 v + (1-beta2) g^2,
+ *   p <- p - lr_k * (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps),  t = k+1,
+ * with lr_k = lr_final + (lr0 - lr_final) * (1 + cos(pi * min(k, total_steps)
+ * / total_steps)) / 2 for the k-th step counted from 0.  Readings where the
+ * paper is silent: beta1 0.9, beta2 0.999, eps 1e-8 are the caller's to set
+ * (defaults of the cited paper); no weight decay; gradient clipping is
+ * optional, by the global 2-norm over all tensors of the call:
+ * g <- g * min(1, max_grad_norm / (norm + 1e-6)), off when max_grad_norm <= 0.
+ *
+ * params, grads, exp_avg, exp_avg_sq: host arrays of n_tensors device
+ * pointers (float, 16-byte aligned; grads are read only, the other three are
+ * updated in place); sizes: host array of element counts (may be 0).
+ * n_tensors <= VER_ADAM_MAX_TENSORS.  step_index = k (0 for the first step).
+ * grad_norm: device float[1] that receives the global 2-norm of the gradients
+ * before clipping, or NULL (only allowed without clipping).  All tensors are
+ * handled by one launch (28 bytes of HBM traffic per parameter); the norm, when
+ * asked for, by a deterministic two-stage reduction before it.
+ * Errors: VER_EINVAL (null pointers, negative sizes, total_steps <= 0,
+ * n_tensors out of range, clipping without grad_norm), VER_EWORKSPACE.
+ */
+#define VER_ADAM_MAX_TENSORS 48
+typedef struct {
+    float lr0;            /* initial learning rate (paper: 2.5e-4) */
+    float lr_final;       /* final learning rate (paper: 0) */
+    int64_t total_steps;  /* optimiser steps over which the cosine runs */
+    float beta1, beta2, eps;
+    float max_grad_norm;  /* <= 0: no clipping */
+} ver_adam_cfg;
+
+size_t ver_adam_workspace_bytes(void);
+int ver_adam_step(const ver_adam_cfg* cfg, int32_t n_tensors, float* const* params, const float* const* grads,
+                  float* const* exp_avg, float* const* exp_avg_sq, const int64_t* sizes, int64_t step_index,
+                  float* grad_norm, void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * Kernel timing for benchmarks (measurement plumbing, not part of the method).
  * While enabled, the library brackets the kernels of the selected classes with
  * HIP events on the stream of the call.  ver_profile_read waits for the
@@ -297,7 +337,8 @@ enum {
     VER_PROF_LSTM_GEMM_DX = 10,
     VER_PROF_LSTM_GEMM_DW = 11,
     VER_PROF_LSTM_DBIAS = 12,
-    VER_PROF_COUNT = 13
+    VER_PROF_ADAM = 13,
+    VER_PROF_COUNT = 14
 };
 int ver_profile_enable(uint32_t mask);
 int ver_profile_read(double* total_ms, int64_t* launches);

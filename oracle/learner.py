@@ -9,7 +9,7 @@ file.
 """
 import numpy as np
 
-from . import lstm, pack, ppo_loss
+from . import adam, lstm, pack, ppo_loss
 
 
 def minibatch_step(rollout_fields, weights, meta, cfg, adv, ret, logp_old, h0=None, c0=None,
@@ -64,3 +64,61 @@ def collection_logp(rollout_fields, weights, dones, env_off, dist, env_started_e
             logp[f0 + t] = ppo_loss.row_logp_entropy(dist, u[t], rollout_fields["actions"][f0 + t],
                                                      w64["log_std"])[0]
     return logp
+
+
+# order of the tensors in an optimiser step: per layer W_ih, W_hh, b_ih, b_hh, then the heads, then log_std
+def _flatten(weights, with_log_std):
+    out = []
+    for lw in weights["layers"]:
+        out += [lw["W_ih"], lw["W_hh"], lw["b_ih"], lw["b_hh"]]
+    out += [weights["W_a"], weights["b_a"], weights["w_v"], weights["b_v"]]
+    if with_log_std:
+        out.append(weights["log_std"])
+    return [np.asarray(a, np.float64) for a in out]
+
+
+def _unflatten(flat, like, with_log_std):
+    it = iter(flat)
+    w = {"layers": [{k: next(it) for k in ("W_ih", "W_hh", "b_ih", "b_hh")} for _ in like["layers"]]}
+    for k in ("W_a", "b_a", "w_v", "b_v"):
+        w[k] = next(it)
+    w["log_std"] = next(it) if with_log_std else np.asarray(like["log_std"], np.float64)
+    return w
+
+
+def ppo_update(rollout, adv, ret, logp_old, cfg, opt, h0_fields=None):
+    """One whole PPO update with the optimiser in the loop (the paper's learning phase followed by its Adam
+    step, section 2.2 and section 4 "Training"): for every epoch and minibatch, pack, forward, loss, backward,
+    Adam.  rollout: dict of workloads.make_rollout; cfg: loss hyper-parameters + "epochs", "minibatches";
+    opt: dict lr0, lr_final, total_steps, beta1, beta2, eps, max_grad_norm.  Returns the final weights (fp64),
+    the list of per-minibatch scalars and the gradient norms."""
+    gauss = cfg["dist"] == ppo_loss.GAUSSIAN
+    weights = _unflatten(_flatten(rollout["weights"], gauss), rollout["weights"], gauss)
+    params = _flatten(weights, gauss)
+    m = [np.zeros_like(p) for p in params]
+    v = [np.zeros_like(p) for p in params]
+    scalars, norms, k = [], [], 0
+    for e in range(cfg["epochs"]):
+        for b in range(cfg["minibatches"]):
+            meta = pack.pack_minibatch(rollout["dones"], rollout["env_off"], rollout["seq_key"][e], cfg["minibatches"], b,
+                                       rollout.get("env_started_episode"))
+            h0 = c0 = None
+            if "rnn_h" in rollout:
+                h0 = pack.initial_states(rollout["rnn_h"], meta["seq_first"], meta["seq_is_ep_start"])
+                c0 = pack.initial_states(rollout["rnn_c"], meta["seq_first"], meta["seq_is_ep_start"])
+            out = minibatch_step(rollout, weights, meta, cfg, adv, ret, logp_old, h0, c0)
+            g = out["grads"]
+            grads = []
+            for lg in g["layers"]:
+                grads += [lg["W_ih"], lg["W_hh"], lg["b_ih"], lg["b_hh"]]
+            grads += [g["W_a"], g["b_a"], g["w_v"], g["b_v"]]
+            if gauss:
+                grads.append(g["log_std"])
+            lr = adam.cosine_lr(k, opt["total_steps"], opt["lr0"], opt["lr_final"])
+            params, m, v, norm = adam.adam_step(params, grads, m, v, k + 1, lr, opt["beta1"], opt["beta2"], opt["eps"],
+                                                opt["max_grad_norm"])
+            weights = _unflatten(params, weights, gauss)
+            scalars.append(out["scalars"])
+            norms.append(norm)
+            k += 1
+    return weights, scalars, norms

@@ -47,6 +47,11 @@ class PpoCfg(C.Structure):
     _fields_ = [("clip", _f), ("value_coef", _f), ("entropy_coef", _f), ("dist", _i32), ("act_dim", _i32)]
 
 
+class AdamCfg(C.Structure):
+    _fields_ = [("lr0", _f), ("lr_final", _f), ("total_steps", C.c_int64), ("beta1", _f), ("beta2", _f), ("eps", _f),
+                ("max_grad_norm", _f)]
+
+
 lib.ver_status_string.restype = C.c_char_p
 lib.ver_status_string.argtypes = [C.c_int]
 lib.ver_gae_workspace_bytes.restype = _sz
@@ -70,14 +75,18 @@ lib.ver_ppo_loss_workspace_bytes.argtypes = [_i32, _i32]
 lib.ver_ppo_loss.restype = C.c_int
 lib.ver_ppo_loss.argtypes = [C.POINTER(PpoCfg), _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                              _vp, _vp, _vp, _vp, _vp, _sz, _vp]
-
+lib.ver_adam_workspace_bytes.restype = _sz
+lib.ver_adam_workspace_bytes.argtypes = []
+lib.ver_adam_step.restype = C.c_int
+lib.ver_adam_step.argtypes = [C.POINTER(AdamCfg), _i32, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp),
+                              C.POINTER(C.c_int64), C.c_int64, _vp, _vp, _sz, _vp]
 
 lib.ver_profile_enable.restype = C.c_int
 lib.ver_profile_enable.argtypes = [C.c_uint32]
 lib.ver_profile_read.restype = C.c_int
 lib.ver_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 PROF_CLASSES = ["gae", "pack_index", "pack_gather", "lstm_prep", "lstm_gemm_fwd", "lstm_rec_fwd", "heads_fwd",
-                "ppo_loss", "heads_bwd", "lstm_rec_bwd", "lstm_gemm_dx", "lstm_gemm_dw", "lstm_dbias"]
+                "ppo_loss", "heads_bwd", "lstm_rec_bwd", "lstm_gemm_dx", "lstm_gemm_dw", "lstm_dbias", "adam"]
 
 
 class VerError(RuntimeError):
@@ -185,6 +194,22 @@ def ver_ppo_loss(cfg, M, head_out, value, log_std, actions_packed, logp_old, adv
     _check(lib.ver_ppo_loss(C.byref(cfg), M, _ptr(head_out), _ptr(value), _ptr(log_std), _ptr(actions_packed),
                             _ptr(logp_old), _ptr(adv), _ptr(ret), _ptr(is_weight), _ptr(scalars),
                             _ptr(d_head_out), _ptr(d_value), _ptr(d_log_std), p, n, _stream()))
+
+
+def adam_cfg(lr0=2.5e-4, lr_final=0.0, total_steps=1, beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=0.0) -> AdamCfg:
+    return AdamCfg(lr0, lr_final, total_steps, beta1, beta2, eps, max_grad_norm)
+
+
+def ver_adam_workspace_bytes() -> int:
+    return lib.ver_adam_workspace_bytes()
+
+
+def ver_adam_step(cfg, params, grads, exp_avg, exp_avg_sq, step_index, grad_norm, workspace):
+    """params, grads, exp_avg, exp_avg_sq: lists of float32 device tensors of equal shapes."""
+    sizes = (C.c_int64 * len(params))(*[t.numel() for t in params])
+    p, n = _ws(workspace)
+    _check(lib.ver_adam_step(C.byref(cfg), len(params), _ptr_array(params), _ptr_array(grads), _ptr_array(exp_avg),
+                             _ptr_array(exp_avg_sq), sizes, step_index, _ptr(grad_norm), p, n, _stream()))
 
 
 def ver_profile_enable(mask: int) -> None:

@@ -1,8 +1,8 @@
 """One PPO update of the VER learner as a sequence of C-ABI calls.
 
 Buffer management and argument marshalling only: every step of the update
-(advantages, minibatch packing, LSTM forward, PPO loss, LSTM backward) runs in
-the HIP library.  Used by the benchmark, the smoke check and the end-to-end
+(advantages, minibatch packing, LSTM forward, PPO loss, LSTM backward, optimiser
+step) runs in the HIP library.  Used by the benchmark, the smoke check and the end-to-end
 tests.  Nothing here synchronises the stream.
 """
 from __future__ import annotations
@@ -25,7 +25,10 @@ class Learner:
     """Device-resident rollout + weights + every scratch buffer of one update."""
 
     def __init__(self, rollout: dict, *, compute: int | None = None, x_bf16: bool | None = None,
-                 want_dx: bool = False, minibatches: int | None = None):
+                 want_dx: bool = False, minibatches: int | None = None, adam_total_steps: int | None = None,
+                 adam: dict | None = None):
+        """adam_total_steps: length of the cosine schedule in optimiser steps; None = no optimiser (gradients only).
+        adam: overrides of the optimiser's hyper-parameters (fields of ver_adam_cfg)."""
         w: Workload = rollout["workload"]
         self.w = w
         self.S, self.N = rollout["S"], rollout["N"]
@@ -85,8 +88,19 @@ class Learner:
         self.ws_lstm = ver.workspace(n)
         self.ws_loss = ver.workspace(ver.ver_ppo_loss_workspace_bytes(M, A))
         self.act_bytes = int(self.actions[0].numel() * self.actions.element_size())
+        # optimiser: Adam state for every weight tensor (and log_std for Gaussian policies)
+        self.adam_cfg = None
+        if adam_total_steps is not None:
+            self.adam_cfg = ver.adam_cfg(total_steps=adam_total_steps, **(adam or {}))
+            self.opt_params = self.weights + ([self.log_std] if w.dist == 1 else [])
+            self.opt_grads = self.grads + ([self.d_log_std] if w.dist == 1 else [])
+            self.exp_avg = [torch.zeros_like(t) for t in self.opt_params]
+            self.exp_avg_sq = [torch.zeros_like(t) for t in self.opt_params]
+            self.grad_norm = torch.zeros(1, **f32)
+            self.ws_adam = ver.workspace(ver.ver_adam_workspace_bytes())
+            self.opt_steps = 0
 
-    # -- the five entry points, in the order of the learning phase ----------------
+    # -- the entry points, in the order of the learning phase ---------------------
     def gae(self):
         ver.ver_gae(self.rewards, self.values, self.dones, self.last_values, self.env_off, self.N, self.S,
                     self.w.gamma, self.w.lam, self.adv, self.ret, self.ws_gae)
@@ -119,11 +133,18 @@ class Learner:
                          self.h0, self.c0, self.seq_cap, self.weights, self.d_head, self.d_value, self.grads,
                          self.d_x, self.ws_lstm)
 
+    def optimizer_step(self):
+        ver.ver_adam_step(self.adam_cfg, self.opt_params, self.opt_grads, self.exp_avg, self.exp_avg_sq, self.opt_steps,
+                          self.grad_norm, self.ws_adam)
+        self.opt_steps += 1
+
     def minibatch(self, epoch: int, b: int):
         self.pack(epoch, b)
         self.forward()
         self.loss()
         self.backward()
+        if self.adam_cfg is not None:
+            self.optimizer_step()
 
     def update(self, on_minibatch=None):
         """One PPO update: advantages once, then epochs x minibatches."""

@@ -66,3 +66,27 @@ def test_argument_checks_precede_any_gpu_work(lib):
     assert lib.ver_pack_minibatch(None, None) == -1
     lib.ver_ppo_loss.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 13 + [C.c_size_t, C.c_void_p]
     assert lib.ver_ppo_loss(None, 4, *([None] * 13), 0, None) == -1
+
+
+def test_adam_argument_checks(lib):
+    class AdamCfg(C.Structure):
+        _fields_ = [("lr0", C.c_float), ("lr_final", C.c_float), ("total_steps", C.c_int64), ("beta1", C.c_float),
+                    ("beta2", C.c_float), ("eps", C.c_float), ("max_grad_norm", C.c_float)]
+    lib.ver_adam_workspace_bytes.restype = C.c_size_t
+    assert lib.ver_adam_workspace_bytes() > 0
+    lib.ver_adam_step.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 5 + [C.c_int64] + [C.c_void_p] * 2 + \
+        [C.c_size_t, C.c_void_p]
+    ok = AdamCfg(2.5e-4, 0.0, 10, 0.9, 0.999, 1e-8, 0.0)
+    empty = (C.c_void_p * 1)()
+    sizes = (C.c_int64 * 1)(0)
+    call = lambda cfg, n, step: lib.ver_adam_step(C.byref(cfg) if cfg else None, n, empty, empty, empty, empty, sizes, step,
+                                                  None, None, 0, None)
+    assert call(None, 0, 0) == -1
+    assert call(ok, 0, 0) == 0                       # nothing to update
+    assert call(ok, 1, 0) == 0                       # one tensor of size 0
+    assert call(ok, -1, 0) == -1 and call(ok, 1000, 0) == -1 and call(ok, 1, -3) == -1
+    assert call(AdamCfg(2.5e-4, 0.0, 0, 0.9, 0.999, 1e-8, 0.0), 1, 0) == -1      # no schedule length
+    assert call(AdamCfg(2.5e-4, 0.0, 10, 1.0, 0.999, 1e-8, 0.0), 1, 0) == -1     # beta1 = 1
+    assert call(AdamCfg(2.5e-4, 0.0, 10, 0.9, 0.999, 1e-8, 1.0), 1, 0) == -1     # clipping needs grad_norm
+    sizes[0] = 8
+    assert call(ok, 1, 0) == -1                      # null tensors of positive size

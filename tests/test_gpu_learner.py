@@ -71,3 +71,41 @@ def test_workload_shaped_update_reduced_width(ver, name, compute):
     w = wl.scaled(w, budget=w.budget // scale, n_envs=max(4, w.n_envs // scale), hidden=128, input_dim=w.input_dim // 4 // 4 * 4,
                   epochs=1)
     run_case(w, seed=2, compute=compute)
+
+
+@pytest.mark.parametrize("dist,clip_norm", [(1, 0.0), (0, 0.5)])
+def test_update_with_optimizer(ver, dist, clip_norm):
+    """A whole update with the Adam step in the loop (2 epochs x 2 minibatches = 4 optimiser steps), fp32 path:
+    the weights after the update against the oracle chain.  Compared is the CHANGE of every tensor, relative to
+    its own scale (the step size is ~lr, far below the size of the weights)."""
+    from paper_2210_05064_amd.learner import Learner
+    base = wl.WORKLOADS["manip" if dist == 1 else "nav"]
+    w = wl.scaled(base, budget=384, n_envs=10, hidden=64, input_dim=20, p_done=0.03, epochs=2, minibatches=2)
+    ro = wl.make_rollout(w, seed=41, bias_scale=0.1)
+    adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
+    logp_old = (olearner.collection_logp(ro, ro["weights"], ro["dones"], ro["env_off"], w.dist,
+                                         ro["env_started_episode"], ro["rnn_h"], ro["rnn_c"])
+                + ro["logp_noise"]).astype(np.float32)
+    opt = dict(lr0=2.5e-4, lr_final=0.0, total_steps=6, beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=clip_norm)
+    L = Learner(ro, compute=0, adam_total_steps=opt["total_steps"],
+                adam={k: v for k, v in opt.items() if k != "total_steps"})
+    L.logp_old.copy_(torch.from_numpy(logp_old).cuda())
+    before = [host(t).astype(np.float64) for t in L.opt_params]
+    L.update()
+    torch.cuda.synchronize()
+    assert not L.lstm_timed_out() and L.opt_steps == 4
+    f32 = lambda x: float(np.float32(x))
+    cfg = dict(dist=w.dist, clip=f32(w.clip), value_coef=w.value_coef, entropy_coef=f32(w.entropy_coef),
+               epochs=w.epochs, minibatches=w.minibatches)
+    opt32 = {k: (f32(v) if k != "total_steps" else v) for k, v in opt.items()}
+    ref_w, ref_scalars, ref_norms = olearner.ppo_update(ro, adv.astype(np.float32), ret.astype(np.float32), logp_old, cfg, opt32)
+    ref = olearner._flatten(ref_w, w.dist == 1)
+    assert len(ref) == len(L.opt_params)
+    assert float(L.grad_norm.item()) == pytest.approx(ref_norms[-1], rel=1e-3)
+    for i, (t, b0, r) in enumerate(zip(L.opt_params, before, ref)):
+        got = host(t).astype(np.float64) - b0
+        want = r - b0
+        assert np.max(np.abs(want)) > 1e-5, "the update must have moved the tensor"
+        assert_close(got, want, 5e-3, f"change of tensor {i}")
+    sc = host(L.scalars)
+    assert abs(sc[0] - ref_scalars[-1]["total"]) <= 1e-3 * max(abs(ref_scalars[-1]["total"]), 1e-2)
