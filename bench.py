@@ -2,7 +2,7 @@
 """Benchmark of the VER learner step on one MI355X.
 
 A "step" is one full PPO update over one synthetic ragged rollout: ver_gae
-once, then epochs x minibatches x (ver_pack_minibatch, ver_lstm_fwd,
+and ver_is_weight once, then epochs x minibatches x (ver_pack_minibatch, ver_lstm_fwd,
 ver_ppo_loss, ver_lstm_bwd, ver_adam_step).  All inputs are resident in HBM before the timed
 region.  Prints ONE JSON line: learner env-steps/s, the roofline position of
 the dominant kernel (timed with HIP events inside the library during the timed
@@ -28,6 +28,8 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 # HBM bytes per launch (read + written) of the dominant kernel class (with two layers: the launch that runs both
 # time loops of one direction), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this script, scaled by a copy of
 # known size: see profiles/hbm_traffic_max_workload.md.  None where unmeasured.
+MAX_IS = 1.0   # truncation of the importance weight (appendix hyper-parameter table)
+
 MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 1785.9e6, ("max", "lstm_rec_fwd"): 2016.2e6}
 
 
@@ -63,11 +65,12 @@ def cpu_baseline(ro, budget_s=15.0):
     GAE over the whole buffer, one minibatch's packing and loss in full, and the
     LSTM forward/backward over as many of that minibatch's pieces (shortest
     first) as fit the time budget, scaled to the whole update by step count."""
-    from oracle import adam as oadam, gae as ogae, lstm as olstm, pack as opack, ppo_loss as oloss
+    from oracle import adam as oadam, gae as ogae, is_weight as ois, lstm as olstm, pack as opack, ppo_loss as oloss
     w = ro["workload"]
     S, B, E = ro["S"], w.minibatches, w.epochs
     t0 = time.perf_counter()
     adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
+    is_w = ois.is_weights(ro["env_off"], MAX_IS)
     t_gae = time.perf_counter() - t0
     t0 = time.perf_counter()
     meta = opack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][0], B, 0, ro["env_started_episode"])
@@ -92,7 +95,7 @@ def cpu_baseline(ro, budget_s=15.0):
     acts = opack.gather_rows(ro["actions"], meta["gather_idx"])
     oloss.ppo_loss(w.dist, u, rng.standard_normal(M), W["log_std"], acts, rng.standard_normal(M),
                    opack.gather_rows(adv, meta["gather_idx"]), opack.gather_rows(ret, meta["gather_idx"]),
-                   w.clip, w.value_coef, w.entropy_coef)
+                   w.clip, w.value_coef, w.entropy_coef, opack.gather_rows(is_w, meta["gather_idx"]))
     t_loss = time.perf_counter() - t0
     flat = [W["layers"][l][k] for l in range(w.n_layers) for k in ("W_ih", "W_hh", "b_ih", "b_hh")] + \
            [W["W_a"], W["b_a"], W["w_v"], W["b_v"], W["log_std"]]
@@ -107,7 +110,7 @@ def cpu_baseline(ro, budget_s=15.0):
         cores = os.cpu_count() or 1
     return {
         "value": S / t_update, "unit": "env-steps/s", "cores": int(cores), "kind": "oracle",
-        "sample": (f"GAE on all {S} steps ({t_gae:.2f}s); packing ({t_pack:.2f}s) and loss ({t_loss:.2f}s) of one "
+        "sample": (f"GAE and importance weights on all {S} steps ({t_gae:.2f}s); packing ({t_pack:.2f}s) and loss ({t_loss:.2f}s) of one "
                    f"minibatch of {M} rows in full; LSTM fwd+bwd on {steps} steps of that minibatch's shortest "
                    f"pieces, scaled to {M} rows ({t_lstm:.1f}s); Adam step on all weights ({t_adam:.2f}s); "
                    f"update = GAE + {E}x{B} minibatches"),
@@ -150,8 +153,8 @@ def main():
 
     w = wl.WORKLOADS[args.workload]
     ro = wl.make_rollout(w, seed=args.seed)
-    # the optimiser runs inside the update: Adam with the paper's cosine schedule over its 500 M training steps
-    learner = Learner(ro, adam_total_steps=max(1, int(500e6 // ro["S"])) * w.epochs * w.minibatches)
+    # the loss carries VER's truncated importance weight, and the optimiser runs inside the update: Adam with the paper's cosine schedule over its 500 M training steps
+    learner = Learner(ro, adam_total_steps=max(1, int(500e6 // ro["S"])) * w.epochs * w.minibatches, max_is=MAX_IS)
     learner.logp_old.copy_(collection_logp(ro, learner.compute, learner.x_bf16))
     torch.cuda.synchronize()
 

@@ -5,6 +5,7 @@
  * (paper section 2.2) for a recurrent actor-critic trained with PPO:
  *
  *     ver_gae              once per rollout
+ *     ver_is_weight        once per rollout (optional)
  *     for every epoch, for every minibatch b:
  *         ver_pack_minibatch -> ver_lstm_fwd -> ver_ppo_loss -> ver_lstm_bwd
  *
@@ -76,6 +77,25 @@ int ver_gae(const float* rewards, const float* values, const uint8_t* dones,
             void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * ver_is_weight - truncated importance weight of every step of the buffer.
+ * Paper: section 4 "Training" (experience from fast environments is
+ * over-represented under variable experience rollouts; corrected with
+ * truncated importance sampling) and the appendix hyper-parameter table
+ * (importance sampling on, maximum weight 1.0).  The paper gives no formula;
+ * reading implemented: every step of environment i carries
+ *     w_i = min(max_is, (S / N) / L_i),   L_i = env_off[i+1] - env_off[i],
+ * the share an environment would have under equal-length rollouts over the
+ * share it has; constant inside a stretch.  The weights feed ver_ppo_loss
+ * (is_weight) after ver_pack_minibatch has gathered them into packed order.
+ *
+ * env_off: device int32[N+1]; weight: device float[S], 16-byte aligned.  The quotient is
+ * formed in double and rounded once.  max_is <= 0 or N <= 0 is VER_EINVAL;
+ * S = 0 is legal (no work).
+ */
+int ver_is_weight(const int32_t* env_off, int32_t N, int32_t S, float max_is,
+                  float* weight, void* stream);
+
+/* ------------------------------------------------------------------------
  * ver_pack_minibatch - VER minibatch creation + packed-sequence layout.
  * Paper: section 2.2 "Learning mini-batch creation" (sequences start at a
  * stretch start or after an episode end; randomly ordered; the first S/B
@@ -109,7 +129,7 @@ int ver_gae(const float* rewards, const float* values, const uint8_t* dones,
  * Optional gathers, each skipped when its source or destination is NULL:
  *   obs[S,D] float        -> obs_packed[M,D]  float, or bf16 when obs_packed_bf16 != 0
  *   actions[S,act_bytes]  -> actions_packed[M,act_bytes]   (raw bytes per step)
- *   logp_old/adv/ret[S]   -> *_packed[M]
+ *   logp_old/adv/ret/is_weight[S] -> *_packed[M]
  *   rnn_h/rnn_c[n_layers,S,H] (state each layer had BEFORE step k at
  *   collection time) -> h0/c0[n_layers,seq_cap,H]: row j = state of piece j's
  *   first step, zeros if the piece is an episode start.  seq_cap >= n_seq
@@ -144,9 +164,11 @@ typedef struct {
     const float* logp_old;
     const float* adv;
     const float* ret;
+    const float* is_weight;
     float* logp_old_packed;
     float* adv_packed;
     float* ret_packed;
+    float* is_weight_packed;
     const float* rnn_h;
     const float* rnn_c;
     int32_t n_layers, H, seq_cap;
@@ -338,7 +360,8 @@ enum {
     VER_PROF_LSTM_GEMM_DW = 11,
     VER_PROF_LSTM_DBIAS = 12,
     VER_PROF_ADAM = 13,
-    VER_PROF_COUNT = 14
+    VER_PROF_IS_WEIGHT = 14,
+    VER_PROF_COUNT = 15
 };
 int ver_profile_enable(uint32_t mask);
 int ver_profile_read(double* total_ms, int64_t* launches);

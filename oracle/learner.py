@@ -9,7 +9,7 @@ file.
 """
 import numpy as np
 
-from . import adam, lstm, pack, ppo_loss
+from . import adam, is_weight, lstm, pack, ppo_loss
 
 
 def minibatch_step(rollout_fields, weights, meta, cfg, adv, ret, logp_old, h0=None, c0=None,
@@ -86,11 +86,12 @@ def _unflatten(flat, like, with_log_std):
     return w
 
 
-def ppo_update(rollout, adv, ret, logp_old, cfg, opt, h0_fields=None):
+def ppo_update(rollout, adv, ret, logp_old, cfg, opt, h0_fields=None, max_is=None):
     """One whole PPO update with the optimiser in the loop (the paper's learning phase followed by its Adam
     step, section 2.2 and section 4 "Training"): for every epoch and minibatch, pack, forward, loss, backward,
     Adam.  rollout: dict of workloads.make_rollout; cfg: loss hyper-parameters + "epochs", "minibatches";
-    opt: dict lr0, lr_final, total_steps, beta1, beta2, eps, max_grad_norm.  Returns the final weights (fp64),
+    opt: dict lr0, lr_final, total_steps, beta1, beta2, eps, max_grad_norm; max_is: truncation of the per-step
+    importance weight of the loss (None = unweighted).  Returns the final weights (fp64),
     the list of per-minibatch scalars and the gradient norms."""
     gauss = cfg["dist"] == ppo_loss.GAUSSIAN
     weights = _unflatten(_flatten(rollout["weights"], gauss), rollout["weights"], gauss)
@@ -98,6 +99,7 @@ def ppo_update(rollout, adv, ret, logp_old, cfg, opt, h0_fields=None):
     m = [np.zeros_like(p) for p in params]
     v = [np.zeros_like(p) for p in params]
     scalars, norms, k = [], [], 0
+    weight = None if max_is is None else is_weight.is_weights(rollout["env_off"], max_is)
     for e in range(cfg["epochs"]):
         for b in range(cfg["minibatches"]):
             meta = pack.pack_minibatch(rollout["dones"], rollout["env_off"], rollout["seq_key"][e], cfg["minibatches"], b,
@@ -106,7 +108,7 @@ def ppo_update(rollout, adv, ret, logp_old, cfg, opt, h0_fields=None):
             if "rnn_h" in rollout:
                 h0 = pack.initial_states(rollout["rnn_h"], meta["seq_first"], meta["seq_is_ep_start"])
                 c0 = pack.initial_states(rollout["rnn_c"], meta["seq_first"], meta["seq_is_ep_start"])
-            out = minibatch_step(rollout, weights, meta, cfg, adv, ret, logp_old, h0, c0)
+            out = minibatch_step(rollout, weights, meta, cfg, adv, ret, logp_old, h0, c0, weight=weight)
             g = out["grads"]
             grads = []
             for lg in g["layers"]:

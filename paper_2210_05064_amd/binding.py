@@ -30,8 +30,8 @@ class PackArgs(C.Structure):
         ("batch_sizes", _vp), ("t_off", _vp), ("gather_idx", _vp),
         ("obs", _vp), ("D", _i32), ("obs_packed", _vp), ("obs_packed_bf16", _i32),
         ("actions", _vp), ("act_bytes", _i32), ("actions_packed", _vp),
-        ("logp_old", _vp), ("adv", _vp), ("ret", _vp),
-        ("logp_old_packed", _vp), ("adv_packed", _vp), ("ret_packed", _vp),
+        ("logp_old", _vp), ("adv", _vp), ("ret", _vp), ("is_weight", _vp),
+        ("logp_old_packed", _vp), ("adv_packed", _vp), ("ret_packed", _vp), ("is_weight_packed", _vp),
         ("rnn_h", _vp), ("rnn_c", _vp), ("n_layers", _i32), ("H", _i32), ("seq_cap", _i32),
         ("h0", _vp), ("c0", _vp),
         ("workspace", _vp), ("workspace_bytes", _sz),
@@ -58,6 +58,8 @@ lib.ver_gae_workspace_bytes.restype = _sz
 lib.ver_gae_workspace_bytes.argtypes = [_i32]
 lib.ver_gae.restype = C.c_int
 lib.ver_gae.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _f, _f, _vp, _vp, _vp, _sz, _vp]
+lib.ver_is_weight.restype = C.c_int
+lib.ver_is_weight.argtypes = [_vp, _i32, _i32, _f, _vp, _vp]
 lib.ver_pack_workspace_bytes.restype = _sz
 lib.ver_pack_workspace_bytes.argtypes = [_i32, _i32, _i32]
 lib.ver_pack_minibatch.restype = C.c_int
@@ -86,7 +88,8 @@ lib.ver_profile_enable.argtypes = [C.c_uint32]
 lib.ver_profile_read.restype = C.c_int
 lib.ver_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 PROF_CLASSES = ["gae", "pack_index", "pack_gather", "lstm_prep", "lstm_gemm_fwd", "lstm_rec_fwd", "heads_fwd",
-                "ppo_loss", "heads_bwd", "lstm_rec_bwd", "lstm_gemm_dx", "lstm_gemm_dw", "lstm_dbias", "adam"]
+                "ppo_loss", "heads_bwd", "lstm_rec_bwd", "lstm_gemm_dx", "lstm_gemm_dw", "lstm_dbias", "adam",
+                "is_weight"]
 
 
 class VerError(RuntimeError):
@@ -127,6 +130,10 @@ def ver_gae(rewards, values, dones, last_values, env_off, N, S, gamma, lam, adv,
     p, n = _ws(workspace)
     _check(lib.ver_gae(_ptr(rewards), _ptr(values), _ptr(dones), _ptr(last_values), _ptr(env_off),
                        N, S, gamma, lam, _ptr(adv), _ptr(ret), p, n, _stream()))
+
+
+def ver_is_weight(env_off, N, S, max_is, weight):
+    _check(lib.ver_is_weight(_ptr(env_off), N, S, max_is, _ptr(weight), _stream()))
 
 
 def ver_pack_workspace_bytes(N: int, S: int, B: int) -> int:

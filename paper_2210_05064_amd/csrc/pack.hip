@@ -282,8 +282,8 @@ struct GatherArgs {
     int M, S;
     const float* obs; int D; void* obs_packed; int obs_bf16;
     const uint8_t* actions; int act_bytes; uint8_t* actions_packed;
-    const float* logp_old; const float* adv; const float* ret;
-    float* logp_old_packed; float* adv_packed; float* ret_packed;
+    const float* logp_old; const float* adv; const float* ret; const float* is_weight;
+    float* logp_old_packed; float* adv_packed; float* ret_packed; float* is_weight_packed;
     const float* rnn_h; const float* rnn_c; int n_layers, H, seq_cap;
     float* h0; float* c0;
 };
@@ -341,6 +341,7 @@ __global__ __launch_bounds__(GATHER_THREADS) void pack_gather_kernel(GatherArgs 
         if (g.logp_old && g.logp_old_packed) g.logp_old_packed[p] = g.logp_old[src];
         if (g.adv && g.adv_packed) g.adv_packed[p] = g.adv[src];
         if (g.ret && g.ret_packed) g.ret_packed[p] = g.ret[src];
+        if (g.is_weight && g.is_weight_packed) g.is_weight_packed[p] = g.is_weight[src];
     }
     // rows of timestep 0 are the pieces' first steps: fetch their initial recurrent state
     if (t == 0 && j < n_seq && j < g.seq_cap) {
@@ -370,8 +371,57 @@ inline size_t pack_ws_layout(int S, int M, void* base, PackWs* ws) {
     return cv.used;
 }
 
+// Truncated importance weight of every step (paper section 4 "Training"; appendix hyper-parameter table:
+// importance sampling on, maximum 1.0): w = min(max_is, (S/N) / L_i) for the steps of environment i.  A thread
+// handles IS_ITEMS consecutive steps: one binary search for the first, then a walk over the stretch boundaries
+// (empty stretches are stepped over).  4 bytes written per step; env_off stays in L2.
+constexpr int IS_THREADS = 256;
+constexpr int IS_ITEMS = 4;
+
+__global__ __launch_bounds__(IS_THREADS) void is_weight_kernel(const int32_t* __restrict__ env_off, int N, int S,
+                                                               double share, float max_is,
+                                                               float* __restrict__ weight) {
+    const int k0 = (blockIdx.x * IS_THREADS + threadIdx.x) * IS_ITEMS;
+    if (k0 >= S) return;
+    int env = segment_of(env_off, N, k0);
+    int end = env_off[env + 1];
+    float w = fminf(max_is, (float)(share / (double)(end - env_off[env])));
+    float out[IS_ITEMS];
+#pragma unroll
+    for (int i = 0; i < IS_ITEMS; ++i) {
+        const int k = k0 + i;
+        if (k < S && k >= end) {
+            int begin;
+            do {
+                begin = end;
+                end = env_off[++env + 1];
+            } while (k >= end);
+            w = fminf(max_is, (float)(share / (double)(end - begin)));
+        }
+        out[i] = w;
+    }
+    if (k0 + IS_ITEMS <= S) {
+        *reinterpret_cast<float4*>(weight + k0) = make_float4(out[0], out[1], out[2], out[3]);
+    } else {
+        for (int i = 0; k0 + i < S; ++i) weight[k0 + i] = out[i];
+    }
+}
+
 }  // namespace
 }  // namespace ver
+
+extern "C" int ver_is_weight(const int32_t* env_off, int32_t N, int32_t S, float max_is, float* weight,
+                             void* stream) {
+    if (N <= 0 || S < 0 || !(max_is > 0.f)) return VER_EINVAL;
+    if (S == 0) return VER_OK;
+    if (!env_off || !weight || (reinterpret_cast<uintptr_t>(weight) & 15)) return VER_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int per_block = ver::IS_THREADS * ver::IS_ITEMS;
+    ver::ProfScope prof(VER_PROF_IS_WEIGHT, s);
+    hipLaunchKernelGGL(ver::is_weight_kernel, dim3((S + per_block - 1) / per_block), dim3(ver::IS_THREADS), 0, s,
+                       env_off, N, S, (double)S / (double)N, max_is, weight);
+    return ver::launch_status();
+}
 
 extern "C" size_t ver_pack_workspace_bytes(int32_t N, int32_t S, int32_t B) {
     if (N < 0 || S <= 0 || B <= 0) return 0;
@@ -408,6 +458,7 @@ extern "C" int ver_pack_minibatch(const ver_pack_args* a, void* stream) {
     g.actions_packed = static_cast<uint8_t*>(a->actions_packed);
     g.logp_old = a->logp_old; g.adv = a->adv; g.ret = a->ret;
     g.logp_old_packed = a->logp_old_packed; g.adv_packed = a->adv_packed; g.ret_packed = a->ret_packed;
+    g.is_weight = a->is_weight; g.is_weight_packed = a->is_weight_packed;
     g.rnn_h = a->rnn_h; g.rnn_c = a->rnn_c; g.n_layers = states ? a->n_layers : 0; g.H = a->H;
     g.seq_cap = a->seq_cap; g.h0 = a->h0; g.c0 = a->c0;
     const int blocks = (M + ver::GATHER_WAVES - 1) / ver::GATHER_WAVES;

@@ -26,8 +26,9 @@ class Learner:
 
     def __init__(self, rollout: dict, *, compute: int | None = None, x_bf16: bool | None = None,
                  want_dx: bool = False, minibatches: int | None = None, adam_total_steps: int | None = None,
-                 adam: dict | None = None):
-        """adam_total_steps: length of the cosine schedule in optimiser steps; None = no optimiser (gradients only).
+                 adam: dict | None = None, max_is: float | None = None):
+        """max_is: truncation of the per-step importance weight; None = unweighted loss.
+        adam_total_steps: length of the cosine schedule in optimiser steps; None = no optimiser (gradients only).
         adam: overrides of the optimiser's hyper-parameters (fields of ver_adam_cfg)."""
         w: Workload = rollout["workload"]
         self.w = w
@@ -50,6 +51,8 @@ class Learner:
         self.rnn_c = _dev(rollout["rnn_c"]) if "rnn_c" in rollout else None
         self.logp_old = torch.zeros(S, **f32)
         self.adv, self.ret = torch.empty(S, **f32), torch.empty(S, **f32)
+        self.max_is = max_is
+        self.is_w = torch.empty(S, **f32) if max_is is not None else None
         # weights, gradients
         wt = rollout["weights"]
         flat = []
@@ -69,6 +72,7 @@ class Learner:
         self.x_packed = torch.empty((M, D), dtype=torch.bfloat16 if self.x_bf16 else torch.float32, device="cuda")
         self.act_packed = torch.empty((M,) + tuple(self.actions.shape[1:]), dtype=self.actions.dtype, device="cuda")
         self.logp_old_p, self.adv_p, self.ret_p = (torch.empty(M, **f32) for _ in range(3))
+        self.is_w_p = torch.empty(M, **f32) if max_is is not None else None
         self.seq_cap = M
         self.h0 = torch.empty((nl, M, H), **f32) if self.rnn_h is not None else None
         self.c0 = torch.empty((nl, M, H), **f32) if self.rnn_c is not None else None
@@ -105,6 +109,9 @@ class Learner:
         ver.ver_gae(self.rewards, self.values, self.dones, self.last_values, self.env_off, self.N, self.S,
                     self.w.gamma, self.w.lam, self.adv, self.ret, self.ws_gae)
 
+    def importance_weights(self):
+        ver.ver_is_weight(self.env_off, self.N, self.S, self.max_is, self.is_w)
+
     def pack(self, epoch: int, b: int):
         ver.ver_pack_minibatch(
             dones=self.dones, env_off=self.env_off, env_started_episode=self.env_started,
@@ -113,8 +120,9 @@ class Learner:
             batch_sizes=self.batch_sizes, t_off=self.t_off, gather_idx=self.gather_idx,
             obs=self.obs, D=self.w.input_dim, obs_packed=self.x_packed, obs_packed_bf16=int(self.x_bf16),
             actions=self.actions, act_bytes=self.act_bytes, actions_packed=self.act_packed,
-            logp_old=self.logp_old, adv=self.adv, ret=self.ret,
+            logp_old=self.logp_old, adv=self.adv, ret=self.ret, is_weight=self.is_w,
             logp_old_packed=self.logp_old_p, adv_packed=self.adv_p, ret_packed=self.ret_p,
+            is_weight_packed=self.is_w_p,
             rnn_h=self.rnn_h, rnn_c=self.rnn_c, n_layers=self.w.n_layers, H=self.w.hidden,
             seq_cap=self.seq_cap, h0=self.h0, c0=self.c0, workspace=self.ws_pack)
 
@@ -125,7 +133,7 @@ class Learner:
     def loss(self):
         ver.ver_ppo_loss(self.ppo_cfg, self.M, self.head_out, self.value,
                          self.log_std if self.w.dist == 1 else None, self.act_packed, self.logp_old_p,
-                         self.adv_p, self.ret_p, None, self.scalars, self.d_head, self.d_value,
+                         self.adv_p, self.ret_p, self.is_w_p, self.scalars, self.d_head, self.d_value,
                          self.d_log_std if self.w.dist == 1 else None, self.ws_loss)
 
     def backward(self):
@@ -147,8 +155,10 @@ class Learner:
             self.optimizer_step()
 
     def update(self, on_minibatch=None):
-        """One PPO update: advantages once, then epochs x minibatches."""
+        """One PPO update: advantages (and importance weights) once, then epochs x minibatches."""
         self.gae()
+        if self.max_is is not None:
+            self.importance_weights()
         for e in range(self.w.epochs):
             for b in range(self.B):
                 self.minibatch(e, b)

@@ -48,6 +48,7 @@ class PackOut:
         self.logp_old_packed = torch.zeros(M, device="cuda")
         self.adv_packed = torch.zeros(M, device="cuda")
         self.ret_packed = torch.zeros(M, device="cuda")
+        self.is_weight_packed = torch.zeros(M, device="cuda")
         self.h0 = torch.full((nl, M, H), float("nan"), device="cuda") if nl else None
         self.c0 = torch.full((nl, M, H), float("nan"), device="cuda") if nl else None
 

@@ -90,3 +90,13 @@ def test_adam_argument_checks(lib):
     assert call(AdamCfg(2.5e-4, 0.0, 10, 0.9, 0.999, 1e-8, 1.0), 1, 0) == -1     # clipping needs grad_norm
     sizes[0] = 8
     assert call(ok, 1, 0) == -1                      # null tensors of positive size
+
+
+def test_is_weight_argument_checks(lib):
+    lib.ver_is_weight.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p]
+    assert lib.ver_is_weight(None, 4, 0, 1.0, None, None) == 0        # empty buffer: nothing to do
+    assert lib.ver_is_weight(None, 4, 16, 1.0, None, None) == -1      # null pointers
+    assert lib.ver_is_weight(None, 0, 0, 1.0, None, None) == -1       # no environments
+    assert lib.ver_is_weight(None, 4, 0, 0.0, None, None) == -1       # truncation must be positive
+    assert lib.ver_is_weight(None, 4, 0, float("nan"), None, None) == -1
+    assert lib.ver_is_weight(None, 4, -1, 1.0, None, None) == -1

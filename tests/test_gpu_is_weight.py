@@ -1,0 +1,58 @@
+"""ver_is_weight against the CPU oracle.  The quotient is formed in double on both sides and rounded to fp32
+once, so the comparison is bit-exact (max_is values are fp32-representable)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import is_weight as ois
+from paper_2210_05064_amd import workloads as wl
+from tests.gpu_util import dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def run(ver, lengths, max_is):
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    N, S = len(lengths), int(off[-1])
+    out = torch.full((S + 8,), float("nan"), device="cuda")
+    ver.ver_is_weight(dev(off), N, S, max_is, out)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.all(np.isnan(got[S:])), "wrote beyond S"
+    want = ois.is_weights(off, max_is).astype(np.float32)
+    assert np.array_equal(got[:S], want)
+    return got[:S]
+
+
+@pytest.mark.parametrize("max_is", [1.0, 0.5, 2.5, float("inf")])
+@pytest.mark.parametrize("seed,n_envs,hi,p_empty", [(0, 1, 9, 0.0), (1, 7, 5, 0.3), (2, 33, 40, 0.1), (3, 300, 3, 0.5),
+                                                      (4, 64, 700, 0.0), (5, 5, 5000, 0.2)])
+def test_ragged_lengths(ver, seed, n_envs, hi, p_empty, max_is):
+    """Ragged stretches with empty environments (several in a row, at both ends), lengths from 1 step to
+    several tiles, S not a multiple of the vector width."""
+    rng = np.random.default_rng(seed)
+    lengths = rng.integers(1, hi + 1, n_envs)
+    lengths[rng.random(n_envs) < p_empty] = 0
+    if lengths.sum() == 0:
+        lengths[n_envs // 2] = 3
+    run(ver, lengths, max_is)
+
+
+def test_equal_lengths_and_one_long_stretch(ver):
+    assert np.all(run(ver, [16] * 12, 1.0) == 1.0)
+    w = run(ver, [0, 0, 4099, 0], 8.0)          # one environment owns the buffer: (S/N)/L = 1/4
+    assert np.all(w == 0.25)
+
+
+@pytest.mark.parametrize("name", ["tiny", "nav", "manip", "large", "max"])
+def test_workload_lengths(ver, name):
+    ro = wl.make_rollout(wl.scaled(wl.WORKLOADS[name], hidden=64, input_dim=8), seed=3, with_states=False)
+    w = run(ver, np.diff(ro["env_off"]), 1.0)
+    assert w.max() <= 1.0 and w.min() > 0.0
+
+
+def test_large_buffer(ver):
+    """8192 environments, about 2 M steps: many blocks, stretch boundaries inside every thread's run."""
+    rng = np.random.default_rng(11)
+    lengths = np.maximum(0, np.round(rng.lognormal(5.0, 1.0, 8192))).astype(np.int64)
+    run(ver, lengths, 1.0)

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import gae as ogae, learner as olearner, pack as opack
+from oracle import gae as ogae, is_weight as ois, learner as olearner, pack as opack
 from paper_2210_05064_amd import workloads as wl
 from tests.gpu_util import GRAD_NAMES, grads_to_list, host
 from tests.util import assert_close, assert_close_bf16
@@ -12,14 +12,15 @@ from tests.util import assert_close, assert_close_bf16
 pytestmark = pytest.mark.gpu
 
 
-def run_case(w, seed, compute=None):
+def run_case(w, seed, compute=None, max_is=None):
     from paper_2210_05064_amd.learner import Learner
     ro = wl.make_rollout(w, seed=seed, bias_scale=0.1)
     adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
     logp_old = (olearner.collection_logp(ro, ro["weights"], ro["dones"], ro["env_off"], w.dist,
                                          ro["env_started_episode"], ro["rnn_h"], ro["rnn_c"])
                 + ro["logp_noise"]).astype(np.float32)
-    L = Learner(ro, compute=compute, want_dx=True)
+    L = Learner(ro, compute=compute, want_dx=True, max_is=max_is)
+    weight = None if max_is is None else ois.is_weights(ro["env_off"], max_is)
     L.logp_old.copy_(torch.from_numpy(logp_old).cuda())
     cfg = dict(dist=w.dist, clip=np.float32(w.clip).item(), value_coef=w.value_coef,
                entropy_coef=np.float32(w.entropy_coef).item())
@@ -35,7 +36,7 @@ def run_case(w, seed, compute=None):
         assert host(L.info).tolist()[:3] == [meta["n_seq"], meta["T_max"], meta["K"]]
         h0 = opack.initial_states(ro["rnn_h"], meta["seq_first"], meta["seq_is_ep_start"])
         c0 = opack.initial_states(ro["rnn_c"], meta["seq_first"], meta["seq_is_ep_start"])
-        ref = olearner.minibatch_step(ro, ro["weights"], meta, cfg, adv, ret, logp_old, h0, c0, want_dx=True)
+        ref = olearner.minibatch_step(ro, ro["weights"], meta, cfg, adv, ret, logp_old, h0, c0, weight=weight, want_dx=True)
         close(host(L.head_out), ref["u"], "head_out")
         close(host(L.value), ref["v"], "value")
         sc = host(L.scalars)
@@ -61,6 +62,16 @@ def test_tiny_workload_update(ver):
     run_case(wl.WORKLOADS["tiny"], seed=1)
 
 
+@pytest.mark.parametrize("name,max_is", [("tiny", 1.0), ("manip", 1.0), ("nav", 1.5)])
+def test_update_with_importance_weights(ver, name, max_is):
+    """The per-step truncated importance weight computed, packed and applied in the loss on the GPU: every
+    minibatch's loss scalars and gradients against the oracle chain given the oracle's weights."""
+    w = wl.WORKLOADS[name]
+    if name != "tiny":
+        w = wl.scaled(w, budget=w.budget // 4, n_envs=w.n_envs // 2, hidden=128, input_dim=w.input_dim // 16 * 4, epochs=1)
+    run_case(w, seed=5, compute=0, max_is=max_is)
+
+
 @pytest.mark.parametrize("name,compute", [("nav", 0), ("manip", 0), ("large", 1), ("max", 1)])
 def test_workload_shaped_update_reduced_width(ver, name, compute):
     """The workload's ragged structure (envs, lengths, dones, epochs x
@@ -73,8 +84,8 @@ def test_workload_shaped_update_reduced_width(ver, name, compute):
     run_case(w, seed=2, compute=compute)
 
 
-@pytest.mark.parametrize("dist,clip_norm", [(1, 0.0), (0, 0.5)])
-def test_update_with_optimizer(ver, dist, clip_norm):
+@pytest.mark.parametrize("dist,clip_norm,max_is", [(1, 0.0, None), (0, 0.5, None), (1, 0.5, 1.0)])
+def test_update_with_optimizer(ver, dist, clip_norm, max_is):
     """A whole update with the Adam step in the loop (2 epochs x 2 minibatches = 4 optimiser steps), fp32 path:
     the weights after the update against the oracle chain.  Compared is the CHANGE of every tensor, relative to
     its own scale (the step size is ~lr, far below the size of the weights)."""
@@ -88,7 +99,7 @@ def test_update_with_optimizer(ver, dist, clip_norm):
                 + ro["logp_noise"]).astype(np.float32)
     opt = dict(lr0=2.5e-4, lr_final=0.0, total_steps=6, beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=clip_norm)
     L = Learner(ro, compute=0, adam_total_steps=opt["total_steps"],
-                adam={k: v for k, v in opt.items() if k != "total_steps"})
+                adam={k: v for k, v in opt.items() if k != "total_steps"}, max_is=max_is)
     L.logp_old.copy_(torch.from_numpy(logp_old).cuda())
     before = [host(t).astype(np.float64) for t in L.opt_params]
     L.update()
@@ -98,7 +109,8 @@ def test_update_with_optimizer(ver, dist, clip_norm):
     cfg = dict(dist=w.dist, clip=f32(w.clip), value_coef=w.value_coef, entropy_coef=f32(w.entropy_coef),
                epochs=w.epochs, minibatches=w.minibatches)
     opt32 = {k: (f32(v) if k != "total_steps" else v) for k, v in opt.items()}
-    ref_w, ref_scalars, ref_norms = olearner.ppo_update(ro, adv.astype(np.float32), ret.astype(np.float32), logp_old, cfg, opt32)
+    ref_w, ref_scalars, ref_norms = olearner.ppo_update(ro, adv.astype(np.float32), ret.astype(np.float32), logp_old, cfg, opt32,
+                                                        max_is=max_is)
     ref = olearner._flatten(ref_w, w.dist == 1)
     assert len(ref) == len(L.opt_params)
     assert float(L.grad_norm.item()) == pytest.approx(ref_norms[-1], rel=1e-3)

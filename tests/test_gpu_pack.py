@@ -31,7 +31,7 @@ def run_pack(ver, dones, off, key, B, b, eps=None, fields=None, bf16=False):
     if act is not None:
         kw.update(actions=dev(act), act_bytes=act[0].nbytes if act.ndim > 1 else act.itemsize,
                   actions_packed=out.actions_packed)
-    for k in ("logp_old", "adv", "ret"):
+    for k in ("logp_old", "adv", "ret", "is_weight"):
         if k in f:
             kw[k] = dev(f[k])
             kw[k + "_packed"] = getattr(out, k + "_packed")
@@ -95,7 +95,8 @@ def test_gathered_fields(ver, bf16):
     rng = np.random.default_rng(0)
     fields = dict(obs=ro["obs"], actions=ro["actions"], logp_old=rng.standard_normal(ro["S"]).astype(np.float32),
                   adv=rng.standard_normal(ro["S"]).astype(np.float32),
-                  ret=rng.standard_normal(ro["S"]).astype(np.float32), rnn_h=ro["rnn_h"], rnn_c=ro["rnn_c"])
+                  ret=rng.standard_normal(ro["S"]).astype(np.float32),
+                  is_weight=rng.random(ro["S"]).astype(np.float32), rnn_h=ro["rnn_h"], rnn_c=ro["rnn_c"])
     for b in range(2):
         out = run_pack(ver, ro["dones"], ro["env_off"], ro["seq_key"][0], 2, b, ro["env_started_episode"], fields, bf16)
         ref = opack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][0], 2, b, ro["env_started_episode"])
@@ -107,7 +108,7 @@ def test_gathered_fields(ver, bf16):
         else:
             assert np.array_equal(host(out.obs_packed), opack.gather_rows(ro["obs"], g))
         assert np.array_equal(host(out.actions_packed), opack.gather_rows(ro["actions"], g))
-        for k in ("logp_old", "adv", "ret"):
+        for k in ("logp_old", "adv", "ret", "is_weight"):
             assert np.array_equal(host(getattr(out, k + "_packed")), opack.gather_rows(fields[k], g))
         n = ref["n_seq"]
         assert np.array_equal(host(out.h0)[:, :n], opack.initial_states(ro["rnn_h"], ref["seq_first"], ref["seq_is_ep_start"]))
