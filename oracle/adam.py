@@ -18,7 +18,9 @@ schedule is lr_k = lr_final + (lr_0 - lr_final) * (1 + cos(pi*k/K)) / 2 for the
 k-th optimiser step counted from 0 (the first step uses lr_0; k is clamped to
 K); gradient clipping is not mentioned: it is optional, by global 2-norm over
 all tensors, g <- g * min(1, max_norm / (norm + 1e-6)), off when
-max_norm <= 0.
+max_norm <= 0.  A tensor may carry bounds (the learned entropy coefficient
+does: appendix hyper-parameter table, bounds [1e-4, 1]); the reading is a
+projection onto them after the step.
 """
 import math
 import numpy as np
@@ -51,3 +53,9 @@ def adam_step(params, grads, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, max_
         new_m.append(mi)
         new_v.append(vi)
     return new_p, new_m, new_v, norm
+
+
+def project(params, lower, upper):
+    """Projection of every tensor onto its box after a step: lower[i] <= p <= upper[i] elementwise
+    (-inf / +inf = unbounded)."""
+    return [np.minimum(np.maximum(np.asarray(p, np.float64), lo), hi) for p, lo, hi in zip(params, lower, upper)]

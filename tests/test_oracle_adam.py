@@ -123,3 +123,13 @@ def test_planted_mistake_is_caught():
     wrong = p - 1e-3 * m / (np.sqrt(v) + 1e-8)
     right, _, _, _ = oadam.adam_step([p], [g], [np.zeros(1)], [np.zeros(1)], 1, 1e-3)
     assert abs(wrong[0] - right[0][0]) > 1e-4
+
+
+def test_projection_is_elementwise_clip():
+    rng = np.random.default_rng(5)
+    params = [rng.standard_normal((3, 4)), rng.standard_normal(1), rng.standard_normal(6)]
+    out = oadam.project(params, [-np.inf, 1e-4, -0.5], [np.inf, 1.0, 0.5])
+    assert np.array_equal(out[0], params[0])
+    assert out[1][0] == min(max(params[1][0], 1e-4), 1.0)
+    assert np.array_equal(out[2], np.clip(params[2], -0.5, 0.5))
+    assert np.all(out[2] <= 0.5) and np.all(out[2] >= -0.5) and np.any(out[2] != params[2])

@@ -74,3 +74,30 @@ def test_workload_generator_shapes():
         assert L.sum() % w.minibatches == 0
     L = wl.apportion_steps(10, np.array([1.0, 1.0, 2.0]))
     assert L.tolist() == [3, 3, 4]
+
+
+@pytest.mark.parametrize("dist,sign", [(1, 1.0), (1, -1.0), (0, 1.0)])
+def test_update_with_learned_entropy_coefficient_first_steps(dist, sign):
+    """Closed form of the chain's alpha trajectory: Adam's first step moves a parameter by lr * sign(gradient), so
+    after one minibatch alpha = project(alpha0 - lr0 * sign * sgn(lambda - H)); the network's first step is the one
+    the fixed-coefficient chain takes at c_e = alpha0 (the policy sees alpha as a constant)."""
+    w = wl.scaled(wl.WORKLOADS["tiny"], dist=dist, act_dim=3, hidden=16, input_dim=8, minibatches=1, epochs=1)
+    ro = wl.make_rollout(w, seed=4, bias_scale=0.2)
+    adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
+    logp_old = learner.collection_logp(ro, ro["weights"], ro["dones"], ro["env_off"], dist,
+                                       ro["env_started_episode"], ro["rnn_h"], ro["rnn_c"]) + ro["logp_noise"]
+    opt = dict(lr0=2.5e-4, lr_final=0.0, total_steps=10, beta1=0.9, beta2=0.999, eps=1e-12, max_grad_norm=0.0)
+    base = dict(dist=dist, clip=w.clip, value_coef=w.value_coef, epochs=1, minibatches=1)
+    alpha0 = 1e-3
+    ref_w, ref_sc, _ = learner.ppo_update(ro, adv, ret, logp_old, dict(base, entropy_coef=alpha0), opt)
+    for lower, upper in [(1e-4, 1.0), (0.9e-3, 1.05e-3)]:      # the paper's bounds (step stays inside), tight ones (it does not)
+        got_w, sc, _, alpha = learner.ppo_update(ro, adv, ret, logp_old, dict(base, target_entropy=0.0, alpha_sign=sign), opt,
+                                                 learned_entropy=dict(alpha0=alpha0, lower=lower, upper=upper))
+        H = sc[0]["entropy"]
+        assert H == ref_sc[0]["entropy"] and H != 0.0
+        free = alpha0 - 2.5e-4 * sign * np.sign(0.0 - H)
+        assert alpha == pytest.approx(min(max(free, lower), upper), rel=1e-9)
+        assert (alpha != pytest.approx(free, rel=1e-9)) == (upper < 1.0)
+        for a, b in zip(learner._flatten(got_w, dist == 1), learner._flatten(ref_w, dist == 1)):
+            assert np.array_equal(a, b)
+        assert sc[0]["total"] == pytest.approx(ref_sc[0]["total"] + alpha0 * (0.0 - H), rel=1e-12)
