@@ -8,6 +8,7 @@
  *     ver_is_weight        once per rollout (optional)
  *     for every epoch, for every minibatch b:
  *         ver_pack_minibatch -> ver_lstm_fwd -> ver_ppo_loss -> ver_lstm_bwd
+ *         -> ver_adam_step
  *
  * Conventions that hold for every entry point
  *  - "device" pointers are HIP device memory owned by the caller; "host"
@@ -297,6 +298,36 @@ int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M,
                  float* scalars, float* d_head_out, float* d_value, float* d_log_std,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * ver_ppo_loss_learned_entropy - the same loss with the learned entropy
+ * coefficient of the training runs in place of the fixed one.
+ * Paper: section 4 "Training" (minimum-entropy constraint with a learned
+ * coefficient: alpha * (lambda - sg[H]) - sg[alpha] * H, sg = stop gradient,
+ * target entropy lambda = 0); appendix hyper-parameter table (initial
+ * coefficient 1e-3, bounds [1e-4, 1.0]).
+ *
+ * alpha: device float[1], read only: the current coefficient.  H is the
+ * (weighted) mean entropy over the M rows, the number scalars[3] reports.
+ *   total = mean(w l_pi) + value_coef * mean(w l_v) + alpha * (target_entropy - H) - alpha * H
+ * The policy is given the gradient of - alpha * H with alpha constant, i.e.
+ * d_head_out, d_value and d_log_std are those of ver_ppo_loss at
+ * entropy_coef = alpha (cfg->entropy_coef is ignored).
+ * d_alpha: device float[1], receives alpha_sign * (target_entropy - H), the
+ * derivative of the expression w.r.t. alpha with H constant.  alpha_sign = +1
+ * is the expression as printed; -1 gives a descending optimiser the ascent
+ * direction of the constraint's multiplier (printed as a minimisation, alpha
+ * shrinks while the entropy is below the target).  Other values: VER_EINVAL.
+ * Keeping alpha inside its bounds is the optimiser's part
+ * (ver_adam_step_bounded).  Everything else as ver_ppo_loss.
+ */
+int ver_ppo_loss_learned_entropy(const ver_ppo_cfg* cfg, int32_t M,
+                                 const float* head_out, const float* value, const float* log_std,
+                                 const void* actions_packed, const float* logp_old, const float* adv,
+                                 const float* ret, const float* is_weight,
+                                 const float* alpha, float target_entropy, float alpha_sign,
+                                 float* scalars, float* d_head_out, float* d_value, float* d_log_std,
+                                 float* d_alpha, void* workspace, size_t workspace_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * ver_adam_step - the optimiser step that follows ver_lstm_bwd.
  * Paper: section 4 "Training" and the appendix hyper-parameter table: Adam,
@@ -336,6 +367,21 @@ size_t ver_adam_workspace_bytes(void);
 int ver_adam_step(const ver_adam_cfg* cfg, int32_t n_tensors, float* const* params, const float* const* grads,
                   float* const* exp_avg, float* const* exp_avg_sq, const int64_t* sizes, int64_t step_index,
                   float* grad_norm, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ver_adam_step_bounded - the same step followed by a projection of every
+ * tensor onto a box: p <- min(max(p, lower[i]), upper[i]) for all elements of
+ * tensor i.  Paper: the learned entropy coefficient is kept inside bounds
+ * (appendix hyper-parameter table: [1e-4, 1.0]); the projection after the step
+ * is our reading of how.  lower, upper: host float arrays of n_tensors entries
+ * (-INFINITY / INFINITY = unbounded), either may be NULL (= unbounded for all).
+ * lower[i] > upper[i] or a NaN bound is VER_EINVAL.  Everything else as
+ * ver_adam_step, which is this call with both arrays NULL.
+ */
+int ver_adam_step_bounded(const ver_adam_cfg* cfg, int32_t n_tensors, float* const* params, const float* const* grads,
+                          float* const* exp_avg, float* const* exp_avg_sq, const int64_t* sizes,
+                          const float* lower, const float* upper, int64_t step_index,
+                          float* grad_norm, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
  * Kernel timing for benchmarks (measurement plumbing, not part of the method).

@@ -77,11 +77,18 @@ lib.ver_ppo_loss_workspace_bytes.argtypes = [_i32, _i32]
 lib.ver_ppo_loss.restype = C.c_int
 lib.ver_ppo_loss.argtypes = [C.POINTER(PpoCfg), _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                              _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.ver_ppo_loss_learned_entropy.restype = C.c_int
+lib.ver_ppo_loss_learned_entropy.argtypes = [C.POINTER(PpoCfg), _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                             _vp, _f, _f, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 lib.ver_adam_workspace_bytes.restype = _sz
 lib.ver_adam_workspace_bytes.argtypes = []
 lib.ver_adam_step.restype = C.c_int
 lib.ver_adam_step.argtypes = [C.POINTER(AdamCfg), _i32, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp),
                               C.POINTER(C.c_int64), C.c_int64, _vp, _vp, _sz, _vp]
+lib.ver_adam_step_bounded.restype = C.c_int
+lib.ver_adam_step_bounded.argtypes = [C.POINTER(AdamCfg), _i32, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_vp),
+                                      C.POINTER(_vp), C.POINTER(C.c_int64), C.POINTER(_f), C.POINTER(_f), C.c_int64,
+                                      _vp, _vp, _sz, _vp]
 
 lib.ver_profile_enable.restype = C.c_int
 lib.ver_profile_enable.argtypes = [C.c_uint32]
@@ -203,6 +210,16 @@ def ver_ppo_loss(cfg, M, head_out, value, log_std, actions_packed, logp_old, adv
                             _ptr(d_head_out), _ptr(d_value), _ptr(d_log_std), p, n, _stream()))
 
 
+def ver_ppo_loss_learned_entropy(cfg, M, head_out, value, log_std, actions_packed, logp_old, adv, ret, is_weight,
+                                 alpha, target_entropy, alpha_sign, scalars, d_head_out, d_value, d_log_std, d_alpha,
+                                 workspace):
+    p, n = _ws(workspace)
+    _check(lib.ver_ppo_loss_learned_entropy(
+        C.byref(cfg), M, _ptr(head_out), _ptr(value), _ptr(log_std), _ptr(actions_packed), _ptr(logp_old), _ptr(adv),
+        _ptr(ret), _ptr(is_weight), _ptr(alpha), target_entropy, alpha_sign, _ptr(scalars), _ptr(d_head_out),
+        _ptr(d_value), _ptr(d_log_std), _ptr(d_alpha), p, n, _stream()))
+
+
 def adam_cfg(lr0=2.5e-4, lr_final=0.0, total_steps=1, beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=0.0) -> AdamCfg:
     return AdamCfg(lr0, lr_final, total_steps, beta1, beta2, eps, max_grad_norm)
 
@@ -217,6 +234,17 @@ def ver_adam_step(cfg, params, grads, exp_avg, exp_avg_sq, step_index, grad_norm
     p, n = _ws(workspace)
     _check(lib.ver_adam_step(C.byref(cfg), len(params), _ptr_array(params), _ptr_array(grads), _ptr_array(exp_avg),
                              _ptr_array(exp_avg_sq), sizes, step_index, _ptr(grad_norm), p, n, _stream()))
+
+
+def ver_adam_step_bounded(cfg, params, grads, exp_avg, exp_avg_sq, lower, upper, step_index, grad_norm, workspace):
+    """lower, upper: one float per tensor (None = unbounded for all tensors)."""
+    sizes = (C.c_int64 * len(params))(*[t.numel() for t in params])
+    lo = (C.c_float * len(params))(*lower) if lower is not None else None
+    hi = (C.c_float * len(params))(*upper) if upper is not None else None
+    p, n = _ws(workspace)
+    _check(lib.ver_adam_step_bounded(C.byref(cfg), len(params), _ptr_array(params), _ptr_array(grads),
+                                     _ptr_array(exp_avg), _ptr_array(exp_avg_sq), sizes, lo, hi, step_index,
+                                     _ptr(grad_norm), p, n, _stream()))
 
 
 def ver_profile_enable(mask: int) -> None:

@@ -30,6 +30,7 @@ struct AdamTensors {
     float* m[VER_ADAM_MAX_TENSORS];
     float* v[VER_ADAM_MAX_TENSORS];
     long long n[VER_ADAM_MAX_TENSORS];
+    float lower[VER_ADAM_MAX_TENSORS], upper[VER_ADAM_MAX_TENSORS];   // box of tensor i (-inf / +inf = none)
     int first_chunk[VER_ADAM_MAX_TENSORS + 1];   // chunks of tensor i: [first_chunk[i], first_chunk[i+1])
     int count;
 };
@@ -93,10 +94,13 @@ struct AdamScalars {
     float inv_c1, inv_c2;   // 1 / (1 - beta^t)
 };
 
-__device__ __forceinline__ void adam_elem(float& p, float g, float& m, float& v, const AdamScalars& a) {
+// One element's step, then the projection onto the tensor's box.
+__device__ __forceinline__ void adam_elem(float& p, float g, float& m, float& v, const AdamScalars& a, float lower,
+                                          float upper) {
     m = a.beta1 * m + a.omb1 * g;
     v = a.beta2 * v + a.omb2 * g * g;
     p -= a.lr * (m * a.inv_c1) / (sqrtf(v * a.inv_c2) + a.eps);
+    p = fminf(fmaxf(p, lower), upper);
 }
 
 __global__ __launch_bounds__(ADAM_THREADS) void adam_update_kernel(AdamTensors t, AdamScalars a, const float* __restrict__ scale) {
@@ -109,6 +113,7 @@ __global__ __launch_bounds__(ADAM_THREADS) void adam_update_kernel(AdamTensors t
     float* m = t.m[i];
     float* v = t.v[i];
     const float gs = scale ? scale[0] : 1.f;
+    const float lower = t.lower[i], upper = t.upper[i];
     for (long long e = lo + threadIdx.x * 4; e < hi; e += ADAM_THREADS * 4) {
         if (e + 4 <= hi) {
             f4 pp = *reinterpret_cast<f4*>(p + e), mm = *reinterpret_cast<f4*>(m + e), vv = *reinterpret_cast<f4*>(v + e);
@@ -116,14 +121,14 @@ __global__ __launch_bounds__(ADAM_THREADS) void adam_update_kernel(AdamTensors t
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 float pk = pp[k], mk = mm[k], vk = vv[k];
-                adam_elem(pk, gg[k] * gs, mk, vk, a);
+                adam_elem(pk, gg[k] * gs, mk, vk, a, lower, upper);
                 pp[k] = pk; mm[k] = mk; vv[k] = vk;
             }
             *reinterpret_cast<f4*>(p + e) = pp;
             *reinterpret_cast<f4*>(m + e) = mm;
             *reinterpret_cast<f4*>(v + e) = vv;
         } else {
-            for (long long k = e; k < hi; ++k) adam_elem(p[k], g[k] * gs, m[k], v[k], a);
+            for (long long k = e; k < hi; ++k) adam_elem(p[k], g[k] * gs, m[k], v[k], a, lower, upper);
         }
     }
 }
@@ -138,6 +143,14 @@ extern "C" size_t ver_adam_workspace_bytes(void) {
 extern "C" int ver_adam_step(const ver_adam_cfg* cfg, int32_t n_tensors, float* const* params, const float* const* grads,
                              float* const* exp_avg, float* const* exp_avg_sq, const int64_t* sizes, int64_t step_index,
                              float* grad_norm, void* workspace, size_t workspace_bytes, void* stream) {
+    return ver_adam_step_bounded(cfg, n_tensors, params, grads, exp_avg, exp_avg_sq, sizes, nullptr, nullptr, step_index,
+                                 grad_norm, workspace, workspace_bytes, stream);
+}
+
+extern "C" int ver_adam_step_bounded(const ver_adam_cfg* cfg, int32_t n_tensors, float* const* params,
+                                     const float* const* grads, float* const* exp_avg, float* const* exp_avg_sq,
+                                     const int64_t* sizes, const float* lower, const float* upper, int64_t step_index,
+                                     float* grad_norm, void* workspace, size_t workspace_bytes, void* stream) {
     using namespace ver;
     if (!cfg || !params || !grads || !exp_avg || !exp_avg_sq || !sizes) return VER_EINVAL;
     if (n_tensors < 0 || n_tensors > VER_ADAM_MAX_TENSORS || cfg->total_steps <= 0 || step_index < 0) return VER_EINVAL;
@@ -149,12 +162,15 @@ extern "C" int ver_adam_step(const ver_adam_cfg* cfg, int32_t n_tensors, float* 
     int chunks = 0;
     for (int i = 0; i < n_tensors; ++i) {
         if (sizes[i] < 0) return VER_EINVAL;
+        const float lo = lower ? lower[i] : -INFINITY, hi = upper ? upper[i] : INFINITY;
+        if (!(lo <= hi)) return VER_EINVAL;   // also rejects NaN
         if (sizes[i] == 0) continue;
         if (!params[i] || !grads[i] || !exp_avg[i] || !exp_avg_sq[i]) return VER_EINVAL;
         const long long c = (sizes[i] + ADAM_CHUNK - 1) / ADAM_CHUNK;
         if (chunks + c > ADAM_MAX_CHUNKS) return VER_EUNSUPPORTED;
         t.p[t.count] = params[i]; t.g[t.count] = grads[i]; t.m[t.count] = exp_avg[i]; t.v[t.count] = exp_avg_sq[i];
         t.n[t.count] = sizes[i];
+        t.lower[t.count] = lo; t.upper[t.count] = hi;
         t.first_chunk[t.count] = chunks;
         chunks += (int)c;
         ++t.count;

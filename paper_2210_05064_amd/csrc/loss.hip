@@ -4,7 +4,10 @@
 //
 // Paper: section 2.2 "Learning method" (PPO), appendix hyper-parameter table
 // (clip 0.2, value coefficient 0.5, no clipped value loss, no advantage
-// normalisation) and the fixed entropy coefficient of the benchmark runs.
+// normalisation) and the fixed entropy coefficient of the benchmark runs; or,
+// as in the training runs (section 4 "Training"), the learned coefficient alpha
+// read from device memory: the total then carries alpha*(lambda - H) - alpha*H
+// and alpha's gradient lambda - H leaves the kernel with the other scalars.
 //
 // One thread owns a row: it reads the row's head outputs, action, old
 // log-probability, advantage and return once, writes the row's gradients once
@@ -48,7 +51,8 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     const float* __restrict__ logp_old, const float* __restrict__ adv, const float* __restrict__ ret,
     const float* __restrict__ is_weight, float* __restrict__ scalars, float* __restrict__ d_u,
     float* __restrict__ d_value, float* __restrict__ d_log_std, float* __restrict__ partials,
-    int* __restrict__ counter) {
+    int* __restrict__ counter, const float* __restrict__ alpha, float target_entropy, float alpha_sign,
+    float* __restrict__ d_alpha) {
     __shared__ float s_red[LOSS_THREADS / VER_WAVE];
     __shared__ float s_ls[64], s_inv_sigma[64];
     __shared__ int s_last;
@@ -56,6 +60,8 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     const int A = cfg.act_dim;
     const int width = LOSS_SCALARS + (DIST == 1 ? A : 0);  // partial sums per workgroup
     const float inv_m = 1.f / (float)M;
+    // entropy coefficient: the fixed one, or the current value of the learned one (a constant for the policy)
+    const float ent_coef = alpha ? alpha[0] : cfg.entropy_coef;
     if (DIST == 1) {
         if (threadIdx.x < A) {
             s_ls[threadIdx.x] = log_std[threadIdx.x];
@@ -96,7 +102,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
                 const float s1 = rho * adv_p;
                 const float s2 = fminf(fmaxf(rho, 1.f - cfg.clip), 1.f + cfg.clip) * adv_p;
                 coef_logp = (s1 <= s2) ? -w * adv_p * rho * inv_m : 0.f;
-                coef_ent = -cfg.entropy_coef * w * inv_m;
+                coef_ent = -ent_coef * w * inv_m;
                 float* dp = d_u + (size_t)p * A;
                 for (int j = 0; j < A; ++j) {
                     const float lq = up[j] - lse;
@@ -120,7 +126,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
                 const float s1 = rho * adv_p;
                 const float s2 = fminf(fmaxf(rho, 1.f - cfg.clip), 1.f + cfg.clip) * adv_p;
                 coef_logp = (s1 <= s2) ? -w * adv_p * rho * inv_m : 0.f;
-                coef_ent = -cfg.entropy_coef * w * inv_m;
+                coef_ent = -ent_coef * w * inv_m;
                 float* dp = d_u + (size_t)p * A;
                 for (int d = 0; d < A; ++d)
                     dp[d] = coef_logp * (ap[d] - up[d]) * s_inv_sigma[d] * s_inv_sigma[d];
@@ -171,7 +177,12 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     __syncthreads();
     if (threadIdx.x == 0) {
         const float pol = s_out[0], val = s_out[1], ent = s_out[2];
-        scalars[0] = pol + cfg.value_coef * val - cfg.entropy_coef * ent;
+        float total = pol + cfg.value_coef * val - ent_coef * ent;
+        if (alpha) {
+            total += ent_coef * (target_entropy - ent);
+            d_alpha[0] = alpha_sign * (target_entropy - ent);
+        }
+        scalars[0] = total;
         scalars[1] = pol;
         scalars[2] = val;
         scalars[3] = ent;
@@ -194,11 +205,13 @@ extern "C" size_t ver_ppo_loss_workspace_bytes(int32_t M, int32_t act_dim) {
     return 256 + ver::align_up((size_t)ver::loss_blocks(M) * (ver::LOSS_SCALARS + act_dim) * 4, 256);
 }
 
-extern "C" int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M, const float* head_out, const float* value,
-                            const float* log_std, const void* actions_packed, const float* logp_old,
-                            const float* adv, const float* ret, const float* is_weight, float* scalars,
-                            float* d_head_out, float* d_value, float* d_log_std, void* workspace,
-                            size_t workspace_bytes, void* stream) {
+namespace ver {
+namespace {
+int ppo_loss_launch(const ver_ppo_cfg* cfg, int32_t M, const float* head_out, const float* value, const float* log_std,
+                    const void* actions_packed, const float* logp_old, const float* adv, const float* ret,
+                    const float* is_weight, float* scalars, float* d_head_out, float* d_value, float* d_log_std,
+                    void* workspace, size_t workspace_bytes, void* stream, const float* alpha, float target_entropy,
+                    float alpha_sign, float* d_alpha) {
     if (!cfg || M <= 0 || !head_out || !value || !actions_packed || !logp_old || !adv || !ret || !scalars ||
         !d_head_out || !d_value)
         return VER_EINVAL;
@@ -207,19 +220,43 @@ extern "C" int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M, const float* head
     if (cfg->dist == 1 && (!log_std || !d_log_std)) return VER_EINVAL;
     if (!workspace || workspace_bytes < ver_ppo_loss_workspace_bytes(M, cfg->act_dim)) return VER_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    ver::Carver cv(workspace);
+    Carver cv(workspace);
     int* counter = cv.take<int>(64);
-    float* partials = cv.take<float>((size_t)ver::loss_blocks(M) * (ver::LOSS_SCALARS + cfg->act_dim));
-    ver::fill_words(counter, 1, 0, s);
-    const int blocks = ver::loss_blocks(M);
-    ver::ProfScope prof(VER_PROF_LOSS, s);
+    float* partials = cv.take<float>((size_t)loss_blocks(M) * (LOSS_SCALARS + cfg->act_dim));
+    fill_words(counter, 1, 0, s);
+    const int blocks = loss_blocks(M);
+    ProfScope prof(VER_PROF_LOSS, s);
     if (cfg->dist == 0)
-        hipLaunchKernelGGL(ver::ppo_loss_kernel<0>, dim3(blocks), dim3(ver::LOSS_THREADS), 0, s, *cfg, M, head_out,
+        hipLaunchKernelGGL(ppo_loss_kernel<0>, dim3(blocks), dim3(LOSS_THREADS), 0, s, *cfg, M, head_out,
                            value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out,
-                           d_value, d_log_std, partials, counter);
+                           d_value, d_log_std, partials, counter, alpha, target_entropy, alpha_sign, d_alpha);
     else
-        hipLaunchKernelGGL(ver::ppo_loss_kernel<1>, dim3(blocks), dim3(ver::LOSS_THREADS), 0, s, *cfg, M, head_out,
+        hipLaunchKernelGGL(ppo_loss_kernel<1>, dim3(blocks), dim3(LOSS_THREADS), 0, s, *cfg, M, head_out,
                            value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out,
-                           d_value, d_log_std, partials, counter);
-    return ver::launch_status();
+                           d_value, d_log_std, partials, counter, alpha, target_entropy, alpha_sign, d_alpha);
+    return launch_status();
+}
+}  // namespace
+}  // namespace ver
+
+extern "C" int ver_ppo_loss(const ver_ppo_cfg* cfg, int32_t M, const float* head_out, const float* value,
+                            const float* log_std, const void* actions_packed, const float* logp_old,
+                            const float* adv, const float* ret, const float* is_weight, float* scalars,
+                            float* d_head_out, float* d_value, float* d_log_std, void* workspace,
+                            size_t workspace_bytes, void* stream) {
+    return ver::ppo_loss_launch(cfg, M, head_out, value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars,
+                                d_head_out, d_value, d_log_std, workspace, workspace_bytes, stream, nullptr, 0.f, 1.f,
+                                nullptr);
+}
+
+extern "C" int ver_ppo_loss_learned_entropy(const ver_ppo_cfg* cfg, int32_t M, const float* head_out, const float* value,
+                                            const float* log_std, const void* actions_packed, const float* logp_old,
+                                            const float* adv, const float* ret, const float* is_weight,
+                                            const float* alpha, float target_entropy, float alpha_sign, float* scalars,
+                                            float* d_head_out, float* d_value, float* d_log_std, float* d_alpha,
+                                            void* workspace, size_t workspace_bytes, void* stream) {
+    if (!alpha || !d_alpha || !(alpha_sign == 1.f || alpha_sign == -1.f)) return VER_EINVAL;
+    return ver::ppo_loss_launch(cfg, M, head_out, value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars,
+                                d_head_out, d_value, d_log_std, workspace, workspace_bytes, stream, alpha,
+                                target_entropy, alpha_sign, d_alpha);
 }

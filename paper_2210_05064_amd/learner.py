@@ -26,8 +26,10 @@ class Learner:
 
     def __init__(self, rollout: dict, *, compute: int | None = None, x_bf16: bool | None = None,
                  want_dx: bool = False, minibatches: int | None = None, adam_total_steps: int | None = None,
-                 adam: dict | None = None, max_is: float | None = None):
-        """max_is: truncation of the per-step importance weight; None = unweighted loss.
+                 adam: dict | None = None, max_is: float | None = None, learned_entropy: dict | None = None):
+        """learned_entropy: dict alpha0, lower, upper, target, sign: the entropy coefficient is a device-resident
+        parameter, the last tensor of the optimiser step, kept inside [lower, upper]; None = fixed coefficient.
+        max_is: truncation of the per-step importance weight; None = unweighted loss.
         adam_total_steps: length of the cosine schedule in optimiser steps; None = no optimiser (gradients only).
         adam: overrides of the optimiser's hyper-parameters (fields of ver_adam_cfg)."""
         w: Workload = rollout["workload"]
@@ -81,6 +83,10 @@ class Learner:
         self.d_head, self.d_value = torch.empty((M, A), **f32), torch.empty(M, **f32)
         self.d_x = torch.empty((M, D), **f32) if want_dx else None
         self.scalars = torch.zeros(6, **f32)
+        self.learned_entropy = learned_entropy
+        if learned_entropy is not None:
+            self.alpha = torch.full((1,), float(learned_entropy["alpha0"]), **f32)
+            self.d_alpha = torch.zeros(1, **f32)
         # configuration structs and workspaces
         self.lstm_cfg = ver.lstm_cfg(nl, D, H, A, self.compute, int(self.x_bf16))
         self.ppo_cfg = ver.ppo_cfg(w.clip, w.value_coef, w.entropy_coef, w.dist, A)
@@ -98,6 +104,13 @@ class Learner:
             self.adam_cfg = ver.adam_cfg(total_steps=adam_total_steps, **(adam or {}))
             self.opt_params = self.weights + ([self.log_std] if w.dist == 1 else [])
             self.opt_grads = self.grads + ([self.d_log_std] if w.dist == 1 else [])
+            self.opt_lower = self.opt_upper = None
+            if learned_entropy is not None:
+                inf = float("inf")
+                self.opt_lower = [-inf] * len(self.opt_params) + [float(learned_entropy["lower"])]
+                self.opt_upper = [inf] * len(self.opt_params) + [float(learned_entropy["upper"])]
+                self.opt_params = self.opt_params + [self.alpha]
+                self.opt_grads = self.opt_grads + [self.d_alpha]
             self.exp_avg = [torch.zeros_like(t) for t in self.opt_params]
             self.exp_avg_sq = [torch.zeros_like(t) for t in self.opt_params]
             self.grad_norm = torch.zeros(1, **f32)
@@ -131,6 +144,14 @@ class Learner:
                          self.h0, self.c0, self.seq_cap, self.weights, self.head_out, self.value, self.ws_lstm)
 
     def loss(self):
+        le = self.learned_entropy
+        if le is not None:
+            ver.ver_ppo_loss_learned_entropy(
+                self.ppo_cfg, self.M, self.head_out, self.value, self.log_std if self.w.dist == 1 else None,
+                self.act_packed, self.logp_old_p, self.adv_p, self.ret_p, self.is_w_p, self.alpha,
+                float(le.get("target", 0.0)), float(le.get("sign", 1.0)), self.scalars, self.d_head, self.d_value,
+                self.d_log_std if self.w.dist == 1 else None, self.d_alpha, self.ws_loss)
+            return
         ver.ver_ppo_loss(self.ppo_cfg, self.M, self.head_out, self.value,
                          self.log_std if self.w.dist == 1 else None, self.act_packed, self.logp_old_p,
                          self.adv_p, self.ret_p, self.is_w_p, self.scalars, self.d_head, self.d_value,
@@ -142,8 +163,8 @@ class Learner:
                          self.d_x, self.ws_lstm)
 
     def optimizer_step(self):
-        ver.ver_adam_step(self.adam_cfg, self.opt_params, self.opt_grads, self.exp_avg, self.exp_avg_sq, self.opt_steps,
-                          self.grad_norm, self.ws_adam)
+        ver.ver_adam_step_bounded(self.adam_cfg, self.opt_params, self.opt_grads, self.exp_avg, self.exp_avg_sq,
+                                  self.opt_lower, self.opt_upper, self.opt_steps, self.grad_norm, self.ws_adam)
         self.opt_steps += 1
 
     def minibatch(self, epoch: int, b: int):

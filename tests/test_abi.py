@@ -100,3 +100,29 @@ def test_is_weight_argument_checks(lib):
     assert lib.ver_is_weight(None, 4, 0, 0.0, None, None) == -1       # truncation must be positive
     assert lib.ver_is_weight(None, 4, 0, float("nan"), None, None) == -1
     assert lib.ver_is_weight(None, 4, -1, 1.0, None, None) == -1
+
+
+def test_learned_entropy_and_bounded_step_argument_checks(lib):
+    lib.ver_ppo_loss_learned_entropy.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 9 + [C.c_float, C.c_float] + \
+        [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
+    one = C.c_void_p(16)      # never dereferenced: the checks below fail before any GPU work
+    assert lib.ver_ppo_loss_learned_entropy(None, 4, *([None] * 9), 0.0, 1.0, *([None] * 6), 0, None) == -1
+    # alpha and d_alpha present, a sign other than +1 / -1
+    assert lib.ver_ppo_loss_learned_entropy(None, 4, *([None] * 8), one, 0.0, 0.5, *([None] * 4), one, None, 0, None) == -1
+    # valid sign, but the remaining arguments are still checked
+    assert lib.ver_ppo_loss_learned_entropy(None, 4, *([None] * 8), one, 0.0, -1.0, *([None] * 4), one, None, 0, None) == -1
+
+    class AdamCfg(C.Structure):
+        _fields_ = [("lr0", C.c_float), ("lr_final", C.c_float), ("total_steps", C.c_int64), ("beta1", C.c_float),
+                    ("beta2", C.c_float), ("eps", C.c_float), ("max_grad_norm", C.c_float)]
+    lib.ver_adam_step_bounded.argtypes = [C.c_void_p, C.c_int32] + [C.c_void_p] * 7 + [C.c_int64] + [C.c_void_p] * 2 + \
+        [C.c_size_t, C.c_void_p]
+    ok = AdamCfg(2.5e-4, 0.0, 10, 0.9, 0.999, 1e-8, 0.0)
+    empty = (C.c_void_p * 1)()
+    sizes = (C.c_int64 * 1)(0)
+    call = lambda lo, hi: lib.ver_adam_step_bounded(C.byref(ok), 1, empty, empty, empty, empty, sizes,
+                                                    (C.c_float * 1)(lo) if lo is not None else None,
+                                                    (C.c_float * 1)(hi) if hi is not None else None, 0, None, None, 0, None)
+    assert call(None, None) == 0 and call(1e-4, 1.0) == 0 and call(None, 1.0) == 0 and call(0.5, 0.5) == 0
+    assert call(1.0, 1e-4) == -1                      # empty box
+    assert call(float("nan"), 1.0) == -1 and call(0.0, float("nan")) == -1

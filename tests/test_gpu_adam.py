@@ -86,3 +86,43 @@ def test_bitwise_reproducible_and_empty(ver):
     assert all(np.array_equal(a, b) for a, b in zip(*outs))
     # nothing to do is not an error
     ver.ver_adam_step(ver.adam_cfg(total_steps=5), [], [], [], [], 0, None, None)
+
+
+def test_bounded_step_projects_after_the_update(ver):
+    """ver_adam_step_bounded: per-tensor boxes.  A tensor without bounds moves as in ver_adam_step; a bounded one
+    is the oracle's step followed by the oracle's projection, bit-exact where the bound is hit."""
+    rng = np.random.default_rng(3)
+    sizes = [(5000,), (1,), (1,), (33,)]
+    lower = [-np.inf, 1e-4, 1e-4, -0.004]
+    upper = [np.inf, 1.0, 1.0, 0.004]
+    p0 = [(0.01 * rng.standard_normal(s)).astype(np.float32) for s in sizes]
+    p0[1][:] = 1.05e-4        # will be pushed below the lower bound
+    p0[2][:] = 0.004          # stays inside (small, so that fp32 resolves the step to 1e-5)
+    grads = [rng.standard_normal(s).astype(np.float32) for s in sizes]
+    grads[1][:] = 3.0
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    cfg_kw = dict(lr0=1e-3, lr_final=0.0, total_steps=10)
+    cfg = ver.adam_cfg(**cfg_kw)
+    ws = ver.workspace(ver.ver_adam_workspace_bytes())
+    p, q = [dev(x) for x in p0], [dev(x) for x in p0]
+    mp, vp = [torch.zeros_like(x) for x in p], [torch.zeros_like(x) for x in p]
+    mq, vq = [torch.zeros_like(x) for x in p], [torch.zeros_like(x) for x in p]
+    g = [dev(x) for x in grads]
+    ver.ver_adam_step_bounded(cfg, p, g, mp, vp, lower, upper, 0, None, ws)
+    ver.ver_adam_step(cfg, q, g, mq, vq, 0, None, ws)
+    torch.cuda.synchronize()
+    f32 = lambda x: float(np.float32(x))
+    new_p, _, _, _ = oadam.adam_step([x.astype(np.float64) for x in p0], grads, [np.zeros(s) for s in sizes],
+                                     [np.zeros(s) for s in sizes], 1, f32(1e-3), f32(0.9), f32(0.999), f32(1e-8))
+    want = oadam.project(new_p, [f32(x) for x in lower], [f32(x) for x in upper])
+    assert torch.equal(p[0], q[0]) and torch.equal(p[2], q[2])            # no bound hit: same as the plain step
+    assert p[1].item() == np.float32(1e-4) and q[1].item() < 1e-4         # clamped exactly to the bound
+    got3 = p[3].cpu().numpy()
+    assert got3.max() == np.float32(0.004) and got3.min() == np.float32(-0.004)
+    hit = (want[3] == f32(0.004)) | (want[3] == f32(-0.004))
+    assert hit.any() and (~hit).any()
+    assert np.array_equal(np.abs(got3) == np.float32(0.004), hit)
+    for i, s in enumerate(sizes):
+        assert_close(p[i].cpu().numpy().astype(np.float64) - p0[i], want[i] - p0[i], 1e-5, f"delta[{i}]")
+    for a, b in zip(mp + vp, mq + vq):
+        assert torch.equal(a, b)                                          # the moments do not see the projection

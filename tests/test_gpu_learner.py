@@ -7,7 +7,7 @@ import torch
 from oracle import gae as ogae, is_weight as ois, learner as olearner, pack as opack
 from paper_2210_05064_amd import workloads as wl
 from tests.gpu_util import GRAD_NAMES, grads_to_list, host
-from tests.util import assert_close, assert_close_bf16
+from tests.util import assert_close, assert_close_bf16, assert_close_update
 
 pytestmark = pytest.mark.gpu
 
@@ -118,6 +118,47 @@ def test_update_with_optimizer(ver, dist, clip_norm, max_is):
         got = host(t).astype(np.float64) - b0
         want = r - b0
         assert np.max(np.abs(want)) > 1e-5, "the update must have moved the tensor"
-        assert_close(got, want, 5e-3, f"change of tensor {i}")
+        assert_close_update(got, want, f"change of tensor {i}")
+    sc = host(L.scalars)
+    assert abs(sc[0] - ref_scalars[-1]["total"]) <= 1e-3 * max(abs(ref_scalars[-1]["total"]), 1e-2)
+
+
+@pytest.mark.parametrize("dist,sign,max_is", [(1, 1.0, None), (1, -1.0, 1.0), (0, -1.0, None)])
+def test_update_with_learned_entropy_coefficient(ver, dist, sign, max_is):
+    """The learned entropy coefficient in the loop (2 epochs x 2 minibatches): it lives in device memory, the loss
+    reads it and hands its gradient to the optimiser, which keeps it inside its bounds.  Its trajectory (bounds
+    tight enough to be hit), the weights and the last minibatch's loss against the oracle chain."""
+    from paper_2210_05064_amd.learner import Learner
+    base = wl.WORKLOADS["manip" if dist == 1 else "nav"]
+    w = wl.scaled(base, budget=384, n_envs=10, hidden=64, input_dim=20, p_done=0.03, epochs=2, minibatches=2)
+    ro = wl.make_rollout(w, seed=43, bias_scale=0.1)
+    adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
+    logp_old = (olearner.collection_logp(ro, ro["weights"], ro["dones"], ro["env_off"], w.dist,
+                                         ro["env_started_episode"], ro["rnn_h"], ro["rnn_c"])
+                + ro["logp_noise"]).astype(np.float32)
+    f32 = lambda x: float(np.float32(x))
+    opt = dict(lr0=2.5e-4, lr_final=0.0, total_steps=6, beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=0.0)
+    le = dict(alpha0=f32(1e-3), lower=f32(6e-4), upper=f32(1.4e-3))       # two steps of 2.5e-4 leave the box
+    L = Learner(ro, compute=0, adam_total_steps=opt["total_steps"],
+                adam={k: v for k, v in opt.items() if k != "total_steps"}, max_is=max_is,
+                learned_entropy=dict(le, target=0.0, sign=sign))
+    L.logp_old.copy_(torch.from_numpy(logp_old).cuda())
+    before = [host(t).astype(np.float64) for t in L.opt_params]
+    alphas = []
+    L.update(on_minibatch=lambda e, b: alphas.append(float(L.alpha.item())))
+    torch.cuda.synchronize()
+    assert not L.lstm_timed_out() and L.opt_steps == 4
+    cfg = dict(dist=w.dist, clip=f32(w.clip), value_coef=w.value_coef, target_entropy=0.0, alpha_sign=sign,
+               epochs=w.epochs, minibatches=w.minibatches)
+    opt32 = {k: (f32(v) if k != "total_steps" else v) for k, v in opt.items()}
+    ref_w, ref_scalars, _, ref_alpha = olearner.ppo_update(ro, adv.astype(np.float32), ret.astype(np.float32), logp_old,
+                                                           cfg, opt32, max_is=max_is, learned_entropy=le)
+    assert alphas[-1] == pytest.approx(ref_alpha, rel=1e-4)
+    assert le["lower"] <= min(alphas) and max(alphas) <= le["upper"]
+    assert alphas[-1] in (np.float32(le["lower"]), np.float32(le["upper"])), "the bound must have been reached"
+    assert abs(alphas[0] - le["alpha0"]) == pytest.approx(2.5e-4, rel=1e-3)     # Adam's first step: lr * sign
+    ref = olearner._flatten(ref_w, w.dist == 1)
+    for i, (t, b0, r) in enumerate(zip(L.opt_params[:-1], before, ref)):
+        assert_close_update(host(t).astype(np.float64) - b0, r - b0, f"change of tensor {i}")
     sc = host(L.scalars)
     assert abs(sc[0] - ref_scalars[-1]["total"]) <= 1e-3 * max(abs(ref_scalars[-1]["total"]), 1e-2)

@@ -112,3 +112,41 @@ def test_reproducible_and_errors(ver):
         cfg = ver.ppo_cfg(0.2, 0.5, 0.0, 0, 64)
         t = torch.zeros(64, device="cuda")
         ver.ver_ppo_loss(cfg, 1, t, t, None, t.to(torch.int32), t, t, t, None, t, t, t, None, ver.workspace(4096))
+
+
+@pytest.mark.parametrize("dist,A,M", [(0, 4, 1024), (1, 11, 8192), (0, 7, 777), (1, 3, 1)])
+@pytest.mark.parametrize("alpha,target,sign", [(1e-3, 0.0, 1.0), (0.35, 1.5, -1.0)])
+def test_learned_entropy_coefficient(ver, dist, A, M, alpha, target, sign):
+    """ver_ppo_loss_learned_entropy against the oracle: the coefficient comes from device memory, the total
+    carries alpha's own term, d_alpha = sign * (target - H); the policy's gradients are those at c_e = alpha."""
+    from oracle import entropy_coef as oec
+    rng = np.random.default_rng(M + A)
+    x = make(rng, dist, M, A)
+    weight = rng.random(M).astype(np.float32) if M > 1 else None
+    cfg = ver.ppo_cfg(0.2, 0.5, 123.0, dist, A)          # the fixed coefficient must be ignored
+    scal = torch.full((6,), float("nan"), device="cuda")
+    d_u = torch.full((M, A), float("nan"), device="cuda")
+    d_v = torch.full((M,), float("nan"), device="cuda")
+    d_ls = torch.full((A,), float("nan"), device="cuda")
+    d_alpha = torch.full((1,), float("nan"), device="cuda")
+    a_dev = torch.tensor([alpha], dtype=torch.float32, device="cuda")
+    ws = ver.workspace(ver.ver_ppo_loss_workspace_bytes(M, A))
+    ws.fill_(-1)
+    ver.ver_ppo_loss_learned_entropy(cfg, M, dev(x["u"]), dev(x["v"]), dev(x["ls"]) if dist == 1 else None, dev(x["act"]),
+                                     dev(x["logp_old"]), dev(x["adv"]), dev(x["ret"]),
+                                     dev(weight) if weight is not None else None, a_dev, target, sign,
+                                     scal, d_u, d_v, d_ls, d_alpha, ws)
+    torch.cuda.synchronize()
+    f32 = lambda c: float(np.float32(c))
+    ref, r_u, r_v, r_ls, r_alpha = oec.ppo_loss_learned_entropy(
+        dist, x["u"], x["v"], x["ls"], x["act"], x["logp_old"], x["adv"], x["ret"], f32(0.2), 0.5, f32(alpha),
+        f32(target), weight, sign)
+    scal = host(scal)
+    for i, n in enumerate(NAMES[:5]):
+        assert abs(scal[i] - ref[n]) <= TOL * max(abs(ref[n]), 1e-2), (n, scal[i], ref[n])
+    assert abs(host(d_alpha)[0] - r_alpha) <= TOL * max(abs(r_alpha), 1e-2)
+    assert host(a_dev)[0] == np.float32(alpha)           # read only
+    assert_close(host(d_u), r_u, TOL, "d_head_out")
+    assert_close(host(d_v), r_v, TOL, "d_value")
+    if dist == 1:
+        assert_close(host(d_ls), r_ls, TOL, "d_log_std")

@@ -39,3 +39,15 @@ def assert_close_bf16(x, ref, what=""):
     e2, em = l2_rel_err(x, ref), rel_err(x, ref)
     assert e2 <= 2e-2, f"{what}: relative 2-norm error {e2:.3e} > 2.0e-02"
     assert em <= 1e-1, f"{what}: elementwise relative error {em:.3e} > 1.0e-01"
+
+
+def assert_close_update(x, ref, what=""):
+    """Bar for the CHANGE of a weight tensor over a few optimiser steps of the fp32 path: 1e-3 relative in the
+    2-norm (measured 1e-5 .. 2e-4), plus an elementwise sanity bound of 1e-1 relative to max(|ref|, rms(ref)).
+    Adam's step m / (sqrt(v) + eps) does not depend on the size of the gradient: an element whose gradient is at
+    the level of fp32 rounding noise still takes a step of full size, in a direction that noise decides, so the
+    largest elementwise error of a big tensor (measured up to 3e-2 on one element of 16384) says nothing about
+    the arithmetic."""
+    e2, em = l2_rel_err(x, ref), rel_err(x, ref)
+    assert e2 <= 1e-3, f"{what}: relative 2-norm error {e2:.3e} > 1.0e-03"
+    assert em <= 1e-1, f"{what}: elementwise relative error {em:.3e} > 1.0e-01"
