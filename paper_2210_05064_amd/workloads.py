@@ -155,3 +155,29 @@ def make_rollout(w: Workload, seed: int, *, with_states: bool = True,
 def scaled(w: Workload, **kw) -> Workload:
     """A copy of a workload with some fields replaced (tests shrink H or S)."""
     return dataclasses.replace(w, **kw)
+
+
+def arrival_order(env_off: np.ndarray, seed: int, t_start: np.ndarray | None = None):
+    """A linear buffer as inference workers would fill it: the S steps of a rollout interleaved across
+    environments, every environment's own steps in time order.
+
+    Every step gets a seeded completion time (environment i's steps at the running sum of its own exponential
+    step durations, so that fast and slow stretches alternate as in the paper's collection phase); the buffer
+    is written in order of completion time.  Returns (arr_env[S], arr_t[S], csr_of_arrival[S]): the environment
+    and the environment's own step counter of the step in arrival slot a (counters start at t_start[i], zero
+    when omitted), and the flat environment-major index that step has in the buffer env_off describes (what
+    a test needs to build the arrival-order copy of any per-step field: field_arrival = field_csr[csr_of_arrival]).
+    """
+    env_off = np.asarray(env_off, np.int64)
+    N, S = len(env_off) - 1, int(env_off[-1])
+    rng = np.random.default_rng(seed)
+    when = np.empty(S)
+    env = np.empty(S, np.int32)
+    t = np.empty(S, np.int32)
+    for i in range(N):
+        a, b = int(env_off[i]), int(env_off[i + 1])
+        when[a:b] = np.cumsum(rng.exponential(1.0 / max(b - a, 1), size=b - a))
+        env[a:b] = i
+        t[a:b] = np.arange(b - a) + (0 if t_start is None else int(t_start[i]))
+    csr_of_arrival = np.argsort(when, kind="stable").astype(np.int32)
+    return env[csr_of_arrival], t[csr_of_arrival], csr_of_arrival
