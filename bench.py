@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the VER learner step on one MI355X.
 
-A "step" is one full PPO update over one synthetic ragged rollout: ver_gae
-and ver_is_weight once, then epochs x minibatches x (ver_pack_minibatch, ver_lstm_fwd,
+A "step" is one full PPO update over one synthetic ragged rollout held as the
+linear collection buffer (steps in arrival order): ver_ingest and its gathers,
+ver_gae and ver_is_weight once, then epochs x minibatches x (ver_pack_minibatch, ver_lstm_fwd,
 ver_ppo_loss, ver_lstm_bwd, ver_adam_step).  All inputs are resident in HBM before the timed
 region.  Prints ONE JSON line: learner env-steps/s, the roofline position of
 the dominant kernel (timed with HIP events inside the library during the timed
@@ -65,9 +66,17 @@ def cpu_baseline(ro, budget_s=15.0):
     GAE over the whole buffer, one minibatch's packing and loss in full, and the
     LSTM forward/backward over as many of that minibatch's pieces (shortest
     first) as fit the time budget, scaled to the whole update by step count."""
-    from oracle import adam as oadam, gae as ogae, is_weight as ois, lstm as olstm, pack as opack, ppo_loss as oloss
+    from oracle import (adam as oadam, gae as ogae, ingest as oing, is_weight as ois, lstm as olstm, pack as opack,
+                        ppo_loss as oloss)
+    from paper_2210_05064_amd import workloads as wl
     w = ro["workload"]
     S, B, E = ro["S"], w.minibatches, w.epochs
+    arr_env, arr_t, csr_of_arrival = wl.arrival_order(ro["env_off"], seed=1)
+    t0 = time.perf_counter()
+    _, order, _ = oing.ingest(arr_env, ro["N"], arr_t)
+    for k in ("rewards", "values", "dones", "obs", "actions"):
+        oing.to_env_major(ro[k][csr_of_arrival], order)
+    t_ingest = time.perf_counter() - t0
     t0 = time.perf_counter()
     adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
     is_w = ois.is_weights(ro["env_off"], MAX_IS)
@@ -102,7 +111,7 @@ def cpu_baseline(ro, budget_s=15.0):
     t0 = time.perf_counter()
     oadam.adam_step(flat, flat, [np.zeros_like(x) for x in flat], [np.zeros_like(x) for x in flat], 1, 2.5e-4)
     t_adam = time.perf_counter() - t0
-    t_update = t_gae + E * B * (t_pack + t_lstm + t_loss + t_adam)
+    t_update = t_ingest + t_gae + E * B * (t_pack + t_lstm + t_loss + t_adam)
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
@@ -110,10 +119,10 @@ def cpu_baseline(ro, budget_s=15.0):
         cores = os.cpu_count() or 1
     return {
         "value": S / t_update, "unit": "env-steps/s", "cores": int(cores), "kind": "oracle",
-        "sample": (f"GAE and importance weights on all {S} steps ({t_gae:.2f}s); packing ({t_pack:.2f}s) and loss ({t_loss:.2f}s) of one "
+        "sample": (f"bucketing of the arrival-order buffer ({t_ingest:.2f}s); GAE and importance weights on all {S} steps ({t_gae:.2f}s); packing ({t_pack:.2f}s) and loss ({t_loss:.2f}s) of one "
                    f"minibatch of {M} rows in full; LSTM fwd+bwd on {steps} steps of that minibatch's shortest "
                    f"pieces, scaled to {M} rows ({t_lstm:.1f}s); Adam step on all weights ({t_adam:.2f}s); "
-                   f"update = GAE + {E}x{B} minibatches"),
+                   f"update = bucketing + GAE + {E}x{B} minibatches"),
     }
 
 
@@ -125,6 +134,8 @@ def main():
     ap.add_argument("--workload", default="max")
     ap.add_argument("--seed", type=int, default=4000)
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle LSTM work (0 = skip)")
+    ap.add_argument("--env-major", action="store_true",
+                    help="hand the rollout over already bucketed by environment (skips ver_ingest)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run three device-to-device copies of MIB mebibytes (a kernel of known HBM traffic "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters by) and exit")
@@ -154,8 +165,9 @@ def main():
     w = wl.WORKLOADS[args.workload]
     ro = wl.make_rollout(w, seed=args.seed)
     # the loss carries VER's truncated importance weight, and the optimiser runs inside the update: Adam with the paper's cosine schedule over its 500 M training steps
-    learner = Learner(ro, adam_total_steps=max(1, int(500e6 // ro["S"])) * w.epochs * w.minibatches, max_is=MAX_IS)
-    learner.logp_old.copy_(collection_logp(ro, learner.compute, learner.x_bf16))
+    learner = Learner(ro, adam_total_steps=max(1, int(500e6 // ro["S"])) * w.epochs * w.minibatches, max_is=MAX_IS,
+                      arrival=None if args.env_major else wl.arrival_order(ro["env_off"], seed=args.seed + 1))
+    learner.set_logp_old(collection_logp(ro, learner.compute, learner.x_bf16))
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):

@@ -4,6 +4,8 @@
  * The library computes the learning phase of Variable Experience Rollout
  * (paper section 2.2) for a recurrent actor-critic trained with PPO:
  *
+ *     ver_ingest           once per rollout, when the buffer comes in arrival
+ *                          order (optional; the other calls take it bucketed)
  *     ver_gae              once per rollout
  *     ver_is_weight        once per rollout (optional)
  *     for every epoch, for every minibatch b:
@@ -53,6 +55,44 @@ enum {
 
 /* Text for a status code; never NULL.  Host only. */
 const char* ver_status_string(int status);
+
+/* ------------------------------------------------------------------------
+ * ver_ingest - from the linear collection buffer to the ragged buffer.
+ * Paper: section 2.2 "Batching computation for learning" (experience is
+ * written into a linear buffer in GPU memory during collection) and section
+ * 2.1 (inference workers store steps as they arrive: environments interleave,
+ * each contributes a different number of steps).
+ *
+ * Slot a of the linear buffer holds a step of environment arr_env[a]; an
+ * environment's own steps arrive in time order.  The call buckets the slots by
+ * environment, arrival order kept inside a bucket (a stable sort):
+ *   env_off[N+1]  exclusive prefix sum of the per-environment step counts
+ *   order[S]      order[k] = arrival slot of flat step k of the ragged buffer
+ *   info[4]       info[0] = steps that continue a stretch but whose counter
+ *                 arr_t is not its predecessor's + 1 (0 when arr_t is NULL:
+ *                 the counters are only checked, never used for ordering);
+ *                 info[1] = slots whose id is outside [0, N): they are placed
+ *                 behind all environments (env_off[N] = S - info[1]) and the
+ *                 result must then not be used; info[2], info[3] = 0.
+ * ver_ingest_gather then brings any per-step field into the new order:
+ * dst row k = src row order[k], rows of row_bytes bytes (src != dst).
+ * ver_ingest_dense is the closed form for equal-length rollouts stored
+ * time-major (slot t*N + i = step t of environment i; the rollouts without
+ * variable experience the paper compares against, section 5): env_off[i] = i*T,
+ * order[i*T + t] = t*N + i.
+ *
+ * All pointers device: arr_env, arr_t (or NULL), order: int32[S]; env_off:
+ * int32[N+1]; info: int32[4].  Outputs are bit-reproducible.  S = 0 is legal
+ * (env_off all zero).  Errors: VER_EINVAL (N <= 0, negative sizes, null
+ * pointers), VER_EUNSUPPORTED (S above 2^24), VER_EWORKSPACE.
+ */
+size_t ver_ingest_workspace_bytes(int32_t N, int32_t S);
+int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t N, int32_t S,
+               int32_t* env_off, int32_t* order, int32_t* info,
+               void* workspace, size_t workspace_bytes, void* stream);
+int ver_ingest_dense(int32_t T, int32_t N, int32_t* env_off, int32_t* order, void* stream);
+int ver_ingest_gather(const int32_t* order, int32_t S, const void* src, int32_t row_bytes,
+                      void* dst, void* stream);
 
 /* ------------------------------------------------------------------------
  * ver_gae - advantages and value targets over the ragged buffer.
@@ -407,7 +447,8 @@ enum {
     VER_PROF_LSTM_DBIAS = 12,
     VER_PROF_ADAM = 13,
     VER_PROF_IS_WEIGHT = 14,
-    VER_PROF_COUNT = 15
+    VER_PROF_INGEST = 15,
+    VER_PROF_COUNT = 16
 };
 int ver_profile_enable(uint32_t mask);
 int ver_profile_read(double* total_ms, int64_t* launches);

@@ -58,6 +58,14 @@ lib.ver_gae_workspace_bytes.restype = _sz
 lib.ver_gae_workspace_bytes.argtypes = [_i32]
 lib.ver_gae.restype = C.c_int
 lib.ver_gae.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _f, _f, _vp, _vp, _vp, _sz, _vp]
+lib.ver_ingest_workspace_bytes.restype = _sz
+lib.ver_ingest_workspace_bytes.argtypes = [_i32, _i32]
+lib.ver_ingest.restype = C.c_int
+lib.ver_ingest.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.ver_ingest_dense.restype = C.c_int
+lib.ver_ingest_dense.argtypes = [_i32, _i32, _vp, _vp, _vp]
+lib.ver_ingest_gather.restype = C.c_int
+lib.ver_ingest_gather.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
 lib.ver_is_weight.restype = C.c_int
 lib.ver_is_weight.argtypes = [_vp, _i32, _i32, _f, _vp, _vp]
 lib.ver_pack_workspace_bytes.restype = _sz
@@ -96,7 +104,7 @@ lib.ver_profile_read.restype = C.c_int
 lib.ver_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 PROF_CLASSES = ["gae", "pack_index", "pack_gather", "lstm_prep", "lstm_gemm_fwd", "lstm_rec_fwd", "heads_fwd",
                 "ppo_loss", "heads_bwd", "lstm_rec_bwd", "lstm_gemm_dx", "lstm_gemm_dw", "lstm_dbias", "adam",
-                "is_weight"]
+                "is_weight", "ingest"]
 
 
 class VerError(RuntimeError):
@@ -137,6 +145,25 @@ def ver_gae(rewards, values, dones, last_values, env_off, N, S, gamma, lam, adv,
     p, n = _ws(workspace)
     _check(lib.ver_gae(_ptr(rewards), _ptr(values), _ptr(dones), _ptr(last_values), _ptr(env_off),
                        N, S, gamma, lam, _ptr(adv), _ptr(ret), p, n, _stream()))
+
+
+def ver_ingest_workspace_bytes(N: int, S: int) -> int:
+    return lib.ver_ingest_workspace_bytes(N, S)
+
+
+def ver_ingest(arr_env, arr_t, N, S, env_off, order, info, workspace):
+    p, n = _ws(workspace)
+    _check(lib.ver_ingest(_ptr(arr_env), _ptr(arr_t), N, S, _ptr(env_off), _ptr(order), _ptr(info), p, n, _stream()))
+
+
+def ver_ingest_dense(T, N, env_off, order):
+    _check(lib.ver_ingest_dense(T, N, _ptr(env_off), _ptr(order), _stream()))
+
+
+def ver_ingest_gather(order, S, src, dst):
+    """dst[k] = src[order[k]] over the leading dimension; src, dst: contiguous tensors of equal shape and dtype."""
+    row_bytes = src.element_size() * (src[0].numel() if S > 0 else 1)
+    _check(lib.ver_ingest_gather(_ptr(order), S, _ptr(src), row_bytes, _ptr(dst), _stream()))
 
 
 def ver_is_weight(env_off, N, S, max_is, weight):

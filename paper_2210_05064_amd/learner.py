@@ -26,8 +26,12 @@ class Learner:
 
     def __init__(self, rollout: dict, *, compute: int | None = None, x_bf16: bool | None = None,
                  want_dx: bool = False, minibatches: int | None = None, adam_total_steps: int | None = None,
-                 adam: dict | None = None, max_is: float | None = None, learned_entropy: dict | None = None):
-        """learned_entropy: dict alpha0, lower, upper, target, sign: the entropy coefficient is a device-resident
+                 adam: dict | None = None, max_is: float | None = None, learned_entropy: dict | None = None,
+                 arrival: tuple | None = None):
+        """arrival: (arr_env, arr_t, csr_of_arrival) of workloads.arrival_order: the rollout is then held as the
+        linear collection buffer (steps in arrival order) and every update starts by bucketing it by environment
+        on the GPU (ver_ingest + one gather per field); None = the rollout is given environment-major.
+        learned_entropy: dict alpha0, lower, upper, target, sign: the entropy coefficient is a device-resident
         parameter, the last tensor of the optimiser step, kept inside [lower, upper]; None = fixed coefficient.
         max_is: truncation of the per-step importance weight; None = unweighted loss.
         adam_total_steps: length of the cosine schedule in optimiser steps; None = no optimiser (gradients only).
@@ -52,6 +56,24 @@ class Learner:
         self.rnn_h = _dev(rollout["rnn_h"]) if "rnn_h" in rollout else None
         self.rnn_c = _dev(rollout["rnn_c"]) if "rnn_c" in rollout else None
         self.logp_old = torch.zeros(S, **f32)
+        self.arrival = None
+        if arrival is not None:
+            arr_env, arr_t, csr_of_arrival = arrival
+            self.csr_of_arrival = torch.from_numpy(np.asarray(csr_of_arrival, np.int64)).cuda()
+            # (arrival-order source, environment-major destination, leading dimensions that are not the step)
+            pairs = [(self.rewards, 0), (self.values, 0), (self.dones, 0), (self.obs, 0), (self.actions, 0),
+                     (self.seq_key, 1), (self.logp_old, 0)]
+            pairs += [(t, 1) for t in (self.rnn_h, self.rnn_c) if t is not None]
+            self.arrival = []
+            for dst, lead in pairs:
+                src = dst.index_select(lead, self.csr_of_arrival).contiguous()
+                dst.fill_(0)                   # the environment-major copy is produced by ingest()
+                self.arrival.append((src, dst, lead))
+            self.arr_env, self.arr_t = _dev(np.asarray(arr_env, np.int32)), _dev(np.asarray(arr_t, np.int32))
+            self.env_off.fill_(0)
+            self.order = torch.empty(S, **i32)
+            self.ingest_info = torch.zeros(4, **i32)
+            self.ws_ingest = ver.workspace(ver.ver_ingest_workspace_bytes(self.N, S))
         self.adv, self.ret = torch.empty(S, **f32), torch.empty(S, **f32)
         self.max_is = max_is
         self.is_w = torch.empty(S, **f32) if max_is is not None else None
@@ -118,6 +140,23 @@ class Learner:
             self.opt_steps = 0
 
     # -- the entry points, in the order of the learning phase ---------------------
+    def set_logp_old(self, flat: torch.Tensor):
+        """Old log-probabilities, given environment-major (stored in arrival order when the buffer is)."""
+        self.logp_old.copy_(flat)
+        if self.arrival is not None:
+            for src, dst, _ in self.arrival:
+                if dst is self.logp_old:
+                    src.copy_(flat[self.csr_of_arrival])
+
+    def ingest(self):
+        ver.ver_ingest(self.arr_env, self.arr_t, self.N, self.S, self.env_off, self.order, self.ingest_info, self.ws_ingest)
+        for src, dst, lead in self.arrival:
+            if lead == 0:
+                ver.ver_ingest_gather(self.order, self.S, src, dst)
+            else:
+                for j in range(src.shape[0]):
+                    ver.ver_ingest_gather(self.order, self.S, src[j], dst[j])
+
     def gae(self):
         ver.ver_gae(self.rewards, self.values, self.dones, self.last_values, self.env_off, self.N, self.S,
                     self.w.gamma, self.w.lam, self.adv, self.ret, self.ws_gae)
@@ -177,6 +216,8 @@ class Learner:
 
     def update(self, on_minibatch=None):
         """One PPO update: advantages (and importance weights) once, then epochs x minibatches."""
+        if self.arrival is not None:
+            self.ingest()
         self.gae()
         if self.max_is is not None:
             self.importance_weights()

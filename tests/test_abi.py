@@ -126,3 +126,21 @@ def test_learned_entropy_and_bounded_step_argument_checks(lib):
     assert call(None, None) == 0 and call(1e-4, 1.0) == 0 and call(None, 1.0) == 0 and call(0.5, 0.5) == 0
     assert call(1.0, 1e-4) == -1                      # empty box
     assert call(float("nan"), 1.0) == -1 and call(0.0, float("nan")) == -1
+
+
+def test_ingest_argument_checks(lib):
+    lib.ver_ingest_workspace_bytes.restype = C.c_size_t
+    lib.ver_ingest_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
+    assert lib.ver_ingest_workspace_bytes(256, 32768) >= 3 * 32768 * 4
+    assert lib.ver_ingest_workspace_bytes(0, 8) == 0 and lib.ver_ingest_workspace_bytes(4, -1) == 0
+    assert lib.ver_ingest_workspace_bytes(4, (1 << 24) + 1) == 0
+    lib.ver_ingest.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 4 + [C.c_size_t, C.c_void_p]
+    assert lib.ver_ingest(None, None, 4, 8, None, None, None, None, 0, None) == -1
+    assert lib.ver_ingest(None, None, 0, 0, None, None, None, None, 0, None) == -1
+    lib.ver_ingest_dense.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    assert lib.ver_ingest_dense(4, 0, None, None, None) == -1 and lib.ver_ingest_dense(-1, 4, None, None, None) == -1
+    assert lib.ver_ingest_dense(4, 4, None, None, None) == -1
+    lib.ver_ingest_gather.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+    assert lib.ver_ingest_gather(None, 0, None, 4, None, None) == 0        # nothing to move
+    assert lib.ver_ingest_gather(None, 8, None, 4, None, None) == -1
+    assert lib.ver_ingest_gather(None, 8, None, 0, None, None) == -1

@@ -1,0 +1,134 @@
+"""ver_ingest / ver_ingest_gather / ver_ingest_dense against the CPU oracle (oracle/ingest.py): integer outputs
+bit-exact, gathered fields bit-exact copies."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gae as ogae, ingest as oing
+from paper_2210_05064_amd import workloads as wl
+from tests.gpu_util import dev, host, run_gae
+from tests.util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def run_ingest(ver, arr_env, N, arr_t=None):
+    S = len(arr_env)
+    env_off = torch.full((N + 1,), -7, dtype=torch.int32, device="cuda")
+    order = torch.full((max(S, 1) + 4,), -7, dtype=torch.int32, device="cuda")
+    info = torch.full((4,), -7, dtype=torch.int32, device="cuda")
+    ws = ver.workspace(ver.ver_ingest_workspace_bytes(N, S))
+    ws.fill_(-1)           # the library must not rely on workspace contents
+    ver.ver_ingest(dev(np.asarray(arr_env, np.int32)) if S else None, dev(np.asarray(arr_t, np.int32)) if arr_t is not None and S else None,
+                   N, S, env_off, order, info, ws)
+    torch.cuda.synchronize()
+    assert np.all(host(order)[S:] == -7), "wrote beyond S"
+    return host(env_off), host(order)[:S], host(info)
+
+
+def check(ver, arr_env, N, arr_t=None):
+    env_off, order, info = run_ingest(ver, arr_env, N, arr_t)
+    r_off, r_order, r_bad = oing.ingest(arr_env, N, arr_t)
+    assert np.array_equal(env_off, r_off), "env_off"
+    assert np.array_equal(order, r_order), "order"
+    assert info.tolist() == [r_bad, 0, 0, 0]
+    return env_off, order
+
+
+@pytest.mark.parametrize("seed,N,S", [(0, 1, 9), (1, 5, 40), (2, 17, 2048), (3, 300, 200), (4, 4, 0), (5, 3, 1),
+                                      (6, 255, 5000), (7, 256, 32768), (8, 511, 4097), (9, 512, 6143), (10, 513, 10000),
+                                      (11, 1023, 70001), (12, 1024, 2049), (13, 8192, 262144 + 77), (14, 2000000, 100003)])
+def test_random_ids(ver, seed, N, S):
+    """One pass (up to 511 environments), two and three passes; ragged tails; more environments than steps; a
+    skewed id distribution so that buckets differ by orders of magnitude; counters broken in a few places."""
+    rng = np.random.default_rng(seed)
+    p = rng.lognormal(0.0, 1.5, size=min(N, 4096))
+    arr_env = rng.choice(len(p), size=S, p=p / p.sum()).astype(np.int64)
+    if N > len(p):
+        arr_env = arr_env * (N // len(p)) + rng.integers(0, N // len(p), S)
+    # consistent counters, then a few broken ones
+    arr_t = np.zeros(S, np.int64)
+    seen = {}
+    for a, e in enumerate(arr_env.tolist()):
+        arr_t[a] = seen.get(e, 100 + e % 5)
+        seen[e] = arr_t[a] + 1
+    check(ver, arr_env, N, arr_t)
+    if S > 8:
+        arr_t[rng.integers(0, S, 5)] += rng.integers(1, 4, 5)
+        check(ver, arr_env, N, arr_t)
+    check(ver, arr_env, N, None)
+
+
+def test_one_environment_owns_everything_and_sorted_input(ver):
+    check(ver, np.full(5000, 3), 7)
+    check(ver, np.sort(np.random.default_rng(0).integers(0, 40, 9000)), 40)
+    check(ver, np.sort(np.random.default_rng(1).integers(0, 40, 9000))[::-1].copy(), 40)
+
+
+def test_ids_out_of_range_are_counted_and_set_aside(ver):
+    rng = np.random.default_rng(2)
+    N, S = 20, 6000
+    arr_env = rng.integers(0, N, S)
+    bad = rng.choice(S, 37, replace=False)
+    arr_env[bad[:20]] = N + rng.integers(0, 1000, 20)
+    arr_env[bad[20:]] = -1 - rng.integers(0, 1000, 17)
+    env_off, order, info = run_ingest(ver, arr_env, N)
+    assert info.tolist() == [0, 37, 0, 0] and env_off[N] == S - 37
+    good = np.flatnonzero((arr_env >= 0) & (arr_env < N))
+    r_off, r_order, _ = oing.ingest(arr_env[good], N)
+    assert np.array_equal(env_off, r_off)
+    assert np.array_equal(order[:S - 37], good[r_order])                 # the valid part is the valid slots' bucketing
+    assert sorted(order[S - 37:].tolist()) == sorted(bad.tolist())       # the rest sits behind, in arrival order
+    assert np.all(np.diff(order[S - 37:]) > 0)
+
+
+@pytest.mark.parametrize("name", ["tiny", "nav", "manip", "large", "max"])
+def test_workload_round_trip_with_fields(ver, name):
+    """The workload's rollout scattered into arrival order by the seeded generator, bucketed on the GPU, every
+    per-step field gathered back (16-byte, 4-byte and 1-byte rows): the rollout itself must come out; then
+    ver_gae on the gathered fields against the oracle's advantages on the original rollout."""
+    w = wl.scaled(wl.WORKLOADS[name], hidden=64, input_dim=12 if name != "tiny" else 7)
+    ro = wl.make_rollout(w, seed=6, with_states=False)
+    N, S = ro["N"], ro["S"]
+    arr_env, arr_t, csr_of_arrival = wl.arrival_order(ro["env_off"], seed=13, t_start=np.arange(N) * 3)
+    env_off, order = check(ver, arr_env, N, arr_t)
+    assert np.array_equal(env_off, ro["env_off"])
+    d_order = dev(order.astype(np.int32))
+    got = {}
+    for k in ("obs", "actions", "rewards", "values", "dones", "seq_key"):
+        field = ro[k][0] if k == "seq_key" else ro[k]
+        src = dev(np.ascontiguousarray(field[csr_of_arrival]))
+        dst = torch.zeros_like(src)
+        ver.ver_ingest_gather(d_order, S, src, dst)
+        torch.cuda.synchronize()
+        got[k] = host(dst)
+        assert np.array_equal(got[k].view(field.dtype) if field.dtype == np.uint32 else got[k], field), k
+    adv, ret = run_gae(ver, got["rewards"], got["values"], got["dones"], ro["last_values"], env_off, w.gamma, w.lam)
+    r_adv, r_ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
+    assert_close(adv, r_adv, 1e-5, "adv")
+    assert_close(ret, r_ret, 1e-5, "ret")
+
+
+@pytest.mark.parametrize("T,N", [(6, 5), (128, 16), (1, 9), (0, 3), (500, 256)])
+def test_dense_time_major(ver, T, N):
+    env_off = torch.full((N + 1,), -7, dtype=torch.int32, device="cuda")
+    order = torch.full((T * N + 4,), -7, dtype=torch.int32, device="cuda")
+    ver.ver_ingest_dense(T, N, env_off, order)
+    torch.cuda.synchronize()
+    r_off, r_order = oing.dense_order(T, N)
+    assert np.array_equal(host(env_off), r_off) and np.array_equal(host(order)[:T * N], r_order)
+    assert np.all(host(order)[T * N:] == -7)
+    if T:
+        g_off, g_order, _ = run_ingest(ver, np.tile(np.arange(N), T), N)           # the general call agrees
+        assert np.array_equal(g_off, r_off) and np.array_equal(g_order, r_order)
+
+
+def test_argument_errors(ver):
+    x = torch.zeros(8, dtype=torch.int32, device="cuda")
+    ws = ver.workspace(ver.ver_ingest_workspace_bytes(4, 8))
+    with pytest.raises(ver.VerError):
+        ver.ver_ingest(x, None, 0, 8, x, x, x, ws)                     # no environments
+    with pytest.raises(ver.VerError):
+        ver.ver_ingest(x, None, 4, 8, x, x, x, ver.workspace(16))      # workspace too small
+    with pytest.raises(ver.VerError):
+        ver.ver_ingest_gather(x, 8, x, x)                              # in place

@@ -12,16 +12,19 @@ from tests.util import assert_close, assert_close_bf16, assert_close_update
 pytestmark = pytest.mark.gpu
 
 
-def run_case(w, seed, compute=None, max_is=None):
+def run_case(w, seed, compute=None, max_is=None, arrival=False):
     from paper_2210_05064_amd.learner import Learner
     ro = wl.make_rollout(w, seed=seed, bias_scale=0.1)
     adv, ret = ogae.gae(ro["rewards"], ro["values"], ro["dones"], ro["last_values"], ro["env_off"], w.gamma, w.lam)
     logp_old = (olearner.collection_logp(ro, ro["weights"], ro["dones"], ro["env_off"], w.dist,
                                          ro["env_started_episode"], ro["rnn_h"], ro["rnn_c"])
                 + ro["logp_noise"]).astype(np.float32)
-    L = Learner(ro, compute=compute, want_dx=True, max_is=max_is)
+    arr = wl.arrival_order(ro["env_off"], seed=seed + 100, t_start=np.arange(ro["N"])) if arrival else None
+    L = Learner(ro, compute=compute, want_dx=True, max_is=max_is, arrival=arr)
     weight = None if max_is is None else ois.is_weights(ro["env_off"], max_is)
-    L.logp_old.copy_(torch.from_numpy(logp_old).cuda())
+    L.set_logp_old(torch.from_numpy(logp_old).cuda())
+    if arrival:
+        assert int(L.env_off.abs().sum().item()) == 0 and float(L.obs.abs().sum().item()) == 0.0   # nothing environment-major yet
     cfg = dict(dist=w.dist, clip=np.float32(w.clip).item(), value_coef=w.value_coef,
                entropy_coef=np.float32(w.entropy_coef).item())
     names = [f"layer{l}.{n}" for l in range(w.n_layers) for n in GRAD_NAMES] + ["W_a", "b_a", "w_v", "b_v"]
@@ -56,10 +59,24 @@ def run_case(w, seed, compute=None, max_is=None):
     assert_close(host(L.adv), adv, 1e-5, "adv")
     assert_close(host(L.ret), ret, 1e-5, "ret")
     assert len(checked) == w.epochs * L.B
+    if arrival:
+        assert np.array_equal(host(L.env_off), ro["env_off"]) and host(L.ingest_info).tolist() == [0, 0, 0, 0]
+        assert np.array_equal(host(L.obs), ro["obs"]) and np.array_equal(host(L.rnn_c), ro["rnn_c"])
 
 
 def test_tiny_workload_update(ver):
     run_case(wl.WORKLOADS["tiny"], seed=1)
+
+
+@pytest.mark.parametrize("name", ["tiny", "manip", "large"])
+def test_update_from_the_arrival_order_buffer(ver, name):
+    """The rollout handed over as the linear collection buffer (steps interleaved across environments): the
+    update buckets it by environment on the GPU first; everything downstream against the oracle chain on the
+    environment-major rollout."""
+    w = wl.WORKLOADS[name]
+    if name != "tiny":
+        w = wl.scaled(w, budget=w.budget // 8, n_envs=w.n_envs // 2, hidden=128, input_dim=w.input_dim // 16 * 4, epochs=1)
+    run_case(w, seed=8, compute=0, max_is=1.0, arrival=True)
 
 
 @pytest.mark.parametrize("name,max_is", [("tiny", 1.0), ("manip", 1.0), ("nav", 1.5)])
