@@ -204,12 +204,14 @@ __device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, 
     __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<E*>(src), 0, (rows - 1) * pitch_bytes + row_bytes,
                                                                     0x00020000);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int shift = (int)(((long long)rot * n) / REC_MAX_GROUP);
+    const int shift = (rot * n) / REC_MAX_GROUP;
+    const bool pow2 = (nseg & (nseg - 1)) == 0;
+    const int lg = 31 - __builtin_clz(nseg);
     unsigned char* lds_b = reinterpret_cast<unsigned char*>(lds);
     for (int s0 = wave; s0 < n; s0 += REC_WAVES) {
         int sg = s0 + shift;
         if (sg >= n) sg -= n;
-        const int r = sg / nseg, part = sg - r * nseg;
+        const int r = pow2 ? sg >> lg : sg / nseg, part = sg - r * nseg;
         const int in_row = part * 1024 + lane * 16;
         if (in_row < row_bytes)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(lds_b + (size_t)r * stride * sizeof(E) + part * 1024), 16,
@@ -504,18 +506,23 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
     const size_t gcol = (size_t)je * 4;
     float creg[REC_PRE];     // cell state of the pieces in this lane's first REC_PRE tiles
     f32x4_t zpre[REC_PRE], znext[REC_PRE];   // their input projections, fetched one timestep ahead
+    unsigned goff[REC_PRE];  // byte offset of this lane's gates inside a timestep's rows (tile q): the same every step
 #pragma unroll
     for (int q = 0; q < REC_PRE; ++q) {
         creg[q] = 0.f;
         zpre[q] = znext[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        goff[q] = ((unsigned)((q * 16 + lr) * X + x) * 4u * (unsigned)H + (unsigned)je * 4u) * 4u;
     }
     if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(a.t_off, pl, 0, a.err)) return;
     if (has_tile && T > 0) {
         const int bs0 = grp_count(a.batch_sizes[0], x, X);
 #pragma unroll
         for (int q = 0; q < REC_PRE; ++q)
-            if (q * 16 + lr < bs0)
-                zpre[q] = *reinterpret_cast<const f32x4_t*>(a.gates + (size_t)((q * 16 + lr) * X + x) * 4 * H + gcol);
+            if (q * 16 + lr < bs0) {
+                const int n = (q * 16 + lr) * X + x;
+                zpre[q] = *reinterpret_cast<const f32x4_t*>(a.gates + (size_t)n * 4 * H + gcol);
+                if (a.c0 && n < a.seq_cap) creg[q] = a.c0[(size_t)n * H + je];   // initial cell state
+            }
     }
 
     // batch sizes of timesteps t, t+1 (and t+2, fetched a step ahead: a scalar load that misses costs about half
@@ -523,7 +530,10 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
     int bs_a = T > 0 ? a.batch_sizes[0] : 0, bs_b = T > 1 ? a.batch_sizes[1] : 0;
     int base = 0, base_prev = 0;
     for (int t = 0; t < T; ++t) {
-        const int bs_c = (t + 2 < T) ? a.batch_sizes[t + 2] : 0;
+        // (the compiler reads it with a vector load, since it cannot prove the array constant; left alone it would
+        // wait for that load, and for every store in flight before it, right here at the top of the step: the
+        // value is kept in a vector register and made uniform only where the step waits for its stores anyway)
+        int bs_c_v = (t + 2 < T) ? a.batch_sizes[t + 2] : 0;
         // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
         const int bs_all = bs_a, bs = grp_count(bs_all, x, X);
         const int bs_next = (t + 1 < T) ? grp_count(bs_b, x, X) : 0, base_next = base + bs_all;
@@ -532,6 +542,17 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
         REC_PROF_MARK(6);
         __amdgpu_buffer_rsrc_t rs_hcopy = __builtin_amdgcn_make_buffer_rsrc(static_cast<E*>(a.hcopy) + (size_t)base * H, 0,
                                                                             PIPE == PIPE_PRODUCER ? bs_all * H * (int)sizeof(E) : 0, 0x00020000);
+        // This timestep's rows of the saved activations and the next one's input projections as buffers: a lane's
+        // offset inside them never changes, and offsets past the alive rows fall outside (no branch per lane, no
+        // 64-bit address arithmetic per timestep).
+        const int row_g = 16 * H;   // bytes of a gates row
+        __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(a.gates + (size_t)base * 4 * H, 0, bs_all * row_g, 0x00020000);
+        __amdgpu_buffer_rsrc_t rs_c = __builtin_amdgcn_make_buffer_rsrc(a.c + (size_t)base * H, 0, bs_all * (row_g / 4), 0x00020000);
+        __amdgpu_buffer_rsrc_t rs_h = __builtin_amdgcn_make_buffer_rsrc(a.hout + (size_t)base * H, 0, bs_all * (row_g / 4), 0x00020000);
+        __amdgpu_buffer_rsrc_t rs_hnext = __builtin_amdgcn_make_buffer_rsrc(hprev + (size_t)base_next * H, 0,
+                                                                            (t + 1 < T ? bs_b : 0) * H * (int)sizeof(E), 0x00020000);
+        __amdgpu_buffer_rsrc_t rs_gnext = __builtin_amdgcn_make_buffer_rsrc(a.gates + (size_t)base_next * 4 * H, 0,
+                                                                            (t + 1 < T ? bs_b : 0) * row_g, 0x00020000);
         if (!rec_wait(flags, G, t + 1, a.err)) return;
         // every workgroup of the group has raised its flag for timestep t-1, i.e. completed that step's stores
         if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0 && t > 0) st_agent(&pl.progress[x], t);
@@ -542,15 +563,14 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
             stage_rows<E>(hprev + ((size_t)base + (size_t)c0 * X + x) * H, rows, H, X * H, sB, stride, rank);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             bar_lds();
-            if (c0 == 0 && has_tile && t + 1 < T) {
+            if (c0 == 0 && has_tile) {
                 // next timestep's input projections.  Issued right after the exchanged rows have arrived: the
                 // memory counter retires in order, so a prefetch must never be queued in front of loads that
                 // the critical path waits for; from here nothing waits for global memory until the flag is
                 // raised at the end of the step.
 #pragma unroll
                 for (int qq = 0; qq < REC_PRE; ++qq)
-                    if (qq * 16 + lr < bs_next)
-                        znext[qq] = *reinterpret_cast<const f32x4_t*>(a.gates + ((size_t)base_next + (qq * 16 + lr) * X + x) * 4 * H + gcol);
+                    znext[qq] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs_gnext, goff[qq], 0, 0));
             }
             REC_PROF_MARK(1);
 #pragma unroll 1
@@ -588,15 +608,22 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                         const float gg = tanhf_(z[2] + zin[2]);
                         const float go = sigmoidf_(z[3] + zin[3]);
                         float c_prev;
-                        if (t == 0) c_prev = (a.c0 && n < a.seq_cap) ? a.c0[(size_t)n * H + je] : 0.f;
-                        else if (in_regs) c_prev = creg[q < REC_PRE ? q : 0];   // this lane computed it one timestep ago
+                        if (in_regs) c_prev = creg[q < REC_PRE ? q : 0];   // this lane computed it one timestep ago (or fetched c0)
+                        else if (t == 0) c_prev = (a.c0 && n < a.seq_cap) ? a.c0[(size_t)n * H + je] : 0.f;
                         else c_prev = a.c[((size_t)base_prev + n) * H + je];
                         const float cn = gf * c_prev + gi * gg;
                         if (in_regs) creg[q < REC_PRE ? q : 0] = cn;
                         hn = go * tanhf_(cn);
-                        *gp = f32x4_t{gi, gf, gg, go};
-                        a.c[p * H + je] = cn;
-                        a.hout[p * H + je] = hn;
+                        if (in_regs) {
+                            const unsigned go_ = goff[q < REC_PRE ? q : 0];
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{gi, gf, gg, go}), rs_g, go_, 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(cn), rs_c, go_ >> 2, 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn), rs_h, go_ >> 2, 0, 0);
+                        } else {
+                            *gp = f32x4_t{gi, gf, gg, go};
+                            a.c[p * H + je] = cn;
+                            a.hout[p * H + je] = hn;
+                        }
                     }
                     // h_t goes to the exchange row of the next timestep through LDS (below)
                     sH[(q * 16 + lr) * UH + wave * 4 + lk] = cvt_finite<E>(hn);
@@ -613,7 +640,7 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                 for (int i = tid; i < live * PIECES; i += REC_THREADS) {
                     const int r = i / PIECES, pc = i % PIECES;
                     const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sH + r * UH + pc * VEC);
-                    *reinterpret_cast<u32x4_t*>(hprev + ((size_t)base_next + (size_t)(c0 + r) * X + x) * H + j0 + pc * VEC) = v;
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rs_hnext, (((c0 + r) * X + x) * H + j0 + pc * VEC) * (int)sizeof(E), 0, 0);
                 }
                 if (PIPE == PIPE_PRODUCER) {
                     // h_t of every row of the chunk in operand type, written through: input of the workers' GEMM
@@ -627,6 +654,8 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
         }
         REC_PROF_MARK(3);
         if (t + 1 < T || PIPE == PIPE_PRODUCER) rec_publish(flags, rank, t + 2);
+        asm volatile("" : "+v"(bs_c_v));
+        const int bs_c = __builtin_amdgcn_readfirstlane(bs_c_v);
 #pragma unroll
         for (int q = 0; q < REC_PRE; ++q) zpre[q] = znext[q];
         base_prev = base;
