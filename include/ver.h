@@ -260,7 +260,8 @@ int ver_pack_minibatch(const ver_pack_args* args /* host */, void* stream);
  * Errors: VER_EUNSUPPORTED unless hidden is a multiple of 64 with
  * 64 <= hidden <= 1024 (compute = 1) or <= 512 (compute = 0) - a wave keeps
  * its share of W_hh in registers and 16 rows of gate gradients in LDS -,
- * input_dim a multiple of 4, 1 <= n_layers <= 8, 1 <= act_dim <= 63.
+ * input_dim a multiple of 4, 1 <= n_layers <= 8, 1 <= act_dim <= 63, and
+ * M * hidden < 2^27 (32-bit byte offsets inside an activation array).
  * workspace word 0 (int32) is non-zero after the stream has drained if a
  * device-side wait timed out (should never happen; results are then
  * undefined).  Outputs are deterministic.

@@ -356,6 +356,8 @@ inline int check_cfg(const ver_lstm_cfg* c, int M) {
     if (c->hidden < 64 || c->hidden % 64 != 0 || c->input_dim < 4 || c->input_dim % 4 != 0) return VER_EUNSUPPORTED;
     // a wave keeps its [16, H] share of W_hh in 128 registers; a 16-row tile of dz ([16, 4H]) must fit in LDS
     if (c->hidden > (c->compute ? 1024 : 512)) return VER_EUNSUPPORTED;
+    // the time-loop kernels address the rows of an activation array with 32-bit byte offsets
+    if ((long long)M * 16 * c->hidden >= (1LL << 31)) return VER_EUNSUPPORTED;
     return VER_OK;
 }
 

@@ -529,6 +529,17 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
     // a microsecond, which would otherwise sit at the top of every step); row offsets follow by addition
     int bs_a = T > 0 ? a.batch_sizes[0] : 0, bs_b = T > 1 ? a.batch_sizes[1] : 0;
     int base = 0, base_prev = 0;
+    // The activation arrays as buffers that never change during the loop (host code guarantees that every
+    // array is shorter than 2^31 bytes); a lane without a piece gets an offset beyond the range, which a load
+    // answers with zero.
+    const unsigned row_g = 16u * (unsigned)H;   // bytes of a gates row
+    constexpr unsigned OUT_OF_RANGE = 0xFFFFFFF0u;
+    constexpr int WHOLE = (int)0x80000000u;
+    const __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(a.gates, 0, WHOLE, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_c = __builtin_amdgcn_make_buffer_rsrc(a.c, 0, WHOLE, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_h = __builtin_amdgcn_make_buffer_rsrc(a.hout, 0, WHOLE, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_hp = __builtin_amdgcn_make_buffer_rsrc(hprev, 0, WHOLE, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_hcopy = __builtin_amdgcn_make_buffer_rsrc(a.hcopy, 0, PIPE == PIPE_PRODUCER ? WHOLE : 0, 0x00020000);
     for (int t = 0; t < T; ++t) {
         // (the compiler reads it with a vector load, since it cannot prove the array constant; left alone it would
         // wait for that load, and for every store in flight before it, right here at the top of the step: the
@@ -540,19 +551,11 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
         if (PIPE == PIPE_CONSUMER && t + 1 < T && (t + 1) % PIPE_CT == 0 &&
             !pipe_wait_chunk(a.t_off, pl, (t + 1) / PIPE_CT, a.err)) return;
         REC_PROF_MARK(6);
-        __amdgpu_buffer_rsrc_t rs_hcopy = __builtin_amdgcn_make_buffer_rsrc(static_cast<E*>(a.hcopy) + (size_t)base * H, 0,
-                                                                            PIPE == PIPE_PRODUCER ? bs_all * H * (int)sizeof(E) : 0, 0x00020000);
-        // This timestep's rows of the saved activations and the next one's input projections as buffers: a lane's
-        // offset inside them never changes, and offsets past the alive rows fall outside (no branch per lane, no
-        // 64-bit address arithmetic per timestep).
-        const int row_g = 16 * H;   // bytes of a gates row
-        __amdgpu_buffer_rsrc_t rs_g = __builtin_amdgcn_make_buffer_rsrc(a.gates + (size_t)base * 4 * H, 0, bs_all * row_g, 0x00020000);
-        __amdgpu_buffer_rsrc_t rs_c = __builtin_amdgcn_make_buffer_rsrc(a.c + (size_t)base * H, 0, bs_all * (row_g / 4), 0x00020000);
-        __amdgpu_buffer_rsrc_t rs_h = __builtin_amdgcn_make_buffer_rsrc(a.hout + (size_t)base * H, 0, bs_all * (row_g / 4), 0x00020000);
-        __amdgpu_buffer_rsrc_t rs_hnext = __builtin_amdgcn_make_buffer_rsrc(hprev + (size_t)base_next * H, 0,
-                                                                            (t + 1 < T ? bs_b : 0) * H * (int)sizeof(E), 0x00020000);
-        __amdgpu_buffer_rsrc_t rs_gnext = __builtin_amdgcn_make_buffer_rsrc(a.gates + (size_t)base_next * 4 * H, 0,
-                                                                            (t + 1 < T ? bs_b : 0) * row_g, 0x00020000);
+        const unsigned so_hcopy = (unsigned)base * (unsigned)(H * (int)sizeof(E));
+        // Where this timestep's rows (and the next one's) begin inside the activation arrays, in bytes: the scalar
+        // offset of the buffer accesses below; a lane's own offset inside a timestep's rows never changes.
+        const unsigned so_g = (unsigned)base * row_g, so_c = so_g >> 2;
+        const unsigned so_gnext = (unsigned)base_next * row_g, so_hnext = (unsigned)base_next * (unsigned)(H * (int)sizeof(E));
         if (!rec_wait(flags, G, t + 1, a.err)) return;
         // every workgroup of the group has raised its flag for timestep t-1, i.e. completed that step's stores
         if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0 && t > 0) st_agent(&pl.progress[x], t);
@@ -570,7 +573,8 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                 // raised at the end of the step.
 #pragma unroll
                 for (int qq = 0; qq < REC_PRE; ++qq)
-                    znext[qq] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs_gnext, goff[qq], 0, 0));
+                    znext[qq] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                                                                rs_g, qq * 16 + lr < bs_next ? goff[qq] : OUT_OF_RANGE, so_gnext, 0));
             }
             REC_PROF_MARK(1);
 #pragma unroll 1
@@ -616,9 +620,9 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                         hn = go * tanhf_(cn);
                         if (in_regs) {
                             const unsigned go_ = goff[q < REC_PRE ? q : 0];
-                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{gi, gf, gg, go}), rs_g, go_, 0, 0);
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(cn), rs_c, go_ >> 2, 0, 0);
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn), rs_h, go_ >> 2, 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{gi, gf, gg, go}), rs_g, go_, so_g, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(cn), rs_c, go_ >> 2, so_c, 0);
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn), rs_h, go_ >> 2, so_c, 0);
                         } else {
                             *gp = f32x4_t{gi, gf, gg, go};
                             a.c[p * H + je] = cn;
@@ -640,14 +644,14 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
                 for (int i = tid; i < live * PIECES; i += REC_THREADS) {
                     const int r = i / PIECES, pc = i % PIECES;
                     const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sH + r * UH + pc * VEC);
-                    __builtin_amdgcn_raw_buffer_store_b128(v, rs_hnext, (((c0 + r) * X + x) * H + j0 + pc * VEC) * (int)sizeof(E), 0, 0);
+                    __builtin_amdgcn_raw_buffer_store_b128(v, rs_hp, (((c0 + r) * X + x) * H + j0 + pc * VEC) * (int)sizeof(E), so_hnext, 0);
                 }
                 if (PIPE == PIPE_PRODUCER) {
                     // h_t of every row of the chunk in operand type, written through: input of the workers' GEMM
                     for (int i = tid; i < min(rows, bs - c0) * PIECES; i += REC_THREADS) {
                         const int r = i / PIECES, pc = i % PIECES;
                         const u32x4_t v = *reinterpret_cast<const u32x4_t*>(sH + r * UH + pc * VEC);
-                        __builtin_amdgcn_raw_buffer_store_b128(v, rs_hcopy, (((c0 + r) * X + x) * H + j0 + pc * VEC) * (int)sizeof(E), 0, 17);
+                        __builtin_amdgcn_raw_buffer_store_b128(v, rs_hcopy, (((c0 + r) * X + x) * H + j0 + pc * VEC) * (int)sizeof(E), so_hcopy, 17);
                     }
                 }
             }
