@@ -195,14 +195,14 @@ __device__ __forceinline__ void rec_publish(int* flags, int rank, int value) {
 // `rot` rotates the order in which this workgroup walks the segments: all workgroups fetch the same rows at
 // the same moment, and starting each one at a different place spreads them over the L2 channels.
 // The caller waits for the loads (s_waitcnt vmcnt(0)) and synchronises the workgroup.
+// The rows start `first` bytes into the buffer `rsrc` (a scalar offset: the buffer itself never changes during
+// a kernel, so no descriptor has to be built per timestep).
 template <typename E>
-__device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, int row_elems, int pitch,
+__device__ __forceinline__ void stage_rows(__amdgpu_buffer_rsrc_t rsrc, unsigned first, int rows, int row_elems, int pitch,
                                            E* __restrict__ lds, int stride, int rot) {
     const int row_bytes = row_elems * (int)sizeof(E), pitch_bytes = pitch * (int)sizeof(E);
     const int nseg = (row_bytes + 1023) >> 10;
     const int n = rows * nseg;
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<E*>(src), 0, (rows - 1) * pitch_bytes + row_bytes,
-                                                                    0x00020000);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int shift = (rot * n) / REC_MAX_GROUP;
     const bool pow2 = (nseg & (nseg - 1)) == 0;
@@ -215,8 +215,17 @@ __device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, 
         const int in_row = part * 1024 + lane * 16;
         if (in_row < row_bytes)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(lds_b + (size_t)r * stride * sizeof(E) + part * 1024), 16,
-                                                     r * pitch_bytes + in_row, 0, 0, 0);
+                                                     r * pitch_bytes + in_row, first, 0, 0);
     }
+}
+
+// The same for rows given by a pointer: builds the buffer over just those rows.
+template <typename E>
+__device__ __forceinline__ void stage_rows(const E* __restrict__ src, int rows, int row_elems, int pitch,
+                                           E* __restrict__ lds, int stride, int rot) {
+    const int row_bytes = row_elems * (int)sizeof(E), pitch_bytes = pitch * (int)sizeof(E);
+    stage_rows<E>(__builtin_amdgcn_make_buffer_rsrc(const_cast<E*>(src), 0, (rows - 1) * pitch_bytes + row_bytes, 0x00020000), 0u,
+                  rows, row_elems, pitch, lds, stride, rot);
 }
 
 // Stores 4 consecutive elements of an exchanged row (8 bytes bf16, 16 bytes fp32).
@@ -563,7 +572,7 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc), nt = (rows + 15) >> 4;
             if (c0 > 0) bar_lds();  // the previous chunk's rows have been consumed
-            stage_rows<E>(hprev + ((size_t)base + (size_t)c0 * X + x) * H, rows, H, X * H, sB, stride, rank);
+            stage_rows<E>(rs_hp, (unsigned)((base + c0 * X + x) * H) * (unsigned)sizeof(E), rows, H, X * H, sB, stride, rank);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             bar_lds();
             if (c0 == 0 && has_tile) {
