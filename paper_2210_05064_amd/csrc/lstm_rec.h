@@ -372,16 +372,26 @@ __device__ __forceinline__ void st_through(__amdgpu_buffer_rsrc_t rs, int off, f
     __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, off, 0, 17);
 }
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
-template <typename E> __device__ __forceinline__ void st_row4_through(__amdgpu_buffer_rsrc_t rs, int off, float a, float b, float c, float d);
-template <> __device__ __forceinline__ void st_row4_through<bf16_t>(__amdgpu_buffer_rsrc_t rs, int off, float a, float b, float c, float d) {
-    u32x2_t v;
-    v.x = (unsigned)to_bf16_finite(a) | ((unsigned)to_bf16_finite(b) << 16);
-    v.y = (unsigned)to_bf16_finite(c) | ((unsigned)to_bf16_finite(d) << 16);
-    __builtin_amdgcn_raw_buffer_store_b64(v, rs, off, 0, 17);
-}
-template <> __device__ __forceinline__ void st_row4_through<float>(__amdgpu_buffer_rsrc_t rs, int off, float a, float b, float c, float d) {
-    u32x4_t v = {__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
-    __builtin_amdgcn_raw_buffer_store_b128(v, rs, off, 0, 17);
+// Stores 4 consecutive elements of a row at byte `off` + scalar offset `so` of a buffer; AUX = 17 writes through to
+// memory (rows that workgroups on other XCDs read), 0 is an ordinary store.
+template <typename E, int AUX> struct StRow4;
+template <int AUX> struct StRow4<bf16_t, AUX> {
+    static __device__ __forceinline__ void go(__amdgpu_buffer_rsrc_t rs, int off, unsigned so, float a, float b, float c, float d) {
+        u32x2_t v;
+        v.x = (unsigned)to_bf16_finite(a) | ((unsigned)to_bf16_finite(b) << 16);
+        v.y = (unsigned)to_bf16_finite(c) | ((unsigned)to_bf16_finite(d) << 16);
+        __builtin_amdgcn_raw_buffer_store_b64(v, rs, off, so, AUX);
+    }
+};
+template <int AUX> struct StRow4<float, AUX> {
+    static __device__ __forceinline__ void go(__amdgpu_buffer_rsrc_t rs, int off, unsigned so, float a, float b, float c, float d) {
+        u32x4_t v = {__float_as_uint(a), __float_as_uint(b), __float_as_uint(c), __float_as_uint(d)};
+        __builtin_amdgcn_raw_buffer_store_b128(v, rs, off, so, AUX);
+    }
+};
+template <typename E, int AUX>
+__device__ __forceinline__ void st_row4_buf(__amdgpu_buffer_rsrc_t rs, int off, unsigned so, float a, float b, float c, float d) {
+    StRow4<E, AUX>::go(rs, off, so, a, b, c, d);
 }
 
 // ---- the product of one timestep (forward kernel) ---------------------------------------------------------
@@ -764,6 +774,16 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
         for (int i = 0; i < NW; ++i)
             wreg[i] = (i < ni) ? *reinterpret_cast<const f32x4_t*>(wrow + i * KBLK) : f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
+    // The arrays as buffers that never change during the loop (host code guarantees that each is shorter than
+    // 2^31 bytes); where a timestep's rows begin is the scalar offset of an access, and this thread's first
+    // (piece, unit) sits at the same place inside every timestep's rows.
+    constexpr int WHOLE = (int)0x80000000u;
+    const __amdgpu_buffer_rsrc_t rs_dzall = __builtin_amdgcn_make_buffer_rsrc(dzw, 0, WHOLE, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_gates = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.gates), 0, WHOLE, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_cell = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.c), 0, WHOLE, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_above = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.dh_above), 0, WHOLE, 0x00020000);
+    const unsigned poff = (unsigned)(((tid / UH) * X + x) * H + j0 + (tid % UH)) * 4u;   // bytes inside an [rows, H] fp32 array
+    const unsigned row_h = 4u * (unsigned)H;
     BwdSaved pre;   // saved activations of this thread's first (piece, unit) of the coming timestep
     pre.g4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
     pre.c = pre.c_prev = pre.dh_above = 0.f;
@@ -787,8 +807,7 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
         const int bs = grp_count(bs_t, x, X);
         const int bs_next = (t + 1 < T) ? grp_count(bs_up, x, X) : 0;
         const int base_prev = base - bs_m1;     // rows of timestep t-1 (unused when t == 0)
-        __amdgpu_buffer_rsrc_t rs_dz = __builtin_amdgcn_make_buffer_rsrc(dzw + (size_t)base * K, 0,
-                                                                         bs_t * K * (int)sizeof(E), 0x00020000);
+        const unsigned so_dz = (unsigned)base * (unsigned)(K * (int)sizeof(E));   // where this timestep's dz rows begin
         // A. gate gradients of this workgroup's units for every alive piece
         for (int i = tid; i < bs * UH; i += REC_THREADS) {
             const int m = i / UH, n = m * X + x, j = j0 + (i % UH);
@@ -800,17 +819,20 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
             float dh = sv.dh_above, dc = 0.f;
             if (carried) {
                 // the pieces of the first chunk hand dh over in LDS, a thread's first item keeps dc in a register
-                dh += (m < 16 * ntc) ? sDh[m * UH + (i % UH)] : a.dh_state[(size_t)n * H + j];
+                // (two separate loads on purpose: written as one conditional expression the compiler loads through
+                // a pointer that is either LDS or global memory, and this compiler's back end then fails on the
+                // null test of that pointer)
+                const float dh_lds = sDh[(m < 16 * ntc ? m : 0) * UH + (i % UH)];
+                float dh_mem = 0.f;
+                if (m >= 16 * ntc) dh_mem = a.dh_state[(size_t)n * H + j];
+                dh += (m < 16 * ntc) ? dh_lds : dh_mem;
                 dc = first ? dcreg : a.dc_state[(size_t)n * H + j];
             }
             const float tc = tanhf_(sv.c);
             dc += dh * go * (1.f - tc * tc);
-            if (PIPE == PIPE_PRODUCER)   // also read by the workers on other XCDs
-                st_row4_through<E>(rs_dz, (n * K + j * 4) * (int)sizeof(E), dc * gg * gi * (1.f - gi), dc * sv.c_prev * gf * (1.f - gf),
-                                   dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
-            else
-                st_row4<E>(dzw + p * K + (size_t)j * 4, dc * gg * gi * (1.f - gi), dc * sv.c_prev * gf * (1.f - gf),
-                           dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
+            // (written through in a two-layer launch: the rows are also read by the workers on other XCDs)
+            st_row4_buf<E, PIPE == PIPE_PRODUCER ? 17 : 0>(rs_dzall, (n * K + j * 4) * (int)sizeof(E), so_dz, dc * gg * gi * (1.f - gi),
+                                                           dc * sv.c_prev * gf * (1.f - gf), dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
             if (first) dcreg = dc * gf;
             else a.dc_state[(size_t)n * H + j] = dc * gf;
         }
@@ -828,7 +850,7 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc);
             if (c0 > 0) bar_lds();
-            stage_rows<E>(dzw + ((size_t)base + (size_t)c0 * X + x) * K, rows, K, X * K, sB, stride, rank);
+            stage_rows<E>(rs_dzall, so_dz + (unsigned)((c0 * X + x) * K) * (unsigned)sizeof(E), rows, K, X * K, sB, stride, rank);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             bar_lds();
             REC_PROF_MARK(11);
@@ -839,8 +861,18 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
                 // saved activations of this thread's first item of timestep t-1, issued once the exchanged rows
                 // have arrived (see the forward kernel): in flight during the MFMA phase
                 const int bs_p = grp_count(bs_m1, x, X);
-                if (tid < bs_p * UH)
-                    pre = load_saved(a, t - 1, base_prev, base_prev - bs_m2, (tid / UH) * X + x, j0 + (tid % UH), H);
+                if (tid < bs_p * UH) {
+                    const unsigned so = (unsigned)base_prev * row_h;
+                    pre.g4 = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs_gates, poff * 4u, so * 4u, 0));
+                    pre.c = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_cell, poff, so, 0));
+                    pre.dh_above = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_above, poff, so, 0));
+                    if (t - 1 == 0) {
+                        const int n = (tid / UH) * X + x;
+                        pre.c_prev = (a.c0 && n < a.seq_cap) ? a.c0[(size_t)n * H + j0 + (tid % UH)] : 0.f;
+                    } else {
+                        pre.c_prev = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_cell, poff, (unsigned)(base_prev - bs_m2) * row_h, 0));
+                    }
+                }
             }
             f32x4_t acc[REC_NTC];
             mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
