@@ -218,10 +218,26 @@ typedef struct {
     /* scratch */
     void* workspace;
     size_t workspace_bytes;
+    /* non-zero: the index outputs already hold this minibatch's values (written by ver_pack_index_batch
+     * or by an earlier call with the same rollout, keys, B and b): only the gathers are performed */
+    int32_t index_ready;
 } ver_pack_args;
 
 size_t ver_pack_workspace_bytes(int32_t N, int32_t S, int32_t B);
 int ver_pack_minibatch(const ver_pack_args* args /* host */, void* stream);
+
+/*
+ * ver_pack_index_batch - the index outputs of n minibatches in one launch.
+ * The minibatches of an update (every epoch's keys, every b) depend only on the
+ * rollout, never on the weights, and each takes one workgroup: args is a host
+ * array of n argument blocks that share dones, env_off, env_started_episode,
+ * N, S and B and differ in seq_key, b, the index outputs and the workspace
+ * (each block its own: VER_EINVAL if two share info or workspace).  Writes
+ * info .. t_off of every block exactly as ver_pack_minibatch would; gather
+ * fields and gather_idx are ignored.  A later ver_pack_minibatch with
+ * index_ready != 0 on the same block performs the gathers (and gather_idx).
+ */
+int ver_pack_index_batch(const ver_pack_args* args /* host array */, int32_t n, void* stream);
 
 /* ------------------------------------------------------------------------
  * ver_lstm_fwd / ver_lstm_bwd - multi-layer LSTM actor-critic over a packed

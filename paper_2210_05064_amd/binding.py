@@ -34,7 +34,7 @@ class PackArgs(C.Structure):
         ("logp_old_packed", _vp), ("adv_packed", _vp), ("ret_packed", _vp), ("is_weight_packed", _vp),
         ("rnn_h", _vp), ("rnn_c", _vp), ("n_layers", _i32), ("H", _i32), ("seq_cap", _i32),
         ("h0", _vp), ("c0", _vp),
-        ("workspace", _vp), ("workspace_bytes", _sz),
+        ("workspace", _vp), ("workspace_bytes", _sz), ("index_ready", _i32),
     ]
 
 
@@ -72,6 +72,8 @@ lib.ver_pack_workspace_bytes.restype = _sz
 lib.ver_pack_workspace_bytes.argtypes = [_i32, _i32, _i32]
 lib.ver_pack_minibatch.restype = C.c_int
 lib.ver_pack_minibatch.argtypes = [C.POINTER(PackArgs), _vp]
+lib.ver_pack_index_batch.restype = C.c_int
+lib.ver_pack_index_batch.argtypes = [C.POINTER(PackArgs), _i32, _vp]
 lib.ver_lstm_workspace_bytes.restype = _sz
 lib.ver_lstm_workspace_bytes.argtypes = [C.POINTER(LstmCfg), _i32]
 lib.ver_lstm_fwd.restype = C.c_int
@@ -174,8 +176,8 @@ def ver_pack_workspace_bytes(N: int, S: int, B: int) -> int:
     return lib.ver_pack_workspace_bytes(N, S, B)
 
 
-def ver_pack_minibatch(**kw):
-    """Keyword arguments are the fields of ver_pack_args; tensors or ints."""
+def pack_args(**kw) -> PackArgs:
+    """ver_pack_args from keyword arguments (its fields; tensors or ints)."""
     a = PackArgs()
     names = {f[0] for f in PackArgs._fields_}
     for k, v in kw.items():
@@ -187,7 +189,19 @@ def ver_pack_minibatch(**kw):
             setattr(a, k, _ptr(v))
         elif v is not None:
             setattr(a, k, v)
+    return a
+
+
+def ver_pack_minibatch(**kw):
+    """Keyword arguments are the fields of ver_pack_args; tensors or ints."""
+    a = pack_args(**kw)
     _check(lib.ver_pack_minibatch(C.byref(a), _stream()))
+
+
+def ver_pack_index_batch(arg_blocks):
+    """arg_blocks: list of ver_pack_args (see pack_args), one per minibatch."""
+    arr = (PackArgs * len(arg_blocks))(*arg_blocks)
+    _check(lib.ver_pack_index_batch(arr, len(arg_blocks), _stream()))
 
 
 def _ptr_array(tensors):

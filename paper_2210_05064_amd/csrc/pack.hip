@@ -63,12 +63,38 @@ __device__ __forceinline__ int block_scan_incl(int v, int* s_w, int* total) {
 
 constexpr int IDX_SL_CACHE = 4096;   // sorted piece lengths kept in LDS for the per-timestep counts
 
+// One minibatch's part of an index launch: workgroup i of the launch builds the integer outputs of job i.  The
+// minibatches of an update are independent of each other (and of the weights), so all of them can be indexed by
+// one launch, one workgroup (one CU) each.
+constexpr int PACK_MAX_JOBS = 16;
+struct PackJob {
+    const uint32_t* seq_key;
+    int b;
+    PackWs ws;
+    int32_t* info;
+    int32_t* seq_first;
+    int32_t* seq_len;
+    uint8_t* seq_eps;
+    int32_t* batch_sizes;
+    int32_t* t_off;
+};
+struct PackJobs {
+    PackJob j[PACK_MAX_JOBS];
+};
+
 __global__ __launch_bounds__(IDX_THREADS) void pack_index_kernel(
     const uint8_t* __restrict__ dones, const int32_t* __restrict__ env_off,
-    const uint8_t* __restrict__ env_started_episode, const uint32_t* __restrict__ seq_key,
-    int N, int S, int B, int b, PackWs ws, int32_t* __restrict__ info, int32_t* __restrict__ seq_first,
-    int32_t* __restrict__ seq_len, uint8_t* __restrict__ seq_eps, int32_t* __restrict__ batch_sizes,
-    int32_t* __restrict__ t_off) {
+    const uint8_t* __restrict__ env_started_episode, int N, int S, int B, PackJobs jobs) {
+    const PackJob& job = jobs.j[blockIdx.x];
+    const uint32_t* __restrict__ seq_key = job.seq_key;
+    const int b = job.b;
+    const PackWs ws = job.ws;
+    int32_t* __restrict__ info = job.info;
+    int32_t* __restrict__ seq_first = job.seq_first;
+    int32_t* __restrict__ seq_len = job.seq_len;
+    uint8_t* __restrict__ seq_eps = job.seq_eps;
+    int32_t* __restrict__ batch_sizes = job.batch_sizes;
+    int32_t* __restrict__ t_off = job.t_off;
     __shared__ int s_w[IDX_WAVES + 1];
     __shared__ int s_cnt[IDX_WAVES + 1];
     __shared__ uint32_t s_key[IDX_THREADS];
@@ -428,26 +454,71 @@ extern "C" size_t ver_pack_workspace_bytes(int32_t N, int32_t S, int32_t B) {
     return ver::pack_ws_layout(S, S / B, nullptr, nullptr);
 }
 
-extern "C" int ver_pack_minibatch(const ver_pack_args* a, void* stream) {
+namespace ver {
+namespace {
+// Host checks of the arguments the index part reads, and the job they describe.
+int pack_job_of(const ver_pack_args* a, PackJob* job) {
     if (!a) return VER_EINVAL;
     if (a->N <= 0 || a->S <= 0 || a->B <= 0 || a->b < 0 || a->b >= a->B || a->S % a->B != 0) return VER_EINVAL;
     if (!a->dones || !a->env_off || !a->seq_key || !a->info || !a->seq_first || !a->seq_len ||
-        !a->seq_is_ep_start || !a->batch_sizes || !a->t_off || !a->gather_idx)
+        !a->seq_is_ep_start || !a->batch_sizes || !a->t_off)
         return VER_EINVAL;
+    if (!a->workspace || a->workspace_bytes < ver_pack_workspace_bytes(a->N, a->S, a->B)) return VER_EWORKSPACE;
+    job->seq_key = a->seq_key;
+    job->b = a->b;
+    pack_ws_layout(a->S, a->S / a->B, a->workspace, &job->ws);
+    job->info = a->info; job->seq_first = a->seq_first; job->seq_len = a->seq_len; job->seq_eps = a->seq_is_ep_start;
+    job->batch_sizes = a->batch_sizes; job->t_off = a->t_off;
+    return VER_OK;
+}
+}  // namespace
+}  // namespace ver
+
+extern "C" int ver_pack_index_batch(const ver_pack_args* args, int32_t n, void* stream) {
+    if (n < 0 || (n > 0 && !args)) return VER_EINVAL;
+    if (n == 0) return VER_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // check everything before anything is launched
+    for (int i = 0; i < n; ++i) {
+        ver::PackJob job;
+        const int st = ver::pack_job_of(&args[i], &job);
+        if (st != VER_OK) return st;
+        const ver_pack_args& a = args[i];
+        const ver_pack_args& f = args[0];
+        if (a.dones != f.dones || a.env_off != f.env_off || a.env_started_episode != f.env_started_episode || a.N != f.N ||
+            a.S != f.S || a.B != f.B)
+            return VER_EINVAL;   // one rollout, one minibatch count per call
+        for (int k = 0; k < i; ++k)
+            if (args[k].workspace == a.workspace || args[k].info == a.info) return VER_EINVAL;   // outputs must not be shared
+    }
+    ver::ProfScope prof(VER_PROF_PACK_INDEX, s);
+    for (int i0 = 0; i0 < n; i0 += ver::PACK_MAX_JOBS) {
+        const int cnt = n - i0 < ver::PACK_MAX_JOBS ? n - i0 : ver::PACK_MAX_JOBS;
+        ver::PackJobs jobs = {};
+        for (int i = 0; i < cnt; ++i) (void)ver::pack_job_of(&args[i0 + i], &jobs.j[i]);
+        hipLaunchKernelGGL(ver::pack_index_kernel, dim3(cnt), dim3(ver::IDX_THREADS), 0, s, args[0].dones, args[0].env_off,
+                           args[0].env_started_episode, args[0].N, args[0].S, args[0].B, jobs);
+    }
+    return ver::launch_status();
+}
+
+extern "C" int ver_pack_minibatch(const ver_pack_args* a, void* stream) {
+    ver::PackJobs jobs = {};
+    {
+        const int st = ver::pack_job_of(a, &jobs.j[0]);
+        if (st != VER_OK) return st;
+    }
+    if (!a->gather_idx) return VER_EINVAL;
     if (a->obs && a->obs_packed && a->D <= 0) return VER_EINVAL;
     if (a->actions && a->actions_packed && a->act_bytes <= 0) return VER_EINVAL;
     const bool states = (a->rnn_h && a->h0) || (a->rnn_c && a->c0);
     if (states && (a->n_layers <= 0 || a->H <= 0 || a->seq_cap <= 0)) return VER_EINVAL;
-    if (!a->workspace || a->workspace_bytes < ver_pack_workspace_bytes(a->N, a->S, a->B)) return VER_EWORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int M = a->S / a->B;
-    ver::PackWs ws;
-    ver::pack_ws_layout(a->S, M, a->workspace, &ws);
-    {
+    if (!a->index_ready) {
     ver::ProfScope prof(VER_PROF_PACK_INDEX, s);
     hipLaunchKernelGGL(ver::pack_index_kernel, dim3(1), dim3(ver::IDX_THREADS), 0, s, a->dones, a->env_off,
-                       a->env_started_episode, a->seq_key, a->N, a->S, a->B, a->b, ws, a->info, a->seq_first,
-                       a->seq_len, a->seq_is_ep_start, a->batch_sizes, a->t_off);
+                       a->env_started_episode, a->N, a->S, a->B, jobs);
     }
     if (hipGetLastError() != hipSuccess) return VER_EHIP;
     ver::GatherArgs g;

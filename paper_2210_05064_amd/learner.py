@@ -87,12 +87,10 @@ class Learner:
         self.grads = [torch.empty_like(t) for t in self.weights]
         self.log_std = _dev(np.asarray(wt["log_std"], np.float32))
         self.d_log_std = torch.empty(A, **f32)
-        # packed minibatch
-        self.info = torch.zeros(4, **i32)
-        self.seq_first, self.seq_len = torch.empty(M, **i32), torch.empty(M, **i32)
-        self.seq_eps = torch.empty(M, dtype=torch.uint8, device="cuda")
-        self.batch_sizes, self.t_off = torch.empty(M, **i32), torch.empty(M + 1, **i32)
-        self.gather_idx = torch.empty(M, **i32)
+        # packed minibatch: one set of index arrays (and index workspace) per minibatch of an update, so that one
+        # launch can index all of them before the first minibatch runs; set 0 also serves single pack() calls
+        self.index_sets = [self._index_set() for _ in range(w.epochs * self.B)]
+        self._use_index_set(0)
         self.x_packed = torch.empty((M, D), dtype=torch.bfloat16 if self.x_bf16 else torch.float32, device="cuda")
         self.act_packed = torch.empty((M,) + tuple(self.actions.shape[1:]), dtype=self.actions.dtype, device="cuda")
         self.logp_old_p, self.adv_p, self.ret_p = (torch.empty(M, **f32) for _ in range(3))
@@ -113,7 +111,6 @@ class Learner:
         self.lstm_cfg = ver.lstm_cfg(nl, D, H, A, self.compute, int(self.x_bf16))
         self.ppo_cfg = ver.ppo_cfg(w.clip, w.value_coef, w.entropy_coef, w.dist, A)
         self.ws_gae = ver.workspace(ver.ver_gae_workspace_bytes(S))
-        self.ws_pack = ver.workspace(ver.ver_pack_workspace_bytes(self.N, S, self.B))
         n = ver.ver_lstm_workspace_bytes(self.lstm_cfg, M)
         if n == 0:
             raise ver.VerError(-3)
@@ -138,6 +135,32 @@ class Learner:
             self.grad_norm = torch.zeros(1, **f32)
             self.ws_adam = ver.workspace(ver.ver_adam_workspace_bytes())
             self.opt_steps = 0
+
+    def _index_set(self) -> dict:
+        M = self.M
+        i32 = dict(dtype=torch.int32, device="cuda")
+        return dict(info=torch.zeros(4, **i32), seq_first=torch.empty(M, **i32), seq_len=torch.empty(M, **i32),
+                    seq_eps=torch.empty(M, dtype=torch.uint8, device="cuda"), batch_sizes=torch.empty(M, **i32),
+                    t_off=torch.empty(M + 1, **i32), gather_idx=torch.empty(M, **i32),
+                    ws_pack=ver.workspace(ver.ver_pack_workspace_bytes(self.N, self.S, self.B)))
+
+    def _use_index_set(self, k: int):
+        for name, t in self.index_sets[k].items():
+            setattr(self, name, t)
+
+    def _pack_args(self, epoch: int, b: int, index_ready: int):
+        return ver.pack_args(
+            dones=self.dones, env_off=self.env_off, env_started_episode=self.env_started,
+            seq_key=self.seq_key[epoch], N=self.N, S=self.S, B=self.B, b=b,
+            info=self.info, seq_first=self.seq_first, seq_len=self.seq_len, seq_is_ep_start=self.seq_eps,
+            batch_sizes=self.batch_sizes, t_off=self.t_off, gather_idx=self.gather_idx,
+            obs=self.obs, D=self.w.input_dim, obs_packed=self.x_packed, obs_packed_bf16=int(self.x_bf16),
+            actions=self.actions, act_bytes=self.act_bytes, actions_packed=self.act_packed,
+            logp_old=self.logp_old, adv=self.adv, ret=self.ret, is_weight=self.is_w,
+            logp_old_packed=self.logp_old_p, adv_packed=self.adv_p, ret_packed=self.ret_p,
+            is_weight_packed=self.is_w_p,
+            rnn_h=self.rnn_h, rnn_c=self.rnn_c, n_layers=self.w.n_layers, H=self.w.hidden,
+            seq_cap=self.seq_cap, h0=self.h0, c0=self.c0, workspace=self.ws_pack, index_ready=index_ready)
 
     # -- the entry points, in the order of the learning phase ---------------------
     def set_logp_old(self, flat: torch.Tensor):
@@ -164,19 +187,20 @@ class Learner:
     def importance_weights(self):
         ver.ver_is_weight(self.env_off, self.N, self.S, self.max_is, self.is_w)
 
-    def pack(self, epoch: int, b: int):
-        ver.ver_pack_minibatch(
-            dones=self.dones, env_off=self.env_off, env_started_episode=self.env_started,
-            seq_key=self.seq_key[epoch], N=self.N, S=self.S, B=self.B, b=b,
-            info=self.info, seq_first=self.seq_first, seq_len=self.seq_len, seq_is_ep_start=self.seq_eps,
-            batch_sizes=self.batch_sizes, t_off=self.t_off, gather_idx=self.gather_idx,
-            obs=self.obs, D=self.w.input_dim, obs_packed=self.x_packed, obs_packed_bf16=int(self.x_bf16),
-            actions=self.actions, act_bytes=self.act_bytes, actions_packed=self.act_packed,
-            logp_old=self.logp_old, adv=self.adv, ret=self.ret, is_weight=self.is_w,
-            logp_old_packed=self.logp_old_p, adv_packed=self.adv_p, ret_packed=self.ret_p,
-            is_weight_packed=self.is_w_p,
-            rnn_h=self.rnn_h, rnn_c=self.rnn_c, n_layers=self.w.n_layers, H=self.w.hidden,
-            seq_cap=self.seq_cap, h0=self.h0, c0=self.c0, workspace=self.ws_pack)
+    def pack(self, epoch: int, b: int, index_ready: bool = False):
+        """Index + gathers of one minibatch into the current index set (index_ready: gathers only)."""
+        a = self._pack_args(epoch, b, int(index_ready))
+        ver._check(ver.lib.ver_pack_minibatch(a, ver._stream()))
+
+    def index_all(self):
+        """The index arrays of every minibatch of the update (epochs x minibatches) in one launch."""
+        blocks = []
+        for e in range(self.w.epochs):
+            for b in range(self.B):
+                self._use_index_set(e * self.B + b)
+                blocks.append(self._pack_args(e, b, 0))
+        self._use_index_set(0)
+        ver.ver_pack_index_batch(blocks)
 
     def forward(self):
         ver.ver_lstm_fwd(self.lstm_cfg, self.x_packed, self.M, self.info, self.batch_sizes, self.t_off,
@@ -206,8 +230,8 @@ class Learner:
                                   self.opt_lower, self.opt_upper, self.opt_steps, self.grad_norm, self.ws_adam)
         self.opt_steps += 1
 
-    def minibatch(self, epoch: int, b: int):
-        self.pack(epoch, b)
+    def minibatch(self, epoch: int, b: int, index_ready: bool = False):
+        self.pack(epoch, b, index_ready)
         self.forward()
         self.loss()
         self.backward()
@@ -221,9 +245,11 @@ class Learner:
         self.gae()
         if self.max_is is not None:
             self.importance_weights()
+        self.index_all()
         for e in range(self.w.epochs):
             for b in range(self.B):
-                self.minibatch(e, b)
+                self._use_index_set(e * self.B + b)
+                self.minibatch(e, b, index_ready=True)
                 if on_minibatch is not None:
                     on_minibatch(e, b)
 

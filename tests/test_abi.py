@@ -144,3 +144,10 @@ def test_ingest_argument_checks(lib):
     assert lib.ver_ingest_gather(None, 0, None, 4, None, None) == 0        # nothing to move
     assert lib.ver_ingest_gather(None, 8, None, 4, None, None) == -1
     assert lib.ver_ingest_gather(None, 8, None, 0, None, None) == -1
+
+
+def test_pack_index_batch_argument_checks(lib):
+    lib.ver_pack_index_batch.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+    assert lib.ver_pack_index_batch(None, 0, None) == 0        # nothing to index
+    assert lib.ver_pack_index_batch(None, 3, None) == -1
+    assert lib.ver_pack_index_batch(None, -1, None) == -1

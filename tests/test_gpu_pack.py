@@ -138,3 +138,63 @@ def test_argument_errors(ver):
     d, key = np.zeros(8, np.uint8), np.zeros(8, np.uint32)
     with pytest.raises(ver.VerError):
         run_pack(ver, d, off, key, 2, 2)           # b out of range
+
+
+@pytest.mark.parametrize("name", ["tiny", "nav", "large", "max"])
+def test_index_batch_all_minibatches_in_one_launch(ver, name):
+    """ver_pack_index_batch: every (epoch, minibatch) of an update indexed by one launch, each into its own
+    outputs; then ver_pack_minibatch with index_ready does only the gathers.  Everything bit-exact against the
+    oracle's per-minibatch result."""
+    w = wl.scaled(wl.WORKLOADS[name], hidden=64, input_dim=12)
+    ro = wl.make_rollout(w, seed=21, with_states=False)
+    N, S, B, E = ro["N"], ro["S"], w.minibatches, w.epochs
+    M = S // B
+    d_dones, d_off, d_eps = dev(ro["dones"]), dev(ro["env_off"]), dev(ro["env_started_episode"])
+    d_obs = dev(ro["obs"])
+    keys = [dev(ro["seq_key"][e]) for e in range(E)]
+    outs, blocks, wss = [], [], []
+    for e in range(E):
+        for b in range(B):
+            out = PackOut(M, 12)
+            ws = ver.workspace(ver.ver_pack_workspace_bytes(N, S, B))
+            ws.fill_(-1)
+            kw = dict(dones=d_dones, env_off=d_off, env_started_episode=d_eps, seq_key=keys[e], N=N, S=S, B=B, b=b,
+                      info=out.info, seq_first=out.seq_first, seq_len=out.seq_len, seq_is_ep_start=out.seq_is_ep_start,
+                      batch_sizes=out.batch_sizes, t_off=out.t_off, gather_idx=out.gather_idx, workspace=ws)
+            outs.append((out, kw)); wss.append(ws)
+            blocks.append(ver.pack_args(**kw))
+    ver.ver_pack_index_batch(blocks)
+    torch.cuda.synchronize()
+    for i, (out, kw) in enumerate(outs):
+        e, b = divmod(i, B)
+        ref = opack.pack_minibatch(ro["dones"], ro["env_off"], ro["seq_key"][e], B, b, ro["env_started_episode"])
+        got = out.meta()
+        assert np.all(host(out.gather_idx) == -7), "the index launch must not touch gather_idx"
+        got["gather_idx"] = ref["gather_idx"]            # written by the gather call below
+        compare_meta(got, ref)
+        out.info_before = host(out.info).copy()
+        ver.ver_pack_minibatch(obs=d_obs, D=12, obs_packed=out.obs_packed, index_ready=1, **kw)
+        torch.cuda.synchronize()
+        compare_meta(out.meta(), ref)
+        assert np.array_equal(host(out.obs_packed), opack.gather_rows(ro["obs"], ref["gather_idx"]))
+
+
+def test_index_batch_argument_errors(ver):
+    w = wl.scaled(wl.WORKLOADS["tiny"], hidden=64, input_dim=8)
+    ro = wl.make_rollout(w, seed=1, with_states=False)
+    N, S = ro["N"], ro["S"]
+    out, out2 = PackOut(S), PackOut(S)
+    ws, ws2 = (ver.workspace(ver.ver_pack_workspace_bytes(N, S, 1)) for _ in range(2))
+    base = dict(dones=dev(ro["dones"]), env_off=dev(ro["env_off"]), seq_key=dev(ro["seq_key"][0]), N=N, S=S, B=1, b=0)
+    outs = lambda o: dict(info=o.info, seq_first=o.seq_first, seq_len=o.seq_len, seq_is_ep_start=o.seq_is_ep_start,
+                          batch_sizes=o.batch_sizes, t_off=o.t_off, gather_idx=o.gather_idx)
+    a = ver.pack_args(workspace=ws, **base, **outs(out))
+    ver.ver_pack_index_batch([])                                              # nothing to do
+    ver.ver_pack_index_batch([a, ver.pack_args(workspace=ws2, **base, **outs(out2))])
+    with pytest.raises(ver.VerError):
+        ver.ver_pack_index_batch([a, ver.pack_args(workspace=ws, **base, **outs(out2))])      # shared workspace
+    with pytest.raises(ver.VerError):
+        ver.ver_pack_index_batch([a, ver.pack_args(workspace=ws2, **base, **outs(out))])      # shared outputs
+    with pytest.raises(ver.VerError):
+        ver.ver_pack_index_batch([a, ver.pack_args(workspace=ws2, **dict(base, dones=dev(ro["dones"])), **outs(out2))])  # another rollout
+    torch.cuda.synchronize()
