@@ -320,6 +320,9 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     ws->err = head;
     ws->flags = cv.take<int>(REC_FLAG_WORDS);
     ws->prof = cv.take<long long>(80);
+    // the hand-over words sit right behind, so that one fill clears everything a launch needs cleared
+    ws->pipe_words = 16 + M / PIPE_CT + 2;
+    ws->pipe = cv.take<int>(ws->pipe_words);
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws->layer[l];
@@ -336,8 +339,6 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     }
     ws->dz[0] = cv.take<char>(Mz * 4 * H * es);
     ws->dz[1] = c.n_layers == 2 ? cv.take<char>(Mz * 4 * H * es) : ws->dz[0];
-    ws->pipe_words = 16 + M / PIPE_CT + 2;
-    ws->pipe = cv.take<int>(ws->pipe_words);
     ws->dh[0] = cv.take<float>(Mz * H);
     ws->dh[1] = cv.take<float>(Mz * H);
     ws->dh_state = cv.take<float>(2 * Mz * H);
@@ -386,9 +387,15 @@ inline size_t pipe_worker_lds() {
     if (MODE == MODE_BF16) return (size_t)PIPE_STAGES * PIPE_STAGE_BYTES;
     return (size_t)(PIPE_BM + PIPE_BN) * GemmGeom<MODE>::LDS_STRIDE * sizeof(typename LdsElem<MODE>::type);
 }
+// Zeroes the flags, ticket counters and (two-layer launches) hand-over words of a recurrent launch with one fill;
+// with_err also clears the sticky time-out word at the start of the workspace (forward call only).
+inline void clear_sync_words(LstmWs& ws, bool with_err, bool with_pipe, hipStream_t s) {
+    int* first = with_err ? ws.err : ws.flags;
+    int* last = with_pipe ? ws.pipe + ws.pipe_words : ws.flags + REC_FLAG_WORDS;
+    fill_words(first, (size_t)(last - first), 0, s);
+}
 inline void pipe_link(const ver_lstm_cfg& c, int M, int N, LstmWs& ws, hipStream_t s, PipeLink* pl) {
-    fill_words(ws.pipe, ws.pipe_words, 0, s);
-    pl->progress = ws.pipe;
+    pl->progress = ws.pipe;   // cleared by the caller together with the flags (clear_sync_words)
     pl->done = ws.pipe + 16;
     pl->tiles_n = (N + PIPE_BN - 1) / PIPE_BN;
     pl->T_all = 0;   // filled in on the device from info[1]
@@ -403,7 +410,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     typedef typename RecGeom<MODE>::E E;
     const int H = c.hidden, A = c.act_dim;
     const bool pipelined = c.n_layers == 2 && !sequential_layers();   // both time loops in one launch
-    fill_words(ws.err, 1, 0, s);
+    if (!pipelined) fill_words(ws.err, 1, 0, s);
 
     // 8 waves = row groups x shares of the contraction (TPW tiles of 16 gate rows per wave): a workgroup owns
     // 8 tiles (32 units) when 32 workgroups need all of H/32 units each, else 4 tiles (16 units)
@@ -480,7 +487,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         prep(0);
         prep(1);
         project(0);
-        fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
+        clear_sync_words(ws, true, true, s);
         PipeFwdArgs pa;
         pa.l0 = rec_args(0);
         pa.l1 = rec_args(1);
@@ -610,7 +617,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     };
 
     if (pipelined) {
-        fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
+        clear_sync_words(ws, false, true, s);
         PipeBwdArgs pa;
         pa.l1 = rec_args(1, ws.dh[0]);
         pa.l0 = rec_args(0, ws.dh[1]);

@@ -27,8 +27,9 @@ class Learner:
     def __init__(self, rollout: dict, *, compute: int | None = None, x_bf16: bool | None = None,
                  want_dx: bool = False, minibatches: int | None = None, adam_total_steps: int | None = None,
                  adam: dict | None = None, max_is: float | None = None, learned_entropy: dict | None = None,
-                 arrival: tuple | None = None):
-        """arrival: (arr_env, arr_t, csr_of_arrival) of workloads.arrival_order: the rollout is then held as the
+                 arrival: tuple | None = None, want_grad_norm: bool = False):
+        """want_grad_norm: have every optimiser step report the global gradient norm (always on with clipping).
+        arrival: (arr_env, arr_t, csr_of_arrival) of workloads.arrival_order: the rollout is then held as the
         linear collection buffer (steps in arrival order) and every update starts by bucketing it by environment
         on the GPU (ver_ingest + one gather per field); None = the rollout is given environment-major.
         learned_entropy: dict alpha0, lower, upper, target, sign: the entropy coefficient is a device-resident
@@ -133,6 +134,7 @@ class Learner:
             self.exp_avg = [torch.zeros_like(t) for t in self.opt_params]
             self.exp_avg_sq = [torch.zeros_like(t) for t in self.opt_params]
             self.grad_norm = torch.zeros(1, **f32)
+            self.want_grad_norm = want_grad_norm or self.adam_cfg.max_grad_norm > 0
             self.ws_adam = ver.workspace(ver.ver_adam_workspace_bytes())
             self.opt_steps = 0
 
@@ -227,7 +229,8 @@ class Learner:
 
     def optimizer_step(self):
         ver.ver_adam_step_bounded(self.adam_cfg, self.opt_params, self.opt_grads, self.exp_avg, self.exp_avg_sq,
-                                  self.opt_lower, self.opt_upper, self.opt_steps, self.grad_norm, self.ws_adam)
+                                  self.opt_lower, self.opt_upper, self.opt_steps,
+                                  self.grad_norm if self.want_grad_norm else None, self.ws_adam)
         self.opt_steps += 1
 
     def minibatch(self, epoch: int, b: int, index_ready: bool = False):

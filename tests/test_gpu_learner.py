@@ -116,7 +116,7 @@ def test_update_with_optimizer(ver, dist, clip_norm, max_is):
                 + ro["logp_noise"]).astype(np.float32)
     opt = dict(lr0=2.5e-4, lr_final=0.0, total_steps=6, beta1=0.9, beta2=0.999, eps=1e-8, max_grad_norm=clip_norm)
     L = Learner(ro, compute=0, adam_total_steps=opt["total_steps"],
-                adam={k: v for k, v in opt.items() if k != "total_steps"}, max_is=max_is)
+                adam={k: v for k, v in opt.items() if k != "total_steps"}, max_is=max_is, want_grad_norm=True)
     L.logp_old.copy_(torch.from_numpy(logp_old).cuda())
     before = [host(t).astype(np.float64) for t in L.opt_params]
     L.update()
