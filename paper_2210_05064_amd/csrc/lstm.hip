@@ -60,29 +60,42 @@ __device__ __forceinline__ float wave_sum_all(float v) {
 }
 
 // head_out[p][a] = W_a[a] . h[p] + b_a[a];  value[p] = w_v . h[p] + b_v: a skinny fp32 GEMM (at most 64 columns)
-// bound by reading h once.  One wave per 16 rows, fp32 MFMA 16x16x4 with the heads (action outputs, then the
-// value) on the N dimension, 16 at a time.
+// bound by reading h once.  One workgroup per 16 rows, fp32 MFMA 16x16x4 with the heads (action outputs, then the
+// value) on the N dimension, 16 at a time; its four waves take a quarter of the contraction each (H is a multiple
+// of 64) and the partial tiles are added in LDS in a fixed order: four times as many waves in flight as with one
+// wave per block, which is what a latency-bound streaming read needs.
 __global__ __launch_bounds__(256) void heads_fwd_kernel(const float* __restrict__ h, int M, int H, int A,
                                                         const float* __restrict__ W_a, const float* __restrict__ b_a,
                                                         const float* __restrict__ w_v, const float* __restrict__ b_v,
                                                         float* __restrict__ head_out, float* __restrict__ value) {
-    const int lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4;
-    const int p0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 16;
-    if (p0 >= M) return;
+    __shared__ f32x4_t s_part[3][64];
+    const int lane = threadIdx.x & 63, lr = lane & 15, lk = lane >> 4, wave = threadIdx.x >> 6;
+    const int p0 = blockIdx.x * 16;
     const bool row_ok = p0 + lr < M;
-    const float* hrow = h + (size_t)(row_ok ? p0 + lr : p0) * H + lk * 4;
+    const int kq = H / 4;   // this wave's share of the contraction: [wave * kq, (wave + 1) * kq)
+    const float* hrow = h + (size_t)(row_ok ? p0 + lr : p0) * H + wave * kq + lk * 4;
     for (int ht = 0; ht * 16 <= A; ++ht) {
         const int hd = ht * 16 + lr;   // this lane's head as B operand
-        const float* wrow = (hd < A ? W_a + (size_t)hd * H : w_v) + lk * 4;
+        const float* wrow = (hd < A ? W_a + (size_t)hd * H : w_v) + wave * kq + lk * 4;
         const bool head_ok = hd <= A;
         f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        for (int k0 = 0; k0 < H; k0 += 16) {
+#pragma unroll 4
+        for (int k0 = 0; k0 < kq; k0 += 16) {
             f32x4_t av = *reinterpret_cast<const f32x4_t*>(hrow + k0);
             f32x4_t wv = *reinterpret_cast<const f32x4_t*>(wrow + k0);
             if (!row_ok) av = f32x4_t{0.f, 0.f, 0.f, 0.f};
             if (!head_ok) wv = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc = mfma_f32_16x16x4(av[e], wv[e], acc);
+        }
+        __syncthreads();   // s_part may still be read from the previous head tile
+        if (wave > 0) s_part[wave - 1][lane] = acc;
+        __syncthreads();
+        if (wave > 0) continue;
+#pragma unroll
+        for (int w = 0; w < 3; ++w) {
+            const f32x4_t o = s_part[w][lane];
+            acc[0] += o[0]; acc[1] += o[1]; acc[2] += o[2]; acc[3] += o[3];
         }
         // element r of the lane: row lk*4 + r, head ht*16 + lr
         if (head_ok) {
@@ -98,63 +111,82 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float* __restrict_
     }
 }
 
-// dh[p][j] = sum_a d_u[p][a] W_a[a][j] + d_v[p] w_v[j].  A thread owns column j for a block of HB_ROWS rows, so a
-// head weight is read once per block instead of once per row (the loss gradients are wave-uniform scalars).
-constexpr int HB_ROWS = 16;
+// dh[p][j] = sum_a d_u[p][a] W_a[a][j] + d_v[p] w_v[j].  A thread owns 4 adjacent columns (16-byte stores; H is a
+// multiple of 64) for a block of HB_ROWS rows, so a head weight is read once per block instead of once per row
+// (the loss gradients are wave-uniform scalars).  Bound by writing dh once.
+constexpr int HB_ROWS = 8;
 __global__ __launch_bounds__(256) void heads_bwd_dh_kernel(const float* __restrict__ d_u, const float* __restrict__ d_v,
                                                            int M, int H, int A, const float* __restrict__ W_a,
                                                            const float* __restrict__ w_v, float* __restrict__ dh) {
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    __shared__ float s_g[HB_ROWS][64];   // the block's loss gradients: heads 0..A-1, then the value head
+    const int j = (blockIdx.x * 256 + threadIdx.x) * 4;
     const int p0 = blockIdx.y * HB_ROWS;
+    for (int i = threadIdx.x; i < HB_ROWS * 64; i += 256) {
+        const int r = i >> 6, a = i & 63, p = p0 + r;
+        s_g[r][a] = (p < M) ? (a < A ? d_u[(size_t)p * A + a] : (a == A ? d_v[p] : 0.f)) : 0.f;
+    }
+    __syncthreads();
     if (j >= H) return;
-    float s[HB_ROWS];
-    const float wv = w_v[j];
+    f32x4_t s[HB_ROWS];
+    const f32x4_t wv = *reinterpret_cast<const f32x4_t*>(w_v + j);
 #pragma unroll
-    for (int r = 0; r < HB_ROWS; ++r) s[r] = (p0 + r < M) ? d_v[p0 + r] * wv : 0.f;
+    for (int r = 0; r < HB_ROWS; ++r) {
+        const float g = s_g[r][A];
+        s[r] = f32x4_t{g * wv[0], g * wv[1], g * wv[2], g * wv[3]};
+    }
     for (int a = 0; a < A; ++a) {
-        const float w = W_a[(size_t)a * H + j];
+        const f32x4_t w = *reinterpret_cast<const f32x4_t*>(W_a + (size_t)a * H + j);
 #pragma unroll
-        for (int r = 0; r < HB_ROWS; ++r)
-            if (p0 + r < M) s[r] += d_u[(size_t)(p0 + r) * A + a] * w;
+        for (int r = 0; r < HB_ROWS; ++r) {
+            const float g = s_g[r][a];   // same address in every lane: a broadcast read
+            s[r][0] += g * w[0]; s[r][1] += g * w[1]; s[r][2] += g * w[2]; s[r][3] += g * w[3];
+        }
     }
 #pragma unroll
     for (int r = 0; r < HB_ROWS; ++r)
-        if (p0 + r < M) dh[(size_t)(p0 + r) * H + j] = s[r];
+        if (p0 + r < M) *reinterpret_cast<f32x4_t*>(dh + (size_t)(p0 + r) * H + j) = s[r];
 }
 
 // Partial sums over a block of rows: part[rb][a][j] = sum_{p in block rb} du(p,a) * h[p][j], a = 0..A (A = value head).
-// h is read once per 16 heads; the loss gradients are wave-uniform scalars.
+// A thread owns 4 adjacent columns (16-byte loads of h; H is a multiple of 64) and reads h once per 8 heads, four
+// rows in flight; the loss gradients are wave-uniform scalars.  Bound by reading h once.
 constexpr int HW_ROWS = 32;  // rows per row block
 __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* __restrict__ d_u,
                                                                   const float* __restrict__ d_v,
                                                                   const float* __restrict__ h, int M, int H, int A,
                                                                   float* __restrict__ part) {
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    __shared__ float s_g[HW_ROWS][64];   // the block's loss gradients: heads 0..A-1, then the value head, then zeros
+    const int j = (blockIdx.x * 256 + threadIdx.x) * 4;
     const int rb = blockIdx.y;
     const int p_lo = rb * HW_ROWS, p_hi = min(M, p_lo + HW_ROWS);
+    for (int i = threadIdx.x; i < HW_ROWS * 64; i += 256) {
+        const int r = i >> 6, a = i & 63, p = p_lo + r;
+        s_g[r][a] = (p < p_hi) ? (a < A ? d_u[(size_t)p * A + a] : (a == A ? d_v[p] : 0.f)) : 0.f;
+    }
+    __syncthreads();
     if (j >= H) return;
-    for (int a0 = 0; a0 <= A; a0 += 16) {
-        float acc[16];
+    for (int a0 = 0; a0 <= A; a0 += 8) {
+        f32x4_t acc[8];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        for (int e = 0; e < 8; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         for (int p = p_lo; p < p_hi; p += 4) {
-            float hv[4];
+            f32x4_t hv[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) hv[u] = (p + u < p_hi) ? h[(size_t)(p + u) * H + j] : 0.f;
+            for (int u = 0; u < 4; ++u)
+                hv[u] = (p + u < p_hi) ? *reinterpret_cast<const f32x4_t*>(h + (size_t)(p + u) * H + j) : f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 if (p + u >= p_hi) continue;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int a = a0 + e;
-                    const float g = (a < A) ? d_u[(size_t)(p + u) * A + a] : (a == A ? d_v[p + u] : 0.f);
-                    acc[e] += g * hv[u];
+                for (int e = 0; e < 8; ++e) {
+                    const float g = s_g[p + u - p_lo][a0 + e];   // same address in every lane: a broadcast read
+                    acc[e][0] += g * hv[u][0]; acc[e][1] += g * hv[u][1]; acc[e][2] += g * hv[u][2]; acc[e][3] += g * hv[u][3];
                 }
             }
         }
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (a0 + e <= A) part[((size_t)rb * (A + 1) + a0 + e) * H + j] = acc[e];
+        for (int e = 0; e < 8; ++e)
+            if (a0 + e <= A) *reinterpret_cast<f32x4_t*>(part + ((size_t)rb * (A + 1) + a0 + e) * H + j) = acc[e];
     }
 }
 
@@ -512,7 +544,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
 #undef VER_FWD_DISPATCH
 #undef VER_FWD_LAUNCH
     ProfScope prof(VER_PROF_HEADS_FWD, s);
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 63) / 64), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3((M + 15) / 16), dim3(256), 0, s, ws.layer[c.n_layers - 1].hout, M, H, A,
                        w[4 * c.n_layers], w[4 * c.n_layers + 1], w[4 * c.n_layers + 2], w[4 * c.n_layers + 3],
                        head_out, value);
     return launch_status();
@@ -529,10 +561,10 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     // heads
     {
     ProfScope prof(VER_PROF_HEADS_BWD, s);
-    hipLaunchKernelGGL(heads_bwd_dh_kernel, dim3((H + 255) / 256, (M + HB_ROWS - 1) / HB_ROWS), dim3(256), 0, s, d_u, d_v, M, H, A, w[4 * nl],
+    hipLaunchKernelGGL(heads_bwd_dh_kernel, dim3((H / 4 + 255) / 256, (M + HB_ROWS - 1) / HB_ROWS), dim3(256), 0, s, d_u, d_v, M, H, A, w[4 * nl],
                        w[4 * nl + 2], ws.dh[0]);
     const int rb_h = (M + HW_ROWS - 1) / HW_ROWS;
-    hipLaunchKernelGGL(heads_wgrad_partial_kernel, dim3((H + 255) / 256, rb_h), dim3(256), 0, s, d_u, d_v, h_top, M, H,
+    hipLaunchKernelGGL(heads_wgrad_partial_kernel, dim3((H / 4 + 255) / 256, rb_h), dim3(256), 0, s, d_u, d_v, h_top, M, H,
                        A, ws.part);
     hipLaunchKernelGGL(heads_wgrad_final_kernel, dim3((H + 255) / 256, A + 1), dim3(256), 0, s, ws.part, rb_h, H, A,
                        gw[4 * nl], gw[4 * nl + 2]);
