@@ -21,25 +21,36 @@ namespace {
 // ---------------------------------------------------------------- weight preparation
 // dst[q][d] = W[(q%4)*H + q/4][d] and dstT[d][q]; q = unit*4 + gate.  A block moves a 64 x 64 tile through LDS so
 // that the reads of W and both writes are contiguous along their fastest index.
+// Four converted elements as one store (8 bytes bf16, 16 bytes fp32).
+__device__ __forceinline__ void st4(float* p, float a, float b, float c, float d) { *reinterpret_cast<f32x4_t*>(p) = f32x4_t{a, b, c, d}; }
+__device__ __forceinline__ void st4(bf16_t* p, float a, float b, float c, float d) {
+    u16x4_t v;
+    v.x = to_bf16(a); v.y = to_bf16(b); v.z = to_bf16(c); v.w = to_bf16(d);
+    *reinterpret_cast<u16x4_t*>(p) = v;
+}
+// A thread moves 4 adjacent elements at a time (16-byte loads, 8- or 16-byte stores; cols is a multiple of 4):
+// 16 lanes cover a tile row in either direction.
 template <typename E>
 __global__ __launch_bounds__(256) void prep_matrix_kernel(const float* __restrict__ W, int H, int cols, E* __restrict__ dst,
                                                           E* __restrict__ dstT) {
     __shared__ float tile[64][65];
     const int q0 = blockIdx.y * 64, d0 = blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) {
-        const int q = q0 + r, d = d0 + tx;
-        float v = 0.f;
-        if (d < cols) {   // 4H is a multiple of 64: q is always a valid row
-            v = W[((size_t)(q & 3) * H + (q >> 2)) * cols + d];
-            dst[(size_t)q * cols + d] = cvt_elem<E>(v);
+    const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
+#pragma unroll
+    for (int r = r0; r < 64; r += 16) {
+        const int q = q0 + r, d = d0 + c4;   // 4H is a multiple of 64: q is always a valid row
+        f32x4_t v = {0.f, 0.f, 0.f, 0.f};
+        if (d < cols) {
+            v = *reinterpret_cast<const f32x4_t*>(W + ((size_t)(q & 3) * H + (q >> 2)) * cols + d);
+            st4(dst + (size_t)q * cols + d, v[0], v[1], v[2], v[3]);
         }
-        tile[r][tx] = v;
+        tile[r][c4] = v[0]; tile[r][c4 + 1] = v[1]; tile[r][c4 + 2] = v[2]; tile[r][c4 + 3] = v[3];
     }
     __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int d = d0 + r, q = q0 + tx;
-        if (d < cols) dstT[(size_t)d * 4 * H + q] = cvt_elem<E>(tile[tx][r]);
+#pragma unroll
+    for (int r = r0; r < 64; r += 16) {
+        const int d = d0 + r, q = q0 + c4;
+        if (d < cols) st4(dstT + (size_t)d * 4 * H + q, tile[c4][r], tile[c4 + 1][r], tile[c4 + 2][r], tile[c4 + 3][r]);
     }
 }
 
