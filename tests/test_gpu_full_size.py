@@ -93,3 +93,50 @@ def test_full_size_minibatch(ver, name, max_steps):
     names = [f"layer{l}.{nme}" for l in range(w.n_layers) for nme in GRAD_NAMES] + ["W_a", "b_a", "w_v", "b_v"]
     for nme, gg, r in zip(names, L.grads, grads_to_list(grads)):
         close(host(gg), r, nme)
+
+
+@pytest.mark.parametrize("name", ["large", "max"])
+def test_full_size_optimizer_step_and_weights(ver, name):
+    """The steps that surround the minibatch loop at full size, in the configuration bench.py times: the Adam step
+    over every weight tensor of the workload's network (the oracle is elementwise numpy: all 17 M parameters of
+    `max` are compared, not a sample), the importance weights of the whole buffer, and the bucketing of the
+    arrival-order buffer."""
+    from oracle import adam as oadam, ingest as oing, is_weight as ois
+    from paper_2210_05064_amd.learner import Learner
+    w = wl.WORKLOADS[name]
+    ro = wl.make_rollout(w, seed=3, with_states=False)
+    arr = wl.arrival_order(ro["env_off"], seed=4)
+    L = Learner(ro, adam_total_steps=1000, max_is=1.0, arrival=arr, want_grad_norm=True)
+    # bucketing and importance weights
+    L.ingest()
+    L.importance_weights()
+    torch.cuda.synchronize()
+    r_off, r_order, _ = oing.ingest(arr[0], ro["N"], arr[1])
+    assert np.array_equal(host(L.env_off), r_off) and np.array_equal(host(L.order), r_order)
+    assert host(L.ingest_info).tolist() == [0, 0, 0, 0]
+    assert np.array_equal(host(L.obs), ro["obs"]) and np.array_equal(host(L.dones), ro["dones"])
+    assert np.array_equal(host(L.is_w), ois.is_weights(ro["env_off"], 1.0).astype(np.float32))
+    # one optimiser step on seeded gradients
+    rng = np.random.default_rng(5)
+    grads = [(rng.standard_normal(tuple(t.shape)) * 10.0 ** rng.integers(-3, 1)).astype(np.float32) for t in L.opt_params]
+    for g_dev, g in zip(L.opt_grads, grads):
+        g_dev.copy_(torch.from_numpy(g).cuda())
+    before = [host(t).astype(np.float64) for t in L.opt_params]
+    L.opt_steps = 37
+    L.optimizer_step()
+    torch.cuda.synchronize()
+    f32 = lambda x: float(np.float32(x))
+    lr = oadam.cosine_lr(37, 1000, f32(2.5e-4), 0.0)
+    new_p, new_m, new_v, norm = oadam.adam_step(before, grads, [np.zeros_like(b) for b in before],
+                                                [np.zeros_like(b) for b in before], 38, lr, f32(0.9), f32(0.999), f32(1e-8))
+    assert float(L.grad_norm.item()) == pytest.approx(norm, rel=1e-5)
+    n_params = 0
+    for i, t in enumerate(L.opt_params):
+        # the step is ~lr while the weights are ~1e-2: compare the moments exactly and the change of the weights
+        # to the resolution fp32 leaves of it
+        assert_close(host(L.exp_avg[i]), new_m[i], 1e-5, f"m[{i}]")
+        assert_close(host(L.exp_avg_sq[i]), new_v[i], 1e-5, f"v[{i}]")
+        got, want = host(t).astype(np.float64) - before[i], new_p[i] - before[i]
+        assert np.max(np.abs(got - want)) <= 2.0 ** -24 * max(1e-30, float(np.max(np.abs(before[i])))) + 1e-5 * np.max(np.abs(want))
+        n_params += t.numel()
+    assert n_params == sum(b.size for b in before) and n_params > (10 ** 7 if name == "max" else 10 ** 6)
