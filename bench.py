@@ -139,6 +139,10 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run three device-to-device copies of MIB mebibytes (a kernel of known HBM traffic "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters by) and exit")
+    ap.add_argument("--hbm-replica", nargs="?", const="all", default=None, metavar="SECTIONS",
+                    help="instead of the update, run every HBM-bound kernel on a roofline-scale replica of the max "
+                         "workload (gigabytes per launch) and print bytes / time against the HBM peak as one JSON line; "
+                         "optionally a comma-separated subset of gae,pack,loss,adam,ingest")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the learner step of ONE GPU; runs on several GPUs are not part of this build "
@@ -160,6 +164,12 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_bytes_read": src.numel() * 4, "copy_calibration_bytes_written": src.numel() * 4}))
+        return
+
+    if args.hbm_replica:
+        from paper_2210_05064_amd import hbm_replica
+        only = None if args.hbm_replica == "all" else args.hbm_replica.split(",")
+        print(json.dumps({"hbm_replica": hbm_replica.run(seed=args.seed + 3000, reps=max(1, args.steps) * 2, only=only)}))
         return
 
     w = wl.WORKLOADS[args.workload]

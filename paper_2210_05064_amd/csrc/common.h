@@ -56,6 +56,23 @@ __device__ __forceinline__ int segment_of(const int32_t* __restrict__ off, int n
     return lo;
 }
 
+// Largest e in [0, n) with off[e] <= k (off non-decreasing, off[0] <= k), found by the whole wave: every
+// round the 64 lanes probe 64 evenly spaced offsets and a ballot keeps one interval (4 dependent loads for a
+// million environments instead of 20).
+__device__ __forceinline__ int segment_of_wave(const int32_t* __restrict__ off, int n, int k) {
+    const int lane = threadIdx.x & (VER_WAVE - 1);
+    int lo = 0, hi = n;
+    while (hi - lo > 1) {
+        const int step = (hi - lo + VER_WAVE - 1) / VER_WAVE;
+        const int p = lo + lane * step;
+        const bool le = p < hi && off[p] <= k;
+        const int c = max(1, (int)__popcll(__ballot(le)));   // lanes 0 .. c-1 (lane 0 probes lo, which holds by the invariant)
+        lo += (c - 1) * step;
+        hi = min(hi, lo + step);
+    }
+    return lo;
+}
+
 // Fills n 32-bit words with v (used instead of memset nodes so that callers may
 // capture the stream into a graph).
 __global__ void fill_words_kernel(int32_t* p, size_t n, int32_t v);

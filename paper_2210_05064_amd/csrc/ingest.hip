@@ -36,7 +36,9 @@ constexpr int ING_TILE = ING_THREADS * ING_ITEMS;     // slots per workgroup
 constexpr int ING_MAX_BITS = 10;
 constexpr int ING_MAX_BINS = 1 << ING_MAX_BITS;
 constexpr int ING_SCAN_THREADS = 1024;
-constexpr int ING_MAX_S = 1 << 24;   // slots per call (keeps the single-workgroup scan of the counters short)
+constexpr int ING_MAX_S = 1 << 24;   // slots per call
+constexpr int ING_SCAN_CHUNK = 4096;            // counters per workgroup of the two-level scan
+constexpr int ING_SCAN_DIRECT = 4 * ING_SCAN_CHUNK;   // up to here one workgroup scans all counters by itself
 
 // Sort key of arrival slot a in the first pass: the environment id, or N for an id outside [0, N).
 __device__ __forceinline__ int key_of_env(int e, int N) { return (unsigned)e < (unsigned)N ? e : N; }
@@ -86,11 +88,45 @@ __global__ __launch_bounds__(ING_SCAN_THREADS) void ingest_scan_kernel(int32_t* 
     }
 }
 
+// Two-level scan for many counters: every workgroup scans its own chunk of ING_SCAN_CHUNK counters in place
+// (exclusive) and leaves the chunk's total in sums[chunk]; ingest_scan_kernel then scans the totals, and the
+// scatter adds sums[i / ING_SCAN_CHUNK] to counter i when it reads it.
+__global__ __launch_bounds__(ING_THREADS) void ingest_scan_chunks_kernel(int32_t* __restrict__ hist, int n,
+                                                                         int32_t* __restrict__ sums) {
+    constexpr int PER = ING_SCAN_CHUNK / ING_THREADS;
+    __shared__ int wsum[ING_WAVES];
+    const int lane = threadIdx.x & (VER_WAVE - 1), wave = threadIdx.x / VER_WAVE;
+    const int lo = blockIdx.x * ING_SCAN_CHUNK + threadIdx.x * PER;
+    int c[PER], s = 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        c[i] = lo + i < n ? hist[lo + i] : 0;
+        s += c[i];
+    }
+    int incl = s;
+#pragma unroll
+    for (int d = 1; d < VER_WAVE; d <<= 1) {
+        const int up = __shfl_up(incl, d, VER_WAVE);
+        if (lane >= d) incl += up;
+    }
+    if (lane == VER_WAVE - 1) wsum[wave] = incl;
+    __syncthreads();
+    int run = incl - s;
+    for (int w = 0; w < wave; ++w) run += wsum[w];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        if (lo + i < n) hist[lo + i] = run;
+        run += c[i];
+    }
+    if (threadIdx.x == ING_THREADS - 1) sums[blockIdx.x] = run;
+}
+
 // Stable scatter of one tile.  Wave w ranks the contiguous slots [tile*TILE + w*WAVE_RUN, +WAVE_RUN) in rounds of
 // 64; wcnt[w][d] is the number of slots with digit d the wave has seen so far.
 __global__ __launch_bounds__(ING_THREADS) void ingest_scatter_kernel(
     const int32_t* __restrict__ keys, const int32_t* __restrict__ vals, int S, int N, int first, int shift, int bits, int tiles,
-    const int32_t* __restrict__ gbase, int32_t* __restrict__ keys_out, int32_t* __restrict__ vals_out) {
+    const int32_t* __restrict__ gbase, const int32_t* __restrict__ sums, int32_t* __restrict__ keys_out,
+    int32_t* __restrict__ vals_out) {
     __shared__ int wcnt[ING_WAVES][ING_MAX_BINS];
     const int bins = 1 << bits, tile = blockIdx.x;
     const int lane = threadIdx.x & (VER_WAVE - 1), wave = threadIdx.x / VER_WAVE;
@@ -123,7 +159,8 @@ __global__ __launch_bounds__(ING_THREADS) void ingest_scatter_kernel(
     __syncthreads();
     // wcnt[w][d] <- first output position of the wave's slots with digit d
     for (int d = threadIdx.x; d < bins; d += ING_THREADS) {
-        int pos = gbase[(size_t)d * tiles + tile];
+        const size_t at = (size_t)d * tiles + tile;
+        int pos = gbase[at] + (sums ? sums[at / ING_SCAN_CHUNK] : 0);
         for (int w = 0; w < ING_WAVES; ++w) {
             const int c = wcnt[w][d];
             wcnt[w][d] = pos;
@@ -188,7 +225,7 @@ inline int bits_for(int n) {   // bits needed to write the value n
 
 struct IngestPlan {
     int tiles, passes, bits[4];
-    size_t hist_words;
+    size_t hist_words, sum_words;
 };
 
 inline IngestPlan ingest_plan(int N, int S) {
@@ -202,6 +239,7 @@ inline IngestPlan ingest_plan(int N, int S) {
         left -= p.bits[i];
     }
     p.hist_words = (size_t)ING_MAX_BINS * (size_t)(p.tiles > 0 ? p.tiles : 1);
+    p.sum_words = p.hist_words / ING_SCAN_CHUNK + 1;
     return p;
 }
 
@@ -212,7 +250,7 @@ extern "C" size_t ver_ingest_workspace_bytes(int32_t N, int32_t S) {
     if (N <= 0 || S < 0 || S > ver::ING_MAX_S) return 0;
     const ver::IngestPlan p = ver::ingest_plan(N, S);
     const size_t per = ver::align_up((size_t)(S > 0 ? S : 1) * 4, 256);
-    return 3 * per + ver::align_up(p.hist_words * 4, 256);
+    return 3 * per + ver::align_up(p.hist_words * 4, 256) + ver::align_up(p.sum_words * 4, 256);
 }
 
 extern "C" int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t N, int32_t S, int32_t* env_off,
@@ -234,6 +272,7 @@ extern "C" int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t 
     int32_t* key_buf[2] = {cv.take<int32_t>(S), cv.take<int32_t>(S)};
     int32_t* val_tmp = cv.take<int32_t>(S);
     int32_t* hist = cv.take<int32_t>(p.hist_words);
+    int32_t* sums = cv.take<int32_t>(p.sum_words);
     // slots ping-pong between `order` and val_tmp so that the last pass writes `order`
     const int32_t* keys_in = arr_env;
     const int32_t* vals_in = nullptr;
@@ -244,9 +283,17 @@ extern "C" int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t 
         int32_t* vals_out = ((p.passes - 1 - pass) & 1) ? val_tmp : order;
         hipLaunchKernelGGL(ingest_hist_kernel, dim3(p.tiles), dim3(ING_THREADS), 0, s, keys_in, S, N, first, shift, bits,
                            p.tiles, hist);
-        hipLaunchKernelGGL(ingest_scan_kernel, dim3(1), dim3(ING_SCAN_THREADS), 0, s, hist, (1 << bits) * p.tiles);
+        const int counters = (1 << bits) * p.tiles;
+        const bool two_level = counters > ING_SCAN_DIRECT;
+        if (two_level) {
+            const int chunks = (counters + ING_SCAN_CHUNK - 1) / ING_SCAN_CHUNK;
+            hipLaunchKernelGGL(ingest_scan_chunks_kernel, dim3(chunks), dim3(ING_THREADS), 0, s, hist, counters, sums);
+            hipLaunchKernelGGL(ingest_scan_kernel, dim3(1), dim3(ING_SCAN_THREADS), 0, s, sums, chunks);
+        } else {
+            hipLaunchKernelGGL(ingest_scan_kernel, dim3(1), dim3(ING_SCAN_THREADS), 0, s, hist, counters);
+        }
         hipLaunchKernelGGL(ingest_scatter_kernel, dim3(p.tiles), dim3(ING_THREADS), 0, s, keys_in, vals_in, S, N, first,
-                           shift, bits, p.tiles, hist, keys_out, vals_out);
+                           shift, bits, p.tiles, hist, two_level ? sums : (const int32_t*)nullptr, keys_out, vals_out);
         keys_in = keys_out;
         vals_in = vals_out;
         shift += bits;

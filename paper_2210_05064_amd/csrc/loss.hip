@@ -9,12 +9,13 @@
 // read from device memory: the total then carries alpha*(lambda - H) - alpha*H
 // and alpha's gradient lambda - H leaves the kernel with the other scalars.
 //
-// One thread owns a row: it reads the row's head outputs, action, old
-// log-probability, advantage and return once, writes the row's gradients once
-// (56 B/row categorical-4, 156 B/row Gaussian-11: HBM bound).  Sums are reduced
-// wave -> workgroup -> per-workgroup partials in the workspace; the workgroup
-// that finishes last adds the partials in index order, so the result does not
-// depend on scheduling.
+// One thread owns a row: the row's head outputs, action, old log-probability,
+// advantage and return are read once, its gradients written once (56 B/row
+// categorical-4, 156 B/row Gaussian-11: HBM bound); rows of up to 16 head
+// outputs travel through LDS so that memory sees whole contiguous blocks.
+// Sums are reduced wave -> workgroup -> per-workgroup partials in the
+// workspace; the workgroup that finishes last adds the partials in index
+// order, so the result does not depend on scheduling.
 #include "common.h"
 
 namespace ver {
@@ -44,7 +45,14 @@ __device__ __forceinline__ float block_sum(float v, float* s_red) {
     return t;
 }
 
-template <int DIST>
+constexpr int LOSS_STAGE_MAX_A = 16;   // widest row that is staged through LDS
+
+// STAGED: the workgroup's 256 rows of head outputs (and Gaussian actions) are contiguous in memory: they are
+// copied into LDS with consecutive lanes on consecutive words, every thread then works on its own row there
+// (row pitch A words), writes the row's gradient over the head outputs it has consumed, and the block is
+// copied out the same way.  Read row by row straight from memory, a wave instruction would touch 64 rows
+// A*4 bytes apart.
+template <int DIST, bool STAGED>
 __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     ver_ppo_cfg cfg, int M, const float* __restrict__ u, const float* __restrict__ value,
     const float* __restrict__ log_std, const void* __restrict__ actions,
@@ -55,11 +63,15 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     float* __restrict__ d_alpha) {
     __shared__ float s_red[LOSS_THREADS / VER_WAVE];
     __shared__ float s_ls[64], s_inv_sigma[64];
+    __shared__ float s_lsacc[LOSS_THREADS / VER_WAVE][64];   // per wave: running sums of the log-std gradient
+    __shared__ float s_u[STAGED ? LOSS_THREADS * LOSS_STAGE_MAX_A : 1];
+    __shared__ float s_a[STAGED && DIST == 1 ? LOSS_THREADS * LOSS_STAGE_MAX_A : 1];
     __shared__ int s_last;
-    __shared__ float s_hand, s_out[LOSS_SCALARS];
+    __shared__ float s_out[LOSS_SCALARS];
     const int A = cfg.act_dim;
     const int width = LOSS_SCALARS + (DIST == 1 ? A : 0);  // partial sums per workgroup
     const float inv_m = 1.f / (float)M;
+    const int lane = threadIdx.x & (VER_WAVE - 1), wave = threadIdx.x / VER_WAVE;
     // entropy coefficient: the fixed one, or the current value of the learned one (a constant for the policy)
     const float ent_coef = alpha ? alpha[0] : cfg.entropy_coef;
     if (DIST == 1) {
@@ -67,20 +79,32 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
             s_ls[threadIdx.x] = log_std[threadIdx.x];
             s_inv_sigma[threadIdx.x] = expf(-log_std[threadIdx.x]);
         }
+        for (int i = threadIdx.x; i < (LOSS_THREADS / VER_WAVE) * 64; i += LOSS_THREADS) (&s_lsacc[0][0])[i] = 0.f;
         __syncthreads();
     }
 
     float acc[LOSS_SCALARS] = {0.f, 0.f, 0.f, 0.f, 0.f};
     const int stride = gridDim.x * LOSS_THREADS;
-    // Rows are visited in rounds so that the Gaussian log-std sums can be reduced round by round.
     const int rounds = (M + stride - 1) / stride;
     float* my_partial = partials + (size_t)blockIdx.x * width;
-    float ls_acc = 0.f;  // thread d < A of the workgroup accumulates dimension d
     for (int round = 0; round < rounds; ++round) {
-        const int p = round * stride + blockIdx.x * LOSS_THREADS + threadIdx.x;
+        const int p0 = round * stride + blockIdx.x * LOSS_THREADS;
+        const int p = p0 + threadIdx.x;
         const bool live = p < M;
+        const int words = max(0, min(LOSS_THREADS, M - p0)) * A;   // the block's rows, as words
+        if (STAGED) {
+            if (round > 0) __syncthreads();   // the previous block has been copied out
+            for (int i = threadIdx.x; i < words; i += LOSS_THREADS) {
+                s_u[i] = u[(size_t)p0 * A + i];
+                if (DIST == 1) s_a[i] = static_cast<const float*>(actions)[(size_t)p0 * A + i];
+            }
+            __syncthreads();
+        }
         float coef_logp = 0.f, coef_ent = 0.f;
-        const float* up = u + (size_t)(live ? p : 0) * A;
+        const float* up = STAGED ? s_u + threadIdx.x * A : u + (size_t)(live ? p : 0) * A;
+        float* dp = STAGED ? s_u + threadIdx.x * A : d_u + (size_t)(live ? p : 0) * A;
+        const float* ap = nullptr;
+        if (DIST == 1) ap = STAGED ? s_a + threadIdx.x * A : static_cast<const float*>(actions) + (size_t)(live ? p : 0) * A;
         if (live) {
             const float w = is_weight ? is_weight[p] : 1.f;
             float logp, ent;
@@ -103,8 +127,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
                 const float s2 = fminf(fmaxf(rho, 1.f - cfg.clip), 1.f + cfg.clip) * adv_p;
                 coef_logp = (s1 <= s2) ? -w * adv_p * rho * inv_m : 0.f;
                 coef_ent = -ent_coef * w * inv_m;
-                float* dp = d_u + (size_t)p * A;
-                for (int j = 0; j < A; ++j) {
+                for (int j = 0; j < A; ++j) {   // (a staged row is overwritten in place: up[j] is read first)
                     const float lq = up[j] - lse;
                     const float q = expf(lq);
                     dp[j] = coef_logp * ((j == a ? 1.f : 0.f) - q) - coef_ent * q * (lq + ent);
@@ -113,7 +136,6 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
                 acc[3] += logp_old[p] - logp;
                 acc[4] += (fabsf(rho - 1.f) > cfg.clip) ? 1.f : 0.f;
             } else {
-                const float* ap = static_cast<const float*>(actions) + (size_t)p * A;
                 logp = 0.f;
                 ent = 0.f;
                 for (int d = 0; d < A; ++d) {
@@ -127,9 +149,6 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
                 const float s2 = fminf(fmaxf(rho, 1.f - cfg.clip), 1.f + cfg.clip) * adv_p;
                 coef_logp = (s1 <= s2) ? -w * adv_p * rho * inv_m : 0.f;
                 coef_ent = -ent_coef * w * inv_m;
-                float* dp = d_u + (size_t)p * A;
-                for (int d = 0; d < A; ++d)
-                    dp[d] = coef_logp * (ap[d] - up[d]) * s_inv_sigma[d] * s_inv_sigma[d];
                 acc[0] += -w * fminf(s1, s2);
                 acc[3] += logp_old[p] - logp;
                 acc[4] += (fabsf(rho - 1.f) > cfg.clip) ? 1.f : 0.f;
@@ -140,26 +159,36 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
             d_value[p] = cfg.value_coef * w * dv * inv_m;
         }
         if (DIST == 1) {
-            // d total / d log_std[d] = sum_rows coef_logp * (zed^2 - 1) + coef_ent
-            const float* ap = static_cast<const float*>(actions) + (size_t)(live ? p : 0) * A;
+            // gradient of the mean, and d total / d log_std[d] = sum_rows coef_logp * (zed^2 - 1) + coef_ent: summed
+            // over the wave's rows with shuffles and added to the wave's own running sum (fixed order)
             for (int d = 0; d < A; ++d) {
                 float term = 0.f;
                 if (live) {
-                    const float zed = (ap[d] - up[d]) * s_inv_sigma[d];
+                    const float diff = ap[d] - up[d], zed = diff * s_inv_sigma[d];
                     term = coef_logp * (zed * zed - 1.f) + coef_ent;
+                    dp[d] = coef_logp * diff * s_inv_sigma[d] * s_inv_sigma[d];
                 }
-                const float t = block_sum(term, s_red);
-                if (threadIdx.x == 0) s_hand = t;
-                __syncthreads();
-                if (threadIdx.x == d) ls_acc += s_hand;
+                const float t = wave_sum(term);
+                if (lane == 0) s_lsacc[wave][d] += t;
             }
+        }
+        if (STAGED) {
+            __syncthreads();
+            for (int i = threadIdx.x; i < words; i += LOSS_THREADS) d_u[(size_t)p0 * A + i] = s_u[i];
         }
     }
     for (int q = 0; q < LOSS_SCALARS; ++q) {
         const float t = block_sum(acc[q], s_red);
         if (threadIdx.x == 0) my_partial[q] = t;
     }
-    if (DIST == 1 && threadIdx.x < A) my_partial[LOSS_SCALARS + threadIdx.x] = ls_acc;
+    if (DIST == 1) {
+        __syncthreads();
+        if (threadIdx.x < A) {
+            float t = 0.f;
+            for (int w = 0; w < LOSS_THREADS / VER_WAVE; ++w) t += s_lsacc[w][threadIdx.x];
+            my_partial[LOSS_SCALARS + threadIdx.x] = t;
+        }
+    }
 
     // Last workgroup to arrive adds the partials in index order.
     __threadfence();
@@ -226,14 +255,17 @@ int ppo_loss_launch(const ver_ppo_cfg* cfg, int32_t M, const float* head_out, co
     fill_words(counter, 1, 0, s);
     const int blocks = loss_blocks(M);
     ProfScope prof(VER_PROF_LOSS, s);
-    if (cfg->dist == 0)
-        hipLaunchKernelGGL(ppo_loss_kernel<0>, dim3(blocks), dim3(LOSS_THREADS), 0, s, *cfg, M, head_out,
-                           value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out,
-                           d_value, d_log_std, partials, counter, alpha, target_entropy, alpha_sign, d_alpha);
-    else
-        hipLaunchKernelGGL(ppo_loss_kernel<1>, dim3(blocks), dim3(LOSS_THREADS), 0, s, *cfg, M, head_out,
-                           value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out,
-                           d_value, d_log_std, partials, counter, alpha, target_entropy, alpha_sign, d_alpha);
+    const bool staged = cfg->act_dim <= LOSS_STAGE_MAX_A;
+#define VER_LOSS_LAUNCH(DIST, STAGED)                                                                                  \
+    hipLaunchKernelGGL((ppo_loss_kernel<DIST, STAGED>), dim3(blocks), dim3(LOSS_THREADS), 0, s, *cfg, M, head_out,      \
+                       value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out, d_value,    \
+                       d_log_std, partials, counter, alpha, target_entropy, alpha_sign, d_alpha)
+    if (cfg->dist == 0) {
+        if (staged) VER_LOSS_LAUNCH(0, true); else VER_LOSS_LAUNCH(0, false);
+    } else {
+        if (staged) VER_LOSS_LAUNCH(1, true); else VER_LOSS_LAUNCH(1, false);
+    }
+#undef VER_LOSS_LAUNCH
     return launch_status();
 }
 }  // namespace

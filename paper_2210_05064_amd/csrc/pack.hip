@@ -455,38 +455,72 @@ inline size_t pack_ws_layout(int S, int M, void* base, PackWs* ws) {
 }
 
 // Truncated importance weight of every step (paper section 4 "Training"; appendix hyper-parameter table:
-// importance sampling on, maximum 1.0): w = min(max_is, (S/N) / L_i) for the steps of environment i.  A thread
-// handles IS_ITEMS consecutive steps: one binary search for the first, then a walk over the stretch boundaries
-// (empty stretches are stepped over).  4 bytes written per step; env_off stays in L2.
+// importance sampling on, maximum 1.0): w = min(max_is, (S/N) / L_i) for the steps of environment i.
+// A workgroup writes IS_TILE consecutive steps: two wave-wide searches find the environments of its first and
+// last step, the offsets in between are copied to LDS, and every thread then places its 4 consecutive steps
+// there (a binary search for the first, a walk over the stretch boundaries for the rest; empty stretches are
+// stepped over).  4 bytes written per step, 16 per store.
 constexpr int IS_THREADS = 256;
 constexpr int IS_ITEMS = 4;
+constexpr int IS_TILE = 4096;
+constexpr int IS_WIN = IS_TILE + 2;   // offsets kept in LDS (more only with many empty environments: then memory is searched)
+
+// off[0 .. n_env]: offsets of the tile's environments (off[0] <= first step, off[n_env] > last step).
+template <typename OffPtr>
+__device__ __forceinline__ void is_weight_tile(OffPtr off, int n_env, int k_lo, int S, double share, float max_is,
+                                               float* __restrict__ weight) {
+    for (int r = 0; r < IS_TILE / (IS_THREADS * IS_ITEMS); ++r) {
+        const int k0 = k_lo + (r * IS_THREADS + (int)threadIdx.x) * IS_ITEMS;
+        if (k0 >= S) return;
+        int lo = 0, hi = n_env;   // off[lo] <= k0 < off[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (off[mid] <= k0) lo = mid; else hi = mid;
+        }
+        int env = lo;
+        int end = off[env + 1];
+        float w = fminf(max_is, (float)(share / (double)(end - off[env])));
+        float out[IS_ITEMS];
+#pragma unroll
+        for (int i = 0; i < IS_ITEMS; ++i) {
+            const int k = k0 + i;
+            if (k < S && k >= end) {
+                int begin;
+                do {
+                    begin = end;
+                    end = off[++env + 1];
+                } while (k >= end);
+                w = fminf(max_is, (float)(share / (double)(end - begin)));
+            }
+            out[i] = w;
+        }
+        if (k0 + IS_ITEMS <= S) {
+            *reinterpret_cast<float4*>(weight + k0) = make_float4(out[0], out[1], out[2], out[3]);
+        } else {
+            for (int i = 0; k0 + i < S; ++i) weight[k0 + i] = out[i];
+        }
+    }
+}
 
 __global__ __launch_bounds__(IS_THREADS) void is_weight_kernel(const int32_t* __restrict__ env_off, int N, int S,
                                                                double share, float max_is,
                                                                float* __restrict__ weight) {
-    const int k0 = (blockIdx.x * IS_THREADS + threadIdx.x) * IS_ITEMS;
-    if (k0 >= S) return;
-    int env = segment_of(env_off, N, k0);
-    int end = env_off[env + 1];
-    float w = fminf(max_is, (float)(share / (double)(end - env_off[env])));
-    float out[IS_ITEMS];
-#pragma unroll
-    for (int i = 0; i < IS_ITEMS; ++i) {
-        const int k = k0 + i;
-        if (k < S && k >= end) {
-            int begin;
-            do {
-                begin = end;
-                end = env_off[++env + 1];
-            } while (k >= end);
-            w = fminf(max_is, (float)(share / (double)(end - begin)));
-        }
-        out[i] = w;
+    __shared__ int s_off[IS_WIN];
+    __shared__ int s_env[2];
+    const int k_lo = blockIdx.x * IS_TILE, k_hi = min(S, k_lo + IS_TILE) - 1;
+    const int wave = threadIdx.x / VER_WAVE;
+    if (wave < 2) {
+        const int e = segment_of_wave(env_off, N, wave == 0 ? k_lo : k_hi);
+        if ((threadIdx.x & (VER_WAVE - 1)) == 0) s_env[wave] = e;
     }
-    if (k0 + IS_ITEMS <= S) {
-        *reinterpret_cast<float4*>(weight + k0) = make_float4(out[0], out[1], out[2], out[3]);
+    __syncthreads();
+    const int e0 = s_env[0], n_env = s_env[1] - e0 + 1;
+    if (n_env + 1 <= IS_WIN) {
+        for (int i = threadIdx.x; i <= n_env; i += IS_THREADS) s_off[i] = env_off[e0 + i];
+        __syncthreads();
+        is_weight_tile(static_cast<const int*>(s_off), n_env, k_lo, S, share, max_is, weight);
     } else {
-        for (int i = 0; k0 + i < S; ++i) weight[k0 + i] = out[i];
+        is_weight_tile(env_off + e0, n_env, k_lo, S, share, max_is, weight);
     }
 }
 
@@ -499,7 +533,7 @@ extern "C" int ver_is_weight(const int32_t* env_off, int32_t N, int32_t S, float
     if (S == 0) return VER_OK;
     if (!env_off || !weight || (reinterpret_cast<uintptr_t>(weight) & 15)) return VER_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int per_block = ver::IS_THREADS * ver::IS_ITEMS;
+    const int per_block = ver::IS_TILE;
     ver::ProfScope prof(VER_PROF_IS_WEIGHT, s);
     hipLaunchKernelGGL(ver::is_weight_kernel, dim3((S + per_block - 1) / per_block), dim3(ver::IS_THREADS), 0, s,
                        env_off, N, S, (double)S / (double)N, max_is, weight);
