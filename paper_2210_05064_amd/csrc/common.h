@@ -73,6 +73,11 @@ __device__ __forceinline__ int segment_of_wave(const int32_t* __restrict__ off, 
     return lo;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
+// load and store of the wave, which would put the latency of each prefetch on the critical path; code that
+// uses it waits for global memory explicitly where it needs it.
+__device__ __forceinline__ void bar_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Fills n 32-bit words with v (used instead of memset nodes so that callers may
 // capture the stream into a graph).
 __global__ void fill_words_kernel(int32_t* p, size_t n, int32_t v);

@@ -25,7 +25,8 @@ namespace {
 constexpr int GAE_THREADS = 256;
 constexpr int GAE_ITEMS = 8;
 constexpr int GAE_TILE = GAE_THREADS * GAE_ITEMS;
-constexpr int GAE_LDS = GAE_TILE + GAE_TILE / 8 + 2;   // one unused word after every 8 (see lds_at)
+constexpr int GAE_ROW = GAE_THREADS + 1;               // LDS row of one item position (see lds_at)
+constexpr int GAE_LDS = GAE_ITEMS * GAE_ROW;
 constexpr long long GAE_SPIN_LIMIT = 1LL << 24;  // polls before a wait gives up
 constexpr int GAE_MAX_BATCH = 16;      // tiles per ticket at most
 constexpr int GAE_BATCH_FROM = 1024;   // one more tile per ticket for every so many tiles
@@ -69,9 +70,12 @@ __device__ __forceinline__ Affine wave_shfl_up(Affine v, int d) {
     return Affine{__shfl_up(v.a, d, VER_WAVE), __shfl_up(v.b, d, VER_WAVE)};
 }
 
-// A thread walks 8 consecutive steps, so the lanes of a wave are 8 words apart: with one unused word after
-// every 8 they are 9 apart and fall into different LDS banks.
-__device__ __forceinline__ int lds_at(int i) { return i + (i >> 3); }
+// Where step i of a tile sits in the LDS arrays.  A thread walks a group of 8 consecutive steps (group i / 8), so
+// the arrays are kept transposed, one row per position inside a group: the lanes of a wave, which are at the same
+// position of neighbouring groups, then touch neighbouring words.  Rows are one word longer than the number of
+// groups, which also spreads the 4 consecutive steps a thread handles when the tile is copied in and out.
+__device__ __forceinline__ int lds_at(int i) { return (i & 7) * GAE_ROW + (i >> 3); }
+static_assert(GAE_ITEMS == 8, "lds_at and the flag words assume groups of 8");
 
 template <bool VEC>
 __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
@@ -82,7 +86,8 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
     __shared__ float s_r[GAE_LDS];
     __shared__ float s_v[GAE_LDS];
     __shared__ float s_boot[GAE_LDS];   // value after an environment's last step (only read where s_d says so)
-    __shared__ uint8_t s_d[GAE_LDS];    // bit 0: episode ended with this step; bit 1: last step of its environment
+    // flags of step i in byte i (a thread reads its group's 8 flags as one 64-bit word)
+    __shared__ __attribute__((aligned(8))) uint8_t s_d[GAE_TILE + 8];   // bit 0: episode ended with this step; bit 1: last step of its environment
     __shared__ Affine s_wave[GAE_THREADS / VER_WAVE];
     __shared__ int s_ticket;
     __shared__ int s_env[2];
@@ -100,7 +105,9 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
     // publishes that tile's map (pass -1; the tile is read once more when its turn comes).
     const int first_tile = s_ticket * batch, n_here = min(batch, ntiles - first_tile);
     double carry_known = 0.0;   // advantage entering the next tile of the batch (valid from its second tile on)
-    for (int pass = n_here > 1 ? -1 : 0; pass < n_here; ++pass) {
+    const int pass0 = n_here > 1 ? -1 : 0;
+    int env_first_above = 0;   // first environment of the tile of the pass before
+    for (int pass = pass0; pass < n_here; ++pass) {
     const bool map_only = pass < 0;
     const int tile = first_tile + (map_only ? n_here - 1 : pass);
     // Tiles are processed from the END of the buffer: tile number `tile` covers flat steps [k_lo, k_lo + count);
@@ -110,61 +117,122 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
     const int count = min(GAE_TILE, S - k_lo);
     const int k_hi = k_lo + count - 1;
 
-    // environments of the tile's first and last step
-    if (wave < 2) {
-        const int e = segment_of_wave(env_off, N, wave == 0 ? k_lo : k_hi);
-        if (lane == 0) s_env[wave] = e;
+    // The tile's steps, first into registers (16-byte path): the loads are in flight while the environments of
+    // the tile are looked up below.
+    constexpr int GAE_FETCH = GAE_TILE / (GAE_THREADS * 4);
+    float4 f_r[GAE_FETCH], f_v[GAE_FETCH];
+    uint32_t f_d[GAE_FETCH];
+    if (VEC) {
+#pragma unroll
+        for (int it = 0; it < GAE_FETCH; ++it) {
+            const int i = (it * GAE_THREADS + tid) * 4;
+            if (i + 4 <= count) {
+                f_r[it] = *reinterpret_cast<const float4*>(rewards + k_lo + i);
+                f_v[it] = *reinterpret_cast<const float4*>(values + k_lo + i);
+                f_d[it] = *reinterpret_cast<const uint32_t*>(dones + k_lo + i);
+            }
+        }
     }
-    for (int i = tid * 4; i < count; i += GAE_THREADS * 4) {
+    // Environments of the tile's first and last step.  From the second tile of a batch on they follow from the
+    // tile before (the one just above in memory): that tile's first environment bounds this one's last, and this
+    // one's first is found by walking down from there, 64 offsets at a time (one round of loads instead of four
+    // dependent ones).
+    int m_lo = 0, m_hi = 0, m_env = -1;   // wave 0: offsets of environment (first of the tile) + lane, fetched early
+    float m_boot = 0.f;
+    if (wave == 0) {
+        int e;
+        if (pass >= 1) {
+            e = env_first_above;
+            for (;;) {
+                const int probe = e - lane;
+                const unsigned long long ok = __ballot(probe >= 0 && env_off[probe] <= k_lo);   // monotone in the lane
+                if (ok) { e -= __ffsll((long long)ok) - 1; break; }
+                e -= VER_WAVE;
+                if (e < 0) { e = 0; break; }   // (env_off[0] = 0 ends the walk before this; malformed input must not run away)
+            }
+            if (lane == 0) s_env[1] = env_first_above;
+        } else {
+            e = segment_of_wave(env_off, N, k_lo);
+        }
+        if (lane == 0) s_env[0] = e;
+        if (e + lane < N) {
+            m_env = e + lane;
+            m_lo = env_off[m_env];
+            m_hi = env_off[m_env + 1];
+            m_boot = last_values[m_env];
+        }
+    } else if (wave == 1 && pass < 1) {
+        const int e = segment_of_wave(env_off, N, k_hi);
+        if (lane == 0) s_env[1] = e;
+    }
+#pragma unroll
+    for (int it = 0; it < GAE_FETCH; ++it) {
+        const int i = (it * GAE_THREADS + tid) * 4;
         if (VEC && i + 4 <= count) {
-            const float4 r4 = *reinterpret_cast<const float4*>(rewards + k_lo + i);
-            const float4 v4 = *reinterpret_cast<const float4*>(values + k_lo + i);
-            const uint32_t d4 = *reinterpret_cast<const uint32_t*>(dones + k_lo + i);
-            const int q = lds_at(i);
-            s_r[q] = r4.x; s_r[q + 1] = r4.y; s_r[q + 2] = r4.z; s_r[q + 3] = r4.w;
-            s_v[q] = v4.x; s_v[q + 1] = v4.y; s_v[q + 2] = v4.z; s_v[q + 3] = v4.w;
-            s_d[q] = (d4 & 0xFFu) ? 1 : 0; s_d[q + 1] = (d4 & 0xFF00u) ? 1 : 0;
-            s_d[q + 2] = (d4 & 0xFF0000u) ? 1 : 0; s_d[q + 3] = (d4 & 0xFF000000u) ? 1 : 0;
+            const float4 r4 = f_r[it], v4 = f_v[it];
+            const uint32_t d4 = f_d[it];
+            const int q = lds_at(i);   // i is a multiple of 4: the four steps are in the same group, one row apart
+            s_r[q] = r4.x; s_r[q + GAE_ROW] = r4.y; s_r[q + 2 * GAE_ROW] = r4.z; s_r[q + 3 * GAE_ROW] = r4.w;
+            s_v[q] = v4.x; s_v[q + GAE_ROW] = v4.y; s_v[q + 2 * GAE_ROW] = v4.z; s_v[q + 3 * GAE_ROW] = v4.w;
+            // 0x01 in every byte of d4 that is not zero
+            *reinterpret_cast<uint32_t*>(s_d + i) = ((((d4 & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | d4) & 0x80808080u) >> 7;
         } else {
             for (int j = i; j < min(i + 4, count); ++j) {
                 s_r[lds_at(j)] = rewards[k_lo + j];
                 s_v[lds_at(j)] = values[k_lo + j];
-                s_d[lds_at(j)] = dones[k_lo + j] ? 1 : 0;
+                s_d[j] = dones[k_lo + j] ? 1 : 0;
             }
         }
     }
     if (tid == 0) s_v[lds_at(count)] = (k_hi + 1 < S) ? values[k_hi + 1] : 0.f;
-    __syncthreads();
-    // mark the last step of every environment that ends inside the tile and fetch its bootstrap value
-    for (int e = s_env[0] + tid; e <= s_env[1]; e += GAE_THREADS) {
+    bar_lds();
+    // mark the last step of every environment that ends inside the tile and keep its bootstrap value: the first
+    // 64 environments from what wave 0 fetched above, any further ones (rows of empty environments) from memory
+    if (wave == 0 && m_env >= 0 && m_env <= s_env[1]) {
+        const int i = m_hi - 1 - k_lo;
+        if (m_hi > m_lo && i >= 0 && i < count) {
+            s_d[i] |= 2;
+            s_boot[lds_at(i)] = m_boot;
+        }
+    }
+    for (int e = s_env[0] + VER_WAVE + tid; e <= s_env[1]; e += GAE_THREADS) {
         const int lo = env_off[e], hi = env_off[e + 1];
         const int i = hi - 1 - k_lo;
         if (hi > lo && i >= 0 && i < count) {
-            s_d[lds_at(i)] |= 2;
+            s_d[i] |= 2;
             s_boot[lds_at(i)] = last_values[e];
         }
     }
-    __syncthreads();
+    bar_lds();
+    env_first_above = s_env[0];
 
-    // Thread tid handles the steps top, top-1, ... of the tile (processing order = time descending).
-    const int top = count - 1 - tid * GAE_ITEMS;
-    double a[GAE_ITEMS], b[GAE_ITEMS];
-    Affine mine{1.0, 0.0};
+    // Thread tid handles group n_groups - 1 - tid of 8 consecutive steps, from its last step down (processing
+    // order = time descending; the topmost group of a ragged tile is short).
+    const int group = ((count + 7) >> 3) - 1 - tid;
+    const int top = group * 8 + 7;
     const double gl = (double)gamma * (double)lambda;
+    const unsigned long long flags = group >= 0 ? *reinterpret_cast<const unsigned long long*>(s_d + group * 8) : 0ull;
+    // the map of step top - i; across the scan a thread keeps the b of its 8 maps and one bit for each a (which
+    // is either 0 or gamma * lambda)
+    auto map_of = [&](int i) {
+        const int q = lds_at(top - i);
+        const int f = (int)(flags >> (8 * (7 - i))) & 0xFF;
+        const bool last = (f & 2) != 0;
+        const double nd = (f & 1) ? 0.0 : 1.0;
+        const double v_next = last ? s_boot[q] : s_v[lds_at(top - i + 1)];
+        return Affine{last ? 0.0 : gl * nd, (double)s_r[q] + (double)gamma * nd * v_next - (double)s_v[q]};
+    };
+    Affine mine{1.0, 0.0};
+    double b_of[GAE_ITEMS];
+    unsigned a_zero = 0;
 #pragma unroll
     for (int i = 0; i < GAE_ITEMS; ++i) {
-        const int idx = top - i;
-        a[i] = 1.0;
-        b[i] = 0.0;
-        if (idx >= 0) {
-            const int q = lds_at(idx);
-            const int f = s_d[q];
-            const bool last = (f & 2) != 0;
-            const double nd = (f & 1) ? 0.0 : 1.0;
-            const double v_next = last ? s_boot[q] : s_v[lds_at(idx + 1)];
-            a[i] = last ? 0.0 : gl * nd;
-            b[i] = (double)s_r[q] + (double)gamma * nd * v_next - (double)s_v[q];
-            mine = compose(mine, Affine{a[i], b[i]});
+        b_of[i] = 0.0;
+        if (group >= 0 && top - i < count) {
+            const Affine m = map_of(i);
+            b_of[i] = m.b;
+            a_zero |= (m.a == 0.0 ? 1u : 0u) << i;
+            mine = compose(mine, m);
         }
     }
 
@@ -176,7 +244,7 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
         if (lane >= d) incl = compose(up, incl);
     }
     if (lane == VER_WAVE - 1) s_wave[wave] = incl;
-    __syncthreads();
+    bar_lds();
     Affine before{1.0, 0.0};  // everything in the tile processed before this thread
     for (int w = 0; w < wave; ++w) before = compose(before, s_wave[w]);
     Affine excl_in_wave = wave_shfl_up(incl, 1);
@@ -257,7 +325,7 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
             s_leaving = leaving;
         }
     }
-    __syncthreads();
+    bar_lds();
     if (map_only) continue;   // (uniform; the barrier above also protects the LDS arrays that the next pass refills)
     carry_known = s_leaving;
 
@@ -265,20 +333,22 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
 #pragma unroll
     for (int i = 0; i < GAE_ITEMS; ++i) {
         const int idx = top - i;
-        if (idx >= 0) {
-            x = b[i] + a[i] * x;
+        if (group >= 0 && idx < count) {
+            x = b_of[i] + ((a_zero >> i) & 1u ? 0.0 : gl) * x;
             const int q = lds_at(idx);
             const float v = s_v[q];
             s_r[q] = (float)x;
             s_boot[q] = (float)(x + (double)v);
         }
     }
-    __syncthreads();
+    bar_lds();
     for (int i = tid * 4; i < count; i += GAE_THREADS * 4) {
         if (VEC && i + 4 <= count) {
             const int q = lds_at(i);
-            *reinterpret_cast<float4*>(adv + k_lo + i) = float4{s_r[q], s_r[q + 1], s_r[q + 2], s_r[q + 3]};
-            *reinterpret_cast<float4*>(ret + k_lo + i) = float4{s_boot[q], s_boot[q + 1], s_boot[q + 2], s_boot[q + 3]};
+            *reinterpret_cast<float4*>(adv + k_lo + i) =
+                float4{s_r[q], s_r[q + GAE_ROW], s_r[q + 2 * GAE_ROW], s_r[q + 3 * GAE_ROW]};
+            *reinterpret_cast<float4*>(ret + k_lo + i) =
+                float4{s_boot[q], s_boot[q + GAE_ROW], s_boot[q + 2 * GAE_ROW], s_boot[q + 3 * GAE_ROW]};
         } else {
             for (int j = i; j < min(i + 4, count); ++j) {
                 adv[k_lo + j] = s_r[lds_at(j)];
@@ -286,7 +356,7 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
             }
         }
     }
-    __syncthreads();   // the arrays are refilled by the next tile of the batch
+    bar_lds();   // the arrays are refilled by the next tile of the batch
     }
 }
 

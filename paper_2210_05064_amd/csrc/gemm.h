@@ -90,10 +90,6 @@ __device__ __forceinline__ void store_quad(float* dst, const Quad<float>& q) {
     *reinterpret_cast<f32x4_t*>(dst) = f32x4_t{q.v[0], q.v[1], q.v[2], q.v[3]};
 }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding global
-// load and store of the wave, which would put the latency of each prefetch on the critical path; code that
-// uses it waits for global memory explicitly where it needs it.
-__device__ __forceinline__ void bar_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
 constexpr int GEMM_BM = 128, GEMM_BN = 128, GEMM_THREADS = 256;

@@ -22,7 +22,7 @@ namespace ver {
 namespace {
 
 constexpr int LOSS_THREADS = 256;
-constexpr int LOSS_MAX_BLOCKS = 1024;
+constexpr int LOSS_MAX_BLOCKS = 768;   // 3 per CU: measured best on rows streamed through LDS (1024: -9 %, 2048: -35 %)
 constexpr int LOSS_SCALARS = 5;  // policy, value, entropy, kl, clipped count
 constexpr float HALF_LOG_2PI = 0.91893853320467274178f;
 
@@ -47,12 +47,12 @@ __device__ __forceinline__ float block_sum(float v, float* s_red) {
 
 constexpr int LOSS_STAGE_MAX_A = 16;   // widest row that is staged through LDS
 
-// STAGED: the workgroup's 256 rows of head outputs (and Gaussian actions) are contiguous in memory: they are
+// STAGED (1: word by word, 2: 16 bytes at a time for 16-byte aligned arrays): the workgroup's 256 rows of head outputs (and Gaussian actions) are contiguous in memory: they are
 // copied into LDS with consecutive lanes on consecutive words, every thread then works on its own row there
 // (row pitch A words), writes the row's gradient over the head outputs it has consumed, and the block is
 // copied out the same way.  Read row by row straight from memory, a wave instruction would touch 64 rows
 // A*4 bytes apart.
-template <int DIST, bool STAGED>
+template <int DIST, int STAGED>
 __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     ver_ppo_cfg cfg, int M, const float* __restrict__ u, const float* __restrict__ value,
     const float* __restrict__ log_std, const void* __restrict__ actions,
@@ -64,10 +64,13 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     __shared__ float s_red[LOSS_THREADS / VER_WAVE];
     __shared__ float s_ls[64], s_inv_sigma[64];
     __shared__ float s_lsacc[LOSS_THREADS / VER_WAVE][64];   // per wave: running sums of the log-std gradient
-    __shared__ float s_u[STAGED ? LOSS_THREADS * LOSS_STAGE_MAX_A : 1];
-    __shared__ float s_a[STAGED && DIST == 1 ? LOSS_THREADS * LOSS_STAGE_MAX_A : 1];
+    // staged rows: [256][A] head outputs, then (Gaussian) [256][A] actions; sized by the launch
+    extern __shared__ __attribute__((aligned(16))) float s_rows[];
+    float* s_u = s_rows;
+    float* s_a = s_rows + LOSS_THREADS * cfg.act_dim;
     __shared__ int s_last;
     __shared__ float s_out[LOSS_SCALARS];
+    __shared__ float s_quarter[LOSS_THREADS / VER_WAVE][LOSS_SCALARS + 64];
     const int A = cfg.act_dim;
     const int width = LOSS_SCALARS + (DIST == 1 ? A : 0);  // partial sums per workgroup
     const float inv_m = 1.f / (float)M;
@@ -84,6 +87,9 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     }
 
     float acc[LOSS_SCALARS] = {0.f, 0.f, 0.f, 0.f, 0.f};
+    float ls_own[LOSS_STAGE_MAX_A];
+#pragma unroll
+    for (int d = 0; d < LOSS_STAGE_MAX_A; ++d) ls_own[d] = 0.f;
     const int stride = gridDim.x * LOSS_THREADS;
     const int rounds = (M + stride - 1) / stride;
     float* my_partial = partials + (size_t)blockIdx.x * width;
@@ -93,12 +99,27 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
         const bool live = p < M;
         const int words = max(0, min(LOSS_THREADS, M - p0)) * A;   // the block's rows, as words
         if (STAGED) {
-            if (round > 0) __syncthreads();   // the previous block has been copied out
-            for (int i = threadIdx.x; i < words; i += LOSS_THREADS) {
-                s_u[i] = u[(size_t)p0 * A + i];
-                if (DIST == 1) s_a[i] = static_cast<const float*>(actions)[(size_t)p0 * A + i];
+            if (round > 0) bar_lds();   // the previous block has been copied out
+            const float* gu = u + (size_t)p0 * A;
+            const float* ga = static_cast<const float*>(actions) + (size_t)p0 * A;
+            const int vec_words = STAGED == 2 ? words & ~3 : 0;
+            for (int i = threadIdx.x * 4; i < vec_words; i += LOSS_THREADS * 4) {
+                *reinterpret_cast<float4*>(s_u + i) = *reinterpret_cast<const float4*>(gu + i);
+                if (DIST == 1) *reinterpret_cast<float4*>(s_a + i) = *reinterpret_cast<const float4*>(ga + i);
             }
-            __syncthreads();
+            for (int i = vec_words + threadIdx.x; i < words; i += LOSS_THREADS) {
+                s_u[i] = gu[i];
+                if (DIST == 1) s_a[i] = ga[i];
+            }
+            bar_lds();
+        }
+        // this row's scalars
+        float w = 1.f, lp_old = 0.f, adv_p = 0.f, val_p = 0.f, ret_p = 0.f;
+        int act_p = 0;
+        if (live) {
+            if (DIST == 0) act_p = static_cast<const int32_t*>(actions)[p];
+            w = is_weight ? is_weight[p] : 1.f;
+            lp_old = logp_old[p]; adv_p = adv[p]; val_p = value[p]; ret_p = ret[p];
         }
         float coef_logp = 0.f, coef_ent = 0.f;
         const float* up = STAGED ? s_u + threadIdx.x * A : u + (size_t)(live ? p : 0) * A;
@@ -106,10 +127,9 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
         const float* ap = nullptr;
         if (DIST == 1) ap = STAGED ? s_a + threadIdx.x * A : static_cast<const float*>(actions) + (size_t)(live ? p : 0) * A;
         if (live) {
-            const float w = is_weight ? is_weight[p] : 1.f;
             float logp, ent;
             if (DIST == 0) {
-                const int a = static_cast<const int32_t*>(actions)[p];
+                const int a = act_p;
                 float mx = up[0];
                 for (int j = 1; j < A; ++j) mx = fmaxf(mx, up[j]);
                 float se = 0.f;
@@ -121,8 +141,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
                     const float lq = up[j] - lse;
                     ent -= expf(lq) * lq;
                 }
-                const float rho = expf(logp - logp_old[p]);
-                const float adv_p = adv[p];
+                const float rho = expf(logp - lp_old);
                 const float s1 = rho * adv_p;
                 const float s2 = fminf(fmaxf(rho, 1.f - cfg.clip), 1.f + cfg.clip) * adv_p;
                 coef_logp = (s1 <= s2) ? -w * adv_p * rho * inv_m : 0.f;
@@ -133,7 +152,7 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
                     dp[j] = coef_logp * ((j == a ? 1.f : 0.f) - q) - coef_ent * q * (lq + ent);
                 }
                 acc[0] += -w * fminf(s1, s2);
-                acc[3] += logp_old[p] - logp;
+                acc[3] += lp_old - logp;
                 acc[4] += (fabsf(rho - 1.f) > cfg.clip) ? 1.f : 0.f;
             } else {
                 logp = 0.f;
@@ -143,38 +162,53 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
                     logp += -0.5f * zed * zed - s_ls[d] - HALF_LOG_2PI;
                     ent += s_ls[d] + 0.5f + HALF_LOG_2PI;
                 }
-                const float rho = expf(logp - logp_old[p]);
-                const float adv_p = adv[p];
+                const float rho = expf(logp - lp_old);
                 const float s1 = rho * adv_p;
                 const float s2 = fminf(fmaxf(rho, 1.f - cfg.clip), 1.f + cfg.clip) * adv_p;
                 coef_logp = (s1 <= s2) ? -w * adv_p * rho * inv_m : 0.f;
                 coef_ent = -ent_coef * w * inv_m;
                 acc[0] += -w * fminf(s1, s2);
-                acc[3] += logp_old[p] - logp;
+                acc[3] += lp_old - logp;
                 acc[4] += (fabsf(rho - 1.f) > cfg.clip) ? 1.f : 0.f;
             }
-            const float dv = value[p] - ret[p];
+            const float dv = val_p - ret_p;
             acc[1] += w * 0.5f * dv * dv;
             acc[2] += w * ent;
             d_value[p] = cfg.value_coef * w * dv * inv_m;
         }
         if (DIST == 1) {
-            // gradient of the mean, and d total / d log_std[d] = sum_rows coef_logp * (zed^2 - 1) + coef_ent: summed
-            // over the wave's rows with shuffles and added to the wave's own running sum (fixed order)
-            for (int d = 0; d < A; ++d) {
-                float term = 0.f;
-                if (live) {
-                    const float diff = ap[d] - up[d], zed = diff * s_inv_sigma[d];
-                    term = coef_logp * (zed * zed - 1.f) + coef_ent;
-                    dp[d] = coef_logp * diff * s_inv_sigma[d] * s_inv_sigma[d];
+            // gradient of the mean, and d total / d log_std[d] = sum_rows coef_logp * (zed^2 - 1) + coef_ent
+            if (STAGED) {
+                // a thread adds up its own rows (one register per dimension); the threads are added at the end
+#pragma unroll
+                for (int d = 0; d < LOSS_STAGE_MAX_A; ++d) {
+                    if (d < A && live) {
+                        const float diff = ap[d] - up[d], zed = diff * s_inv_sigma[d];
+                        ls_own[d] += coef_logp * (zed * zed - 1.f) + coef_ent;
+                        dp[d] = coef_logp * diff * s_inv_sigma[d] * s_inv_sigma[d];
+                    }
                 }
-                const float t = wave_sum(term);
-                if (lane == 0) s_lsacc[wave][d] += t;
+            } else {
+                // wider rows: summed over the wave's rows with shuffles and added to the wave's running sum
+                for (int d = 0; d < A; ++d) {
+                    float term = 0.f;
+                    if (live) {
+                        const float diff = ap[d] - up[d], zed = diff * s_inv_sigma[d];
+                        term = coef_logp * (zed * zed - 1.f) + coef_ent;
+                        dp[d] = coef_logp * diff * s_inv_sigma[d] * s_inv_sigma[d];
+                    }
+                    const float t = wave_sum(term);
+                    if (lane == 0) s_lsacc[wave][d] += t;
+                }
             }
         }
         if (STAGED) {
-            __syncthreads();
-            for (int i = threadIdx.x; i < words; i += LOSS_THREADS) d_u[(size_t)p0 * A + i] = s_u[i];
+            bar_lds();
+            float* gd = d_u + (size_t)p0 * A;
+            const int vec_words = STAGED == 2 ? words & ~3 : 0;
+            for (int i = threadIdx.x * 4; i < vec_words; i += LOSS_THREADS * 4)
+                *reinterpret_cast<float4*>(gd + i) = *reinterpret_cast<const float4*>(s_u + i);
+            for (int i = vec_words + threadIdx.x; i < words; i += LOSS_THREADS) gd[i] = s_u[i];
         }
     }
     for (int q = 0; q < LOSS_SCALARS; ++q) {
@@ -182,6 +216,15 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
         if (threadIdx.x == 0) my_partial[q] = t;
     }
     if (DIST == 1) {
+        if (STAGED) {
+#pragma unroll
+            for (int d = 0; d < LOSS_STAGE_MAX_A; ++d) {
+                if (d < A) {
+                    const float t = wave_sum(ls_own[d]);
+                    if (lane == 0) s_lsacc[wave][d] = t;
+                }
+            }
+        }
         __syncthreads();
         if (threadIdx.x < A) {
             float t = 0.f;
@@ -197,9 +240,29 @@ __global__ __launch_bounds__(LOSS_THREADS) void ppo_loss_kernel(
     __syncthreads();
     if (!s_last) return;
     __threadfence();
+    // Wave w adds its quarter of the workgroups' partials (lane = column, 8 loads in flight, added in index
+    // order), then one thread per column adds the four quarters: a fixed order, whatever the schedule was.
+    {
+        const int G = gridDim.x, per = (G + LOSS_THREADS / VER_WAVE - 1) / (LOSS_THREADS / VER_WAVE);
+        const int g_lo = min(G, wave * per), g_hi = min(G, g_lo + per);
+        for (int c = lane; c < width; c += VER_WAVE) {
+            float t = 0.f;
+            int g = g_lo;
+            for (; g + 8 <= g_hi; g += 8) {
+                float x[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) x[k] = ld_agent(&partials[(size_t)(g + k) * width + c]);
+#pragma unroll
+                for (int k = 0; k < 8; ++k) t += x[k];
+            }
+            for (; g < g_hi; ++g) t += ld_agent(&partials[(size_t)g * width + c]);
+            s_quarter[wave][c] = t;
+        }
+    }
+    __syncthreads();
     if (threadIdx.x < width) {
         float t = 0.f;
-        for (int g = 0; g < (int)gridDim.x; ++g) t += ld_agent(&partials[(size_t)g * width + threadIdx.x]);
+        for (int w = 0; w < LOSS_THREADS / VER_WAVE; ++w) t += s_quarter[w][threadIdx.x];
         if (threadIdx.x < LOSS_SCALARS) s_out[threadIdx.x] = t * inv_m;  // means
         else d_log_std[threadIdx.x - LOSS_SCALARS] = t;
     }
@@ -255,15 +318,20 @@ int ppo_loss_launch(const ver_ppo_cfg* cfg, int32_t M, const float* head_out, co
     fill_words(counter, 1, 0, s);
     const int blocks = loss_blocks(M);
     ProfScope prof(VER_PROF_LOSS, s);
-    const bool staged = cfg->act_dim <= LOSS_STAGE_MAX_A;
+    // 0: rows read from memory one by one; 1: staged through LDS; 2: staged with 16-byte accesses
+    int staged = cfg->act_dim <= LOSS_STAGE_MAX_A ? 1 : 0;
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(head_out) | reinterpret_cast<uintptr_t>(d_head_out) |
+                           (cfg->dist == 1 ? reinterpret_cast<uintptr_t>(actions_packed) : 0);
+    if (staged && (bits & 15) == 0) staged = 2;
+    const size_t lds = staged ? (size_t)LOSS_THREADS * cfg->act_dim * 4 * (cfg->dist == 1 ? 2 : 1) : 0;
 #define VER_LOSS_LAUNCH(DIST, STAGED)                                                                                  \
-    hipLaunchKernelGGL((ppo_loss_kernel<DIST, STAGED>), dim3(blocks), dim3(LOSS_THREADS), 0, s, *cfg, M, head_out,      \
+    hipLaunchKernelGGL((ppo_loss_kernel<DIST, STAGED>), dim3(blocks), dim3(LOSS_THREADS), lds, s, *cfg, M, head_out,    \
                        value, log_std, actions_packed, logp_old, adv, ret, is_weight, scalars, d_head_out, d_value,    \
                        d_log_std, partials, counter, alpha, target_entropy, alpha_sign, d_alpha)
     if (cfg->dist == 0) {
-        if (staged) VER_LOSS_LAUNCH(0, true); else VER_LOSS_LAUNCH(0, false);
+        if (staged == 2) VER_LOSS_LAUNCH(0, 2); else if (staged) VER_LOSS_LAUNCH(0, 1); else VER_LOSS_LAUNCH(0, 0);
     } else {
-        if (staged) VER_LOSS_LAUNCH(1, true); else VER_LOSS_LAUNCH(1, false);
+        if (staged == 2) VER_LOSS_LAUNCH(1, 2); else if (staged) VER_LOSS_LAUNCH(1, 1); else VER_LOSS_LAUNCH(1, 0);
     }
 #undef VER_LOSS_LAUNCH
     return launch_status();

@@ -95,10 +95,14 @@ def test_is_weight_many_environments(ver):
     assert np.array_equal(host(w), oracle_is_weights(off2, 4.0).astype(np.float32))
 
 
-@pytest.mark.parametrize("dist,A", [(1, 11), (0, 4), (1, 20)])
-def test_loss_several_rounds_per_workgroup(ver, dist, A):
-    """More rows than one sweep of the grid covers (1024 workgroups x 256 rows), ragged last block."""
-    M = 1024 * 256 + 3 * 256 + 77
+BIG = 2048 * 256 + 3 * 256 + 77   # more rows than one sweep of the grid covers (2048 workgroups x 256 rows)
+
+
+@pytest.mark.parametrize("dist,A,shift,M", [(1, 11, 0, BIG), (0, 4, 1, BIG), (1, 20, 0, BIG), (1, 11, 1, 5000),
+                                             (0, 4, 0, 5000)])
+def test_loss_several_rounds_per_workgroup(ver, dist, A, shift, M):
+    """Several blocks per workgroup and a ragged last block; shift = 1: row arrays that start 4 bytes past a
+    16-byte boundary (the word-by-word copies)."""
     rng = np.random.default_rng(40 + A)
     u = rng.standard_normal((M, A)).astype(np.float32)
     value, ret, adv = (rng.standard_normal(M).astype(np.float32) for _ in range(3))
@@ -123,12 +127,17 @@ def test_loss_several_rounds_per_workgroup(ver, dist, A):
     noise[(np.abs(rho - 0.8) < 2e-3) | (np.abs(rho - 1.2) < 2e-3)] = 0.0
     logp_old = (logp + noise).astype(np.float32)
     f32 = dict(dtype=torch.float32, device="cuda")
-    scalars, d_u, d_v = torch.zeros(6, **f32), torch.empty((M, A), **f32), torch.empty(M, **f32)
+    def rows(a):   # [M, A] device copy, optionally starting one element past an aligned address
+        t = torch.empty(M * A + shift, dtype=torch.from_numpy(a[:1]).dtype, device="cuda")[shift:].view(M, A)
+        t.copy_(torch.from_numpy(a))
+        return t
+    scalars, d_v = torch.zeros(6, **f32), torch.empty(M, **f32)
+    d_u = torch.empty(M * A + shift, **f32)[shift:].view(M, A)
     d_ls = torch.empty(A, **f32)
     ws = ver.workspace(ver.ver_ppo_loss_workspace_bytes(M, A))
-    ver.ver_ppo_loss(ver.ppo_cfg(0.2, 0.5, 1e-2, dist, A), M, dev(u), dev(value), dev(log_std) if dist == 1 else None,
-                     dev(acts), dev(logp_old), dev(adv), dev(ret), dev(isw), scalars, d_u, d_v,
-                     d_ls if dist == 1 else None, ws)
+    ver.ver_ppo_loss(ver.ppo_cfg(0.2, 0.5, 1e-2, dist, A), M, rows(u), dev(value), dev(log_std) if dist == 1 else None,
+                     rows(acts) if dist == 1 else dev(acts), dev(logp_old), dev(adv), dev(ret), dev(isw), scalars, d_u,
+                     d_v, d_ls if dist == 1 else None, ws)
     r_scalars, r_du, r_dv, r_dls = oracle_ppo_loss(dist, u, value, log_std, acts, logp_old, adv, ret, 0.2, 0.5, 1e-2,
                                                    weight=isw)
     names = ["total", "policy", "value", "entropy", "approx_kl", "clip_frac"]
