@@ -23,6 +23,9 @@
 //
 // Traffic per pass: ids and slots read twice and written once (20 B/slot); the
 // gather of a per-step field into the new order reads and writes it once.
+// Buffers of 2^20 slots and more use larger tiles that leave through LDS in
+// sorted order and carry the step counters along (+8 B/slot and pass), which
+// keeps the stores contiguous and spares the last kernel a random gather.
 #include "common.h"
 
 namespace ver {
@@ -49,15 +52,16 @@ __device__ __forceinline__ int load_key(const int32_t* __restrict__ keys, int a,
 }
 
 // hist[d * tiles + tile] = number of slots of the tile whose digit is d.
+template <int ITEMS>
 __global__ __launch_bounds__(ING_THREADS) void ingest_hist_kernel(const int32_t* __restrict__ keys, int S, int N, int first,
                                                                   int shift, int bits, int tiles, int32_t* __restrict__ hist) {
     __shared__ int cnt[ING_MAX_BINS];
     const int bins = 1 << bits, tile = blockIdx.x;
     for (int d = threadIdx.x; d < bins; d += ING_THREADS) cnt[d] = 0;
     __syncthreads();
-    const int base = tile * ING_TILE;
+    const int base = tile * (ING_THREADS * ITEMS);
 #pragma unroll
-    for (int it = 0; it < ING_ITEMS; ++it) {
+    for (int it = 0; it < ITEMS; ++it) {
         const int a = base + it * ING_THREADS + threadIdx.x;
         if (a < S) atomicAdd(&cnt[(load_key(keys, a, N, first) >> shift) & (bins - 1)], 1);
     }
@@ -179,20 +183,153 @@ __global__ __launch_bounds__(ING_THREADS) void ingest_scatter_kernel(
     }
 }
 
+// The same scatter for large buffers: tiles of ING_BIG_ITEMS slots per lane, and the tile leaves through LDS in
+// sorted order.  Written straight from the lanes that ranked them, the slots of one digit go out as single
+// 4-byte stores from different lanes at different times: one L2 request each and partly filled sectors towards
+// memory (measured: 5.5 times the algorithmic traffic).  Here every slot is first put at its place inside the
+// sorted tile in LDS; consecutive threads then write consecutive sorted slots, so a digit's slots of this tile
+// (a run of S / (tiles * bins) on average) leave as contiguous stores.
+constexpr int ING_BIG_ITEMS = 16;
+constexpr int ING_BIG_TILE = ING_THREADS * ING_BIG_ITEMS;
+constexpr int ING_BIG_FROM = 1 << 20;   // slots from which the large-buffer kernels are used
+
+__global__ __launch_bounds__(ING_THREADS) void ingest_scatter_sorted_kernel(
+    const int32_t* __restrict__ keys, const int32_t* __restrict__ vals, int S, int N, int first, int shift, int bits, int tiles,
+    const int32_t* __restrict__ gbase, const int32_t* __restrict__ sums, int32_t* __restrict__ keys_out,
+    int32_t* __restrict__ vals_out, const int32_t* __restrict__ t_in, int32_t* __restrict__ t_out) {
+    extern __shared__ int ing_smem[];
+    const int bins = 1 << bits, tile = blockIdx.x;
+    int* wcnt = ing_smem;                       // [ING_WAVES][bins] slots of digit d seen by wave w, later: before wave w
+    int* lstart = wcnt + ING_WAVES * bins;      // [bins] first place of digit d inside the sorted tile
+    int* gpos = lstart + bins;                  // [bins] output position of the tile's sorted slot j with digit d, minus j
+    int* s_key = gpos + bins;                   // [ING_BIG_TILE] the tile in sorted order
+    int* s_val = s_key + ING_BIG_TILE;
+    __shared__ int s_wsum[ING_WAVES];
+    const int lane = threadIdx.x & (VER_WAVE - 1), wave = threadIdx.x / VER_WAVE;
+    for (int d = threadIdx.x; d < ING_WAVES * bins; d += ING_THREADS) wcnt[d] = 0;
+    __syncthreads();
+    volatile int* mine = wcnt + wave * bins;
+    const int run0 = tile * ING_BIG_TILE + wave * (ING_BIG_ITEMS * VER_WAVE);
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+    int key[ING_BIG_ITEMS], val[ING_BIG_ITEMS], rank[ING_BIG_ITEMS];
+#pragma unroll
+    for (int it = 0; it < ING_BIG_ITEMS; ++it) {
+        const int a = run0 + it * VER_WAVE + lane;
+        const bool live = a < S;
+        key[it] = live ? load_key(keys, a, N, first) : 0;
+        val[it] = live ? (first ? a : vals[a]) : 0;
+        const int d = (key[it] >> shift) & (bins - 1);
+        unsigned long long peers = __ballot(live);
+        for (int b = 0; b < bits; ++b) {
+            const bool bit = (d >> b) & 1;
+            const unsigned long long with = __ballot(live && bit);
+            peers &= bit ? with : ~with;
+        }
+        int seen = 0;
+        if (live) seen = mine[d];
+        rank[it] = seen + __popcll(peers & lanes_below);
+        if (live && (peers & lanes_below) == 0ull) mine[d] = seen + __popcll(peers);   // lowest peer advances the count
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    // per digit: slots in the tile, and how many of them the waves before each wave hold
+    for (int d = threadIdx.x; d < bins; d += ING_THREADS) {
+        int before = 0;
+        for (int w = 0; w < ING_WAVES; ++w) {
+            const int c = wcnt[w * bins + d];
+            wcnt[w * bins + d] = before;
+            before += c;
+        }
+        lstart[d] = before;
+    }
+    __syncthreads();
+    // exclusive prefix sum of lstart over the digits (bins <= 4 per thread)
+    {
+        const int per = (bins + ING_THREADS - 1) / ING_THREADS;
+        const int lo = min(bins, (int)threadIdx.x * per), hi = min(bins, lo + per);
+        int sum = 0;
+        for (int d = lo; d < hi; ++d) sum += lstart[d];
+        int incl = sum;
+#pragma unroll
+        for (int dd = 1; dd < VER_WAVE; dd <<= 1) {
+            const int up = __shfl_up(incl, dd, VER_WAVE);
+            if (lane >= dd) incl += up;
+        }
+        if (lane == VER_WAVE - 1) s_wsum[wave] = incl;
+        __syncthreads();
+        int run = incl - sum;
+        for (int w = 0; w < wave; ++w) run += s_wsum[w];
+        for (int d = lo; d < hi; ++d) {
+            const int c = lstart[d];
+            lstart[d] = run;
+            const size_t at = (size_t)d * tiles + tile;
+            gpos[d] = gbase[at] + (sums ? sums[at / ING_SCAN_CHUNK] : 0) - run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    // the step counters travel with the slots (t_in: in arrival order in the first pass, else as the pass before
+    // left them), so that the last kernel finds them next to each other instead of gathering them at random
+    int cnt_t[ING_BIG_ITEMS];
+    if (t_in) {
+#pragma unroll
+        for (int it = 0; it < ING_BIG_ITEMS; ++it) {
+            const int a = run0 + it * VER_WAVE + lane;
+            cnt_t[it] = a < S ? t_in[a] : 0;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < ING_BIG_ITEMS; ++it) {
+        const int a = run0 + it * VER_WAVE + lane;
+        if (a < S) {
+            const int d = (key[it] >> shift) & (bins - 1);
+            const int at = lstart[d] + wcnt[wave * bins + d] + rank[it];
+            rank[it] = at;   // place inside the sorted tile
+            s_key[at] = key[it];
+            s_val[at] = val[it];
+        }
+    }
+    __syncthreads();
+    const int n_tile = min(ING_BIG_TILE, S - tile * ING_BIG_TILE);
+    for (int j = threadIdx.x; j < n_tile; j += ING_THREADS) {
+        const int k = s_key[j];
+        const int pos = gpos[(k >> shift) & (bins - 1)] + j;
+        keys_out[pos] = k;
+        vals_out[pos] = s_val[j];
+        s_val[j] = pos;   // kept for the counters
+    }
+    if (t_in) {
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < ING_BIG_ITEMS; ++it)
+            if (run0 + it * VER_WAVE + lane < S) s_key[rank[it]] = cnt_t[it];
+        __syncthreads();
+        for (int j = threadIdx.x; j < n_tile; j += ING_THREADS) t_out[s_val[j]] = s_key[j];
+    }
+}
+
 // Offsets from the sorted keys, count of ids outside [0, N), check of the per-environment step counters.
 __global__ __launch_bounds__(ING_THREADS) void ingest_finish_kernel(const int32_t* __restrict__ keys,
                                                                     const int32_t* __restrict__ order,
-                                                                    const int32_t* __restrict__ arr_t, int S, int N,
+                                                                    const int32_t* __restrict__ arr_t,
+                                                                    const int32_t* __restrict__ t_sorted, int S, int N,
                                                                     int32_t* __restrict__ env_off, int32_t* __restrict__ info) {
     const int k = blockIdx.x * ING_THREADS + threadIdx.x;
+    // the step counter of flat step k (from the sorted copy the large-buffer passes leave, else gathered: a random
+    // access), handed to the next lane
+    const int lane = threadIdx.x & (VER_WAVE - 1);
+    int t_here = 0;
+    if (arr_t && k < S) t_here = t_sorted ? t_sorted[k] : arr_t[order[k]];
+    int t_prev = __shfl_up(t_here, 1, VER_WAVE);
     if (k >= S) return;
+    if (arr_t && lane == 0 && k > 0) t_prev = t_sorted ? t_sorted[k - 1] : arr_t[order[k - 1]];
     const int key = keys[k], prev = k > 0 ? keys[k - 1] : -1;
     // k is the first flat step whose key is >= e for every e in (prev, key]
     for (int e = prev + 1; e <= key; ++e) env_off[e] = k;
     if (k == S - 1)
         for (int e = key + 1; e <= N; ++e) env_off[e] = S;
     if (key == N && prev != N) info[1] = S - k;            // slots with an id outside [0, N)
-    if (arr_t && key == prev && key < N && arr_t[order[k]] != arr_t[order[k - 1]] + 1) atomicAdd(&info[0], 1);
+    if (arr_t && key == prev && key < N && t_here != t_prev + 1) atomicAdd(&info[0], 1);
 }
 
 __global__ __launch_bounds__(ING_THREADS) void ingest_dense_kernel(int T, int N, int32_t* __restrict__ env_off,
@@ -225,12 +362,15 @@ inline int bits_for(int n) {   // bits needed to write the value n
 
 struct IngestPlan {
     int tiles, passes, bits[4];
+    bool big;   // large-buffer kernels (tiles of ING_BIG_TILE slots)
     size_t hist_words, sum_words;
 };
 
 inline IngestPlan ingest_plan(int N, int S) {
     IngestPlan p;
-    p.tiles = (S + ING_TILE - 1) / ING_TILE;
+    p.big = S >= ING_BIG_FROM;
+    const int tile = p.big ? ING_BIG_TILE : ING_TILE;
+    p.tiles = (S + tile - 1) / tile;
     const int total = bits_for(N);                       // keys run from 0 to N (N = the bucket of bad ids)
     p.passes = (total + ING_MAX_BITS - 1) / ING_MAX_BITS;
     int left = total;
@@ -250,7 +390,7 @@ extern "C" size_t ver_ingest_workspace_bytes(int32_t N, int32_t S) {
     if (N <= 0 || S < 0 || S > ver::ING_MAX_S) return 0;
     const ver::IngestPlan p = ver::ingest_plan(N, S);
     const size_t per = ver::align_up((size_t)(S > 0 ? S : 1) * 4, 256);
-    return 3 * per + ver::align_up(p.hist_words * 4, 256) + ver::align_up(p.sum_words * 4, 256);
+    return (p.big ? 5 : 3) * per + ver::align_up(p.hist_words * 4, 256) + ver::align_up(p.sum_words * 4, 256);
 }
 
 extern "C" int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t N, int32_t S, int32_t* env_off,
@@ -273,6 +413,9 @@ extern "C" int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t 
     int32_t* val_tmp = cv.take<int32_t>(S);
     int32_t* hist = cv.take<int32_t>(p.hist_words);
     int32_t* sums = cv.take<int32_t>(p.sum_words);
+    int32_t* t_buf[2] = {nullptr, nullptr};
+    if (p.big && arr_t) { t_buf[0] = cv.take<int32_t>(S); t_buf[1] = cv.take<int32_t>(S); }
+    const int32_t* t_in = arr_t;
     // slots ping-pong between `order` and val_tmp so that the last pass writes `order`
     const int32_t* keys_in = arr_env;
     const int32_t* vals_in = nullptr;
@@ -281,8 +424,12 @@ extern "C" int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t 
         const int first = pass == 0, bits = p.bits[pass];
         int32_t* keys_out = key_buf[pass & 1];
         int32_t* vals_out = ((p.passes - 1 - pass) & 1) ? val_tmp : order;
-        hipLaunchKernelGGL(ingest_hist_kernel, dim3(p.tiles), dim3(ING_THREADS), 0, s, keys_in, S, N, first, shift, bits,
-                           p.tiles, hist);
+        if (p.big)
+            hipLaunchKernelGGL(ingest_hist_kernel<ING_BIG_ITEMS>, dim3(p.tiles), dim3(ING_THREADS), 0, s, keys_in, S, N, first,
+                               shift, bits, p.tiles, hist);
+        else
+            hipLaunchKernelGGL(ingest_hist_kernel<ING_ITEMS>, dim3(p.tiles), dim3(ING_THREADS), 0, s, keys_in, S, N, first,
+                               shift, bits, p.tiles, hist);
         const int counters = (1 << bits) * p.tiles;
         const bool two_level = counters > ING_SCAN_DIRECT;
         if (two_level) {
@@ -292,14 +439,23 @@ extern "C" int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t 
         } else {
             hipLaunchKernelGGL(ingest_scan_kernel, dim3(1), dim3(ING_SCAN_THREADS), 0, s, hist, counters);
         }
-        hipLaunchKernelGGL(ingest_scatter_kernel, dim3(p.tiles), dim3(ING_THREADS), 0, s, keys_in, vals_in, S, N, first,
-                           shift, bits, p.tiles, hist, two_level ? sums : (const int32_t*)nullptr, keys_out, vals_out);
+        const int32_t* sums_in = two_level ? sums : (const int32_t*)nullptr;
+        if (p.big) {
+            const size_t lds = ((size_t)(ING_WAVES + 2) * (1 << bits) + 2 * ING_BIG_TILE) * sizeof(int);   // <= 56 KB
+            hipLaunchKernelGGL(ingest_scatter_sorted_kernel, dim3(p.tiles), dim3(ING_THREADS), lds, s, keys_in, vals_in, S, N,
+                               first, shift, bits, p.tiles, hist, sums_in, keys_out, vals_out, arr_t ? t_in : nullptr,
+                               t_buf[pass & 1]);
+            t_in = t_buf[pass & 1];
+        } else {
+            hipLaunchKernelGGL(ingest_scatter_kernel, dim3(p.tiles), dim3(ING_THREADS), 0, s, keys_in, vals_in, S, N, first,
+                               shift, bits, p.tiles, hist, sums_in, keys_out, vals_out);
+        }
         keys_in = keys_out;
         vals_in = vals_out;
         shift += bits;
     }
     hipLaunchKernelGGL(ingest_finish_kernel, dim3((S + ING_THREADS - 1) / ING_THREADS), dim3(ING_THREADS), 0, s, keys_in,
-                       order, arr_t, S, N, env_off, info);
+                       order, arr_t, (p.big && arr_t) ? t_in : (const int32_t*)nullptr, S, N, env_off, info);
     return launch_status();
 }
 

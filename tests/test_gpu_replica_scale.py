@@ -163,11 +163,32 @@ def test_ingest_two_passes_two_level_scan(ver):
     env_off, order, info = torch.empty(N + 1, **i32), torch.empty(S, **i32), torch.empty(4, **i32)
     ws = ver.workspace(ver.ver_ingest_workspace_bytes(N, S))
     ws.fill_(-1)
-    ver.ver_ingest(dev(arr_env), None, N, S, env_off, order, info, ws)
+    arr_t = arr_t.copy()
+    arr_t[np.random.default_rng(12).choice(S, 6, replace=False)] -= 2
+    ver.ver_ingest(dev(arr_env), dev(arr_t), N, S, env_off, order, info, ws)
     good = np.flatnonzero((arr_env >= 0) & (arr_env < N))
-    ref_off, ref_order, _ = oracle_ingest(arr_env[good], N)
+    ref_off, ref_order, ref_viol = oracle_ingest(arr_env[good], N, arr_t[good])
     assert np.array_equal(host(env_off), ref_off)
     n_good = len(good)
     assert np.array_equal(host(order)[:n_good], good[ref_order])
-    assert host(info).tolist() == [0, len(bad), 0, 0]
+    assert ref_viol > 0 and host(info).tolist() == [ref_viol, len(bad), 0, 0]
     assert host(order)[n_good:].tolist() == sorted(bad.tolist())
+
+
+def test_ingest_large_buffer_one_pass_with_counter_check(ver):
+    """2^20 + 777 slots of 300 environments (one digit pass, tiles that leave through LDS in sorted order, ragged
+    last tile), with the per-environment step counters checked and a few of them broken on purpose."""
+    S, N = (1 << 20) + 777, 300
+    _, off = _ragged(N, S, seed=21, empty_every=7)
+    arr_env, arr_t, _ = wl.arrival_order(off, seed=22)
+    arr_t = arr_t.copy()
+    arr_t[np.random.default_rng(23).choice(S, 9, replace=False)] += 3
+    i32 = dict(dtype=torch.int32, device="cuda")
+    env_off, order, info = torch.empty(N + 1, **i32), torch.empty(S, **i32), torch.empty(4, **i32)
+    ws = ver.workspace(ver.ver_ingest_workspace_bytes(N, S))
+    ws.fill_(-1)
+    ver.ver_ingest(dev(arr_env), dev(arr_t), N, S, env_off, order, info, ws)
+    ref_off, ref_order, ref_bad = oracle_ingest(arr_env, N, arr_t)
+    assert np.array_equal(host(env_off), ref_off)
+    assert np.array_equal(host(order), ref_order)
+    assert ref_bad > 0 and host(info).tolist() == [ref_bad, 0, 0, 0]
