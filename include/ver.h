@@ -109,7 +109,9 @@ int ver_ingest_gather(const int32_t* order, int32_t S, const void* src, int32_t 
  *
  * All pointers device.  rewards, values, adv, ret: float[S]; dones: uint8[S];
  * last_values: float[N]; env_off: int32[N+1].  S = 0 is legal (no work).
- * Output is deterministic (no atomics on floats).
+ * Output is deterministic (no atomics on floats).  Any alignment is accepted;
+ * 16-byte aligned rewards, values, adv, ret (4-byte aligned dones) take
+ * 16-byte accesses.
  */
 size_t ver_gae_workspace_bytes(int32_t S);
 int ver_gae(const float* rewards, const float* values, const uint8_t* dones,

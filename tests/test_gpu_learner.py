@@ -179,3 +179,26 @@ def test_update_with_learned_entropy_coefficient(ver, dist, sign, max_is):
         assert_close_update(host(t).astype(np.float64) - b0, r - b0, f"change of tensor {i}")
     sc = host(L.scalars)
     assert abs(sc[0] - ref_scalars[-1]["total"]) <= 1e-3 * max(abs(ref_scalars[-1]["total"]), 1e-2)
+
+
+@pytest.mark.parametrize("name,compute", [("manip", 0), ("large", 1)])
+def test_whole_update_is_bitwise_reproducible(ver, name, compute):
+    """Two learners built from the same rollout run two updates each (arrival-order buffer, importance weights,
+    optimiser with norm clipping): every weight, Adam moment and loss scalar must come out bit-identical: no
+    result in the path depends on the order in which workgroups happen to run."""
+    from paper_2210_05064_amd.learner import Learner
+    w = wl.scaled(wl.WORKLOADS[name], hidden=128, input_dim=36)
+    ro = wl.make_rollout(w, seed=77, bias_scale=0.1)
+    logp_old = torch.from_numpy(ro["logp_noise"] - 1.0).cuda()
+    runs = []
+    for _ in range(2):
+        L = Learner(ro, compute=compute, max_is=1.0, arrival=wl.arrival_order(ro["env_off"], seed=78),
+                    adam_total_steps=100, adam=dict(max_grad_norm=0.5), want_grad_norm=True)
+        L.set_logp_old(logp_old)
+        L.update()
+        L.update()
+        torch.cuda.synchronize()
+        assert not L.lstm_timed_out()
+        runs.append([host(t).copy() for t in L.weights + L.exp_avg + L.exp_avg_sq + [L.scalars, L.grad_norm, L.adv]])
+    for a, b in zip(*runs):
+        assert np.array_equal(a, b)
