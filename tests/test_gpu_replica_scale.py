@@ -81,15 +81,19 @@ def test_gae_carry_through_every_tile_and_batch(ver):
     assert np.array_equal(ret, expect)
 
 
-def test_is_weight_many_environments(ver):
-    S, N = 1 << 22, 1 << 15
+@pytest.mark.parametrize("S,N", [(1 << 22, 1 << 15), ((1 << 25) + 5, 1 << 18)])
+def test_is_weight_many_environments(ver, S, N):
+    """The larger case gives a workgroup several consecutive tiles (offsets of a tile taken from next to the
+    tile before)."""
     _, off = _ragged(N, S, seed=5, empty_every=50)
     w = torch.empty(S, device="cuda")
     ver.ver_is_weight(dev(off), N, S, 1.0, w)
     ref = oracle_is_weights(off, 1.0).astype(np.float32)
     assert np.array_equal(host(w), ref)
-    # a window of more environments than a workgroup keeps in LDS: thousands of empty environments in a row
-    off2 = np.concatenate([[0], np.full(6000, 3000), [S // 2] * 5000, [S]]).astype(np.int32)
+    # windows of more environments than a workgroup keeps in LDS, and more than the near window holds: thousands
+    # of empty environments in a row, in the middle of a tile and across tile boundaries
+    off2 = np.concatenate([[0], np.full(6000, 3000), [S // 2] * 5000, np.full(700, S // 2 + 4096 * 3 + 17),
+                           np.arange(S // 2 + 4096 * 3 + 18, S // 2 + 4096 * 3 + 18 + 3000), [S]]).astype(np.int32)
     N2 = len(off2) - 1
     ver.ver_is_weight(dev(off2), N2, S, 4.0, w)
     assert np.array_equal(host(w), oracle_is_weights(off2, 4.0).astype(np.float32))
