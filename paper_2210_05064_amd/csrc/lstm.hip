@@ -484,6 +484,19 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         LayerWs& L = ws.layer[l];
         ProfScope prof(VER_PROF_LSTM_GEMM_FWD, s);
         if (l == 0) {
+            if constexpr (MODE == MODE_BF16) {
+                // bf16 rows on both sides: the LDS-direct tiles of the two-layer launch, as a launch of their own
+                if (c.x_bf16 && (size_t)M * D * 2 < 0x7fffffff && (size_t)4 * H * D * 2 < 0x7fffffff &&
+                    (size_t)M * 4 * H * 4 < 0x7fffffff &&
+                    set_lds(lstm_proj_dma_kernel, (size_t)PIPE_STAGES * PIPE_STAGE_BYTES)) {
+                    PipeWork pw{};
+                    pw.A = x; pw.B = L.wih; pw.C = L.gates; pw.bias = L.bias; pw.K = D; pw.N = 4 * H;
+                    const int tiles_n = (4 * H + PIPE_BN - 1) / PIPE_BN, tiles_m = (M + PIPE_BM - 1) / PIPE_BM;
+                    hipLaunchKernelGGL(lstm_proj_dma_kernel, dim3(tiles_m * tiles_n), dim3(REC_THREADS),
+                                       (size_t)PIPE_STAGES * PIPE_STAGE_BYTES, s, pw, M, tiles_n);
+                    return;
+                }
+            }
             if (c.x_bf16)
                 gemm_launch<MODE, bf16_t, E, false>(static_cast<const bf16_t*>(x), D, static_cast<const E*>(L.wih), D,
                                                     L.gates, 4 * H, M, 4 * H, D, L.bias, 0, ws.gemm_part, true, s);

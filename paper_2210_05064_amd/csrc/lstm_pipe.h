@@ -155,12 +155,19 @@ __device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, int row0, int 
 // lane / 8, position lane % 8), so the swizzle is applied on the global side.
 constexpr int PIPE_STAGES = 3;
 constexpr int PIPE_STAGE_BYTES = (PIPE_BM + PIPE_BN) * 128;
+// K need not be a multiple of 64 (it is a multiple of 4): the last K-tile then also fetches what follows the rows'
+// ends (the next row, or zeros past the end of the arrays), and the A operand is cleared beyond K in registers, so
+// that whatever was fetched on the B side is multiplied by zero.
+// COHERENT: A is being written by other XCDs during this launch and C is read by them (loads and stores that
+// bypass the non-coherent caches); false for a launch of its own.
+template <bool COHERENT>
 __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, int row_end, int col0, unsigned char* smem) {
     constexpr int BK = 64;
+    constexpr int AUX = COHERENT ? 17 : 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = (wave >> 2) * 64, wn = (wave & 3) * 64;
     const int lr = lane & 15, lk = lane >> 4;
-    const int K = w.K, N = w.N, nk = K / BK;
+    const int K = w.K, N = w.N, nk = (K + BK - 1) / BK, k_tail = K % BK;
     const int ncols = min(N - col0, PIPE_BN);
     __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t*>(static_cast<const bf16_t*>(w.A)) + (size_t)row0 * K, 0, (row_end - row0) * K * 2, 0x00020000);
@@ -183,7 +190,7 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, 
         unsigned char* st = smem + (kt % PIPE_STAGES) * PIPE_STAGE_BYTES;
 #pragma unroll
         for (int j = 0; j < 2; ++j)   // producer rows: written by other XCDs during this launch
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)(st + (wave * 2 + j) * 1024), 16, voffA[j], kt * BK * 2, 0, 17);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, (lds_ptr_t)(st + (wave * 2 + j) * 1024), 16, voffA[j], kt * BK * 2, 0, AUX);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr_t)(st + PIPE_BM * 128 + (wave * 4 + j) * 1024), 16, voffB[j],
@@ -218,6 +225,17 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, 
 #pragma unroll
             for (int i = 0; i < 4; ++i)
                 a[i] = *reinterpret_cast<const u16x8_t*>(st + arow[i] + (((ks * 4 + lk) ^ asw[i]) << 4));
+            if (k_tail != 0 && kt == nk - 1) {
+                // this lane's 8 elements start at ks * 32 + lk * 8 of the K-tile: clear the pairs beyond K
+                const int e0 = ks * 32 + lk * 8;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    u32x4_t v = __builtin_bit_cast(u32x4_t, a[i]);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) v[q] = e0 + 2 * q < k_tail ? v[q] : 0u;
+                    a[i] = __builtin_bit_cast(u16x8_t, v);
+                }
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 b[j] = *reinterpret_cast<const u16x8_t*>(st + brow[j] + (((ks * 4 + lk) ^ bsw[j]) << 4));
@@ -239,9 +257,18 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int lrow = wm + i * 16 + lk * 4 + e;   // rows past the end of the chunk are dropped (buffer bounds)
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][e] + bv), rsC, (lrow * N + n) * 4, 0, 17);
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][e] + bv), rsC, (lrow * N + n) * 4, 0, AUX);
             }
         }
+}
+
+// The same tiles as a launch of its own: C[M, N] = A[M, K] B[N, K]^T + bias, bf16 operands (the input projection
+// of the first layer).  One workgroup per tile; consecutive workgroups (dealt round-robin to the XCDs) take the
+// column tiles of one row tile, so that a row tile of A is fetched from memory by one round of workgroups.
+__global__ __launch_bounds__(REC_THREADS) void lstm_proj_dma_kernel(PipeWork w, int M, int tiles_n) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char proj_smem[];
+    const int rt = blockIdx.x / tiles_n, ct = blockIdx.x % tiles_n;
+    pipe_gemm_tile_dma<false>(w, rt * PIPE_BM, min(M, (rt + 1) * PIPE_BM), ct * PIPE_BN, proj_smem);
 }
 
 // Worker loop.  Items are the tiles of all chunks in the order the consumer needs the chunks (DESCEND: last
@@ -295,7 +322,7 @@ __device__ __forceinline__ void pipe_worker(const PipeWork& w, const PipeLink& p
         const int row0 = pipe_chunk_row0(w.t_off, c), rows = pipe_chunk_rows(w.t_off, T_all, c);
         const int rt = local / pl.tiles_n, ct = local % pl.tiles_n;
         if constexpr (MODE == MODE_BF16)
-            pipe_gemm_tile_dma(w, row0 + rt * PIPE_BM, min(row0 + rows, row0 + (rt + 1) * PIPE_BM), ct * PIPE_BN, smem);
+            pipe_gemm_tile_dma<true>(w, row0 + rt * PIPE_BM, min(row0 + rows, row0 + (rt + 1) * PIPE_BM), ct * PIPE_BN, smem);
         else
             pipe_gemm_tile<MODE, typename LdsElem<MODE>::type>(w, row0 + rt * PIPE_BM, min(row0 + rows, row0 + (rt + 1) * PIPE_BM),
                                                                 ct * PIPE_BN, smem);
