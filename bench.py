@@ -31,7 +31,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 # known size: see profiles/hbm_traffic_max_workload.md.  None where unmeasured.
 MAX_IS = 1.0   # truncation of the importance weight (appendix hyper-parameter table)
 
-MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 1786.4e6, ("max", "lstm_rec_fwd"): 2051.6e6}
+MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 1785.9e6, ("max", "lstm_rec_fwd"): 2048.9e6}
 
 
 def collection_logp(ro, compute, x_bf16):
