@@ -196,3 +196,22 @@ def test_ingest_large_buffer_one_pass_with_counter_check(ver):
     assert np.array_equal(host(env_off), ref_off)
     assert np.array_equal(host(order), ref_order)
     assert ref_bad > 0 and host(info).tolist() == [ref_bad, 0, 0, 0]
+
+
+def test_ingest_at_its_size_limit(ver):
+    """2^24 slots is the most one call takes (511 environments: one 9-bit pass); one more is refused."""
+    S, N = 1 << 24, 511
+    rng = np.random.default_rng(31)
+    arr_env = rng.integers(0, N, size=S).astype(np.int32)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    env_off, order, info = torch.empty(N + 1, **i32), torch.empty(S, **i32), torch.empty(4, **i32)
+    ws = ver.workspace(ver.ver_ingest_workspace_bytes(N, S))
+    ver.ver_ingest(dev(arr_env), None, N, S, env_off, order, info, ws)
+    ref_off, ref_order, _ = oracle_ingest(arr_env, N)
+    assert np.array_equal(host(env_off), ref_off)
+    assert np.array_equal(host(order), ref_order)
+    assert host(info).tolist() == [0, 0, 0, 0]
+    assert ver.ver_ingest_workspace_bytes(N, S + 1) == 0
+    with pytest.raises(ver.VerError) as e:
+        ver.ver_ingest(dev(arr_env), None, N, S + 1, env_off, order, info, ws)
+    assert e.value.status == -3
