@@ -168,3 +168,11 @@ def test_unsupported_shapes(ver):
         c.update(kw)
         cfg = ver.lstm_cfg(c["n_layers"], c["input_dim"], c["hidden"], c["act_dim"], 0, 0)
         assert ver.ver_lstm_workspace_bytes(cfg, 16) == 0
+
+
+@pytest.mark.parametrize("input_dim", [4, 60, 64, 68, 124, 128, 196])
+def test_bf16_input_projection_any_width(ver, input_dim):
+    """bf16 rows into the first layer: the projection walks the input width in tiles of 64, so widths just below,
+    at and just above a multiple of 64 (and narrower than one tile), over three row tiles with a ragged last one."""
+    case(ver, wl.scaled(wl.WORKLOADS["large"], budget=300, n_envs=5, hidden=64, input_dim=input_dim, p_done=0.02,
+                        minibatches=1), seed=40 + input_dim, compute=1, x_bf16=True)
