@@ -7,7 +7,8 @@ ver_gae and ver_is_weight once, then epochs x minibatches x (ver_pack_minibatch,
 ver_ppo_loss, ver_lstm_bwd, ver_adam_step).  All inputs are resident in HBM before the timed
 region.  Prints ONE JSON line: learner env-steps/s, the roofline position of
 the dominant kernel (timed with HIP events inside the library during the timed
-region) and the CPU oracle timed on a bounded sample of the same workload.
+region), the HBM-bound kernels on roofline-scale replicas of the workload, and
+the CPU oracle timed on a bounded sample of the same workload.
 
     python bench.py [--workload max|large|manip|nav|tiny] [--steps K] [--warmup W]
 """
@@ -31,7 +32,7 @@ PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}   # MI355X dense MFMA peaks
 # known size: see profiles/hbm_traffic_max_workload.md.  None where unmeasured.
 MAX_IS = 1.0   # truncation of the importance weight (appendix hyper-parameter table)
 
-MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 1785.9e6, ("max", "lstm_rec_fwd"): 2048.9e6}
+MEASURED_TRAFFIC = {("max", "lstm_rec_bwd"): 1786.0e6, ("max", "lstm_rec_fwd"): 2004.5e6}
 
 
 def collection_logp(ro, compute, x_bf16):
@@ -136,6 +137,8 @@ def main():
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle LSTM work (0 = skip)")
     ap.add_argument("--env-major", action="store_true",
                     help="hand the rollout over already bucketed by environment (skips ver_ingest)")
+    ap.add_argument("--no-replica", action="store_true",
+                    help="leave the roofline-scale replicas of the HBM-bound kernels out of the JSON line")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="only run three device-to-device copies of MIB mebibytes (a kernel of known HBM traffic "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters by) and exit")
@@ -239,6 +242,17 @@ def main():
         "loss_scalars_last_minibatch": dict(zip(["total", "policy", "value", "entropy", "approx_kl", "clip_frac"],
                                                 scalars)),
     }
+    if not args.no_replica:
+        # the HBM-bound kernels once more on gigabyte-sized replicas of the workload (untimed part of the run): at the
+        # workload's own sizes they sit at the launch-latency floor, which says nothing about the kernels
+        del learner
+        torch.cuda.empty_cache()
+        try:
+            from paper_2210_05064_amd import hbm_replica
+            out["hbm_replica"] = [{k: r[k] for k in ("kernel", "shape", "bytes", "ms", "achieved", "peak", "unit", "frac")}
+                                  for r in hbm_replica.run(seed=args.seed + 3000, reps=4)]
+        except Exception as e:   # the headline figures above do not depend on this part
+            out["hbm_replica_error"] = repr(e)
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(ro, args.cpu_budget)
     print(json.dumps(out))
