@@ -417,6 +417,20 @@ inline bool set_lds(K kernel, size_t bytes) {
                                (int)bytes) == hipSuccess;
 }
 
+// C[M, N] = A[M, K] B[N, K]^T (+ bias), all three row-major, A and B bf16: the LDS-direct 128 x 256 tiles, one
+// workgroup per tile.  False if the shape does not fit the kernel's 32-bit byte offsets (the caller then uses
+// the general GEMM).
+inline bool launch_proj_dma(const void* A, const void* B, float* C, const float* bias, int M, int N, int K, hipStream_t s) {
+    if ((size_t)M * K * 2 >= 0x7fffffff || (size_t)N * K * 2 >= 0x7fffffff || (size_t)M * N * 4 >= 0x7fffffff) return false;
+    if (!set_lds(lstm_proj_dma_kernel, (size_t)PIPE_STAGES * PIPE_STAGE_BYTES)) return false;
+    PipeWork pw{};
+    pw.A = A; pw.B = B; pw.C = C; pw.bias = bias; pw.K = K; pw.N = N;
+    const int tiles_n = (N + PIPE_BN - 1) / PIPE_BN, tiles_m = (M + PIPE_BM - 1) / PIPE_BM;
+    hipLaunchKernelGGL(lstm_proj_dma_kernel, dim3(tiles_m * tiles_n), dim3(REC_THREADS), (size_t)PIPE_STAGES * PIPE_STAGE_BYTES, s,
+                       pw, M, tiles_n);
+    return true;
+}
+
 // Diagnostic switch: with VER_LSTM_SEQUENTIAL=1 in the environment two-layer networks run one launch per layer,
 // like any other depth (used by the tests to check both paths against each other and by timing comparisons).
 inline bool sequential_layers() {
@@ -486,16 +500,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         if (l == 0) {
             if constexpr (MODE == MODE_BF16) {
                 // bf16 rows on both sides: the LDS-direct tiles of the two-layer launch, as a launch of their own
-                if (c.x_bf16 && (size_t)M * D * 2 < 0x7fffffff && (size_t)4 * H * D * 2 < 0x7fffffff &&
-                    (size_t)M * 4 * H * 4 < 0x7fffffff &&
-                    set_lds(lstm_proj_dma_kernel, (size_t)PIPE_STAGES * PIPE_STAGE_BYTES)) {
-                    PipeWork pw{};
-                    pw.A = x; pw.B = L.wih; pw.C = L.gates; pw.bias = L.bias; pw.K = D; pw.N = 4 * H;
-                    const int tiles_n = (4 * H + PIPE_BN - 1) / PIPE_BN, tiles_m = (M + PIPE_BM - 1) / PIPE_BM;
-                    hipLaunchKernelGGL(lstm_proj_dma_kernel, dim3(tiles_m * tiles_n), dim3(REC_THREADS),
-                                       (size_t)PIPE_STAGES * PIPE_STAGE_BYTES, s, pw, M, tiles_n);
-                    return;
-                }
+                if (c.x_bf16 && launch_proj_dma(x, L.wih, L.gates, L.bias, M, 4 * H, D, s)) return;
             }
             if (c.x_bf16)
                 gemm_launch<MODE, bf16_t, E, false>(static_cast<const bf16_t*>(x), D, static_cast<const E*>(L.wih), D,
@@ -642,8 +647,11 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         // gradient w.r.t. the layer input: dx[M, D] = dz[M, 4H] . W_ih[4H, D]
         if (dx) {
             ProfScope prof(VER_PROF_LSTM_GEMM_DX, s);
-            gemm_launch<MODE, E, E, false>(dz, 4 * H, static_cast<const E*>(L.wihT), 4 * H, dx, D, M, D, 4 * H,
-                                           nullptr, 0, ws.gemm_part, true, s);
+            bool done = false;
+            if constexpr (MODE == MODE_BF16) done = launch_proj_dma(dz, L.wihT, dx, nullptr, M, D, 4 * H, s);
+            if (!done)
+                gemm_launch<MODE, E, E, false>(dz, 4 * H, static_cast<const E*>(L.wihT), 4 * H, dx, D, M, D, 4 * H,
+                                               nullptr, 0, ws.gemm_part, true, s);
         }
         // dW_ih[4H, D] = dz^T x ; dW_hh[4H, H] = dz^T h_{t-1}; stored gate-major
         {
