@@ -375,6 +375,41 @@ extern "C" size_t ver_gae_workspace_bytes(int32_t S) {
     return 256 + 3 * ver::align_up(t * 8, 256);
 }
 
+namespace ver {
+namespace {
+// Enqueues the scan with `mem` (ver_gae_workspace_bytes(S) bytes of device memory) as its scratch.
+int gae_launch(const float* rewards, const float* values, const uint8_t* dones, const float* last_values,
+               const int32_t* env_off, int32_t N, int32_t S, float gamma, float lambda, float* adv, float* ret,
+               void* mem, hipStream_t s) {
+    const int tiles = gae_tiles(S);
+    Carver cv(mem);
+    int* head = cv.take<int>(64);
+    GaeWs ws;
+    ws.ticket = head;
+    ws.error = head + 1;
+    ws.inc = cv.take<unsigned long long>(tiles);
+    ws.agg_a = cv.take<unsigned long long>(tiles);
+    ws.agg_b = cv.take<unsigned long long>(tiles);
+    // ticket, error and every published word must start at zero (the blocks are adjacent)
+    fill_words(reinterpret_cast<int32_t*>(head), cv.used / 4, 0, s);
+    ProfScope prof(VER_PROF_GAE, s);
+    // 16-byte accesses need 16-byte aligned arrays (tiles start at multiples of the tile size)
+    const uintptr_t bits = reinterpret_cast<uintptr_t>(rewards) | reinterpret_cast<uintptr_t>(values) |
+                           reinterpret_cast<uintptr_t>(adv) | reinterpret_cast<uintptr_t>(ret) |
+                           (reinterpret_cast<uintptr_t>(dones) << 2);
+    // tiles per ticket: 1 while tickets are few, up to GAE_MAX_BATCH for buffers of many thousands of tiles
+    const int batch = gae_batch(tiles), groups = (tiles + batch - 1) / batch;
+    if ((bits & 15) == 0)
+        hipLaunchKernelGGL(gae_kernel<true>, dim3(groups), dim3(GAE_THREADS), 0, s, rewards, values, dones,
+                           last_values, env_off, N, S, tiles, batch, gamma, lambda, adv, ret, ws);
+    else
+        hipLaunchKernelGGL(gae_kernel<false>, dim3(groups), dim3(GAE_THREADS), 0, s, rewards, values, dones,
+                           last_values, env_off, N, S, tiles, batch, gamma, lambda, adv, ret, ws);
+    return launch_status();
+}
+}  // namespace
+}  // namespace ver
+
 extern "C" int ver_gae(const float* rewards, const float* values, const uint8_t* dones,
                        const float* last_values, const int32_t* env_off, int32_t N, int32_t S,
                        float gamma, float lambda, float* adv, float* ret,
@@ -383,30 +418,6 @@ extern "C" int ver_gae(const float* rewards, const float* values, const uint8_t*
     if (S == 0) return VER_OK;
     if (!rewards || !values || !dones || !last_values || !env_off || !adv || !ret || N == 0) return VER_EINVAL;
     if (!workspace || workspace_bytes < ver_gae_workspace_bytes(S)) return VER_EWORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int tiles = ver::gae_tiles(S);
-    ver::Carver cv(workspace);
-    int* head = cv.take<int>(64);
-    ver::GaeWs ws;
-    ws.ticket = head;
-    ws.error = head + 1;
-    ws.inc = cv.take<unsigned long long>(tiles);
-    ws.agg_a = cv.take<unsigned long long>(tiles);
-    ws.agg_b = cv.take<unsigned long long>(tiles);
-    // ticket, error and every published word must start at zero (the blocks are adjacent)
-    ver::fill_words(reinterpret_cast<int32_t*>(head), cv.used / 4, 0, s);
-    ver::ProfScope prof(VER_PROF_GAE, s);
-    // 16-byte accesses need 16-byte aligned arrays (tiles start at multiples of the tile size)
-    const uintptr_t bits = reinterpret_cast<uintptr_t>(rewards) | reinterpret_cast<uintptr_t>(values) |
-                           reinterpret_cast<uintptr_t>(adv) | reinterpret_cast<uintptr_t>(ret) |
-                           (reinterpret_cast<uintptr_t>(dones) << 2);
-    // tiles per ticket: 1 while tickets are few, up to GAE_MAX_BATCH for buffers of many thousands of tiles
-    const int batch = ver::gae_batch(tiles), groups = (tiles + batch - 1) / batch;
-    if ((bits & 15) == 0)
-        hipLaunchKernelGGL(ver::gae_kernel<true>, dim3(groups), dim3(ver::GAE_THREADS), 0, s, rewards, values, dones,
-                           last_values, env_off, N, S, tiles, batch, gamma, lambda, adv, ret, ws);
-    else
-        hipLaunchKernelGGL(ver::gae_kernel<false>, dim3(groups), dim3(ver::GAE_THREADS), 0, s, rewards, values, dones,
-                           last_values, env_off, N, S, tiles, batch, gamma, lambda, adv, ret, ws);
-    return ver::launch_status();
+    return ver::gae_launch(rewards, values, dones, last_values, env_off, N, S, gamma, lambda, adv, ret, workspace,
+                           static_cast<hipStream_t>(stream));
 }
