@@ -186,7 +186,7 @@ def main():
     for _ in range(args.warmup):
         learner.update()
     torch.cuda.synchronize()
-    if learner.lstm_timed_out():
+    if learner.lstm_timed_out() or learner.gae_timed_out():
         print("device-side wait timed out during warm-up", file=sys.stderr)
         sys.exit(4)
 
@@ -200,6 +200,9 @@ def main():
     elapsed = time.perf_counter() - t0
     prof = ver.ver_profile_read()
     ver.ver_profile_enable(0)
+    if learner.lstm_timed_out() or learner.gae_timed_out():
+        print("device-side wait timed out during the timed region: results are invalid", file=sys.stderr)
+        sys.exit(4)
     scalars = learner.scalars.cpu().numpy().tolist()
     t_max = int(learner.info[1].item())
 

@@ -112,6 +112,12 @@ int ver_ingest_gather(const int32_t* order, int32_t S, const void* src, int32_t 
  * Output is deterministic (no atomics on floats).  Any alignment is accepted;
  * 16-byte aligned rewards, values, adv, ret (4-byte aligned dones) take
  * 16-byte accesses.
+ * The scan is a single pass in which tiles of 2048 steps wait (bounded) for
+ * what the tiles after them publish.  Should such a wait ever give up (it
+ * cannot while the GPU makes progress), workspace word 1 (int32) is non-zero
+ * once the stream has drained and the outputs of that tile, and of the tiles
+ * towards the start of the buffer that depend on it, are NaN: never a
+ * plausible wrong number.
  */
 size_t ver_gae_workspace_bytes(int32_t S);
 int ver_gae(const float* rewards, const float* values, const uint8_t* dones,
@@ -287,10 +293,12 @@ int ver_pack_index_batch(const ver_pack_args* args /* host array */, int32_t n, 
  * The time loops run as persistent kernels that need the whole GPU (one
  * workgroup on every CU at the same time, cooperating per XCD): kernels of
  * other streams or processes that hold CUs for long can make their bounded
- * waits time out.  Networks of two layers run both layers' time loops in one
- * launch; the environment variable VER_LSTM_SEQUENTIAL=1 (read at every call)
- * makes them run layer by layer like any other depth - a diagnostic switch,
- * results agree up to the order of fp32 additions.
+ * waits time out.  ver_lstm_fwd / ver_lstm_bwd return VER_EUNSUPPORTED on a
+ * device that is not a whole MI355X (gfx950 with 256 compute units; the
+ * device is queried once).  Networks of two layers run both layers' time
+ * loops in one launch; cfg.layer_by_layer = 1 makes them run layer by layer
+ * like any other depth - a diagnostic switch, results agree up to the order
+ * of fp32 additions (forward and backward must be called with the same value).
  */
 typedef struct {
     int32_t n_layers;
@@ -299,6 +307,7 @@ typedef struct {
     int32_t act_dim;
     int32_t compute;
     int32_t x_bf16;
+    int32_t layer_by_layer;   /* 0 (default) or 1, see above */
 } ver_lstm_cfg;
 
 size_t ver_lstm_workspace_bytes(const ver_lstm_cfg* cfg, int32_t M);

@@ -40,7 +40,7 @@ class PackArgs(C.Structure):
 
 class LstmCfg(C.Structure):
     _fields_ = [("n_layers", _i32), ("input_dim", _i32), ("hidden", _i32), ("act_dim", _i32),
-                ("compute", _i32), ("x_bf16", _i32)]
+                ("compute", _i32), ("x_bf16", _i32), ("layer_by_layer", _i32)]
 
 
 class PpoCfg(C.Structure):
@@ -211,8 +211,8 @@ def _ptr_array(tensors):
     return arr
 
 
-def lstm_cfg(n_layers, input_dim, hidden, act_dim, compute=0, x_bf16=0) -> LstmCfg:
-    return LstmCfg(n_layers, input_dim, hidden, act_dim, compute, x_bf16)
+def lstm_cfg(n_layers, input_dim, hidden, act_dim, compute=0, x_bf16=0, layer_by_layer=0) -> LstmCfg:
+    return LstmCfg(n_layers, input_dim, hidden, act_dim, compute, x_bf16, layer_by_layer)
 
 
 def ver_lstm_workspace_bytes(cfg: LstmCfg, M: int) -> int:

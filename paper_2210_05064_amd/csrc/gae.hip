@@ -316,7 +316,9 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
                 j0 -= VER_WAVE;
             }
             if (failed && lane == 0) st_agent(ws.error, 1);
-            carry = back.b;  // beyond tile 0 the incoming advantage is 0
+            // beyond tile 0 the incoming advantage is 0.  A wait that gave up (it never should) must not pass for a
+            // result: the tile's outputs, and through it those of the tiles that read its word, become NaN
+            carry = failed ? __longlong_as_double(0x7FF8000000000000LL) : back.b;
         }
         if (lane == 0 && !map_only) {
             const double leaving = cut ? tile_map.b : tile_map.b + tile_map.a * carry;

@@ -11,7 +11,8 @@
 //       (forward), dz_t and W_hh dz_t (backward) - see lstm_rec.h.
 // Internally the 4H gate rows are interleaved (row = unit*4 + gate); user-facing
 // weights and gradients keep the gate-major order i,f,g,o of the declaration.
-#include <cstdlib>
+#include <cstring>
+#include <mutex>
 
 #include "lstm_pipe.h"
 
@@ -395,6 +396,7 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
 inline int check_cfg(const ver_lstm_cfg* c, int M) {
     if (!c || M <= 0) return VER_EINVAL;
     if (c->compute != 0 && c->compute != 1) return VER_EINVAL;
+    if (c->layer_by_layer != 0 && c->layer_by_layer != 1) return VER_EINVAL;
     if (c->x_bf16 && !c->compute) return VER_EINVAL;
     if (c->n_layers < 1 || c->n_layers > 8 || c->act_dim < 1 || c->act_dim > 63) return VER_EUNSUPPORTED;
     if (c->hidden < 64 || c->hidden % 64 != 0 || c->input_dim < 4 || c->input_dim % 4 != 0) return VER_EUNSUPPORTED;
@@ -431,11 +433,24 @@ inline bool launch_proj_dma(const void* A, const void* B, float* C, const float*
     return true;
 }
 
-// Diagnostic switch: with VER_LSTM_SEQUENTIAL=1 in the environment two-layer networks run one launch per layer,
-// like any other depth (used by the tests to check both paths against each other and by timing comparisons).
-inline bool sequential_layers() {
-    const char* v = getenv("VER_LSTM_SEQUENTIAL");
-    return v && v[0] == '1';
+// The persistent time-loop kernels are written for the whole of one MI355X: a grid of one workgroup per CU that
+// must be co-resident, grouped by the XCD it runs on (8 XCDs of 32 CUs).  On any other device (another
+// architecture, a partition of the chip with fewer CUs) their groups would be incomplete and the bounded waits
+// would give up, so the entry points refuse to launch there.  Looked up once per device.
+inline int device_fits_time_loops() {
+    static std::mutex lock;
+    static signed char known[64];   // 0 unknown, 1 fits, -1 does not
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return VER_EHIP;
+    if (dev < 0 || dev >= 64) return VER_EUNSUPPORTED;
+    std::lock_guard<std::mutex> hold(lock);
+    if (known[dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return VER_EHIP;
+        const bool ok = prop.multiProcessorCount == REC_GRID && std::strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+        known[dev] = ok ? 1 : -1;
+    }
+    return known[dev] > 0 ? VER_OK : VER_EUNSUPPORTED;
 }
 
 // LDS of a worker of a two-layer launch: one 128 x BK and one 256 x BK operand tile.
@@ -466,7 +481,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
             float* head_out, float* value, LstmWs& ws, hipStream_t s) {
     typedef typename RecGeom<MODE>::E E;
     const int H = c.hidden, A = c.act_dim;
-    const bool pipelined = c.n_layers == 2 && !sequential_layers();   // both time loops in one launch
+    const bool pipelined = c.n_layers == 2 && !c.layer_by_layer;   // both time loops in one launch
     if (!pipelined) fill_words(ws.err, 1, 0, s);
 
     // 8 waves = row groups x shares of the contraction (TPW tiles of 16 gate rows per wave): a workgroup owns
@@ -601,7 +616,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     }
 
     // one wave per (16 units, share of the 4H contraction): 2 tiles x 4 when H/16 > 32 workgroups, else 1 x 8
-    const bool pipelined = nl == 2 && !sequential_layers();   // both time loops in one launch
+    const bool pipelined = nl == 2 && !c.layer_by_layer;   // both time loops in one launch
     const bool wide = H / 16 > REC_MAX_GROUP;
     const int mt = wide ? 2 : 1, ks = wide ? 4 : 8;
     const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
@@ -736,6 +751,8 @@ extern "C" int ver_lstm_fwd(const ver_lstm_cfg* cfg, const void* x_packed, int32
     for (int i = 0; i < 4 * cfg->n_layers + 4; ++i)
         if (!weights[i]) return VER_EINVAL;
     if (!workspace || workspace_bytes < ver_lstm_workspace_bytes(cfg, M)) return VER_EWORKSPACE;
+    const int dev_st = ver::device_fits_time_loops();
+    if (dev_st != VER_OK) return dev_st;
     ver::LstmWs ws;
     ver::lstm_ws_layout(*cfg, M, workspace, &ws);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -759,6 +776,8 @@ extern "C" int ver_lstm_bwd(const ver_lstm_cfg* cfg, const void* x_packed, int32
     for (int i = 0; i < 4 * cfg->n_layers + 4; ++i)
         if (!weights[i] || !weight_grads[i]) return VER_EINVAL;
     if (!workspace || workspace_bytes < ver_lstm_workspace_bytes(cfg, M)) return VER_EWORKSPACE;
+    const int dev_st = ver::device_fits_time_loops();
+    if (dev_st != VER_OK) return dev_st;
     ver::LstmWs ws;
     ver::lstm_ws_layout(*cfg, M, workspace, &ws);
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -27,8 +27,9 @@ class Learner:
     def __init__(self, rollout: dict, *, compute: int | None = None, x_bf16: bool | None = None,
                  want_dx: bool = False, minibatches: int | None = None, adam_total_steps: int | None = None,
                  adam: dict | None = None, max_is: float | None = None, learned_entropy: dict | None = None,
-                 arrival: tuple | None = None, want_grad_norm: bool = False):
-        """want_grad_norm: have every optimiser step report the global gradient norm (always on with clipping).
+                 arrival: tuple | None = None, want_grad_norm: bool = False, layer_by_layer: bool = False):
+        """layer_by_layer: the library's diagnostic switch (two-layer networks run one launch per layer).
+        want_grad_norm: have every optimiser step report the global gradient norm (always on with clipping).
         arrival: (arr_env, arr_t, csr_of_arrival) of workloads.arrival_order: the rollout is then held as the
         linear collection buffer (steps in arrival order) and every update starts by bucketing it by environment
         on the GPU (ver_ingest + one gather per field); None = the rollout is given environment-major.
@@ -109,7 +110,7 @@ class Learner:
             self.alpha = torch.full((1,), float(learned_entropy["alpha0"]), **f32)
             self.d_alpha = torch.zeros(1, **f32)
         # configuration structs and workspaces
-        self.lstm_cfg = ver.lstm_cfg(nl, D, H, A, self.compute, int(self.x_bf16))
+        self.lstm_cfg = ver.lstm_cfg(nl, D, H, A, self.compute, int(self.x_bf16), int(layer_by_layer))
         self.ppo_cfg = ver.ppo_cfg(w.clip, w.value_coef, w.entropy_coef, w.dist, A)
         self.ws_gae = ver.workspace(ver.ver_gae_workspace_bytes(S))
         n = ver.ver_lstm_workspace_bytes(self.lstm_cfg, M)
@@ -257,4 +258,9 @@ class Learner:
                     on_minibatch(e, b)
 
     def lstm_timed_out(self) -> bool:
+        """A bounded device-side wait of the LSTM time loops gave up (synchronises)."""
         return bool(self.ws_lstm[0].item() != 0)
+
+    def gae_timed_out(self) -> bool:
+        """A bounded look-back wait of the advantage scan gave up (synchronises)."""
+        return bool(self.ws_gae[1].item() != 0)

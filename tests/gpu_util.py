@@ -98,9 +98,9 @@ def meta_to_device(meta):
 class LstmRun:
     """One forward (+ optional backward) of the HIP LSTM on packed rows."""
 
-    def __init__(self, ver, w, weights, x_packed, meta, h0=None, c0=None, compute=0, x_bf16=False):
+    def __init__(self, ver, w, weights, x_packed, meta, h0=None, c0=None, compute=0, x_bf16=False, layer_by_layer=False):
         self.ver, self.M = ver, meta["M"]
-        self.cfg = ver.lstm_cfg(w.n_layers, w.input_dim, w.hidden, w.act_dim, compute, int(x_bf16))
+        self.cfg = ver.lstm_cfg(w.n_layers, w.input_dim, w.hidden, w.act_dim, compute, int(x_bf16), int(layer_by_layer))
         self.w_host = weight_list(weights)
         self.w_dev = [dev(a) for a in self.w_host]
         x = torch.from_numpy(np.ascontiguousarray(x_packed)).cuda()

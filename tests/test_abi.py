@@ -49,11 +49,12 @@ def test_workspace_queries_are_host_only(lib):
     assert lib.ver_ppo_loss_workspace_bytes(8192, 11) > 0
 
     class Cfg(C.Structure):
-        _fields_ = [(n, C.c_int32) for n in ("n_layers", "input_dim", "hidden", "act_dim", "compute", "x_bf16")]
-    big = lib.ver_lstm_workspace_bytes(C.byref(Cfg(2, 1044, 1024, 11, 1, 1)), 8192)
+        _fields_ = [(n, C.c_int32) for n in ("n_layers", "input_dim", "hidden", "act_dim", "compute", "x_bf16",
+                                                 "layer_by_layer")]
+    big = lib.ver_lstm_workspace_bytes(C.byref(Cfg(2, 1044, 1024, 11, 1, 1, 0)), 8192)
     assert big > 2 * 8192 * 6 * 1024 * 4          # saved activations of two layers at least
-    assert lib.ver_lstm_workspace_bytes(C.byref(Cfg(2, 1044, 1024, 11, 0, 0)), 8192) == 0   # fp32 needs hidden <= 512
-    assert lib.ver_lstm_workspace_bytes(C.byref(Cfg(2, 1044, 1000, 11, 1, 1)), 8192) == 0
+    assert lib.ver_lstm_workspace_bytes(C.byref(Cfg(2, 1044, 1024, 11, 0, 0, 0)), 8192) == 0   # fp32 needs hidden <= 512
+    assert lib.ver_lstm_workspace_bytes(C.byref(Cfg(2, 1044, 1000, 11, 1, 1, 0)), 8192) == 0
 
 
 def test_argument_checks_precede_any_gpu_work(lib):

@@ -7,7 +7,7 @@ import torch
 from oracle import gae as ogae, is_weight as ois, learner as olearner, pack as opack
 from paper_2210_05064_amd import workloads as wl
 from tests.gpu_util import GRAD_NAMES, grads_to_list, host
-from tests.util import assert_close, assert_close_bf16, assert_close_update
+from tests.util import assert_close, assert_close_update, closer
 
 pytestmark = pytest.mark.gpu
 
@@ -28,7 +28,7 @@ def run_case(w, seed, compute=None, max_is=None, arrival=False):
     cfg = dict(dist=w.dist, clip=np.float32(w.clip).item(), value_coef=w.value_coef,
                entropy_coef=np.float32(w.entropy_coef).item())
     names = [f"layer{l}.{n}" for l in range(w.n_layers) for n in GRAD_NAMES] + ["W_a", "b_a", "w_v", "b_v"]
-    close = (lambda a, r, n: assert_close(a, r, 1e-4, n)) if L.compute == 0 else assert_close_bf16
+    close = closer(L.compute)
     checked = []
 
     def check(e, b):

@@ -1,5 +1,18 @@
 """Shared comparison helper for the tests (no method arithmetic)."""
+import os
+
 import numpy as np
+
+
+def _record(bar, what, em, e2):
+    """With VER_PARITY_LOG=<file> in the environment every comparison that goes through a bar of this module
+    appends its measured errors there (test id, bar, tensor, elementwise, 2-norm): the figures quoted next to the
+    bars below and in profiles/ come from such a log (tests/parity_report.py formats it)."""
+    path = os.environ.get("VER_PARITY_LOG")
+    if path:
+        test = os.environ.get("PYTEST_CURRENT_TEST", "?").split(" ")[0]
+        with open(path, "a") as f:
+            f.write(f"{test}\t{bar}\t{what}\t{em:.3e}\t{e2:.3e}\n")
 
 
 def rel_err(x, ref):
@@ -30,24 +43,53 @@ def l2_rel_err(x, ref):
 
 
 def assert_close_bf16(x, ref, what=""):
-    """Bar for the bf16-operand LSTM path: 2e-2 relative per tensor, taken in
-    the 2-norm (each bf16 operand carries a relative rounding error of up to
-    2^-9, and the largest of millions of such elementwise errors is an
-    extreme-value statistic, not a measure of the arithmetic), plus an
-    elementwise sanity bound of 1e-1 on the error relative to
-    max(|ref|, rms(ref))."""
+    """The stated bar of the bf16-operand LSTM path: every element within 2e-2 of max(|ref|, rms(ref)), the
+    metric of every other floating-point comparison here.  Holds for what the forward pass hands out (head
+    outputs, values), the loss scalars and their gradient, and the gradients of the heads (largest measured:
+    1.3e-2)."""
     e2, em = l2_rel_err(x, ref), rel_err(x, ref)
-    assert e2 <= 2e-2, f"{what}: relative 2-norm error {e2:.3e} > 2.0e-02"
+    _record("bf16", what, em, e2)
+    assert em <= 2e-2, f"{what}: elementwise relative error {em:.3e} > 2.0e-02"
+
+
+def assert_close_bf16_bptt(x, ref, what=""):
+    """Bar for the tensors that come out of back-propagation through time with bf16 operands: d_x and the
+    gradients of W_ih, W_hh, b_ih, b_hh of every layer.  They are contractions of the gate gradients dz (rounded
+    to bf16 as an MFMA operand, and themselves a product of saved gates that carry the forward pass's bf16
+    rounding) with bf16 rows, over thousands of terms: an element's error is close to normal with a standard
+    deviation of the tensor's relative 2-norm error (measured 1e-3 .. 4.7e-3), and the largest of 10^5 .. 10^7
+    such elements relative to max(|ref|, rms(ref)) sits at 5 to 12 standard deviations (measured up to 5.5e-2 for
+    W_hh, 4.6e-2 W_ih, 3.2e-2 d_x, 2.3e-2 biases): above the stated 2e-2 although the arithmetic is as accurate as
+    bf16 operands allow.  Asserted instead: 1e-2 in the 2-norm and 1e-1 elementwise, both about twice the largest
+    value measured over all tests (the log that VER_PARITY_LOG writes has every figure)."""
+    e2, em = l2_rel_err(x, ref), rel_err(x, ref)
+    _record("bf16-bptt", what, em, e2)
+    assert e2 <= 1e-2, f"{what}: relative 2-norm error {e2:.3e} > 1.0e-02"
     assert em <= 1e-1, f"{what}: elementwise relative error {em:.3e} > 1.0e-01"
+
+
+def _is_bptt_tensor(what):
+    head = what.split(" ")[0]
+    return head == "d_x" or head.split(".")[-1] in ("W_ih", "W_hh", "b_ih", "b_hh")
+
+
+def closer(compute):
+    """close(x, ref, what) for the LSTM path in use: fp32 contractions -> 1e-4 elementwise; bf16 operands -> the
+    stated 2e-2 elementwise, except for the tensors named in assert_close_bf16_bptt."""
+    if compute == 0:
+        return lambda x, ref, what="": assert_close(x, ref, 1e-4, what)
+    return lambda x, ref, what="": (assert_close_bf16_bptt if _is_bptt_tensor(what) else assert_close_bf16)(x, ref, what)
 
 
 def assert_close_update(x, ref, what=""):
-    """Bar for the CHANGE of a weight tensor over a few optimiser steps of the fp32 path: 1e-3 relative in the
-    2-norm (measured 1e-5 .. 2e-4), plus an elementwise sanity bound of 1e-1 relative to max(|ref|, rms(ref)).
+    """Bar for the CHANGE of a weight tensor over a few optimiser steps of the fp32 path: 2e-4 relative in the
+    2-norm (measured 3e-6 .. 8.3e-5) and 2.5e-2 elementwise relative to max(|ref|, rms(ref)) (measured up to
+    1.05e-2, on one element of a 16384-element tensor; every other tensor below 4e-3).
     Adam's step m / (sqrt(v) + eps) does not depend on the size of the gradient: an element whose gradient is at
     the level of fp32 rounding noise still takes a step of full size, in a direction that noise decides, so the
-    largest elementwise error of a big tensor (measured up to 3e-2 on one element of 16384) says nothing about
-    the arithmetic."""
+    largest elementwise error of a big tensor says little about the arithmetic; a single step from given
+    gradients is held to 1e-5 elementwise elsewhere."""
     e2, em = l2_rel_err(x, ref), rel_err(x, ref)
-    assert e2 <= 1e-3, f"{what}: relative 2-norm error {e2:.3e} > 1.0e-03"
-    assert em <= 1e-1, f"{what}: elementwise relative error {em:.3e} > 1.0e-01"
+    _record("update", what, em, e2)
+    assert e2 <= 2e-4, f"{what}: relative 2-norm error {e2:.3e} > 2.0e-04"
+    assert em <= 2.5e-2, f"{what}: elementwise relative error {em:.3e} > 2.5e-02"
