@@ -50,7 +50,8 @@ enum {
     VER_EINVAL = -1,       /* null pointer, negative size, b outside [0,B), B does not divide S ... */
     VER_EWORKSPACE = -2,   /* workspace missing or too small */
     VER_EUNSUPPORTED = -3, /* shape outside what the kernels handle (see each call) */
-    VER_EHIP = -4          /* a HIP call or kernel launch failed */
+    VER_EHIP = -4,         /* a HIP call or kernel launch failed */
+    VER_ETOOLARGE = -5     /* input above the stated maximum of an entry point with fixed scratch */
 };
 
 /* Text for a status code; never NULL.  Host only. */
@@ -124,6 +125,31 @@ int ver_gae(const float* rewards, const float* values, const uint8_t* dones,
             const float* last_values, const int32_t* env_off, int32_t N, int32_t S,
             float gamma, float lambda, float* adv, float* ret,
             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ver_gae_static - ver_gae for callers that cannot allocate device memory or
+ * have none to hand over as a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels as ver_gae, without the workspace: the scan's scratch (ticket, error
+ * word, three 64-bit words per tile of 2048 steps) lives in a device array of
+ * fixed size inside the library, 48.25 KiB that every GPU the library is used
+ * on holds until the process ends.  The call allocates and frees nothing; the
+ * first call on a device looks the array's address up (once per device, with
+ * that device current).
+ * Limit: S <= VER_GAE_STATIC_MAX_STEPS, otherwise VER_ETOOLARGE and nothing is
+ * enqueued (the largest rollout of the paper's configurations has 32768 steps).
+ * Every call on a GPU uses that GPU's one array: the part a call uses is
+ * cleared on the stream before its kernel starts, so calls one after the other
+ * on a stream need nothing from the caller, but two calls of one process that
+ * may overlap in time on the same GPU (issued on different streams) race on it
+ * and must be ordered by the caller.  Another process has its own copy.
+ * The error word of ver_gae's workspace has no counterpart that the caller
+ * can read here: a wait that gave up shows as NaN outputs only.
+ */
+#define VER_GAE_STATIC_MAX_STEPS (1 << 22)
+int ver_gae_static(const float* rewards, const float* values, const uint8_t* dones,
+                   const float* last_values, const int32_t* env_off, int32_t N, int32_t S,
+                   float gamma, float lambda, float* adv, float* ret, void* stream);
 
 /* ------------------------------------------------------------------------
  * ver_is_weight - truncated importance weight of every step of the buffer.

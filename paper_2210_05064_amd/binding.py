@@ -58,6 +58,8 @@ lib.ver_gae_workspace_bytes.restype = _sz
 lib.ver_gae_workspace_bytes.argtypes = [_i32]
 lib.ver_gae.restype = C.c_int
 lib.ver_gae.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _f, _f, _vp, _vp, _vp, _sz, _vp]
+lib.ver_gae_static.restype = C.c_int
+lib.ver_gae_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _f, _f, _vp, _vp, _vp]
 lib.ver_ingest_workspace_bytes.restype = _sz
 lib.ver_ingest_workspace_bytes.argtypes = [_i32, _i32]
 lib.ver_ingest.restype = C.c_int
@@ -147,6 +149,11 @@ def ver_gae(rewards, values, dones, last_values, env_off, N, S, gamma, lam, adv,
     p, n = _ws(workspace)
     _check(lib.ver_gae(_ptr(rewards), _ptr(values), _ptr(dones), _ptr(last_values), _ptr(env_off),
                        N, S, gamma, lam, _ptr(adv), _ptr(ret), p, n, _stream()))
+
+
+def ver_gae_static(rewards, values, dones, last_values, env_off, N, S, gamma, lam, adv, ret):
+    _check(lib.ver_gae_static(_ptr(rewards), _ptr(values), _ptr(dones), _ptr(last_values), _ptr(env_off),
+                              N, S, gamma, lam, _ptr(adv), _ptr(ret), _stream()))
 
 
 def ver_ingest_workspace_bytes(N: int, S: int) -> int:

@@ -71,6 +71,7 @@ extern "C" const char* ver_status_string(int status) {
         case VER_EWORKSPACE: return "workspace missing or too small";
         case VER_EUNSUPPORTED: return "unsupported shape";
         case VER_EHIP: return "HIP call or kernel launch failed";
+        case VER_ETOOLARGE: return "input larger than the fixed scratch of this entry point (use the variant that takes a workspace)";
         default: return "unknown status";
     }
 }

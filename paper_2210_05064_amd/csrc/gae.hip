@@ -17,6 +17,8 @@
 // last step in LDS.
 // HBM traffic is the algorithmic 17 bytes per step: reward, value, done read
 // once (16-byte loads, staged through LDS), advantage and return written once.
+#include <mutex>
+
 #include "common.h"
 
 namespace ver {
@@ -421,5 +423,62 @@ extern "C" int ver_gae(const float* rewards, const float* values, const uint8_t*
     if (!rewards || !values || !dones || !last_values || !env_off || !adv || !ret || N == 0) return VER_EINVAL;
     if (!workspace || workspace_bytes < ver_gae_workspace_bytes(S)) return VER_EWORKSPACE;
     return ver::gae_launch(rewards, values, dones, last_values, env_off, N, S, gamma, lambda, adv, ret, workspace,
+                           static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------- ver_gae_static
+// The same scan for callers that cannot allocate device memory: the ticket, the error word and the words the
+// tiles publish live in a file-scope device array instead of a caller workspace.  Every GPU the library runs
+// on holds its own copy of the array at its own address, which is looked up once per device.
+namespace ver {
+namespace {
+constexpr size_t GAE_STATIC_TILES = (VER_GAE_STATIC_MAX_STEPS + GAE_TILE - 1) / GAE_TILE;
+constexpr size_t GAE_STATIC_BYTES = 256 + 3 * ((GAE_STATIC_TILES * 8 + 255) / 256 * 256);
+constexpr int GAE_STATIC_MAX_DEVICES = 64;
+}  // namespace
+}  // namespace ver
+
+static __device__ __align__(256) unsigned char scratch[ver::GAE_STATIC_BYTES];
+
+namespace ver {
+namespace {
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[GAE_STATIC_MAX_DEVICES];   // device address of `scratch` on every device seen so far
+
+// Address of the current device's copy of `scratch` (the array's name is only a host-side handle of the symbol).
+int scratch_of_current_device(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return VER_EHIP;
+    if (dev < 0 || dev >= GAE_STATIC_MAX_DEVICES) return VER_EUNSUPPORTED;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return VER_EHIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return VER_OK;
+}
+}  // namespace
+}  // namespace ver
+
+extern "C" int ver_gae_static(const float* rewards, const float* values, const uint8_t* dones,
+                              const float* last_values, const int32_t* env_off, int32_t N, int32_t S,
+                              float gamma, float lambda, float* adv, float* ret, void* stream) {
+    if (N < 0 || S < 0) return VER_EINVAL;
+    if (S == 0) return VER_OK;
+    if (!rewards || !values || !dones || !last_values || !env_off || !adv || !ret || N == 0) return VER_EINVAL;
+    if (S > VER_GAE_STATIC_MAX_STEPS) return VER_ETOOLARGE;
+    static_assert(ver::GAE_STATIC_BYTES >= 256 + 3 * 256, "scratch holds at least one tile");
+    if (ver_gae_workspace_bytes(S) > ver::GAE_STATIC_BYTES) return VER_ETOOLARGE;
+    void* mem = nullptr;
+    const int st = ver::scratch_of_current_device(&mem);
+    if (st != VER_OK) return st;
+    // the launch clears the part of the array it uses (a fill kernel, no memset node), so what the call
+    // before left there does not matter
+    return ver::gae_launch(rewards, values, dones, last_values, env_off, N, S, gamma, lambda, adv, ret, mem,
                            static_cast<hipStream_t>(stream));
 }

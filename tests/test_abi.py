@@ -34,8 +34,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings(lib):
     lib.ver_status_string.restype = C.c_char_p
-    seen = {lib.ver_status_string(c).decode() for c in (0, -1, -2, -3, -4)}
-    assert len(seen) == 5 and lib.ver_status_string(-99)
+    seen = {lib.ver_status_string(c).decode() for c in (0, -1, -2, -3, -4, -5)}
+    assert len(seen) == 6 and lib.ver_status_string(-99)
 
 
 def test_workspace_queries_are_host_only(lib):
