@@ -33,17 +33,43 @@ constexpr long long GAE_SPIN_LIMIT = 1LL << 24;  // polls before a wait gives up
 constexpr int GAE_MAX_BATCH = 16;      // tiles per ticket at most
 constexpr int GAE_BATCH_FROM = 1024;   // one more tile per ticket for every so many tiles
 
-// The maps are composed in fp64: the kernel is HBM bound, fp64 costs nothing here,
-// and the fp32 outputs then carry one rounding instead of an error that grows
-// with the length of the episode (returns = advantage + value cancels heavily
-// when the critic is far from the returns).
+// A map's offset b is kept in fp64 everywhere: advantages are sums of TD errors that cancel heavily (with
+// lambda = 1 they telescope to a discounted reward sum minus a value), so an fp32 sum of a thousand terms of size 1
+// leaves an error of 1e-5 of a return of size 0.1; fp64 sums leave the fp32 outputs with one rounding.  Inside a
+// tile the slope a (a product of at most 2048 factors gamma * lambda, or 0) is fp32: its rounding, a random walk
+// of ~3e-6 relative at most, scales what enters from above only.  From tile to tile both travel as fp64.
 struct Affine {
     double a, b;  // x -> b + a * x
+};
+struct AffineF {
+    float a;
+    double b;
 };
 // `first` is applied to the incoming value first (it is later in time), `then` after it.
 __device__ __forceinline__ Affine compose(Affine first, Affine then) {
     return Affine{then.a * first.a, then.b + then.a * first.b};
 }
+__device__ __forceinline__ AffineF compose(AffineF first, AffineF then) {
+    return AffineF{then.a * first.a, fma((double)then.a, first.b, then.b)};
+}
+// The value `v` of the lane that a data-parallel-primitive control selects, `idle` where it selects none: the wave
+// scan below moves maps between lanes with these (register-to-register) instead of through the LDS crossbar.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp(float idle, float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(idle), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ AffineF dpp_map(AffineF v) {   // lanes the control leaves out get the identity map
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(v.b);
+    const float lo = dpp<CTRL, ROW_MASK>(0.f, __uint_as_float((unsigned)bits));
+    const float hi = dpp<CTRL, ROW_MASK>(0.f, __uint_as_float((unsigned)(bits >> 32)));
+    const unsigned long long moved = ((unsigned long long)__float_as_uint(hi) << 32) | __float_as_uint(lo);
+    return AffineF{dpp<CTRL, ROW_MASK>(1.f, v.a), __longlong_as_double((long long)moved)};
+}
+constexpr int DPP_ROW_SHR = 0x110;      // + n: lane i of a row of 16 reads lane i - n of its row
+constexpr int DPP_WAVE_SHR1 = 0x138;    // lane i reads lane i - 1 of the wave
+constexpr int DPP_ROW_BCAST15 = 0x142;  // lane 15 of every row to all lanes of the next row
+constexpr int DPP_ROW_BCAST31 = 0x143;  // lane 31 to all lanes of rows 2 and 3
 
 // What a tile tells the tiles after it, one 64-bit word per number.  A word carries its own "present" mark:
 // 0 (what the workspace is cleared to) means not written yet, anything else is the bits of a double plus one
@@ -71,6 +97,16 @@ __device__ __forceinline__ void st_word(unsigned long long* p, unsigned long lon
 __device__ __forceinline__ Affine wave_shfl_up(Affine v, int d) {
     return Affine{__shfl_up(v.a, d, VER_WAVE), __shfl_up(v.b, d, VER_WAVE)};
 }
+// Inclusive scan of the wave's maps in lane order (lane l's map is applied after those of the lanes below it).
+__device__ __forceinline__ AffineF wave_scan(AffineF m) {
+    m = compose(dpp_map<DPP_ROW_SHR + 1, 0xf>(m), m);
+    m = compose(dpp_map<DPP_ROW_SHR + 2, 0xf>(m), m);
+    m = compose(dpp_map<DPP_ROW_SHR + 4, 0xf>(m), m);
+    m = compose(dpp_map<DPP_ROW_SHR + 8, 0xf>(m), m);     // every row of 16 lanes is scanned
+    m = compose(dpp_map<DPP_ROW_BCAST15, 0xa>(m), m);     // rows 1 and 3 take in the whole row below
+    m = compose(dpp_map<DPP_ROW_BCAST31, 0xc>(m), m);     // rows 2 and 3 take in the lower half of the wave
+    return m;
+}
 
 // Where step i of a tile sits in the LDS arrays.  A thread walks a group of 8 consecutive steps (group i / 8), so
 // the arrays are kept transposed, one row per position inside a group: the lanes of a wave, which are at the same
@@ -90,7 +126,7 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
     __shared__ float s_boot[GAE_LDS];   // value after an environment's last step (only read where s_d says so)
     // flags of step i in byte i (a thread reads its group's 8 flags as one 64-bit word)
     __shared__ __attribute__((aligned(8))) uint8_t s_d[GAE_TILE + 8];   // bit 0: episode ended with this step; bit 1: last step of its environment
-    __shared__ Affine s_wave[GAE_THREADS / VER_WAVE];
+    __shared__ AffineF s_wave[GAE_THREADS / VER_WAVE];
     __shared__ int s_ticket;
     __shared__ int s_env[2];
     __shared__ double s_carry, s_leaving;
@@ -213,6 +249,7 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
     const int group = ((count + 7) >> 3) - 1 - tid;
     const int top = group * 8 + 7;
     const double gl = (double)gamma * (double)lambda;
+    const float glf = (float)gl;
     const unsigned long long flags = group >= 0 ? *reinterpret_cast<const unsigned long long*>(s_d + group * 8) : 0ull;
     // the map of step top - i; across the scan a thread keeps the b of its 8 maps and one bit for each a (which
     // is either 0 or gamma * lambda)
@@ -220,42 +257,36 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
         const int q = lds_at(top - i);
         const int f = (int)(flags >> (8 * (7 - i))) & 0xFF;
         const bool last = (f & 2) != 0;
-        const double nd = (f & 1) ? 0.0 : 1.0;
+        const bool cut = (f & 1) != 0;
         const double v_next = last ? s_boot[q] : s_v[lds_at(top - i + 1)];
-        return Affine{last ? 0.0 : gl * nd, (double)s_r[q] + (double)gamma * nd * v_next - (double)s_v[q]};
+        return AffineF{(last || cut) ? 0.f : glf, fma(cut ? 0.0 : (double)gamma, v_next, (double)s_r[q]) - (double)s_v[q]};
     };
-    Affine mine{1.0, 0.0};
+    AffineF mine{1.f, 0.0};
     double b_of[GAE_ITEMS];
     unsigned a_zero = 0;
 #pragma unroll
     for (int i = 0; i < GAE_ITEMS; ++i) {
         b_of[i] = 0.0;
         if (group >= 0 && top - i < count) {
-            const Affine m = map_of(i);
+            const AffineF m = map_of(i);
             b_of[i] = m.b;
-            a_zero |= (m.a == 0.0 ? 1u : 0u) << i;
+            a_zero |= (m.a == 0.f ? 1u : 0u) << i;
             mine = compose(mine, m);
         }
     }
 
     // Exclusive scan of the per-thread maps over the tile (thread order = processing order).
-    Affine incl = mine;
-#pragma unroll
-    for (int d = 1; d < VER_WAVE; d <<= 1) {
-        Affine up = wave_shfl_up(incl, d);
-        if (lane >= d) incl = compose(up, incl);
-    }
+    const AffineF incl = wave_scan(mine);
     if (lane == VER_WAVE - 1) s_wave[wave] = incl;
     bar_lds();
-    Affine before{1.0, 0.0};  // everything in the tile processed before this thread
+    AffineF before{1.f, 0.0};  // everything in the tile processed before this thread
     for (int w = 0; w < wave; ++w) before = compose(before, s_wave[w]);
-    Affine excl_in_wave = wave_shfl_up(incl, 1);
-    if (lane > 0) before = compose(before, excl_in_wave);
+    before = compose(before, dpp_map<DPP_WAVE_SHR1, 0xf>(incl));   // (lane 0 gets the identity)
 
     // Chained scan across tiles (wave 0).
     if (wave == 0) {
         Affine tile_map{1.0, 0.0};
-        for (int w = 0; w < GAE_THREADS / VER_WAVE; ++w) tile_map = compose(tile_map, s_wave[w]);
+        for (int w = 0; w < GAE_THREADS / VER_WAVE; ++w) tile_map = compose(tile_map, Affine{(double)s_wave[w].a, (double)s_wave[w].b});
         const bool cut = tile == 0 || tile_map.a == 0.0;   // incoming value is 0 or irrelevant
         if (lane == 0) {
             if (cut) {
@@ -333,12 +364,12 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
     if (map_only) continue;   // (uniform; the barrier above also protects the LDS arrays that the next pass refills)
     carry_known = s_leaving;
 
-    double x = before.b + before.a * s_carry;  // advantage at the step after this thread's first
+    double x = fma((double)before.a, s_carry, before.b);  // advantage at the step after this thread's first
 #pragma unroll
     for (int i = 0; i < GAE_ITEMS; ++i) {
         const int idx = top - i;
         if (group >= 0 && idx < count) {
-            x = b_of[i] + ((a_zero >> i) & 1u ? 0.0 : gl) * x;
+            x = fma((a_zero >> i) & 1u ? 0.0 : gl, x, b_of[i]);
             const int q = lds_at(idx);
             const float v = s_v[q];
             s_r[q] = (float)x;

@@ -11,9 +11,9 @@
 //                      K sequences / n_seq pieces, far below a microsecond of
 //                      HBM time, so one CU with LDS-staged prefix sums and
 //                      wave ballots beats a multi-launch device-wide version.
-//   pack_gather_kernel one wave per packed row: resolves the row's flat step
-//                      (binary search in t_off) and copies the row's fields
-//                      with 16-byte accesses.  This is the HBM-bound part:
+//   pack_gather_kernel a workgroup per 8 packed rows: resolves their flat steps
+//                      (one search in t_off per workgroup) and copies the rows'
+//                      fields with 16-byte accesses.  This is the HBM-bound part:
 //                      2*4*D bytes per row (6*D with bf16 output) + small fields.
 #include "common.h"
 
@@ -342,94 +342,138 @@ __device__ __forceinline__ void copy_state_row(float* __restrict__ dst, const fl
     }
 }
 
-__global__ __launch_bounds__(GATHER_THREADS) void pack_gather_kernel(GatherArgs g) {
-    const int lane = threadIdx.x & (VER_WAVE - 1);
-    const int p = blockIdx.x * GATHER_WAVES + threadIdx.x / VER_WAVE;  // one wave per packed row
-    if (p >= g.M) return;
-    const int n_seq = g.info[0], t_max = g.info[1];
-    // timestep of row p: t_off[t] <= p < t_off[t+1].  A 64-ary search: every lane probes one of 64 evenly spaced
-    // offsets of the current range and a ballot counts how many are <= p, so the range shrinks 64-fold per
-    // (dependent) load instead of 2-fold: 3 round trips to L2 instead of 13 for 8192 timesteps.
-    int a = 0, z = t_max;  // invariant: t_off[a] <= p < t_off[z]
-    while (z - a > 1) {
-        const int step = (z - a + VER_WAVE - 1) / VER_WAVE;
-        const int idx = a + lane * step;
-        const bool le = idx < z && g.t_off[idx] <= p;      // true for a prefix of the lanes (lane 0 always)
-        const int cnt = __popcll(__ballot(le));
-        a += (cnt - 1) * step;
-        z = min(z, a + step);
-    }
-    const int t = a, j = p - g.t_off[a];
-    const int src = g.seq_first[j] + t;
-    if (lane == 0) g.gather_idx[p] = src;
+constexpr int GATHER_ROWS = 8;   // packed rows per workgroup, two per wave (measured: 4 -> 57 %, 8 -> 61 %, 16 -> 59 %, 32 -> 57 % of the HBM peak)
 
-    if (g.obs && g.obs_packed) {
-        const float* in = g.obs + (size_t)src * g.D;
-        if ((g.D & 3) == 0) {
-            const f32x4* in4 = reinterpret_cast<const f32x4*>(in);
-            if (g.obs_bf16) {
-                u16x4* out4 = reinterpret_cast<u16x4*>(static_cast<unsigned short*>(g.obs_packed) + (size_t)p * g.D);
-                // four loads in flight per lane before the first conversion (a row is read once, from memory)
-                const int n4 = g.D / 4;
-                for (int i0 = lane; i0 < n4; i0 += 4 * VER_WAVE) {
-                    f32x4 v[4];
+// Copies the observation rows A and (unless inB is null) B, n4 16-byte chunks each, with the loads of both rows
+// in flight before the first store (a row is read once, from memory).  BF16: converts to bf16 on the way.
+template <bool BF16>
+__device__ __forceinline__ void copy_obs_pair(const f32x4* __restrict__ inA, const f32x4* __restrict__ inB,
+                                              void* __restrict__ outA, void* __restrict__ outB, int n4, int lane) {
+    for (int c0 = 0; c0 < n4; c0 += 4 * VER_WAVE) {
+        f32x4 va[4], vb[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * VER_WAVE;
-                        v[u] = __builtin_nontemporal_load(in4 + (i < n4 ? i : lane));
-                    }
+        for (int u = 0; u < 4; ++u) {
+            if (c0 + u * VER_WAVE >= n4) break;   // (uniform: whole chunk groups beyond the row are skipped)
+            const int i = c0 + u * VER_WAVE + lane;
+            // (ordinary loads: non-temporal ones measured 2 % slower here, non-temporal stores 1 % slower)
+            va[u] = inA[i < n4 ? i : c0];
+            if (inB) vb[u] = inB[i < n4 ? i : c0];
+        }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * VER_WAVE;
-                        if (i >= n4) break;
-                        u16x4 o;
-                        o.x = f32_to_bf16_rne(v[u].x); o.y = f32_to_bf16_rne(v[u].y);
-                        o.z = f32_to_bf16_rne(v[u].z); o.w = f32_to_bf16_rne(v[u].w);
-                        out4[i] = o;
-                    }
+        for (int u = 0; u < 4; ++u) {
+            if (c0 + u * VER_WAVE >= n4) break;
+            const int i = c0 + u * VER_WAVE + lane;
+            if (i >= n4) continue;
+            if (BF16) {
+                u16x4 o;
+                o.x = f32_to_bf16_rne(va[u].x); o.y = f32_to_bf16_rne(va[u].y);
+                o.z = f32_to_bf16_rne(va[u].z); o.w = f32_to_bf16_rne(va[u].w);
+                static_cast<u16x4*>(outA)[i] = o;
+                if (inB) {
+                    o.x = f32_to_bf16_rne(vb[u].x); o.y = f32_to_bf16_rne(vb[u].y);
+                    o.z = f32_to_bf16_rne(vb[u].z); o.w = f32_to_bf16_rne(vb[u].w);
+                    static_cast<u16x4*>(outB)[i] = o;
                 }
             } else {
-                f32x4* out4 = reinterpret_cast<f32x4*>(static_cast<float*>(g.obs_packed) + (size_t)p * g.D);
-                const int n4 = g.D / 4;
-                for (int i0 = lane; i0 < n4; i0 += 4 * VER_WAVE) {
-                    f32x4 v[4];
+                static_cast<f32x4*>(outA)[i] = va[u];
+                if (inB) static_cast<f32x4*>(outB)[i] = vb[u];
+            }
+        }
+    }
+}
+
+// A workgroup gathers GATHER_ROWS consecutive packed rows.  Wave 0 places them: a 64-ary search in t_off for the
+// timestep of the first row (every lane probes one of 64 evenly spaced offsets of the current range and a ballot
+// counts how many are <= p: 3 dependent loads for 8192 timesteps), then ONE load of the next offsets, from which
+// every row's timestep follows by counting (a timestep holds at least one row, so n rows span at most n
+// timesteps), then one load of the piece's first step.  After that all four waves copy rows, two rows and up to
+// eight 16-byte loads per lane in flight at a time, and the small per-row fields go lane-parallel over the rows.
+__global__ __launch_bounds__(GATHER_THREADS) void pack_gather_kernel(GatherArgs g) {
+    __shared__ int s_src[GATHER_ROWS], s_t[GATHER_ROWS], s_j[GATHER_ROWS];
+    const int tid = threadIdx.x, lane = tid & (VER_WAVE - 1), wave = tid / VER_WAVE;
+    const int p0 = blockIdx.x * GATHER_ROWS;
+    const int nrows = min(GATHER_ROWS, g.M - p0);
+    if (nrows <= 0) return;
+    const int n_seq = g.info[0], t_max = g.info[1];
+    if (wave == 0) {
+        int a = 0, z = t_max;  // invariant: t_off[a] <= p0 < t_off[z]
+        while (z - a > 1) {
+            const int step = (z - a + VER_WAVE - 1) / VER_WAVE;
+            const int idx = a + lane * step;
+            const bool le = idx < z && g.t_off[idx] <= p0;      // true for a prefix of the lanes (lane 0 always)
+            const int cnt = max(1, (int)__popcll(__ballot(le)));
+            a += (cnt - 1) * step;
+            z = min(z, a + step);
+        }
+        // lane l: t_off[a + l] for l = 0 .. GATHER_ROWS (t_off[t_max] = M lies above every row)
+        const int o = g.t_off[min(a + min(lane, GATHER_ROWS), t_max)];
+        const int p = p0 + min(lane, nrows - 1);
+        int cnt = 0;
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * VER_WAVE;
-                        v[u] = __builtin_nontemporal_load(in4 + (i < n4 ? i : lane));
-                    }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int i = i0 + u * VER_WAVE;
-                        if (i < n4) out4[i] = v[u];
-                    }
-                }
+        for (int i = 1; i <= GATHER_ROWS; ++i) cnt += (__shfl(o, i, VER_WAVE) <= p) ? 1 : 0;
+        cnt = min(cnt, GATHER_ROWS - 1);   // (holds for well-formed offsets; keeps the shuffle below in range otherwise)
+        const int t = a + cnt;
+        const int j = p - __shfl(o, cnt, VER_WAVE);
+        if (lane < nrows) {
+            const int src = g.seq_first[j] + t;
+            s_src[lane] = src; s_t[lane] = t; s_j[lane] = j;
+            g.gather_idx[p] = src;
+        }
+    }
+    __syncthreads();
+
+    if (g.obs && g.obs_packed) {
+        if ((g.D & 3) == 0) {
+            const int n4 = g.D / 4;
+            const size_t out_row = (size_t)g.D * (g.obs_bf16 ? 2 : 4);
+            for (int r = wave; r < nrows; r += 2 * GATHER_WAVES) {
+                const int rb = r + GATHER_WAVES;
+                const f32x4* inA = reinterpret_cast<const f32x4*>(g.obs + (size_t)s_src[r] * g.D);
+                const f32x4* inB = rb < nrows ? reinterpret_cast<const f32x4*>(g.obs + (size_t)s_src[rb] * g.D) : nullptr;
+                char* outA = static_cast<char*>(g.obs_packed) + (size_t)(p0 + r) * out_row;
+                char* outB = static_cast<char*>(g.obs_packed) + (size_t)(p0 + rb) * out_row;
+                if (g.obs_bf16) copy_obs_pair<true>(inA, inB, outA, outB, n4, lane);
+                else copy_obs_pair<false>(inA, inB, outA, outB, n4, lane);
             }
         } else {
-            for (int i = lane; i < g.D; i += VER_WAVE) {
-                if (g.obs_bf16) static_cast<unsigned short*>(g.obs_packed)[(size_t)p * g.D + i] = f32_to_bf16_rne(in[i]);
-                else static_cast<float*>(g.obs_packed)[(size_t)p * g.D + i] = in[i];
+            for (int r = wave; r < nrows; r += GATHER_WAVES) {
+                const float* in = g.obs + (size_t)s_src[r] * g.D;
+                const size_t po = (size_t)(p0 + r) * g.D;
+                for (int i = lane; i < g.D; i += VER_WAVE) {
+                    if (g.obs_bf16) static_cast<unsigned short*>(g.obs_packed)[po + i] = f32_to_bf16_rne(in[i]);
+                    else static_cast<float*>(g.obs_packed)[po + i] = in[i];
+                }
             }
         }
     }
     if (g.actions && g.actions_packed) {
-        const uint8_t* in = g.actions + (size_t)src * g.act_bytes;
-        uint8_t* out = g.actions_packed + (size_t)p * g.act_bytes;
         if ((g.act_bytes & 3) == 0) {
-            for (int i = lane; i < g.act_bytes / 4; i += VER_WAVE)
-                reinterpret_cast<int32_t*>(out)[i] = reinterpret_cast<const int32_t*>(in)[i];
+            const int aw = g.act_bytes / 4;
+            for (int i = tid; i < nrows * aw; i += GATHER_THREADS) {
+                const int r = i / aw, c = i - r * aw;
+                reinterpret_cast<int32_t*>(g.actions_packed + (size_t)(p0 + r) * g.act_bytes)[c] =
+                    reinterpret_cast<const int32_t*>(g.actions + (size_t)s_src[r] * g.act_bytes)[c];
+            }
         } else {
-            for (int i = lane; i < g.act_bytes; i += VER_WAVE) out[i] = in[i];
+            for (int i = tid; i < nrows * g.act_bytes; i += GATHER_THREADS) {
+                const int r = i / g.act_bytes, c = i - r * g.act_bytes;
+                g.actions_packed[(size_t)(p0 + r) * g.act_bytes + c] = g.actions[(size_t)s_src[r] * g.act_bytes + c];
+            }
         }
     }
-    if (lane == 0) {
-        if (g.logp_old && g.logp_old_packed) g.logp_old_packed[p] = g.logp_old[src];
-        if (g.adv && g.adv_packed) g.adv_packed[p] = g.adv[src];
-        if (g.ret && g.ret_packed) g.ret_packed[p] = g.ret[src];
-        if (g.is_weight && g.is_weight_packed) g.is_weight_packed[p] = g.is_weight[src];
+    // the per-row scalars: field f of row r in thread f * GATHER_ROWS + r
+    for (int i = tid; i < 4 * nrows; i += GATHER_THREADS) {
+        const int f = i / nrows, r = i - f * nrows;
+        const int src = s_src[r], p = p0 + r;
+        if (f == 0 && g.logp_old && g.logp_old_packed) g.logp_old_packed[p] = g.logp_old[src];
+        if (f == 1 && g.adv && g.adv_packed) g.adv_packed[p] = g.adv[src];
+        if (f == 2 && g.ret && g.ret_packed) g.ret_packed[p] = g.ret[src];
+        if (f == 3 && g.is_weight && g.is_weight_packed) g.is_weight_packed[p] = g.is_weight[src];
     }
     // rows of timestep 0 are the pieces' first steps: fetch their initial recurrent state
-    if (t == 0 && j < n_seq && j < g.seq_cap) {
+    for (int r = wave; r < nrows; r += GATHER_WAVES) {
+        const int j = s_j[r], src = s_src[r];
+        if (s_t[r] != 0 || j >= n_seq || j >= g.seq_cap) continue;
         const bool zero = g.seq_eps[j] != 0;
         for (int l = 0; l < g.n_layers; ++l) {
             const size_t in_off = ((size_t)l * g.S + src) * g.H, out_off = ((size_t)l * g.seq_cap + j) * g.H;
@@ -625,7 +669,7 @@ extern "C" int ver_pack_minibatch(const ver_pack_args* a, void* stream) {
     g.seq_cap = a->seq_cap; g.h0 = a->h0; g.c0 = a->c0;
     g.state_vec4 = a->H % 4 == 0 && ((reinterpret_cast<uintptr_t>(a->rnn_h) | reinterpret_cast<uintptr_t>(a->rnn_c) |
                                       reinterpret_cast<uintptr_t>(a->h0) | reinterpret_cast<uintptr_t>(a->c0)) & 15) == 0;
-    const int blocks = (M + ver::GATHER_WAVES - 1) / ver::GATHER_WAVES;
+    const int blocks = (M + ver::GATHER_ROWS - 1) / ver::GATHER_ROWS;
     ver::ProfScope prof(VER_PROF_PACK_GATHER, s);
     hipLaunchKernelGGL(ver::pack_gather_kernel, dim3(blocks), dim3(ver::GATHER_THREADS), 0, s, g);
     return ver::launch_status();

@@ -103,10 +103,13 @@ BIG = 2048 * 256 + 3 * 256 + 77   # more rows than one sweep of the grid covers 
 
 
 @pytest.mark.parametrize("dist,A,shift,M", [(1, 11, 0, BIG), (0, 4, 1, BIG), (1, 20, 0, BIG), (1, 11, 1, 5000),
-                                             (0, 4, 0, 5000)])
+                                             (0, 4, 0, 5000), (1, 11, 0, BIG - 1), (0, 4, 0, BIG), (1, 6, 0, BIG + 1),
+                                             (1, 16, 0, 70001), (0, 3, 0, 40004), (1, 1, 0, 12)])
 def test_loss_several_rounds_per_workgroup(ver, dist, A, shift, M):
     """Several blocks per workgroup and a ragged last block; shift = 1: row arrays that start 4 bytes past a
-    16-byte boundary (the word-by-word copies)."""
+    16-byte boundary (the word-by-word copies).  Aligned arrays with M * A a multiple of 4 and A <= 16 take the
+    kernel specialised on the row width (BIG - 1 rows of 11, BIG of 4, BIG + 1 of 6, 70001 of 16, 40004 of 3, 12 of
+    1), every other case the general one."""
     rng = np.random.default_rng(40 + A)
     u = rng.standard_normal((M, A)).astype(np.float32)
     value, ret, adv = (rng.standard_normal(M).astype(np.float32) for _ in range(3))
