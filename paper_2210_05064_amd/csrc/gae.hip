@@ -16,7 +16,8 @@
 // the offsets for the tile's ends, then the environments in between mark their
 // last step in LDS.
 // HBM traffic is the algorithmic 17 bytes per step: reward, value, done read
-// once (16-byte loads, staged through LDS), advantage and return written once.
+// once, advantage and return written once, by the thread that works on the 8
+// consecutive steps, 16 bytes at a time (nothing is staged through LDS).
 #include <mutex>
 
 #include "common.h"
@@ -27,8 +28,6 @@ namespace {
 constexpr int GAE_THREADS = 256;
 constexpr int GAE_ITEMS = 8;
 constexpr int GAE_TILE = GAE_THREADS * GAE_ITEMS;
-constexpr int GAE_ROW = GAE_THREADS + 1;               // LDS row of one item position (see lds_at)
-constexpr int GAE_LDS = GAE_ITEMS * GAE_ROW;
 constexpr long long GAE_SPIN_LIMIT = 1LL << 24;  // polls before a wait gives up
 constexpr int GAE_MAX_BATCH = 16;      // tiles per ticket at most
 constexpr int GAE_BATCH_FROM = 1024;   // one more tile per ticket for every so many tiles
@@ -108,12 +107,7 @@ __device__ __forceinline__ AffineF wave_scan(AffineF m) {
     return m;
 }
 
-// Where step i of a tile sits in the LDS arrays.  A thread walks a group of 8 consecutive steps (group i / 8), so
-// the arrays are kept transposed, one row per position inside a group: the lanes of a wave, which are at the same
-// position of neighbouring groups, then touch neighbouring words.  Rows are one word longer than the number of
-// groups, which also spreads the 4 consecutive steps a thread handles when the tile is copied in and out.
-__device__ __forceinline__ int lds_at(int i) { return (i & 7) * GAE_ROW + (i >> 3); }
-static_assert(GAE_ITEMS == 8, "lds_at and the flag words assume groups of 8");
+static_assert(GAE_ITEMS == 8, "a thread's group of steps: two 16-byte loads per array, one 64-bit word of flags");
 
 template <bool VEC>
 __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
@@ -121,19 +115,20 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
     const uint8_t* __restrict__ dones, const float* __restrict__ last_values,
     const int32_t* __restrict__ env_off, int N, int S, int ntiles, int batch, float gamma, float lambda,
     float* __restrict__ adv, float* __restrict__ ret, GaeWs ws) {
-    __shared__ float s_r[GAE_LDS];
-    __shared__ float s_v[GAE_LDS];
-    __shared__ float s_boot[GAE_LDS];   // value after an environment's last step (only read where s_d says so)
-    // flags of step i in byte i (a thread reads its group's 8 flags as one 64-bit word)
-    __shared__ __attribute__((aligned(8))) uint8_t s_d[GAE_TILE + 8];   // bit 0: episode ended with this step; bit 1: last step of its environment
+    // The tile's steps never pass through LDS: a thread reads the 8 consecutive steps it works on straight into
+    // registers (two 16-byte loads per array) and writes its 8 results the same way.  LDS only holds which steps
+    // end an environment, and the value after such a step.
+    __shared__ float s_boot[GAE_TILE];   // value after an environment's last step (only read where s_last says so)
+    __shared__ __attribute__((aligned(8))) uint8_t s_last[GAE_TILE + 8];   // byte i: non-zero if step i of the tile is the last of its environment
     __shared__ AffineF s_wave[GAE_THREADS / VER_WAVE];
     __shared__ int s_ticket;
-    __shared__ int s_env[2];
     __shared__ double s_carry, s_leaving;
 
     const int tid = threadIdx.x;
     const int lane = tid & (VER_WAVE - 1), wave = tid / VER_WAVE;
     if (tid == 0) s_ticket = atomicAdd(ws.ticket, 1);
+    *reinterpret_cast<unsigned long long*>(s_last + tid * 8) = 0ull;   // (every reader clears what it has read)
+    if (tid == 0) *reinterpret_cast<unsigned long long*>(s_last + GAE_TILE) = 0ull;
     __syncthreads();
     // A ticket stands for `batch` consecutive tiles, which this workgroup processes one after the other and hands
     // the advantage from one to the next itself (a ticket is an atomic on one address, ~50 ns each across the
@@ -155,32 +150,45 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
     const int count = min(GAE_TILE, S - k_lo);
     const int k_hi = k_lo + count - 1;
 
-    // The tile's steps, first into registers (16-byte path): the loads are in flight while the environments of
-    // the tile are looked up below.
-    constexpr int GAE_FETCH = GAE_TILE / (GAE_THREADS * 4);
-    float4 f_r[GAE_FETCH], f_v[GAE_FETCH];
-    uint32_t f_d[GAE_FETCH];
-    if (VEC) {
+    // Thread tid handles group n_groups - 1 - tid of 8 consecutive steps, from its last step down (processing
+    // order = time descending; the topmost group of a ragged tile is short).
+    const int group = ((count + 7) >> 3) - 1 - tid;
+    const int g0 = group * 8;                      // the group's first step inside the tile
+    const bool whole = VEC && group >= 0 && g0 + 8 <= count;
+    // (Fetching the next tile's steps a pass ahead into a second set of registers was measured: no faster, the
+    // registers cost a wave per SIMD.)
+    float r8[GAE_ITEMS], v8[GAE_ITEMS];
+    uint32_t d_lo = 0, d_hi = 0;                   // the 8 done bytes
+    float v_after = 0.f;                           // value of the step after the group's last one (0 beyond the buffer)
+    if (whole) {
+        const float4 ra = *reinterpret_cast<const float4*>(rewards + k_lo + g0), rb = *reinterpret_cast<const float4*>(rewards + k_lo + g0 + 4);
+        const float4 va = *reinterpret_cast<const float4*>(values + k_lo + g0), vb = *reinterpret_cast<const float4*>(values + k_lo + g0 + 4);
+        d_lo = *reinterpret_cast<const uint32_t*>(dones + k_lo + g0);
+        d_hi = *reinterpret_cast<const uint32_t*>(dones + k_lo + g0 + 4);
+        r8[0] = ra.x; r8[1] = ra.y; r8[2] = ra.z; r8[3] = ra.w; r8[4] = rb.x; r8[5] = rb.y; r8[6] = rb.z; r8[7] = rb.w;
+        v8[0] = va.x; v8[1] = va.y; v8[2] = va.z; v8[3] = va.w; v8[4] = vb.x; v8[5] = vb.y; v8[6] = vb.z; v8[7] = vb.w;
+    } else {
 #pragma unroll
-        for (int it = 0; it < GAE_FETCH; ++it) {
-            const int i = (it * GAE_THREADS + tid) * 4;
-            if (i + 4 <= count) {
-                f_r[it] = *reinterpret_cast<const float4*>(rewards + k_lo + i);
-                f_v[it] = *reinterpret_cast<const float4*>(values + k_lo + i);
-                f_d[it] = *reinterpret_cast<const uint32_t*>(dones + k_lo + i);
+        for (int j = 0; j < GAE_ITEMS; ++j) {
+            r8[j] = v8[j] = 0.f;
+            if (group >= 0 && g0 + j < count) {
+                r8[j] = rewards[k_lo + g0 + j];
+                v8[j] = values[k_lo + g0 + j];
+                const uint32_t d = dones[k_lo + g0 + j] ? 1u : 0u;
+                if (j < 4) d_lo |= d << (8 * j); else d_hi |= d << (8 * (j - 4));
             }
         }
     }
-    // Environments of the tile's first and last step.  From the second tile of a batch on they follow from the
-    // tile before (the one just above in memory): that tile's first environment bounds this one's last, and this
-    // one's first is found by walking down from there, 64 offsets at a time (one round of loads instead of four
-    // dependent ones).
-    int m_lo = 0, m_hi = 0, m_env = -1;   // wave 0: offsets of environment (first of the tile) + lane, fetched early
-    float m_boot = 0.f;
+    if (group >= 0 && k_lo + g0 + 8 < S) v_after = values[k_lo + g0 + 8];
+
+    // Which steps of the tile end an environment (wave 0; the loads above are in flight meanwhile).  Environments
+    // of the tile's first and last step: from the second tile of a batch on they follow from the tile before (the
+    // one just above in memory): that tile's first environment bounds this one's last, and this one's first is
+    // found by walking down from there, 64 offsets at a time (one round of loads instead of four dependent ones).
     if (wave == 0) {
-        int e;
+        int e, e_hi;
         if (pass >= 1) {
-            e = env_first_above;
+            e = e_hi = env_first_above;
             for (;;) {
                 const int probe = e - lane;
                 const unsigned long long ok = __ballot(probe >= 0 && env_off[probe] <= k_lo);   // monotone in the lane
@@ -188,87 +196,45 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
                 e -= VER_WAVE;
                 if (e < 0) { e = 0; break; }   // (env_off[0] = 0 ends the walk before this; malformed input must not run away)
             }
-            if (lane == 0) s_env[1] = env_first_above;
         } else {
             e = segment_of_wave(env_off, N, k_lo);
+            e_hi = segment_of_wave(env_off, N, k_hi);
         }
-        if (lane == 0) s_env[0] = e;
-        if (e + lane < N) {
-            m_env = e + lane;
-            m_lo = env_off[m_env];
-            m_hi = env_off[m_env + 1];
-            m_boot = last_values[m_env];
-        }
-    } else if (wave == 1 && pass < 1) {
-        const int e = segment_of_wave(env_off, N, k_hi);
-        if (lane == 0) s_env[1] = e;
-    }
-#pragma unroll
-    for (int it = 0; it < GAE_FETCH; ++it) {
-        const int i = (it * GAE_THREADS + tid) * 4;
-        if (VEC && i + 4 <= count) {
-            const float4 r4 = f_r[it], v4 = f_v[it];
-            const uint32_t d4 = f_d[it];
-            const int q = lds_at(i);   // i is a multiple of 4: the four steps are in the same group, one row apart
-            s_r[q] = r4.x; s_r[q + GAE_ROW] = r4.y; s_r[q + 2 * GAE_ROW] = r4.z; s_r[q + 3 * GAE_ROW] = r4.w;
-            s_v[q] = v4.x; s_v[q + GAE_ROW] = v4.y; s_v[q + 2 * GAE_ROW] = v4.z; s_v[q + 3 * GAE_ROW] = v4.w;
-            // 0x01 in every byte of d4 that is not zero
-            *reinterpret_cast<uint32_t*>(s_d + i) = ((((d4 & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | d4) & 0x80808080u) >> 7;
-        } else {
-            for (int j = i; j < min(i + 4, count); ++j) {
-                s_r[lds_at(j)] = rewards[k_lo + j];
-                s_v[lds_at(j)] = values[k_lo + j];
-                s_d[j] = dones[k_lo + j] ? 1 : 0;
+        env_first_above = e;
+        // mark the last step of every environment that ends inside the tile and keep its bootstrap value
+        for (int m = e + lane; m <= e_hi; m += VER_WAVE) {
+            const int lo = env_off[m], hi = env_off[m + 1];
+            const int i = hi - 1 - k_lo;
+            if (hi > lo && i >= 0 && i < count) {
+                s_last[i] = 1;
+                s_boot[i] = last_values[m];
             }
         }
     }
-    if (tid == 0) s_v[lds_at(count)] = (k_hi + 1 < S) ? values[k_hi + 1] : 0.f;
     bar_lds();
-    // mark the last step of every environment that ends inside the tile and keep its bootstrap value: the first
-    // 64 environments from what wave 0 fetched above, any further ones (rows of empty environments) from memory
-    if (wave == 0 && m_env >= 0 && m_env <= s_env[1]) {
-        const int i = m_hi - 1 - k_lo;
-        if (m_hi > m_lo && i >= 0 && i < count) {
-            s_d[i] |= 2;
-            s_boot[lds_at(i)] = m_boot;
-        }
+    unsigned long long lasts = 0ull;
+    if (group >= 0) {
+        lasts = *reinterpret_cast<const unsigned long long*>(s_last + g0);
+        if (lasts) *reinterpret_cast<unsigned long long*>(s_last + g0) = 0ull;   // clean for the next tile
     }
-    for (int e = s_env[0] + VER_WAVE + tid; e <= s_env[1]; e += GAE_THREADS) {
-        const int lo = env_off[e], hi = env_off[e + 1];
-        const int i = hi - 1 - k_lo;
-        if (hi > lo && i >= 0 && i < count) {
-            s_d[i] |= 2;
-            s_boot[lds_at(i)] = last_values[e];
-        }
-    }
-    bar_lds();
-    env_first_above = s_env[0];
 
-    // Thread tid handles group n_groups - 1 - tid of 8 consecutive steps, from its last step down (processing
-    // order = time descending; the topmost group of a ragged tile is short).
-    const int group = ((count + 7) >> 3) - 1 - tid;
-    const int top = group * 8 + 7;
     const double gl = (double)gamma * (double)lambda;
     const float glf = (float)gl;
-    const unsigned long long flags = group >= 0 ? *reinterpret_cast<const unsigned long long*>(s_d + group * 8) : 0ull;
-    // the map of step top - i; across the scan a thread keeps the b of its 8 maps and one bit for each a (which
-    // is either 0 or gamma * lambda)
-    auto map_of = [&](int i) {
-        const int q = lds_at(top - i);
-        const int f = (int)(flags >> (8 * (7 - i))) & 0xFF;
-        const bool last = (f & 2) != 0;
-        const bool cut = (f & 1) != 0;
-        const double v_next = last ? s_boot[q] : s_v[lds_at(top - i + 1)];
-        return AffineF{(last || cut) ? 0.f : glf, fma(cut ? 0.0 : (double)gamma, v_next, (double)s_r[q]) - (double)s_v[q]};
-    };
+    // the map of step g0 + 7 - i; across the scan a thread keeps the b of its 8 maps and one bit for each a
+    // (which is either 0 or gamma * lambda)
     AffineF mine{1.f, 0.0};
     double b_of[GAE_ITEMS];
     unsigned a_zero = 0;
 #pragma unroll
     for (int i = 0; i < GAE_ITEMS; ++i) {
+        const int j = GAE_ITEMS - 1 - i;               // position inside the group
         b_of[i] = 0.0;
-        if (group >= 0 && top - i < count) {
-            const AffineF m = map_of(i);
+        if (group >= 0 && g0 + j < count) {
+            const bool cut = ((j < 4 ? d_lo >> (8 * j) : d_hi >> (8 * (j - 4))) & 0xFFu) != 0;
+            const bool last = ((lasts >> (8 * j)) & 0xFFull) != 0;
+            float v_next = j + 1 < GAE_ITEMS ? v8[j + 1 < GAE_ITEMS ? j + 1 : j] : v_after;
+            if (last) v_next = s_boot[g0 + j];
+            const AffineF m{(last || cut) ? 0.f : glf, fma(cut ? 0.0 : (double)gamma, (double)v_next, (double)r8[j]) - (double)v8[j]};
             b_of[i] = m.b;
             a_zero |= (m.a == 0.f ? 1u : 0u) << i;
             mine = compose(mine, m);
@@ -361,37 +327,32 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
         }
     }
     bar_lds();
-    if (map_only) continue;   // (uniform; the barrier above also protects the LDS arrays that the next pass refills)
+    if (map_only) continue;   // (uniform)
     carry_known = s_leaving;
 
     double x = fma((double)before.a, s_carry, before.b);  // advantage at the step after this thread's first
 #pragma unroll
     for (int i = 0; i < GAE_ITEMS; ++i) {
-        const int idx = top - i;
-        if (group >= 0 && idx < count) {
+        const int j = GAE_ITEMS - 1 - i;
+        if (group >= 0 && g0 + j < count) {
             x = fma((a_zero >> i) & 1u ? 0.0 : gl, x, b_of[i]);
-            const int q = lds_at(idx);
-            const float v = s_v[q];
-            s_r[q] = (float)x;
-            s_boot[q] = (float)(x + (double)v);
+            r8[j] = (float)x;                        // advantage
+            v8[j] = (float)(x + (double)v8[j]);      // return
         }
     }
-    bar_lds();
-    for (int i = tid * 4; i < count; i += GAE_THREADS * 4) {
-        if (VEC && i + 4 <= count) {
-            const int q = lds_at(i);
-            *reinterpret_cast<float4*>(adv + k_lo + i) =
-                float4{s_r[q], s_r[q + GAE_ROW], s_r[q + 2 * GAE_ROW], s_r[q + 3 * GAE_ROW]};
-            *reinterpret_cast<float4*>(ret + k_lo + i) =
-                float4{s_boot[q], s_boot[q + GAE_ROW], s_boot[q + 2 * GAE_ROW], s_boot[q + 3 * GAE_ROW]};
-        } else {
-            for (int j = i; j < min(i + 4, count); ++j) {
-                adv[k_lo + j] = s_r[lds_at(j)];
-                ret[k_lo + j] = s_boot[lds_at(j)];
+    if (whole) {
+        *reinterpret_cast<float4*>(adv + k_lo + g0) = float4{r8[0], r8[1], r8[2], r8[3]};
+        *reinterpret_cast<float4*>(adv + k_lo + g0 + 4) = float4{r8[4], r8[5], r8[6], r8[7]};
+        *reinterpret_cast<float4*>(ret + k_lo + g0) = float4{v8[0], v8[1], v8[2], v8[3]};
+        *reinterpret_cast<float4*>(ret + k_lo + g0 + 4) = float4{v8[4], v8[5], v8[6], v8[7]};
+    } else {
+#pragma unroll
+        for (int j = 0; j < GAE_ITEMS; ++j)
+            if (group >= 0 && g0 + j < count) {
+                adv[k_lo + g0 + j] = r8[j];
+                ret[k_lo + g0 + j] = v8[j];
             }
-        }
     }
-    bar_lds();   // the arrays are refilled by the next tile of the batch
     }
 }
 
