@@ -32,10 +32,11 @@ def _ragged(n_envs, budget, seed, empty_every=0):
 
 
 @pytest.mark.parametrize("S,N,aligned", [(1 << 24, 1 << 17, True), ((1 << 22) + 4099, 30000, True),
-                                          ((1 << 22) + 6, 30000, False)])
+                                          ((1 << 22) + 6, 30000, False), ((1 << 27) + 1000, 1 << 20, True)])
 def test_gae_many_tiles_sampled_environments(ver, S, N, aligned):
-    """8192 (or 2049) tiles: several tiles share a ticket.  Environments are independent, so the oracle
-    recomputes sampled ones: random ones and those that contain a tile boundary next to a batch boundary."""
+    """8192 (or 2049, or 65537) tiles: several tiles share a ticket (8, 2, and the maximum of 64).  Environments are
+    independent, so the oracle recomputes sampled ones: random ones and those that contain a tile boundary next
+    to a batch boundary."""
     rng, off = _ragged(N, S, seed=S % 1000, empty_every=97)
     r = (0.1 * rng.standard_normal(S)).astype(np.float32)
     v = rng.standard_normal(S).astype(np.float32)
