@@ -11,7 +11,7 @@
 //                      K sequences / n_seq pieces, far below a microsecond of
 //                      HBM time, so one CU with LDS-staged prefix sums and
 //                      wave ballots beats a multi-launch device-wide version.
-//   pack_gather_kernel a workgroup per 8 packed rows: resolves their flat steps
+//   pack_gather_kernel a workgroup per 4 or 8 packed rows: resolves their flat steps
 //                      (one search in t_off per workgroup) and copies the rows'
 //                      fields with 16-byte accesses.  This is the HBM-bound part:
 //                      2*4*D bytes per row (6*D with bf16 output) + small fields.
@@ -342,7 +342,10 @@ __device__ __forceinline__ void copy_state_row(float* __restrict__ dst, const fl
     }
 }
 
-constexpr int GATHER_ROWS = 8;   // packed rows per workgroup, two per wave (measured: 4 -> 57 %, 8 -> 61 %, 16 -> 59 %, 32 -> 57 % of the HBM peak)
+// Packed rows per workgroup: 8 (two per wave) when a launch moves gigabytes (measured on 2^18 rows: 4 -> 57 %, 8 -> 61 %,
+// 16 -> 59 %, 32 -> 57 % of the HBM peak), 4 (one per wave) for minibatches of the paper's sizes, where the launch is a
+// matter of latency and more, shorter workgroups finish sooner (8192 rows: 22 us against 29).
+constexpr int GATHER_ROWS_BIG = 8, GATHER_ROWS_SMALL = 4, GATHER_BIG_FROM = 1 << 16;
 
 // Copies the observation rows A and (unless inB is null) B, n4 16-byte chunks each, with the loads of both rows
 // in flight before the first store (a row is read once, from memory).  BF16: converts to bf16 on the way.
@@ -382,12 +385,13 @@ __device__ __forceinline__ void copy_obs_pair(const f32x4* __restrict__ inA, con
     }
 }
 
-// A workgroup gathers GATHER_ROWS consecutive packed rows.  Wave 0 places them: a 64-ary search in t_off for the
+// A workgroup gathers GATHER_ROWS (4 or 8) consecutive packed rows.  Wave 0 places them: a 64-ary search in t_off for the
 // timestep of the first row (every lane probes one of 64 evenly spaced offsets of the current range and a ballot
 // counts how many are <= p: 3 dependent loads for 8192 timesteps), then ONE load of the next offsets, from which
 // every row's timestep follows by counting (a timestep holds at least one row, so n rows span at most n
 // timesteps), then one load of the piece's first step.  After that all four waves copy rows, two rows and up to
 // eight 16-byte loads per lane in flight at a time, and the small per-row fields go lane-parallel over the rows.
+template <int GATHER_ROWS>
 __global__ __launch_bounds__(GATHER_THREADS) void pack_gather_kernel(GatherArgs g) {
     __shared__ int s_src[GATHER_ROWS], s_t[GATHER_ROWS], s_j[GATHER_ROWS];
     const int tid = threadIdx.x, lane = tid & (VER_WAVE - 1), wave = tid / VER_WAVE;
@@ -669,8 +673,12 @@ extern "C" int ver_pack_minibatch(const ver_pack_args* a, void* stream) {
     g.seq_cap = a->seq_cap; g.h0 = a->h0; g.c0 = a->c0;
     g.state_vec4 = a->H % 4 == 0 && ((reinterpret_cast<uintptr_t>(a->rnn_h) | reinterpret_cast<uintptr_t>(a->rnn_c) |
                                       reinterpret_cast<uintptr_t>(a->h0) | reinterpret_cast<uintptr_t>(a->c0)) & 15) == 0;
-    const int blocks = (M + ver::GATHER_ROWS - 1) / ver::GATHER_ROWS;
     ver::ProfScope prof(VER_PROF_PACK_GATHER, s);
-    hipLaunchKernelGGL(ver::pack_gather_kernel, dim3(blocks), dim3(ver::GATHER_THREADS), 0, s, g);
+    if (M >= ver::GATHER_BIG_FROM)
+        hipLaunchKernelGGL(ver::pack_gather_kernel<ver::GATHER_ROWS_BIG>, dim3((M + ver::GATHER_ROWS_BIG - 1) / ver::GATHER_ROWS_BIG),
+                           dim3(ver::GATHER_THREADS), 0, s, g);
+    else
+        hipLaunchKernelGGL(ver::pack_gather_kernel<ver::GATHER_ROWS_SMALL>, dim3((M + ver::GATHER_ROWS_SMALL - 1) / ver::GATHER_ROWS_SMALL),
+                           dim3(ver::GATHER_THREADS), 0, s, g);
     return ver::launch_status();
 }

@@ -88,9 +88,12 @@ def test_ragged_edge_cases(ver, seed, n_envs, max_len, p_done, B):
         compare_meta(out.meta(), opack.pack_minibatch(dones, off, key, B, b, eps))
 
 
+@pytest.mark.parametrize("budget,n_envs", [(512, 8), (1 << 17, 700)])
 @pytest.mark.parametrize("bf16", [False, True])
-def test_gathered_fields(ver, bf16):
-    w = wl.scaled(wl.WORKLOADS["manip"], input_dim=36, hidden=64, budget=512, n_envs=8)
+def test_gathered_fields(ver, bf16, budget, n_envs):
+    """Every gathered field of both minibatches; 2 x 256 rows, and 2 x 65536 rows (from there on a workgroup of the
+    gather kernel takes 8 rows instead of 4)."""
+    w = wl.scaled(wl.WORKLOADS["manip"], input_dim=36, hidden=64, budget=budget, n_envs=n_envs)
     ro = wl.make_rollout(w, seed=9)
     rng = np.random.default_rng(0)
     fields = dict(obs=ro["obs"], actions=ro["actions"], logp_old=rng.standard_normal(ro["S"]).astype(np.float32),
