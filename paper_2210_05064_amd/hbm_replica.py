@@ -144,8 +144,7 @@ def _loss(out, w, g, randn, reps, scale):
     """Loss: 2^24 rows."""
     f32 = F32
     A = w.act_dim
-    import os
-    M = int(os.environ.get("VER_REPLICA_LOSS_M", 1 << 24)) // scale
+    M = (1 << 24) // scale
     head, value, acts = randn(M, A), randn(M), randn(M, A)
     logp, adv, ret, isw = randn(M) - 15.0, randn(M), randn(M), torch.rand(M, generator=g, **f32)
     log_std, d_log_std = torch.zeros(A, **f32), torch.empty(A, **f32)
