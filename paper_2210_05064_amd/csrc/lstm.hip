@@ -318,11 +318,13 @@ struct LayerWs {
 struct LstmWs {
     int* err;          // word 0 of the workspace
     int* flags;        // [REC_FLAG_WORDS]: per-workgroup flags of a recurrent launch, then its ticket counters
-    long long* prof;   // [64] phase counters of the recurrent kernels (forward 0..15, backward 16..31; +32: consumer layer)
+    long long* prof;   // [128] phase counters of the recurrent kernels (forward 0..15, backward 16..31; +32: consumer layer), timeline, workers
     LayerWs layer[8];
     void* dz[2];       // [M, 4H] operand type; the second one only when two layers share a launch
-    int* pipe;         // hand-over words of a two-layer launch: progress[8], queue at [8], done[] from [16]
+    int* pipe;         // hand-over words of a two-layer launch: progress[8], queues at [8], done[][] from [16]
     int pipe_words;
+    int* plan;         // which pieces every group of a two-layer launch runs, and its chunks (lstm_pipe.h)
+    float* plan_scratch;
     float* dh[2];      // [M, H] ping-pong: gradient arriving at a layer's h
     float* dh_state;   // [M, H]
     float* dc_state;   // [M, H]
@@ -363,10 +365,12 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     int* head = cv.take<int>(64);
     ws->err = head;
     ws->flags = cv.take<int>(REC_FLAG_WORDS);
-    ws->prof = cv.take<long long>(80);
+    ws->prof = cv.take<long long>(128);
     // the hand-over words sit right behind, so that one fill clears everything a launch needs cleared
-    ws->pipe_words = 16 + M / PIPE_CT + 2;
+    ws->pipe_words = pipe_sync_words(M);
     ws->pipe = cv.take<int>(ws->pipe_words);
+    ws->plan = cv.take<int>(plan_words(M));
+    ws->plan_scratch = cv.take<float>(plan_scratch_floats(M));
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws->layer[l];
@@ -426,7 +430,7 @@ inline bool launch_proj_dma(const void* A, const void* B, float* C, const float*
     if ((size_t)M * K * 2 >= 0x7fffffff || (size_t)N * K * 2 >= 0x7fffffff || (size_t)M * N * 4 >= 0x7fffffff) return false;
     if (!set_lds(lstm_proj_dma_kernel, (size_t)PIPE_STAGES * PIPE_STAGE_BYTES)) return false;
     PipeWork pw{};
-    pw.A = A; pw.B = B; pw.C = C; pw.bias = bias; pw.K = K; pw.N = N;
+    pw.A = A; pw.B = B; pw.C = C; pw.bias = bias; pw.K = K; pw.N = N; pw.M = M;
     const int tiles_n = (N + PIPE_BN - 1) / PIPE_BN, tiles_m = (M + PIPE_BM - 1) / PIPE_BM;
     hipLaunchKernelGGL(lstm_proj_dma_kernel, dim3(tiles_m * tiles_n), dim3(REC_THREADS), (size_t)PIPE_STAGES * PIPE_STAGE_BYTES, s,
                        pw, M, tiles_n);
@@ -459,20 +463,22 @@ inline size_t pipe_worker_lds() {
     if (MODE == MODE_BF16) return (size_t)PIPE_STAGES * PIPE_STAGE_BYTES;
     return (size_t)(PIPE_BM + PIPE_BN) * GemmGeom<MODE>::LDS_STRIDE * sizeof(typename LdsElem<MODE>::type);
 }
-// Zeroes the flags, ticket counters and (two-layer launches) hand-over words of a recurrent launch with one fill;
-// with_err also clears the sticky time-out word at the start of the workspace (forward call only).
-inline void clear_sync_words(LstmWs& ws, bool with_err, bool with_pipe, hipStream_t s) {
+// Before a two-layer launch: one small kernel zeroes the flags, ticket counters and hand-over words (with_err:
+// also the sticky time-out word at the start of the workspace, forward call only) and writes the launch's plan.
+inline void pipe_prepare(LstmWs& ws, bool with_err, int M, const int32_t* info, const int32_t* batch_sizes, const PlanCost& cost,
+                         hipStream_t s) {
     int* first = with_err ? ws.err : ws.flags;
-    int* last = with_pipe ? ws.pipe + ws.pipe_words : ws.flags + REC_FLAG_WORDS;
-    fill_words(first, (size_t)(last - first), 0, s);
+    int* last = ws.pipe + ws.pipe_words;
+    hipLaunchKernelGGL(lstm_pipe_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, info, batch_sizes, M, ws.plan, ws.plan_scratch, first,
+                       (int)(last - first), cost);
 }
-inline void pipe_link(const ver_lstm_cfg& c, int M, int N, LstmWs& ws, hipStream_t s, PipeLink* pl) {
-    pl->progress = ws.pipe;   // cleared by the caller together with the flags (clear_sync_words)
-    pl->done = ws.pipe + 16;
-    pl->tiles_n = (N + PIPE_BN - 1) / PIPE_BN;
-    pl->T_all = 0;   // filled in on the device from info[1]
-    pl->M = M;
-    (void)c;
+inline void pipe_work(const LstmWs& ws, int M, const int32_t* t_off, PipeWork* pw) {
+    pw->M = M;
+    pw->t_off = t_off;
+    pw->plan = ws.plan;
+    pw->sync = ws.pipe;
+    pw->err = ws.err;
+    pw->prof_all = ws.prof;
 }
 
 template <int MODE>
@@ -536,7 +542,7 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.h0 = h0 ? h0 + (size_t)l * seq_cap * H : nullptr;
         ra.c0 = c0 ? c0 + (size_t)l * seq_cap * H : nullptr;
         ra.H = H; ra.seq_cap = seq_cap; ra.M = M; ra.flags = ws.flags; ra.ticket = ws.flags + 8 * REC_MAX_GROUP;
-        ra.err = ws.err; ra.prof = ws.prof + (pipelined && l == 1 ? 32 : 0);
+        ra.err = ws.err; ra.prof = ws.prof + (pipelined && l == 1 ? 32 : 0); ra.prof_all = ws.prof;
         ra.G = H / (4 * mt); ra.ntc = ntc;
         return ra;
     };
@@ -563,14 +569,14 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         prep(0);
         prep(1);
         project(0);
-        clear_sync_words(ws, true, true, s);
+        pipe_prepare(ws, true, M, info, batch_sizes, PLAN_COST_FWD, s);
         PipeFwdArgs pa;
         pa.l0 = rec_args(0);
         pa.l1 = rec_args(1);
-        pipe_link(c, M, 4 * H, ws, s, &pa.link);
         pa.work.A = ws.layer[0].hcopy; pa.work.B = ws.layer[1].wih; pa.work.C = ws.layer[1].gates;
         pa.work.bias = ws.layer[1].bias; pa.work.K = H; pa.work.N = 4 * H;
-        pa.work.batch_sizes = batch_sizes; pa.work.t_off = t_off; pa.work.queue = ws.pipe + 8; pa.work.err = ws.err;
+        pipe_work(ws, M, t_off, &pa.work);
+        pa.tiles_n = (4 * H + PIPE_BN - 1) / PIPE_BN;
         ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
         VER_FWD_DISPATCH(lstm_pipe_fwd_kernel, pa);
         if (!ok) return VER_EHIP;
@@ -638,7 +644,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         ra.dh_state = ws.dh_state + (pipelined ? (size_t)l * M * H : 0);
         ra.dc_state = ws.dc_state + (pipelined ? (size_t)l * M * H : 0);
         ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + 8 * REC_MAX_GROUP;
-        ra.err = ws.err; ra.prof = ws.prof + 16 + (pipelined && l == 0 ? 32 : 0);
+        ra.err = ws.err; ra.prof = ws.prof + 16 + (pipelined && l == 0 ? 32 : 0); ra.prof_all = ws.prof;
         ra.G = H / (16 * mt); ra.ntc = ntc;
         return ra;
     };
@@ -696,14 +702,14 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     };
 
     if (pipelined) {
-        clear_sync_words(ws, false, true, s);
+        pipe_prepare(ws, false, M, info, batch_sizes, PLAN_COST_BWD, s);
         PipeBwdArgs pa;
         pa.l1 = rec_args(1, ws.dh[0]);
         pa.l0 = rec_args(0, ws.dh[1]);
-        pipe_link(c, M, H, ws, s, &pa.link);
         pa.work.A = ws.dz[1]; pa.work.B = ws.layer[1].wihT; pa.work.C = ws.dh[1]; pa.work.bias = nullptr;
         pa.work.K = 4 * H; pa.work.N = H;
-        pa.work.batch_sizes = batch_sizes; pa.work.t_off = t_off; pa.work.queue = ws.pipe + 8; pa.work.err = ws.err;
+        pipe_work(ws, M, t_off, &pa.work);
+        pa.tiles_n = (H + PIPE_BN - 1) / PIPE_BN;
         {
         ProfScope prof(VER_PROF_LSTM_REC_BWD, s);
         VER_BWD_DISPATCH(lstm_pipe_bwd_kernel, pa);

@@ -5,39 +5,204 @@
 // chip idle, and the second layer's step t only needs the first layer's output of step t: so the two time
 // loops run side by side, a few timesteps apart, instead of one after the other.
 //
-//   XCD 0..2   time loop of the producer layer (forward: layer 0; backward: layer 1), pieces dealt to 3 groups
-//   XCD 3..5   time loop of the consumer layer, same dealing (backward: XCD 3..6, 4 groups)
-//   the rest   workers: for every finished chunk of PIPE_CT timesteps, the GEMM that turns the producer's rows
+//   XCD 0..2   time loop of the producer layer (forward: layer 0; backward: layer 1), one group per XCD
+//   XCD 3..5   time loop of the consumer layer, group g on XCD 3 + g
+//   XCD 6..7   workers: for every finished chunk of a group's timesteps, the GEMM that turns the producer's rows
 //              into the consumer's input (forward: gates_1 = h_0 W_ih1^T + b; backward: dh_0 = dz_1 W_ih1),
-//              one 128 x 256 tile at a time from a shared queue, in the order the consumer needs them
+//              one 128 x 256 tile at a time
+//
+// Which pieces a group runs.  A timestep of a time loop costs a fixed latency (one exchange between the group's
+// workgroups, ~3 us) plus a little per alive piece, and the launch lasts as long as its slowest group.  The
+// pieces are sorted longest first, so they are cut into three blocks of consecutive pieces: group 0 gets the few
+// longest ones (its chain of T_max dependent steps is what bounds the launch, so its steps should be the
+// cheapest), the last group the many short ones (few steps, each with many pieces).  lstm_pipe_plan_kernel
+// picks the two cuts that minimise the largest predicted group time
+//     sum over the group's timesteps of (step + piece * b_t + pair * b_t^2),   b_t = alive pieces of the group,
+// which it evaluates in O(1) per candidate from prefix sums over the pieces' lengths (sum_t b_t = sum of the
+// lengths, sum_t b_t^2 = sum_j length_j * (2 j + 1) over the block's pieces j = 0, 1, ... in order).  Producer and
+// consumer group g run the same block, and everything between them is per group: chunks of the group's own
+// timesteps, tiles over the group's own rows (gathered: a group's rows of a timestep are consecutive, those of
+// a chunk are not), a queue and completion counters of its own.  So a group never waits for another one: with
+// the pieces dealt round-robin all groups had to march in step, and every step paid for a third of all alive pieces.
 //
 // Hand-over (lstm_rec.h, PipeLink): producer rows are written through to memory and their completion is
-// published per group; a worker waits for all producer groups before it reads a chunk's rows with loads that
-// bypass the non-coherent caches, writes its tile through, waits for the stores and counts the tile in
-// done[chunk]; a consumer group waits until done[chunk] has reached the number of tiles of the chunk.  Waiting
-// only ever points backwards along producer -> worker -> consumer and the queue is ordered by chunk, so the
-// launch cannot deadlock; every wait is bounded and raises the shared error word on time-out.
+// published per group; a worker takes the next tile of a group's queue, waits for that group's producer, reads
+// the chunk's rows with loads that bypass the non-coherent caches, writes its tile through, waits for the stores
+// and counts the tile in done[group][chunk]; the consumer group waits until that count has reached the number of
+// tiles of the chunk.  Waiting only ever points backwards along producer -> worker -> consumer and a queue hands
+// out a group's tiles in the order its consumer needs them, so the launch cannot deadlock; every wait is bounded
+// and raises the shared error word on time-out.
 #pragma once
 #include "lstm_rec.h"
 
 namespace ver {
 
-constexpr int PIPE_GROUPS = 3;        // groups (XCDs) of the producer layer
-constexpr int PIPE_GROUPS_C_FWD = 3;  // groups of the consumer layer, forward: two XCDs of workers
-constexpr int PIPE_GROUPS_C_BWD = 4;  // backward (heavier steps, lighter GEMM): one XCD of workers (measured best)
+constexpr int PIPE_GROUPS = 3;       // groups (XCDs) per layer
 constexpr int PIPE_XCDS = 8;         // XCDs of the chip: those beyond the two layers' groups are workers
+constexpr int PIPE_WORKERS = (PIPE_XCDS - 2 * PIPE_GROUPS) * REC_MAX_GROUP;
+
+// The plan of a launch (ints in global memory, written by lstm_pipe_plan_kernel):
+constexpr int PLAN_KB = 0;           // [PIPE_GROUPS + 1] first piece of every group's block, then the number of pieces
+constexpr int PLAN_T = 8;            // [PIPE_GROUPS] timesteps of the group (those of its first piece; 0 if it has none)
+constexpr int PLAN_CT = 12;          // [PIPE_GROUPS] timesteps per chunk
+constexpr int PLAN_HDR = 16;         // then rp[PIPE_GROUPS][M + 1]: rows of the group in the timesteps before t
+inline __host__ __device__ size_t plan_words(int M) { return PLAN_HDR + (size_t)PIPE_GROUPS * ((size_t)M + 1); }
+inline __host__ __device__ size_t plan_scratch_floats(int M) { return 3 * ((size_t)M + 1); }
+// The words a launch synchronises through (zero at launch): progress[g] at g, queue[g] at 8 + g, then
+// done[g][chunk] from 16 with PIPE_GROUPS rows of pipe_done_stride(M) words.
+constexpr int PIPE_CT_MIN = 4;
+inline __host__ __device__ int pipe_done_stride(int M) { return M / PIPE_CT_MIN + 2; }
+inline __host__ __device__ int pipe_sync_words(int M) { return 16 + PIPE_GROUPS * pipe_done_stride(M); }
+
+// Predicted microseconds of a timestep: step + piece * b + pair * b^2 (b alive pieces of the group; measured on
+// equally long pieces), and the timesteps per chunk: at most ct0 for group 0 (every timestep of a chunk delays the
+// end of the launch once), at most ct for the other groups (which have time to spare: fewer, fuller tiles), and
+// no more than chunk_rows / (pieces of the group): the consumer of a group ends one chunk of GEMM tiles and one
+// chunk of its own steps after the producer, and starts as much later.
+struct PlanCost {
+    float step, piece, pair;
+    int ct0, ct, chunk_rows;
+};
+#ifndef VER_PLAN_CT0
+#define VER_PLAN_CT0 8
+#endif
+#ifndef VER_PLAN_CT
+#define VER_PLAN_CT 16
+#endif
+#ifndef VER_PLAN_CHUNK_ROWS
+#define VER_PLAN_CHUNK_ROWS 256
+#endif
+constexpr PlanCost PLAN_COST_FWD = {2.85f, 0.080f, 0.0019f, VER_PLAN_CT0, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
+constexpr PlanCost PLAN_COST_BWD = {2.94f, 0.111f, 0.0025f, VER_PLAN_CT0, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
 
 struct PipeWork {
     const void* A;      // producer rows [M, K], operand type (forward: h, backward: dz)
     const void* B;      // [N, K] operand type, K contiguous
     float* C;           // [M, N]
     const float* bias;  // [N] or NULL
-    int K, N;
-    const int32_t* batch_sizes;
+    int K, N, M;
     const int32_t* t_off;
-    int* queue;         // next item, zero at launch
+    const int* plan;
+    int* sync;          // progress, queues, done counters (see above)
     int* err;
+    long long* prof_all;   // profiling words (only touched by builds with VER_REC_PROF)
 };
+
+constexpr int PLAN_THREADS = 1024;
+// Exclusive prefix sum of v over the 1024 threads of the block (thread order); total: the sum.  s_w: 16 words of LDS.
+template <typename T>
+__device__ __forceinline__ T plan_scan(T v, T* s_w, T& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    T inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const T o = __shfl_up(inc, d, VER_WAVE);
+        if (lane >= d) inc += o;
+    }
+    if (lane == 63) s_w[wave] = inc;
+    __syncthreads();
+    T off = 0;
+    total = 0;
+    for (int w = 0; w < PLAN_THREADS / 64; ++w) {
+        const T x = s_w[w];
+        if (w < wave) off += x;
+        total += x;
+    }
+    __syncthreads();
+    return off + inc - v;
+}
+
+// One workgroup: clears the launch's synchronisation words and writes its plan (see the top of this file).
+// scratch: plan_scratch_floats(M) floats.
+__global__ __launch_bounds__(PLAN_THREADS) void lstm_pipe_plan_kernel(const int32_t* __restrict__ info, const int32_t* __restrict__ batch_sizes,
+                                                                      int M, int* __restrict__ plan, float* __restrict__ scratch,
+                                                                      int* __restrict__ clear_first, int n_clear, PlanCost pc) {
+    __shared__ float s_wf[PLAN_THREADS / 64];
+    __shared__ int s_wi[PLAN_THREADS / 64];
+    __shared__ float s_obj[PLAN_THREADS];
+    __shared__ int s_k1[PLAN_THREADS], s_k2[PLAN_THREADS];
+    __shared__ int s_kb[PIPE_GROUPS + 1];
+    const int tid = threadIdx.x;
+    const int n_seq = min(max(info[0], 0), M), T = min(max(info[1], 0), M);
+    for (int i = tid; i < n_clear; i += PLAN_THREADS) clear_first[i] = 0;
+    float* len = scratch;          // [n_seq] timesteps of piece n
+    float* S1 = scratch + M + 1;   // [n_seq + 1] sum of len[j], j < n
+    float* S2 = S1 + M + 1;        // [n_seq + 1] sum of j * len[j], j < n
+    for (int t = tid; t < T; t += PLAN_THREADS) {
+        const int hi = min(batch_sizes[t], n_seq), lo = t + 1 < T ? min(batch_sizes[t + 1], n_seq) : 0;
+        for (int n = lo; n < hi; ++n) len[n] = (float)(t + 1);   // the pieces that end with timestep t
+    }
+    __syncthreads();
+    float c1 = 0.f, c2 = 0.f;
+    for (int b0 = 0; b0 < n_seq; b0 += PLAN_THREADS) {
+        const int n = b0 + tid;
+        const float l = n < n_seq ? len[n] : 0.f;
+        float t1, t2;
+        const float e1 = plan_scan<float>(l, s_wf, t1);
+        const float e2 = plan_scan<float>(l * (float)n, s_wf, t2);
+        if (n < n_seq) { S1[n] = c1 + e1; S2[n] = c2 + e2; }
+        c1 += t1; c2 += t2;
+    }
+    if (tid == 0) { S1[n_seq] = c1; S2[n_seq] = c2; }
+    __syncthreads();
+    // predicted time of a group that runs the pieces [lo, hi)
+    auto cost = [&](int lo, int hi) -> float {
+        if (hi <= lo) return 0.f;
+        const float R = S1[hi] - S1[lo];
+        const float Q = 2.f * (S2[hi] - S2[lo]) - (float)(2 * lo - 1) * R;
+        return pc.step * len[lo] + pc.piece * R + pc.pair * Q;
+    };
+    // every first cut k1 with the second cut that balances the two remaining groups; ties go to the smaller cuts
+    float best = 3.0e38f;
+    int bk1 = n_seq, bk2 = n_seq;
+    for (int k1 = 1 + tid; k1 <= n_seq; k1 += PLAN_THREADS) {
+        int lo = k1, hi = n_seq;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (cost(k1, mid) >= cost(mid, n_seq)) hi = mid; else lo = mid + 1;
+        }
+        const float c0 = cost(0, k1);
+        for (int k2 = max(lo - 1, k1); k2 <= lo; ++k2) {
+            const float obj = fmaxf(c0, fmaxf(cost(k1, k2), cost(k2, n_seq)));
+            if (obj < best) { best = obj; bk1 = k1; bk2 = k2; }
+        }
+    }
+    s_obj[tid] = best; s_k1[tid] = bk1; s_k2[tid] = bk2;
+    __syncthreads();
+    for (int w = PLAN_THREADS / 2; w > 0; w >>= 1) {
+        if (tid < w) {
+            const float o = s_obj[tid + w];
+            const int o1 = s_k1[tid + w], o2 = s_k2[tid + w];
+            const bool take = o < s_obj[tid] || (o == s_obj[tid] && (o1 < s_k1[tid] || (o1 == s_k1[tid] && o2 < s_k2[tid])));
+            if (take) { s_obj[tid] = o; s_k1[tid] = o1; s_k2[tid] = o2; }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        s_kb[0] = 0; s_kb[1] = s_k1[0]; s_kb[2] = s_k2[0]; s_kb[3] = n_seq;
+        for (int g = 0; g <= PIPE_GROUPS; ++g) plan[PLAN_KB + g] = s_kb[g];
+    }
+    __syncthreads();
+    for (int g = 0; g < PIPE_GROUPS; ++g) {
+        const int lo = s_kb[g], cap = s_kb[g + 1] - lo;
+        const int Tg = cap > 0 ? (int)len[lo] : 0;
+        if (tid == 0) {
+            plan[PLAN_T + g] = Tg;
+            plan[PLAN_CT + g] = min(g == 0 ? pc.ct0 : pc.ct, max(PIPE_CT_MIN, pc.chunk_rows / max(cap, 1)));
+        }
+        int* rp = plan + PLAN_HDR + (size_t)g * ((size_t)M + 1);
+        int carry = 0;
+        for (int b0 = 0; b0 < Tg; b0 += PLAN_THREADS) {
+            const int t = b0 + tid;
+            const int cnt = t < Tg ? min(max(batch_sizes[t] - lo, 0), cap) : 0;
+            int tot;
+            const int e = plan_scan<int>(cnt, s_wi, tot);
+            if (t < Tg) rp[t] = carry + e;
+            carry += tot;
+        }
+        if (tid == 0) rp[Tg] = carry;
+    }
+}
 
 template <typename E, typename T> __device__ __forceinline__ Quad<E> load_quad_coh(__amdgpu_buffer_rsrc_t r, int byte_off);
 template <> __device__ __forceinline__ Quad<float> load_quad_coh<float, float>(__amdgpu_buffer_rsrc_t r, int byte_off) {
@@ -49,11 +214,15 @@ template <> __device__ __forceinline__ Quad<bf16_t> load_quad_coh<bf16_t, bf16_t
     return Quad<bf16_t>{{(bf16_t)(t.x & 0xffff), (bf16_t)(t.x >> 16), (bf16_t)(t.y & 0xffff), (bf16_t)(t.y >> 16)}};
 }
 
-// One 128 x 256 tile of C = A B^T (+ bias) for rows [row0, row_end) and columns from col0, by 8 waves (2 x 4
-// of 64 x 64).  Same K-tile pipeline as gemm_kernel: the next K-tile's global loads are in flight while the
-// current one is multiplied out of LDS.
+// A row that a tile does not have: an offset beyond every buffer (loads return zero, stores are dropped), which
+// stays there when a K-tile's offset is added.
+constexpr int PIPE_NO_ROW = (int)0x80000000u;
+
+// One 128 x 256 tile of C = A B^T (+ bias) for the rows rowmap[0 .. 127] (LDS; -1: none) and columns from col0,
+// by 8 waves (2 x 4 of 64 x 64).  Same K-tile pipeline as gemm_kernel: the next K-tile's global loads are in
+// flight while the current one is multiplied out of LDS.
 template <int MODE, typename TA>
-__device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, int row0, int row_end, int col0, unsigned char* smem) {
+__device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, const int* rowmap, int col0, unsigned char* smem) {
     typedef typename LdsElem<MODE>::type E;
     constexpr int BK = GemmGeom<MODE>::BK, STRIDE = GemmGeom<MODE>::LDS_STRIDE;
     constexpr int CPR = BK / 4, RPP = REC_THREADS / CPR, QA = PIPE_BM / RPP, QB = PIPE_BN / RPP;
@@ -64,9 +233,15 @@ __device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, int row0, int 
     const int lr = lane & 15, lk = lane >> 4;
     const int c = tid % CPR, r = tid / CPR;
     const int K = w.K, N = w.N;
-    __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<TA*>(static_cast<const TA*>(w.A)) + (size_t)row0 * K, 0,
-                                                                   (row_end - row0) * K * (int)sizeof(TA), 0x00020000);
+    __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<TA*>(static_cast<const TA*>(w.A)), 0,
+                                                                   w.M * K * (int)sizeof(TA), 0x00020000);
     const E* Bp = static_cast<const E*>(w.B);
+    int rowoff[QA];
+#pragma unroll
+    for (int i = 0; i < QA; ++i) {
+        const int g = rowmap[r + i * RPP];
+        rowoff[i] = g >= 0 ? g * K * (int)sizeof(TA) : PIPE_NO_ROW;
+    }
 
     f32x4_t acc[4][4];
 #pragma unroll
@@ -78,8 +253,7 @@ __device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, int row0, int 
     auto load_tiles = [&](int k0) {
 #pragma unroll
         for (int i = 0; i < QA; ++i) {
-            const int lrow = r + i * RPP;   // rows past the end of the chunk read zero (buffer bounds)
-            ra[i] = load_quad_coh<E, TA>(rsA, (lrow * K + k0 + c * 4) * (int)sizeof(TA));
+            ra[i] = load_quad_coh<E, TA>(rsA, rowoff[i] + (k0 + c * 4) * (int)sizeof(TA));   // rows the tile does not have read zero
         }
 #pragma unroll
         for (int i = 0; i < QB; ++i) {
@@ -131,20 +305,25 @@ __device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, int row0, int 
         bar_lds();
     }
     // C fragment: element e of lane l is row (l / 16) * 4 + e, column l % 16 of the 16x16 tile; written through
-    __amdgpu_buffer_rsrc_t rsC = __builtin_amdgcn_make_buffer_rsrc(w.C + (size_t)row0 * N, 0, (row_end - row0) * N * 4, 0x00020000);
+    __amdgpu_buffer_rsrc_t rsC = __builtin_amdgcn_make_buffer_rsrc(w.C, 0, w.M * N * 4, 0x00020000);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
+        int crow[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int g = rowmap[wm + i * 16 + lk * 4 + e];
+            crow[e] = g >= 0 ? g * N * 4 : PIPE_NO_ROW;   // rows the tile does not have are dropped (buffer bounds)
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = col0 + wn + j * 16 + lr;
             if (n >= N) continue;
             const float bv = w.bias ? w.bias[n] : 0.f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int lrow = wm + i * 16 + lk * 4 + e;   // rows past the end of the chunk are dropped (buffer bounds)
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][e] + bv), rsC, (lrow * N + n) * 4, 0, 17);
-            }
+            for (int e = 0; e < 4; ++e)
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][e] + bv), rsC, crow[e] + n * 4, 0, 17);
         }
+    }
 }
 
 // The same tile for bf16 operands on both sides, built for a workgroup that has the CU to itself: K-tiles of
@@ -158,10 +337,12 @@ constexpr int PIPE_STAGE_BYTES = (PIPE_BM + PIPE_BN) * 128;
 // K need not be a multiple of 64 (it is a multiple of 4): the last K-tile then also fetches what follows the rows'
 // ends (the next row, or zeros past the end of the arrays), and the A operand is cleared beyond K in registers, so
 // that whatever was fetched on the B side is multiplied by zero.
-// COHERENT: A is being written by other XCDs during this launch and C is read by them (loads and stores that
-// bypass the non-coherent caches); false for a launch of its own.
+// COHERENT (a worker's tile): the tile's rows are rowmap[0 .. 127] (LDS; -1: none), A is being written by other
+// XCDs during this launch and C is read by them (loads and stores that bypass the non-coherent caches).
+// Otherwise (a launch of its own): the rows [row0, row_end).
 template <bool COHERENT>
-__device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, int row_end, int col0, unsigned char* smem) {
+__device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, const int* rowmap, int row0, int row_end, int col0,
+                                                   unsigned char* smem) {
     constexpr int BK = 64;
     constexpr int AUX = COHERENT ? 17 : 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -169,8 +350,10 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, 
     const int lr = lane & 15, lk = lane >> 4;
     const int K = w.K, N = w.N, nk = (K + BK - 1) / BK, k_tail = K % BK;
     const int ncols = min(N - col0, PIPE_BN);
-    __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<bf16_t*>(static_cast<const bf16_t*>(w.A)) + (size_t)row0 * K, 0, (row_end - row0) * K * 2, 0x00020000);
+    __amdgpu_buffer_rsrc_t rsA = COHERENT
+        ? __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(static_cast<const bf16_t*>(w.A)), 0, w.M * K * 2, 0x00020000)
+        : __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(static_cast<const bf16_t*>(w.A)) + (size_t)row0 * K, 0,
+                                            (row_end - row0) * K * 2, 0x00020000);
     __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t*>(static_cast<const bf16_t*>(w.B)) + (size_t)col0 * K, 0, ncols * K * 2, 0x00020000);
     // source offsets of this lane in the 2 (A) + 4 (B) load instructions of this wave per K-tile
@@ -179,7 +362,12 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, 
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int row = (wave * 2 + j) * 8 + row_in;
-        voffA[j] = row * K * 2 + ((pos ^ ((row >> 1) & 7)) << 4);
+        int src = row * K * 2;
+        if (COHERENT) {
+            const int g = rowmap[row];
+            src = g >= 0 ? g * K * 2 : PIPE_NO_ROW;
+        }
+        voffA[j] = src + ((pos ^ ((row >> 1) & 7)) << 4);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -246,20 +434,30 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, 
         }
     }
     // C fragment: element e of lane l is row (l / 16) * 4 + e, column l % 16 of the 16x16 tile; written through
-    __amdgpu_buffer_rsrc_t rsC = __builtin_amdgcn_make_buffer_rsrc(w.C + (size_t)row0 * N, 0, (row_end - row0) * N * 4, 0x00020000);
+    __amdgpu_buffer_rsrc_t rsC = COHERENT ? __builtin_amdgcn_make_buffer_rsrc(w.C, 0, w.M * N * 4, 0x00020000)
+                                          : __builtin_amdgcn_make_buffer_rsrc(w.C + (size_t)row0 * N, 0, (row_end - row0) * N * 4, 0x00020000);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 4; ++i) {
+        int crow[4];   // rows the tile does not have are dropped (buffer bounds)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int lrow = wm + i * 16 + lk * 4 + e;
+            crow[e] = lrow * N * 4;
+            if (COHERENT) {
+                const int g = rowmap[lrow];
+                crow[e] = g >= 0 ? g * N * 4 : PIPE_NO_ROW;
+            }
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int n = col0 + wn + j * 16 + lr;
             if (n >= N) continue;
             const float bv = w.bias ? w.bias[n] : 0.f;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int lrow = wm + i * 16 + lk * 4 + e;   // rows past the end of the chunk are dropped (buffer bounds)
-                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][e] + bv), rsC, (lrow * N + n) * 4, 0, AUX);
-            }
+            for (int e = 0; e < 4; ++e)
+                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][e] + bv), rsC, crow[e] + n * 4, 0, AUX);
         }
+    }
 }
 
 // The same tiles as a launch of its own: C[M, N] = A[M, K] B[N, K]^T + bias, bf16 operands (the input projection
@@ -268,42 +466,71 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, int row0, 
 __global__ __launch_bounds__(REC_THREADS) void lstm_proj_dma_kernel(PipeWork w, int M, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) unsigned char proj_smem[];
     const int rt = blockIdx.x / tiles_n, ct = blockIdx.x % tiles_n;
-    pipe_gemm_tile_dma<false>(w, rt * PIPE_BM, min(M, (rt + 1) * PIPE_BM), ct * PIPE_BN, proj_smem);
+    pipe_gemm_tile_dma<false>(w, nullptr, rt * PIPE_BM, min(M, (rt + 1) * PIPE_BM), ct * PIPE_BN, proj_smem);
 }
 
-// Worker loop.  Items are the tiles of all chunks in the order the consumer needs the chunks (DESCEND: last
-// chunk first); item -> (chunk, row tile, column tile) is found by walking the chunks, which a worker only ever
-// does forwards because the queue hands out increasing items.
+// One group's view of the hand-over words, from the plan.
+__device__ __forceinline__ PipeLink pipe_link_of(const int* plan, int* sync, int M, int tiles_n, int g) {
+    PipeLink pl;
+    pl.progress = sync + g;
+    pl.done = sync + 16 + g * pipe_done_stride(M);
+    pl.rp = plan + PLAN_HDR + (size_t)g * ((size_t)M + 1);
+    pl.ct = plan[PLAN_CT + g];
+    pl.tiles_n = tiles_n;
+    pl.T = plan[PLAN_T + g];
+    return pl;
+}
+__device__ __forceinline__ PieceSet pipe_pieces_of(const int* plan, int g) {
+    const int lo = plan[PLAN_KB + g];
+    return PieceSet{lo, 1, plan[PLAN_KB + g + 1] - lo, g};
+}
+
+// Worker loop.  A worker serves one group's queue until it is empty, then the next group's (it starts with the
+// group `home`).  The items of a queue are the tiles of the group's chunks in the order the consumer needs the
+// chunks (DESCEND: last chunk first); item -> (chunk, row tile, column tile) is found by walking the chunks,
+// which a worker only ever does forwards because a queue hands out increasing items.
 template <int MODE, bool DESCEND>
-__device__ __forceinline__ void pipe_worker(const PipeWork& w, const PipeLink& pl, unsigned char* smem) {
-    __shared__ int s_item[4];    // chunk, local tile, ok
-    __shared__ int s_Tg[PIPE_GROUPS];
-    const int T_all = pl.T_all;
-    for (int g = 0; g < PIPE_GROUPS; ++g) {
-        const int tg = grp_steps(w.batch_sizes, T_all, g);
-        if (threadIdx.x == 0) s_Tg[g] = tg;
-    }
-    const int n_chunks = (T_all + PIPE_CT - 1) / PIPE_CT;
-    int cur = 0, prefix = 0;     // thread 0's cursor: chunks [0, cur) in queue order hold items [0, prefix)
-    for (;;) {
-        if (threadIdx.x == 0) {
-            const int item = __hip_atomic_fetch_add(w.queue, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            int ok = 0, c = 0, local = 0;
-            while (cur < n_chunks) {
-                c = DESCEND ? n_chunks - 1 - cur : cur;
-                const int tiles = pipe_chunk_tiles(w.t_off, pl, c);
-                if (item < prefix + tiles) { local = item - prefix; ok = 1; break; }
-                prefix += tiles;
-                ++cur;
-            }
-            if (ok) {
-                // all producer groups must have completed the chunk's timesteps
-                const int t_lo = c * PIPE_CT, t_hi = min(t_lo + PIPE_CT, T_all);
-                long long spins = 0;
-                for (int g = 0; g < PIPE_GROUPS && ok == 1; ++g) {
-                    const int tg = s_Tg[g];
-                    const int need = DESCEND ? tg - min(t_lo, tg) : min(t_hi, tg);
-                    while (ld_agent(&pl.progress[g]) < need) {
+__device__ __forceinline__ void pipe_worker(const PipeWork& w, int tiles_n, int home, unsigned char* smem) {
+    __shared__ int s_item[4];    // chunk, local tile, ok (0: leave, 1: tile, 2: queue empty)
+    __shared__ int s_rp[PIPE_CT_MAX + 1], s_to[PIPE_CT_MAX];
+    __shared__ int s_rowmap[PIPE_BM];
+    const int tid = threadIdx.x;
+#ifdef VER_REC_PROF
+    long long* wst = w.prof_all + 96 + home * 4;   // per home group: tiles, time in tiles, time waiting for producers, time in the queue (100 MHz)
+    long long wt = 0;
+#endif
+    for (int visit = 0; visit < PIPE_GROUPS; ++visit) {
+        const int g = (home + visit) % PIPE_GROUPS;
+        const PipeLink pl = pipe_link_of(w.plan, w.sync, w.M, tiles_n, g);
+        const int lo = w.plan[PLAN_KB + g];
+        int* queue = w.sync + 8 + g;
+        const int n_chunks = (pl.T + pl.ct - 1) / pl.ct;
+        int cur = 0, prefix = 0;     // thread 0's cursor: chunks [0, cur) in queue order hold items [0, prefix)
+        for (;;) {
+            if (tid == 0) {
+#ifdef VER_REC_PROF
+                wt = wall_clock64();
+#endif
+                int ok = 2, c = 0, local = 0;
+                if (cur < n_chunks) {
+                    const int item = __hip_atomic_fetch_add(queue, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    while (cur < n_chunks) {
+                        c = DESCEND ? n_chunks - 1 - cur : cur;
+                        const int tiles = pipe_chunk_tiles(pl, c);
+                        if (item < prefix + tiles) { local = item - prefix; ok = 1; break; }
+                        prefix += tiles;
+                        ++cur;
+                    }
+                }
+#ifdef VER_REC_PROF
+                { const long long now = wall_clock64(); atomicAdd((unsigned long long*)&wst[3], (unsigned long long)(now - wt)); wt = now; }
+#endif
+                if (ok == 1) {
+                    // the group's producer must have completed the chunk's timesteps
+                    const int t_lo = c * pl.ct, t_hi = min(t_lo + pl.ct, pl.T);
+                    const int need = DESCEND ? pl.T - t_lo : t_hi;
+                    long long spins = 0;
+                    while (ld_agent(pl.progress) < need) {
                         ++spins;
                         if ((spins & 255) == 0 && (spins > REC_SPIN_LIMIT || ld_agent(w.err) != 0)) {
                             st_agent(w.err, 1);
@@ -312,23 +539,46 @@ __device__ __forceinline__ void pipe_worker(const PipeWork& w, const PipeLink& p
                         }
                     }
                 }
+                s_item[0] = c; s_item[1] = local; s_item[2] = ok;
+#ifdef VER_REC_PROF
+                { const long long now = wall_clock64(); atomicAdd((unsigned long long*)&wst[2], (unsigned long long)(now - wt)); wt = now; }
+#endif
             }
-            s_item[0] = c; s_item[1] = local; s_item[2] = ok;
+            bar_lds();
+            const int c = s_item[0], local = s_item[1], ok = s_item[2];
+            if (ok == 0) return;
+            if (ok == 2) { bar_lds(); break; }   // this queue is empty: on to the next group
+            // the rows of the tile: the group's rows of the chunk's timesteps, in time order, PIPE_BM at a time
+            const int t0 = c * pl.ct, nt = min(pl.ct, pl.T - t0);
+            const int rt = local / tiles_n, ctile = local % tiles_n;
+            if (tid <= nt) s_rp[tid] = pl.rp[t0 + tid];
+            if (tid < nt) s_to[tid] = w.t_off[t0 + tid];
+            bar_lds();                      // (s_item may be rewritten from here on)
+            if (tid < PIPE_BM) {
+                const int slot = s_rp[0] + rt * PIPE_BM + tid;
+                int row = -1;
+                if (slot < s_rp[nt]) {
+                    int i = 0;
+                    while (s_rp[i + 1] <= slot) ++i;   // ends: s_rp[nt] > slot
+                    row = s_to[i] + lo + (slot - s_rp[i]);
+                }
+                s_rowmap[tid] = row;
+            }
+            bar_lds();
+            if constexpr (MODE == MODE_BF16)
+                pipe_gemm_tile_dma<true>(w, s_rowmap, 0, 0, ctile * PIPE_BN, smem);
+            else
+                pipe_gemm_tile<MODE, typename LdsElem<MODE>::type>(w, s_rowmap, ctile * PIPE_BN, smem);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            bar_lds();
+            if (tid == 0) __hip_atomic_fetch_add(&pl.done[c], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#ifdef VER_REC_PROF
+            if (tid == 0) {
+                atomicAdd((unsigned long long*)&wst[1], (unsigned long long)(wall_clock64() - wt));
+                atomicAdd((unsigned long long*)&wst[0], 1ull);
+            }
+#endif
         }
-        bar_lds();
-        const int c = s_item[0], local = s_item[1], ok = s_item[2];
-        bar_lds();                      // s_item may be rewritten from here on
-        if (!ok) return;
-        const int row0 = pipe_chunk_row0(w.t_off, c), rows = pipe_chunk_rows(w.t_off, T_all, c);
-        const int rt = local / pl.tiles_n, ct = local % pl.tiles_n;
-        if constexpr (MODE == MODE_BF16)
-            pipe_gemm_tile_dma<true>(w, row0 + rt * PIPE_BM, min(row0 + rows, row0 + (rt + 1) * PIPE_BM), ct * PIPE_BN, smem);
-        else
-            pipe_gemm_tile<MODE, typename LdsElem<MODE>::type>(w, row0 + rt * PIPE_BM, min(row0 + rows, row0 + (rt + 1) * PIPE_BM),
-                                                                ct * PIPE_BN, smem);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        bar_lds();
-        if (threadIdx.x == 0) __hip_atomic_fetch_add(&pl.done[c], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -345,33 +595,51 @@ __device__ __forceinline__ int xcc_ticket(int* tickets, int& xcc) {
     return s_t;
 }
 
+// The kernels below run one of three roles per workgroup, each with its own set of arguments.  Taken by value, all
+// of them are loaded into scalar registers at the top of the kernel and stay there (or rather in spill lanes, from
+// where the time loops fetch them again and again); read in place from the kernel-argument segment (the struct is
+// the kernel's only parameter, so it sits at its start), a role loads what it uses where it uses it.
+template <typename A>
+__device__ __forceinline__ const A& pipe_args_in_place(const A&) {
+    return *(const A*)__builtin_amdgcn_kernarg_segment_ptr();   // (from the constant address space: only a C-style cast does that)
+}
+
 struct PipeFwdArgs {
     RecFwdArgs l0, l1;   // producer (layer 0) and consumer (layer 1)
-    PipeLink link;
     PipeWork work;
+    int tiles_n;         // column tiles per row tile of the workers' GEMM
 };
+// Which group's queue a worker serves first: group 0's chunks are short and its consumer must never wait long,
+// the last group has the most rows.
+__device__ __forceinline__ int pipe_worker_home(int xcc, int rank) {
+    const int wid = (xcc - 2 * PIPE_GROUPS) * REC_MAX_GROUP + rank;
+    const int k = wid & 7;
+    return k < 3 ? 0 : (k < 5 ? 1 : 2);
+}
 template <int MODE, int TPW, int KS, int NBW, bool STATIC>
-__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_pipe_fwd_kernel(PipeFwdArgs p) {
+__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_pipe_fwd_kernel(PipeFwdArgs p_by_value) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const PipeFwdArgs& p = pipe_args_in_place<PipeFwdArgs>(p_by_value);
     int xcc;
     const int rank = xcc_ticket(p.l0.ticket, xcc);
-    PipeLink link = p.link;
-    link.T_all = p.l0.info[1];
+    const int g = xcc < PIPE_GROUPS ? xcc : xcc - PIPE_GROUPS;
 #ifdef VER_REC_PROF
-    const bool stamp = threadIdx.x == 0 && rank == 0 && (xcc == 0 || xcc == PIPE_GROUPS || xcc == PIPE_GROUPS + PIPE_GROUPS_C_FWD);
-    long long* tl = p.l0.prof + 64 + (xcc == 0 ? 0 : (xcc == PIPE_GROUPS ? 2 : 4));
+    const bool stamp = threadIdx.x == 0 && rank == 0 && xcc < PIPE_XCDS;   // when every XCD's first workgroup starts and ends
+    long long* tl = p.l0.prof + 64 + xcc * 2;
     if (stamp) tl[0] = wall_clock64();
 #endif
-    if (xcc < PIPE_GROUPS) {
-        if (rank < p.l0.G)
-            rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_PRODUCER>(p.l0, rank, xcc, PIPE_GROUPS, p.l0.flags + xcc * REC_MAX_GROUP,
-                                                                    link, smem);
-    } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C_FWD) {
-        if (rank < p.l1.G)
-            rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_CONSUMER>(p.l1, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C_FWD,
-                                                                    p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
-    } else if (xcc < PIPE_XCDS) {
-        pipe_worker<MODE, false>(p.work, link, smem);
+    if (xcc < 2 * PIPE_GROUPS) {
+        const PipeLink link = pipe_link_of(p.work.plan, p.work.sync, p.work.M, p.tiles_n, g);
+        const PieceSet ps = pipe_pieces_of(p.work.plan, g);
+        if (xcc < PIPE_GROUPS) {
+            if (rank < p.l0.G)
+                rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_PRODUCER>(p.l0, rank, ps, link.T, p.l0.flags + xcc * REC_MAX_GROUP, link, smem);
+        } else {
+            if (rank < p.l1.G)
+                rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_CONSUMER>(p.l1, rank, ps, link.T, p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
+        }
+    } else if (xcc < PIPE_XCDS && rank < REC_MAX_GROUP) {
+        pipe_worker<MODE, false>(p.work, p.tiles_n, pipe_worker_home(xcc, rank), smem);
     }
 #ifdef VER_REC_PROF
     if (stamp) tl[1] = wall_clock64();
@@ -380,27 +648,37 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
 
 struct PipeBwdArgs {
     RecBwdArgs l1, l0;   // producer (layer 1) and consumer (layer 0)
-    PipeLink link;
     PipeWork work;
+    int tiles_n;
 };
 template <int MODE, int MT, int KS, int NI>
-__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_pipe_bwd_kernel(PipeBwdArgs p) {
-    typedef typename RecGeom<MODE>::E E;
+__global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lstm_pipe_bwd_kernel(PipeBwdArgs p_by_value) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const PipeBwdArgs& p = pipe_args_in_place<PipeBwdArgs>(p_by_value);
     int xcc;
     const int rank = xcc_ticket(p.l1.ticket, xcc);
-    PipeLink link = p.link;
-    link.T_all = p.l1.info[1];
-    if (xcc < PIPE_GROUPS) {
-        if (rank < p.l1.G)
-            rec_bwd_body<MODE, MT, KS, NI, PIPE_PRODUCER>(p.l1, rank, xcc, PIPE_GROUPS, p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
-    } else if (xcc < PIPE_GROUPS + PIPE_GROUPS_C_BWD) {
-        if (rank < p.l0.G)
-            rec_bwd_body<MODE, MT, KS, NI, PIPE_CONSUMER>(p.l0, rank, xcc - PIPE_GROUPS, PIPE_GROUPS_C_BWD,
-                                                          p.l0.flags + xcc * REC_MAX_GROUP, link, smem);
-    } else if (xcc < PIPE_XCDS) {
-        pipe_worker<MODE, true>(p.work, link, smem);
+    const int g = xcc < PIPE_GROUPS ? xcc : xcc - PIPE_GROUPS;
+#ifdef VER_REC_PROF
+    const bool stamp = threadIdx.x == 0 && rank == 0 && xcc < PIPE_XCDS;
+    long long* tl = p.l1.prof - 16 + 64 + xcc * 2;
+    if (stamp) tl[0] = wall_clock64();
+#endif
+    if (xcc < 2 * PIPE_GROUPS) {
+        const PipeLink link = pipe_link_of(p.work.plan, p.work.sync, p.work.M, p.tiles_n, g);
+        const PieceSet ps = pipe_pieces_of(p.work.plan, g);
+        if (xcc < PIPE_GROUPS) {
+            if (rank < p.l1.G)
+                rec_bwd_body<MODE, MT, KS, NI, PIPE_PRODUCER>(p.l1, rank, ps, link.T, p.l1.flags + xcc * REC_MAX_GROUP, link, smem);
+        } else {
+            if (rank < p.l0.G)
+                rec_bwd_body<MODE, MT, KS, NI, PIPE_CONSUMER>(p.l0, rank, ps, link.T, p.l0.flags + xcc * REC_MAX_GROUP, link, smem);
+        }
+    } else if (xcc < PIPE_XCDS && rank < REC_MAX_GROUP) {
+        pipe_worker<MODE, true>(p.work, p.tiles_n, pipe_worker_home(xcc, rank), smem);
     }
+#ifdef VER_REC_PROF
+    if (stamp) tl[1] = wall_clock64();
+#endif
 }
 
 }  // namespace ver

@@ -43,7 +43,10 @@ namespace ver {
 // Optional phase timing (build with -DVER_REC_PROF): thread 0 of the rank-0 workgroup adds the core-clock
 // cycles spent in each phase of the time loop to prof[phase]; prof[15] counts timesteps.  Off in the product build.
 #ifdef VER_REC_PROF
-#define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof; const bool prof_on = threadIdx.x == 0 && rank == 0 && x == 0;
+#ifndef VER_REC_PROF_GROUP
+#define VER_REC_PROF_GROUP 0
+#endif
+#define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof; const bool prof_on = threadIdx.x == 0 && rank == 0 && ps.id == VER_REC_PROF_GROUP;
 #define REC_PROF_START() do { if (prof_on) prof_t = clock64(); } while (0)
 #define REC_PROF_MARK(i) do { if (prof_on) { long long now_ = clock64(); prof_out[i] += now_ - prof_t; prof_t = now_; } } while (0)
 #define REC_PROF_STEP() do { if (prof_on) prof_out[15] += 1; } while (0)
@@ -131,9 +134,17 @@ __device__ __forceinline__ int rec_rank(int* tickets, int G, int& grp) {
     grp = s_grp;
     return s_rank;
 }
-// Pieces of group x (of X groups) alive when `bs` pieces are alive in all: n = x, x + X, ... < bs.
-__device__ __forceinline__ int grp_count(int bs, int x, int X) { return bs > x ? (bs - x + X - 1) / X : 0; }
-// Timesteps at which group x has an alive piece: batch sizes never grow, so that is how many exceed x.
+// Which pieces a group runs: n = x + m * X for m = 0 .. cap-1.  Dealt round-robin to X groups (x = group, cap
+// unbounded) or a block of consecutive pieces (x = first piece, X = 1, cap = pieces in the block).
+struct PieceSet {
+    int x, X, cap;
+    int id;   // index of the group (only named by the profiling build)
+};
+// Pieces of the set alive when `bs` pieces are alive in all (the alive ones are always the first of the set).
+__device__ __forceinline__ int grp_count(int bs, const PieceSet& ps) {
+    return bs > ps.x ? min((bs - ps.x + ps.X - 1) / ps.X, ps.cap) : 0;
+}
+// Timesteps at which piece x is alive: batch sizes never grow, so that is how many exceed x.
 __device__ __forceinline__ int grp_steps(const int32_t* batch_sizes, int T, int x) {
     __shared__ int s_T;
     if (threadIdx.x == 0) s_T = 0;
@@ -317,40 +328,39 @@ __device__ __forceinline__ void mma_dispatch(const f32x4_t (&wreg)[NW], const ty
 }
 
 // ---- two layers in one launch ---------------------------------------------------------------------------
-// With two layers, both time loops run in the same launch on different XCDs: the groups of the first
-// ("producer") layer in time order publish how far they are; workgroups on the remaining XCDs ("workers")
-// turn each finished chunk of PIPE_CT timesteps into the second layer's input (a GEMM tile at a time,
-// gemm_pipe.h); the groups of the second ("consumer") layer wait for the chunk that holds their next timestep.
-// Everything that crosses XCDs is written through to memory (the L2s of different XCDs are not coherent),
-// completed (s_waitcnt) before it is announced, and announced/read with agent-scope atomics.
-#ifndef VER_PIPE_CT
-#define VER_PIPE_CT 4
-#endif
-constexpr int PIPE_CT = VER_PIPE_CT;   // timesteps per chunk
+// With two layers, both time loops run in the same launch on different XCDs.  Group g of the first
+// ("producer") layer and group g of the second ("consumer") layer run the same block of consecutive pieces
+// (lstm_pipe.h says how the blocks are chosen); a producer group publishes how far it is; workgroups on the
+// remaining XCDs ("workers") turn each finished chunk of a group's timesteps into the consumer group's input (a
+// GEMM tile at a time); a consumer group waits for the chunk that holds its next timestep.  Groups never wait
+// for each other.  Everything that crosses XCDs is written through to memory (the L2s of different XCDs are not
+// coherent), completed (s_waitcnt) before it is announced, and announced/read with agent-scope atomics.
 constexpr int PIPE_BM = 128;         // rows per GEMM tile
 constexpr int PIPE_BN = 256;         // columns per GEMM tile
+constexpr int PIPE_CT_MAX = 32;      // at most this many timesteps per chunk
 enum { PIPE_NONE = 0, PIPE_PRODUCER = 1, PIPE_CONSUMER = 2 };
+// One group's view of the hand-over (producer and consumer groups with the same index run the same pieces).
 struct PipeLink {
-    int* progress;   // [producer groups] timesteps whose rows are complete in memory
-    int* done;       // [chunks] GEMM tiles finished per chunk
+    int* progress;   // the group's word: timesteps whose producer rows are complete in memory
+    int* done;       // the group's [chunks]: GEMM tiles finished per chunk
+    const int* rp;   // the group's [T + 1]: rows of the group in the timesteps before t
+    int ct;          // timesteps per chunk of the group: chunk c = timesteps [c*ct, (c+1)*ct)
     int tiles_n;     // column tiles per row tile of the GEMM
-    int T_all;       // timesteps of the minibatch
-    int M;           // rows of the minibatch
+    int T;           // the group's timesteps
 };
-// Rows of the chunk of timesteps [c*PIPE_CT, (c+1)*PIPE_CT) and the GEMM tiles that cover them.
-__device__ __forceinline__ int pipe_chunk_row0(const int32_t* t_off, int c) { return t_off[c * PIPE_CT]; }
-__device__ __forceinline__ int pipe_chunk_rows(const int32_t* t_off, int T_all, int c) {
-    const int t1 = min((c + 1) * PIPE_CT, T_all);
-    return t_off[t1] - t_off[c * PIPE_CT];
-}
-__device__ __forceinline__ int pipe_chunk_tiles(const int32_t* t_off, const PipeLink& pl, int c) {
-    return (pipe_chunk_rows(t_off, pl.T_all, c) + PIPE_BM - 1) / PIPE_BM * pl.tiles_n;
+// GEMM tiles that cover the group's rows of chunk c.
+__device__ __forceinline__ int pipe_chunk_tiles(const PipeLink& pl, int c) {
+    const int t0 = c * pl.ct, t1 = min(t0 + pl.ct, pl.T);
+    return (pl.rp[t1] - pl.rp[t0] + PIPE_BM - 1) / PIPE_BM * pl.tiles_n;
 }
 // Consumer: blocks until the workers have finished chunk c.  False if the wait was abandoned.
-__device__ __forceinline__ bool pipe_wait_chunk(const int32_t* t_off, const PipeLink& pl, int c, int* err) {
+__device__ __forceinline__ bool pipe_wait_chunk(const PipeLink& pl, int c, int* err, long long* waited = nullptr) {
     __shared__ int s_ok2;
     if (threadIdx.x == 0) {
-        const int need = pipe_chunk_tiles(t_off, pl, c);
+#ifdef VER_REC_PROF
+        const long long w0 = wall_clock64();
+#endif
+        const int need = pipe_chunk_tiles(pl, c);
         long long spins = 0;
         bool alive = true;
         while (ld_agent(&pl.done[c]) < need) {
@@ -362,10 +372,18 @@ __device__ __forceinline__ bool pipe_wait_chunk(const int32_t* t_off, const Pipe
             }
         }
         s_ok2 = alive ? 1 : 0;
+#ifdef VER_REC_PROF
+        if (waited) *waited += wall_clock64() - w0;   // (100 MHz clock)
+#endif
     }
     bar_lds();
     return s_ok2 != 0;
 }
+#ifdef VER_REC_PROF
+#define REC_PROF_CHUNK_ACC(a, rank, ps) ((rank) == 0 ? (a).prof_all + 88 + (ps).id : nullptr)
+#else
+#define REC_PROF_CHUNK_ACC(a, rank, ps) nullptr
+#endif
 // Stores that are written through to memory (visible to the other XCDs once complete).  rs: buffer resource
 // (wave-uniform) of the rows of one timestep; off: this lane's byte offset in it.
 __device__ __forceinline__ void st_through(__amdgpu_buffer_rsrc_t rs, int off, float v) {
@@ -467,6 +485,7 @@ struct RecFwdArgs {
     int* ticket;        // [REC_GROUPS] zero at launch
     int* err;
     long long* prof;    // [16] phase cycle counters (only touched by builds with VER_REC_PROF)
+    long long* prof_all;   // start of the profiling words
 };
 
 // Waves are (row group rg, contraction share ks): REC_WAVES = RG * KS; a wave multiplies TPW tiles of 16 gate
@@ -476,8 +495,9 @@ struct RecFwdArgs {
 // rank: this workgroup's rank in its group; the group runs the pieces n = m * X + x, m = 0, 1, ...; flags: the
 // group's flag words.  PIPE: alone, or producer / consumer of a two-layer launch (pl).
 template <int MODE, int TPW, int KS, int NBW, bool STATIC, int PIPE>
-__device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int x, int X, int* flags, const PipeLink& pl,
-                                             unsigned char* smem) {
+__device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, const PieceSet ps, int T, int* flags,
+                                             const PipeLink& pl, unsigned char* smem) {
+    const int x = ps.x, X = ps.X;
     typedef typename RecGeom<MODE>::E E;
     constexpr int PAD = RecGeom<MODE>::PAD, KBLK = RecGeom<MODE>::KBLK, VEC = RecGeom<MODE>::VEC;
     constexpr int RG = REC_WAVES / KS, MT = RG * TPW, UH = 4 * MT, ROWS = 16 * MT;
@@ -492,7 +512,7 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
     const int rg = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
     const int j0 = rank * UH;
-    const int n_seq = grp_count(a.info[0], x, X), T = grp_steps(a.batch_sizes, a.info[1], x);
+    const int n_seq = grp_count(a.info[0], ps);
     E* hprev = static_cast<E*>(a.hprev);
     const int k_lo = ((ks + rank) % KS) * (H / KS);   // which share a wave takes rotates with the rank, too
     const int nb = (H / KS) / KBLK;
@@ -532,9 +552,10 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
         zpre[q] = znext[q] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         goff[q] = ((unsigned)((q * 16 + lr) * X + x) * 4u * (unsigned)H + (unsigned)je * 4u) * 4u;
     }
-    if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(a.t_off, pl, 0, a.err)) return;
+    if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(pl, 0, a.err, REC_PROF_CHUNK_ACC(a, rank, ps))) return;
+    int c_wait = 1;   // consumer: the chunk it has to wait for next
     if (has_tile && T > 0) {
-        const int bs0 = grp_count(a.batch_sizes[0], x, X);
+        const int bs0 = grp_count(a.batch_sizes[0], ps);
 #pragma unroll
         for (int q = 0; q < REC_PRE; ++q)
             if (q * 16 + lr < bs0) {
@@ -565,10 +586,12 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
         // value is kept in a vector register and made uniform only where the step waits for its stores anyway)
         int bs_c_v = (t + 2 < T) ? a.batch_sizes[t + 2] : 0;
         // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
-        const int bs_all = bs_a, bs = grp_count(bs_all, x, X);
-        const int bs_next = (t + 1 < T) ? grp_count(bs_b, x, X) : 0, base_next = base + bs_all;
-        if (PIPE == PIPE_CONSUMER && t + 1 < T && (t + 1) % PIPE_CT == 0 &&
-            !pipe_wait_chunk(a.t_off, pl, (t + 1) / PIPE_CT, a.err)) return;
+        const int bs_all = bs_a, bs = grp_count(bs_all, ps);
+        const int bs_next = (t + 1 < T) ? grp_count(bs_b, ps) : 0, base_next = base + bs_all;
+        if (PIPE == PIPE_CONSUMER && t + 1 < T && t + 1 == c_wait * pl.ct) {
+            if (!pipe_wait_chunk(pl, c_wait, a.err, REC_PROF_CHUNK_ACC(a, rank, ps))) return;
+            ++c_wait;
+        }
         REC_PROF_MARK(6);
         const unsigned so_hcopy = (unsigned)base * (unsigned)(H * (int)sizeof(E));
         // Where this timestep's rows (and the next one's) begin inside the activation arrays, in bytes: the scalar
@@ -577,7 +600,7 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
         const unsigned so_gnext = (unsigned)base_next * row_g, so_hnext = (unsigned)base_next * (unsigned)(H * (int)sizeof(E));
         if (!rec_wait(flags, G, t + 1, a.err)) return;
         // every workgroup of the group has raised its flag for timestep t-1, i.e. completed that step's stores
-        if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0 && t > 0) st_agent(&pl.progress[x], t);
+        if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0 && t > 0) st_agent(pl.progress, t);
         REC_PROF_MARK(0);
         for (int c0 = 0; c0 < bs; c0 += 16 * ntc) {
             const int rows = min(bs - c0, 16 * ntc), nt = (rows + 15) >> 4;
@@ -690,7 +713,7 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, int 
     }
     if (PIPE == PIPE_PRODUCER && rank == 0) {   // the last timestep is complete once every flag says so
         if (T > 0 && !rec_wait(flags, G, T + 1, a.err)) return;
-        if (tid == 0) st_agent(&pl.progress[x], T);
+        if (tid == 0) st_agent(pl.progress, T);
     }
 }
 
@@ -701,7 +724,9 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     const int rank = rec_rank(a.ticket, a.G, grp);
     if (rank < 0) return;
     PipeLink none = {};
-    rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_NONE>(a, rank, grp, REC_GROUPS, a.flags + grp * REC_MAX_GROUP, none, smem);
+    const PieceSet ps = {grp, REC_GROUPS, 0x7fffffff, grp};
+    const int T = grp_steps(a.batch_sizes, a.info[1], grp);
+    rec_fwd_body<MODE, TPW, KS, NBW, STATIC, PIPE_NONE>(a, rank, ps, T, a.flags + grp * REC_MAX_GROUP, none, smem);
 }
 
 // ======================================================================================================
@@ -724,6 +749,7 @@ struct RecBwdArgs {
     int* ticket;
     int* err;
     long long* prof;
+    long long* prof_all;
 };
 
 // What the gate-gradient step needs from the forward pass for one (piece, unit).
@@ -744,8 +770,9 @@ __device__ __forceinline__ BwdSaved load_saved(const RecBwdArgs& a, int t, int b
 
 // MT 16-unit tiles per workgroup, KS waves per tile split the contraction over the 4H gate rows.
 template <int MODE, int MT, int KS, int NI, int PIPE>
-__device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int x, int X, int* flags, const PipeLink& pl,
-                                             unsigned char* smem) {
+__device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, const PieceSet ps, int T, int* flags,
+                                             const PipeLink& pl, unsigned char* smem) {
+    const int x = ps.x, X = ps.X;
     static_assert(MT * KS == REC_WAVES, "one wave per (tile, k-split)");
     static_assert(MT * REC_NTC <= REC_WAVES, "one wave per tile sum");
     typedef typename RecGeom<MODE>::E E;
@@ -762,7 +789,6 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
     const int mt = wave / KS, ks = wave % KS;
     const int lr = lane & 15, lk = lane >> 4;
     const int j0 = rank * UH;
-    const int T = grp_steps(a.batch_sizes, a.info[1], x);
     E* dzw = static_cast<E*>(a.dz);
     const int k_lo = ks * (K / KS);
     const int ni = (K / KS) / KBLK;
@@ -788,14 +814,15 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
     pre.g4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
     pre.c = pre.c_prev = pre.dh_above = 0.f;
     float dcreg = 0.f;   // cell-state gradient of that (piece, unit), carried from timestep to timestep
-    if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(a.t_off, pl, (T - 1) / PIPE_CT, a.err)) return;
+    int c_wait = T > 0 ? (T - 1) / pl.ct : 0;   // consumer: the chunk of the timestep it runs next
+    if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(pl, c_wait, a.err, REC_PROF_CHUNK_ACC(a, rank, ps))) return;
     // batch sizes of timesteps t+1, t, t-1, t-2 (t-3 is fetched a step ahead, see the forward kernel); row offsets
     // follow by subtraction
     int bs_up = 0, bs_t = T > 0 ? a.batch_sizes[T - 1] : 0, bs_m1 = T > 1 ? a.batch_sizes[T - 2] : 0,
         bs_m2 = T > 2 ? a.batch_sizes[T - 3] : 0;
     int base = T > 0 ? a.t_off[T - 1] : 0;
     if (T > 0) {
-        const int bs_l = grp_count(bs_t, x, X);
+        const int bs_l = grp_count(bs_t, ps);
         if (tid < bs_l * UH)
             pre = load_saved(a, T - 1, base, base - bs_m1, (tid / UH) * X + x, j0 + (tid % UH), H);
     }
@@ -804,8 +831,8 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
     for (int t = T - 1; t >= 0; --t) {
         // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
         const int bs_m3 = t > 2 ? a.batch_sizes[t - 3] : 0;
-        const int bs = grp_count(bs_t, x, X);
-        const int bs_next = (t + 1 < T) ? grp_count(bs_up, x, X) : 0;
+        const int bs = grp_count(bs_t, ps);
+        const int bs_next = (t + 1 < T) ? grp_count(bs_up, ps) : 0;
         const int base_prev = base - bs_m1;     // rows of timestep t-1 (unused when t == 0)
         const unsigned so_dz = (unsigned)base * (unsigned)(K * (int)sizeof(E));   // where this timestep's dz rows begin
         // A. gate gradients of this workgroup's units for every alive piece
@@ -831,7 +858,7 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
             const float tc = tanhf_(sv.c);
             dc += dh * go * (1.f - tc * tc);
             // (written through in a two-layer launch: the rows are also read by the workers on other XCDs)
-            st_row4_buf<E, PIPE == PIPE_PRODUCER ? 17 : 0>(rs_dzall, (n * K + j * 4) * (int)sizeof(E), so_dz, dc * gg * gi * (1.f - gi),
+                        st_row4_buf<E, PIPE == PIPE_PRODUCER ? 17 : 0>(rs_dzall, (n * K + j * 4) * (int)sizeof(E), so_dz, dc * gg * gi * (1.f - gi),
                                                            dc * sv.c_prev * gf * (1.f - gf), dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
             if (first) dcreg = dc * gf;
             else a.dc_state[(size_t)n * H + j] = dc * gf;
@@ -843,7 +870,7 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
         if (t == 0 && rank != 0) break;
         if (!rec_wait(flags, G, T - t, a.err)) return;
         // every workgroup of the group has completed the dz rows of timesteps >= t
-        if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0) st_agent(&pl.progress[x], T - t);
+        if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0) st_agent(pl.progress, T - t);
         if (t == 0) break;
         REC_PROF_MARK(10);
         // B. dh carried to t-1: dh[n][k] = sum_q dz[n][q] * W_hh[q][k] for this workgroup's columns k
@@ -854,13 +881,15 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, int 
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             bar_lds();
             REC_PROF_MARK(11);
-            if (PIPE == PIPE_CONSUMER && c0 == 0 && t % PIPE_CT == 0 && !pipe_wait_chunk(a.t_off, pl, (t - 1) / PIPE_CT, a.err))
-                return;
+            if (PIPE == PIPE_CONSUMER && c0 == 0 && t == c_wait * pl.ct) {   // timestep t-1 opens the chunk below
+                --c_wait;
+                if (!pipe_wait_chunk(pl, c_wait, a.err, REC_PROF_CHUNK_ACC(a, rank, ps))) return;
+            }
             REC_PROF_MARK(13);
             if (c0 == 0) {
                 // saved activations of this thread's first item of timestep t-1, issued once the exchanged rows
                 // have arrived (see the forward kernel): in flight during the MFMA phase
-                const int bs_p = grp_count(bs_m1, x, X);
+                const int bs_p = grp_count(bs_m1, ps);
                 if (tid < bs_p * UH) {
                     const unsigned so = (unsigned)base_prev * row_h;
                     pre.g4 = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs_gates, poff * 4u, so * 4u, 0));
@@ -918,7 +947,9 @@ __global__ __launch_bounds__(REC_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     const int rank = rec_rank(a.ticket, a.G, grp);
     if (rank < 0) return;
     PipeLink none = {};
-    rec_bwd_body<MODE, MT, KS, NI, PIPE_NONE>(a, rank, grp, REC_GROUPS, a.flags + grp * REC_MAX_GROUP, none, smem);
+    const PieceSet ps = {grp, REC_GROUPS, 0x7fffffff, grp};
+    const int T = grp_steps(a.batch_sizes, a.info[1], grp);
+    rec_bwd_body<MODE, MT, KS, NI, PIPE_NONE>(a, rank, ps, T, a.flags + grp * REC_MAX_GROUP, none, smem);
 }
 
 }  // namespace ver
