@@ -17,9 +17,10 @@
 // longest ones (its chain of T_max dependent steps is what bounds the launch, so its steps should be the
 // cheapest), the last group the many short ones (few steps, each with many pieces).  lstm_pipe_plan_kernel
 // picks the two cuts that minimise the largest predicted group time
-//     sum over the group's timesteps of (step + piece * b_t + pair * b_t^2),   b_t = alive pieces of the group,
-// which it evaluates in O(1) per candidate from prefix sums over the pieces' lengths (sum_t b_t = sum of the
-// lengths, sum_t b_t^2 = sum_j length_j * (2 j + 1) over the block's pieces j = 0, 1, ... in order).  Producer and
+//     sum over the group's timesteps of (step + piece * b_t + tile * (ceil(b_t / 16) - 1)),   b_t = alive pieces of the group
+// (a time loop works through the alive pieces 16 at a time: the MFMA's columns), which it evaluates per candidate
+// from the pieces' lengths: sum_t b_t = sum of the block's lengths (a prefix sum), and the timesteps with more
+// than 16 k alive pieces are those of the block's piece number 16 k.  Producer and
 // consumer group g run the same block, and everything between them is per group: chunks of the group's own
 // timesteps, tiles over the group's own rows (gathered: a group's rows of a timestep are consecutive, those of
 // a chunk are not), a queue and completion counters of its own.  So a group never waits for another one: with
@@ -47,20 +48,21 @@ constexpr int PLAN_T = 8;            // [PIPE_GROUPS] timesteps of the group (th
 constexpr int PLAN_CT = 12;          // [PIPE_GROUPS] timesteps per chunk
 constexpr int PLAN_HDR = 16;         // then rp[PIPE_GROUPS][M + 1]: rows of the group in the timesteps before t
 inline __host__ __device__ size_t plan_words(int M) { return PLAN_HDR + (size_t)PIPE_GROUPS * ((size_t)M + 1); }
-inline __host__ __device__ size_t plan_scratch_floats(int M) { return 3 * ((size_t)M + 1); }
+inline __host__ __device__ size_t plan_scratch_floats(int M) { return 2 * ((size_t)M + 1); }
 // The words a launch synchronises through (zero at launch): progress[g] at g, queue[g] at 8 + g, then
 // done[g][chunk] from 16 with PIPE_GROUPS rows of pipe_done_stride(M) words.
 constexpr int PIPE_CT_MIN = 4;
 inline __host__ __device__ int pipe_done_stride(int M) { return M / PIPE_CT_MIN + 2; }
 inline __host__ __device__ int pipe_sync_words(int M) { return 16 + PIPE_GROUPS * pipe_done_stride(M); }
 
-// Predicted microseconds of a timestep: step + piece * b + pair * b^2 (b alive pieces of the group; measured on
-// equally long pieces), and the timesteps per chunk: at most ct0 for group 0 (every timestep of a chunk delays the
+// Predicted microseconds of a timestep: step + piece * b + tile * (ceil(b / 16) - 1) (b alive pieces of the group;
+// least-squares fit to the measured times of the groups of 16 minibatches of the paper's largest configuration:
+// residual 26 us (forward) and 31 us (backward) rms on group times of 0.8-2 ms), and the timesteps per chunk: at most ct0 for group 0 (every timestep of a chunk delays the
 // end of the launch once), at most ct for the other groups (which have time to spare: fewer, fuller tiles), and
 // no more than chunk_rows / (pieces of the group): the consumer of a group ends one chunk of GEMM tiles and one
 // chunk of its own steps after the producer, and starts as much later.
 struct PlanCost {
-    float step, piece, pair;
+    float step, piece, tile;
     int ct0, ct, chunk_rows;
 };
 #ifndef VER_PLAN_CT0
@@ -72,8 +74,8 @@ struct PlanCost {
 #ifndef VER_PLAN_CHUNK_ROWS
 #define VER_PLAN_CHUNK_ROWS 256
 #endif
-constexpr PlanCost PLAN_COST_FWD = {2.85f, 0.080f, 0.0019f, VER_PLAN_CT0, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
-constexpr PlanCost PLAN_COST_BWD = {2.94f, 0.111f, 0.0025f, VER_PLAN_CT0, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
+constexpr PlanCost PLAN_COST_FWD = {2.96f, 0.082f, 1.48f, VER_PLAN_CT0, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
+constexpr PlanCost PLAN_COST_BWD = {2.83f, 0.167f, 1.95f, VER_PLAN_CT0, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
 
 struct PipeWork {
     const void* A;      // producer rows [M, K], operand type (forward: h, backward: dz)
@@ -127,30 +129,31 @@ __global__ __launch_bounds__(PLAN_THREADS) void lstm_pipe_plan_kernel(const int3
     for (int i = tid; i < n_clear; i += PLAN_THREADS) clear_first[i] = 0;
     float* len = scratch;          // [n_seq] timesteps of piece n
     float* S1 = scratch + M + 1;   // [n_seq + 1] sum of len[j], j < n
-    float* S2 = S1 + M + 1;        // [n_seq + 1] sum of j * len[j], j < n
     for (int t = tid; t < T; t += PLAN_THREADS) {
         const int hi = min(batch_sizes[t], n_seq), lo = t + 1 < T ? min(batch_sizes[t + 1], n_seq) : 0;
         for (int n = lo; n < hi; ++n) len[n] = (float)(t + 1);   // the pieces that end with timestep t
     }
     __syncthreads();
-    float c1 = 0.f, c2 = 0.f;
+    float c1 = 0.f;
     for (int b0 = 0; b0 < n_seq; b0 += PLAN_THREADS) {
         const int n = b0 + tid;
         const float l = n < n_seq ? len[n] : 0.f;
-        float t1, t2;
+        float t1;
         const float e1 = plan_scan<float>(l, s_wf, t1);
-        const float e2 = plan_scan<float>(l * (float)n, s_wf, t2);
-        if (n < n_seq) { S1[n] = c1 + e1; S2[n] = c2 + e2; }
-        c1 += t1; c2 += t2;
+        if (n < n_seq) S1[n] = c1 + e1;
+        c1 += t1;
     }
-    if (tid == 0) { S1[n_seq] = c1; S2[n_seq] = c2; }
+    if (tid == 0) S1[n_seq] = c1;
     __syncthreads();
     // predicted time of a group that runs the pieces [lo, hi)
     auto cost = [&](int lo, int hi) -> float {
         if (hi <= lo) return 0.f;
-        const float R = S1[hi] - S1[lo];
-        const float Q = 2.f * (S2[hi] - S2[lo]) - (float)(2 * lo - 1) * R;
-        return pc.step * len[lo] + pc.piece * R + pc.pair * Q;
+        // timesteps with more than 16, 32, ... alive pieces; beyond 64 such terms the rest by the midpoint rule
+        float P = 0.f;
+        int k = lo + 16;
+        for (int i = 0; i < 64 && k < hi; ++i, k += 16) P += len[k];
+        if (k < hi) P += (S1[hi] - S1[k - 8]) * (1.f / 16.f);
+        return pc.step * len[lo] + pc.piece * (S1[hi] - S1[lo]) + pc.tile * P;
     };
     // every first cut k1 with the second cut that balances the two remaining groups; ties go to the smaller cuts
     float best = 3.0e38f;
