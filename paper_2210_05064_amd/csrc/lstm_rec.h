@@ -868,7 +868,31 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
         rec_publish(flags, rank, T - t);
         REC_PROF_MARK(9);
         if (t == 0 && rank != 0) break;
-        if (!rec_wait(flags, G, T - t, a.err)) return;
+        if (t > 0) {
+            if (PIPE == PIPE_CONSUMER && t == c_wait * pl.ct) {   // timestep t-1 opens the chunk below
+                --c_wait;
+                if (!pipe_wait_chunk(pl, c_wait, a.err, REC_PROF_CHUNK_ACC(a, rank, ps))) return;
+            }
+            REC_PROF_MARK(13);
+            // Saved activations of this thread's first item of timestep t-1.  They come from memory (the forward pass
+            // wrote them long ago), which takes longer than a whole MFMA phase: so they are requested here, before the
+            // wait for the other workgroups, by waves that do not poll (a poll waits for everything its wave has in
+            // flight); the wait for the exchanged rows below then also covers them.
+            const int bs_p = grp_count(bs_m1, ps);
+            if (tid < bs_p * UH) {
+                const unsigned so = (unsigned)base_prev * row_h;
+                pre.g4 = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs_gates, poff * 4u, so * 4u, 0));
+                pre.c = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_cell, poff, so, 0));
+                pre.dh_above = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_above, poff, so, 0));
+                if (t - 1 == 0) {
+                    const int n = (tid / UH) * X + x;
+                    pre.c_prev = (a.c0 && n < a.seq_cap) ? a.c0[(size_t)n * H + j0 + (tid % UH)] : 0.f;
+                } else {
+                    pre.c_prev = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_cell, poff, (unsigned)(base_prev - bs_m2) * row_h, 0));
+                }
+            }
+        }
+        if (!rec_wait(flags, G, T - t, a.err, REC_WAVES - 1)) return;
         // every workgroup of the group has completed the dz rows of timesteps >= t
         if (PIPE == PIPE_PRODUCER && rank == 0 && tid == 0) st_agent(pl.progress, T - t);
         if (t == 0) break;
@@ -881,28 +905,6 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             bar_lds();
             REC_PROF_MARK(11);
-            if (PIPE == PIPE_CONSUMER && c0 == 0 && t == c_wait * pl.ct) {   // timestep t-1 opens the chunk below
-                --c_wait;
-                if (!pipe_wait_chunk(pl, c_wait, a.err, REC_PROF_CHUNK_ACC(a, rank, ps))) return;
-            }
-            REC_PROF_MARK(13);
-            if (c0 == 0) {
-                // saved activations of this thread's first item of timestep t-1, issued once the exchanged rows
-                // have arrived (see the forward kernel): in flight during the MFMA phase
-                const int bs_p = grp_count(bs_m1, ps);
-                if (tid < bs_p * UH) {
-                    const unsigned so = (unsigned)base_prev * row_h;
-                    pre.g4 = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs_gates, poff * 4u, so * 4u, 0));
-                    pre.c = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_cell, poff, so, 0));
-                    pre.dh_above = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_above, poff, so, 0));
-                    if (t - 1 == 0) {
-                        const int n = (tid / UH) * X + x;
-                        pre.c_prev = (a.c0 && n < a.seq_cap) ? a.c0[(size_t)n * H + j0 + (tid % UH)] : 0.f;
-                    } else {
-                        pre.c_prev = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs_cell, poff, (unsigned)(base_prev - bs_m2) * row_h, 0));
-                    }
-                }
-            }
             f32x4_t acc[REC_NTC];
             mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
 #pragma unroll
