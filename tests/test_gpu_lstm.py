@@ -118,6 +118,29 @@ def test_single_long_piece(ver):
                         minibatches=1), seed=7)
 
 
+@pytest.mark.parametrize("compute", [0, 1])
+def test_two_pieces_leave_a_group_empty(ver, compute):
+    """Two-layer launch with fewer pieces than groups: the third group has no piece and no timestep."""
+    case(ver, wl.scaled(wl.WORKLOADS["nav"], budget=200, n_envs=2, hidden=64, input_dim=8, p_done=0.0,
+                        minibatches=1, speed_sigma=1.0), seed=11, compute=compute)
+
+
+def test_thousands_of_pieces(ver):
+    """Two-layer launch over 4000 pieces of 2 timesteps: the plan's prefix sums run over several blocks of
+    pieces, a group holds more than 64 tiles of 16 pieces, a timestep of a group more rows than a GEMM tile."""
+    _, meta = case(ver, wl.scaled(wl.WORKLOADS["nav"], budget=8000, n_envs=4000, hidden=64, input_dim=8, p_done=0.0,
+                                  minibatches=1, speed_sigma=0.0), seed=12, compute=1)
+    assert meta["n_seq"] >= 4000
+
+
+def test_long_and_short_pieces(ver):
+    """Two-layer launch with more than 1024 timesteps (the plan's row prefix runs over several blocks of
+    timesteps) and pieces of very different lengths."""
+    _, meta = case(ver, wl.scaled(wl.WORKLOADS["nav"], budget=3000, n_envs=6, hidden=64, input_dim=8, p_done=0.001,
+                                  minibatches=1, speed_sigma=1.5), seed=13, compute=0)
+    assert meta["T_max"] > 1024
+
+
 def test_three_layers_wide_input(ver):
     case(ver, wl.scaled(wl.WORKLOADS["manip"], budget=256, n_envs=6, hidden=192, input_dim=260, n_layers=3,
                         p_done=0.03, minibatches=1), seed=8)
