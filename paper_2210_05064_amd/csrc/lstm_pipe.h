@@ -75,7 +75,10 @@ struct PlanCost {
 #define VER_PLAN_CHUNK_ROWS 256
 #endif
 constexpr PlanCost PLAN_COST_FWD = {2.96f, 0.082f, 1.48f, VER_PLAN_CT0, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
-constexpr PlanCost PLAN_COST_BWD = {2.83f, 0.167f, 1.95f, VER_PLAN_CT0, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
+#ifndef VER_PLAN_CT0_BWD
+#define VER_PLAN_CT0_BWD VER_PLAN_CT0
+#endif
+constexpr PlanCost PLAN_COST_BWD = {2.83f, 0.167f, 1.95f, VER_PLAN_CT0_BWD, VER_PLAN_CT, VER_PLAN_CHUNK_ROWS};
 
 struct PipeWork {
     const void* A;      // producer rows [M, K], operand type (forward: h, backward: dz)

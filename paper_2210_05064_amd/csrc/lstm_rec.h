@@ -360,10 +360,12 @@ __device__ __forceinline__ bool pipe_wait_chunk(const PipeLink& pl, int c, int* 
 #ifdef VER_REC_PROF
         const long long w0 = wall_clock64();
 #endif
+        int have = ld_agent(&pl.done[c]);            // (in flight together with the two loads behind `need`)
         const int need = pipe_chunk_tiles(pl, c);
         long long spins = 0;
         bool alive = true;
-        while (ld_agent(&pl.done[c]) < need) {
+        while (have < need) {
+            have = ld_agent(&pl.done[c]);
             ++spins;
             if ((spins & 255) == 0 && (spins > REC_SPIN_LIMIT || ld_agent(err) != 0)) {
                 st_agent(err, 1);
