@@ -323,7 +323,7 @@ struct LstmWs {
     void* dz[2];       // [M, 4H] operand type; the second one only when two layers share a launch
     int* pipe;         // hand-over words of a two-layer launch: progress[8], queues at [8], done[][] from [16]
     int pipe_words;
-    int* plan;         // which pieces every group of a two-layer launch runs, and its chunks (lstm_pipe.h)
+    int* plan[2];      // which pieces every group of a two-layer launch runs, and its chunks (lstm_pipe.h): forward, backward
     float* plan_scratch;
     float* dh[2];      // [M, H] ping-pong: gradient arriving at a layer's h
     float* dh_state;   // [M, H]
@@ -369,7 +369,8 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     // the hand-over words sit right behind, so that one fill clears everything a launch needs cleared
     ws->pipe_words = pipe_sync_words(M);
     ws->pipe = cv.take<int>(ws->pipe_words);
-    ws->plan = cv.take<int>(plan_words(M));
+    ws->plan[0] = cv.take<int>(plan_words(M));
+    ws->plan[1] = cv.take<int>(plan_words(M));
     ws->plan_scratch = cv.take<float>(plan_scratch_floats(M));
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t D = l == 0 ? c.input_dim : H;
@@ -463,19 +464,22 @@ inline size_t pipe_worker_lds() {
     if (MODE == MODE_BF16) return (size_t)PIPE_STAGES * PIPE_STAGE_BYTES;
     return (size_t)(PIPE_BM + PIPE_BN) * GemmGeom<MODE>::LDS_STRIDE * sizeof(typename LdsElem<MODE>::type);
 }
-// Before a two-layer launch: one small kernel zeroes the flags, ticket counters and hand-over words (with_err:
-// also the sticky time-out word at the start of the workspace, forward call only) and writes the launch's plan.
-inline void pipe_prepare(LstmWs& ws, bool with_err, int M, const int32_t* info, const int32_t* batch_sizes, const PlanCost& cost,
-                         hipStream_t s) {
-    int* first = with_err ? ws.err : ws.flags;
+// Before the forward two-layer launch: one small kernel zeroes the flags, ticket counters, hand-over words and the
+// sticky time-out word at the start of the workspace, and writes the plans of both launches of the minibatch (the
+// backward call runs on the packing of the forward call whose activations it finds in the workspace).  Before the
+// backward launch only the words are cleared.
+inline void pipe_prepare_fwd(LstmWs& ws, int M, const int32_t* info, const int32_t* batch_sizes, hipStream_t s) {
     int* last = ws.pipe + ws.pipe_words;
-    hipLaunchKernelGGL(lstm_pipe_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, info, batch_sizes, M, ws.plan, ws.plan_scratch, first,
-                       (int)(last - first), cost);
+    hipLaunchKernelGGL(lstm_pipe_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, info, batch_sizes, M, ws.plan[0], ws.plan[1],
+                       ws.plan_scratch, ws.err, (int)(last - ws.err), PLAN_COST_FWD, PLAN_COST_BWD);
 }
-inline void pipe_work(const LstmWs& ws, int M, const int32_t* t_off, PipeWork* pw) {
+inline void pipe_prepare_bwd(LstmWs& ws, hipStream_t s) {
+    fill_words(ws.flags, (size_t)(ws.pipe + ws.pipe_words - ws.flags), 0, s);
+}
+inline void pipe_work(const LstmWs& ws, int dir, int M, const int32_t* t_off, PipeWork* pw) {
     pw->M = M;
     pw->t_off = t_off;
-    pw->plan = ws.plan;
+    pw->plan = ws.plan[dir];
     pw->sync = ws.pipe;
     pw->err = ws.err;
     pw->prof_all = ws.prof;
@@ -569,13 +573,13 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         prep(0);
         prep(1);
         project(0);
-        pipe_prepare(ws, true, M, info, batch_sizes, PLAN_COST_FWD, s);
+        pipe_prepare_fwd(ws, M, info, batch_sizes, s);
         PipeFwdArgs pa;
         pa.l0 = rec_args(0);
         pa.l1 = rec_args(1);
         pa.work.A = ws.layer[0].hcopy; pa.work.B = ws.layer[1].wih; pa.work.C = ws.layer[1].gates;
         pa.work.bias = ws.layer[1].bias; pa.work.K = H; pa.work.N = 4 * H;
-        pipe_work(ws, M, t_off, &pa.work);
+        pipe_work(ws, 0, M, t_off, &pa.work);
         pa.tiles_n = (4 * H + PIPE_BN - 1) / PIPE_BN;
         ProfScope prof(VER_PROF_LSTM_REC_FWD, s);
         VER_FWD_DISPATCH(lstm_pipe_fwd_kernel, pa);
@@ -702,13 +706,13 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     };
 
     if (pipelined) {
-        pipe_prepare(ws, false, M, info, batch_sizes, PLAN_COST_BWD, s);
+        pipe_prepare_bwd(ws, s);
         PipeBwdArgs pa;
         pa.l1 = rec_args(1, ws.dh[0]);
         pa.l0 = rec_args(0, ws.dh[1]);
         pa.work.A = ws.dz[1]; pa.work.B = ws.layer[1].wihT; pa.work.C = ws.dh[1]; pa.work.bias = nullptr;
         pa.work.K = 4 * H; pa.work.N = H;
-        pipe_work(ws, M, t_off, &pa.work);
+        pipe_work(ws, 1, M, t_off, &pa.work);
         pa.tiles_n = (H + PIPE_BN - 1) / PIPE_BN;
         {
         ProfScope prof(VER_PROF_LSTM_REC_BWD, s);

@@ -94,60 +94,81 @@ struct PipeWork {
 };
 
 constexpr int PLAN_THREADS = 1024;
-// Exclusive prefix sum of v over the 1024 threads of the block (thread order); total: the sum.  s_w: 16 words of LDS.
-template <typename T>
-__device__ __forceinline__ T plan_scan(T v, T* s_w, T& total) {
+// Exclusive prefix sums of N values per thread over the 1024 threads of the block (thread order); total: the sums.
+// s_w: 16 * N words of LDS.
+template <typename T, int N>
+__device__ __forceinline__ void plan_scan(T (&v)[N], T* s_w, T (&total)[N]) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    T inc = v;
+    T inc[N];
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const T o = __shfl_up(inc, d, VER_WAVE);
-        if (lane >= d) inc += o;
-    }
-    if (lane == 63) s_w[wave] = inc;
+    for (int i = 0; i < N; ++i) inc[i] = v[i];
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1)
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const T o = __shfl_up(inc[i], d, VER_WAVE);
+            if (lane >= d) inc[i] += o;
+        }
+    if (lane == 63)
+#pragma unroll
+        for (int i = 0; i < N; ++i) s_w[wave * N + i] = inc[i];
     __syncthreads();
-    T off = 0;
-    total = 0;
-    for (int w = 0; w < PLAN_THREADS / 64; ++w) {
-        const T x = s_w[w];
-        if (w < wave) off += x;
-        total += x;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        T off = 0, tot = 0;
+        for (int w = 0; w < PLAN_THREADS / 64; ++w) {
+            const T x = s_w[w * N + i];
+            if (w < wave) off += x;
+            tot += x;
+        }
+        total[i] = tot;
+        v[i] = off + inc[i] - v[i];
     }
     __syncthreads();
-    return off + inc - v;
 }
 
-// One workgroup: clears the launch's synchronisation words and writes its plan (see the top of this file).
-// scratch: plan_scratch_floats(M) floats.
-__global__ __launch_bounds__(PLAN_THREADS) void lstm_pipe_plan_kernel(const int32_t* __restrict__ info, const int32_t* __restrict__ batch_sizes,
-                                                                      int M, int* __restrict__ plan, float* __restrict__ scratch,
-                                                                      int* __restrict__ clear_first, int n_clear, PlanCost pc) {
-    __shared__ float s_wf[PLAN_THREADS / 64];
-    __shared__ int s_wi[PLAN_THREADS / 64];
-    __shared__ float s_obj[PLAN_THREADS];
-    __shared__ int s_k1[PLAN_THREADS], s_k2[PLAN_THREADS];
-    __shared__ int s_kb[PIPE_GROUPS + 1];
+// The plans of the forward and of the backward launch of one minibatch (the same packing, two cost models).
+// IN_LDS: the batch sizes and the per-piece arrays (lengths and their prefix sums) live in LDS (up to PLAN_LDS_N
+// pieces and timesteps: the search for the cuts is a chain of dependent reads of them), else in global memory.
+constexpr int PLAN_LDS_N = 4096;
+constexpr int PLAN_DIRS = 2;
+template <bool IN_LDS>
+__device__ __forceinline__ void plan_body(const int32_t* __restrict__ batch_sizes, int M, int n_seq, int T, int* __restrict__ plan_fwd,
+                                          int* __restrict__ plan_bwd, float* __restrict__ scratch, int* s_bs, float* s_len, float* s_S1,
+                                          const PlanCost& pc_fwd, const PlanCost& pc_bwd) {
+    constexpr int WAVES = PLAN_THREADS / 64, NR = PLAN_DIRS * PIPE_GROUPS;
+    __shared__ float s_wf[WAVES];
+    __shared__ int s_wi[WAVES * NR];
+    __shared__ float s_obj[WAVES];
+    __shared__ int s_k1[WAVES], s_k2[WAVES];
+    __shared__ int s_kb[PLAN_DIRS][PIPE_GROUPS + 1];
     const int tid = threadIdx.x;
-    const int n_seq = min(max(info[0], 0), M), T = min(max(info[1], 0), M);
-    for (int i = tid; i < n_clear; i += PLAN_THREADS) clear_first[i] = 0;
-    float* len = scratch;          // [n_seq] timesteps of piece n
-    float* S1 = scratch + M + 1;   // [n_seq + 1] sum of len[j], j < n
+    const int32_t* bs = batch_sizes;
+    if (IN_LDS) {
+        for (int t = tid; t < T; t += PLAN_THREADS) s_bs[t] = batch_sizes[t];
+        __syncthreads();
+        bs = s_bs;
+    }
+    float* len = IN_LDS ? s_len : scratch;          // [n_seq] timesteps of piece n
+    float* S1 = IN_LDS ? s_S1 : scratch + M + 1;    // [n_seq + 1] sum of len[j], j < n
     for (int t = tid; t < T; t += PLAN_THREADS) {
-        const int hi = min(batch_sizes[t], n_seq), lo = t + 1 < T ? min(batch_sizes[t + 1], n_seq) : 0;
+        const int hi = min(bs[t], n_seq), lo = t + 1 < T ? min(bs[t + 1], n_seq) : 0;
         for (int n = lo; n < hi; ++n) len[n] = (float)(t + 1);   // the pieces that end with timestep t
     }
     __syncthreads();
     float c1 = 0.f;
     for (int b0 = 0; b0 < n_seq; b0 += PLAN_THREADS) {
         const int n = b0 + tid;
-        const float l = n < n_seq ? len[n] : 0.f;
-        float t1;
-        const float e1 = plan_scan<float>(l, s_wf, t1);
-        if (n < n_seq) S1[n] = c1 + e1;
-        c1 += t1;
+        float l[1] = {n < n_seq ? len[n] : 0.f}, t1[1];
+        plan_scan<float, 1>(l, s_wf, t1);
+        if (n < n_seq) S1[n] = c1 + l[0];
+        c1 += t1[0];
     }
     if (tid == 0) S1[n_seq] = c1;
     __syncthreads();
+    // The first half of the block searches the cuts of the forward plan, the second half those of the backward plan.
+    const int dir = tid / (PLAN_THREADS / PLAN_DIRS), rank = tid % (PLAN_THREADS / PLAN_DIRS);
+    const PlanCost pc = dir == 0 ? pc_fwd : pc_bwd;
     // predicted time of a group that runs the pieces [lo, hi)
     auto cost = [&](int lo, int hi) -> float {
         if (hi <= lo) return 0.f;
@@ -161,7 +182,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void lstm_pipe_plan_kernel(const int3
     // every first cut k1 with the second cut that balances the two remaining groups; ties go to the smaller cuts
     float best = 3.0e38f;
     int bk1 = n_seq, bk2 = n_seq;
-    for (int k1 = 1 + tid; k1 <= n_seq; k1 += PLAN_THREADS) {
+    for (int k1 = 1 + rank; k1 <= n_seq; k1 += PLAN_THREADS / PLAN_DIRS) {
         int lo = k1, hi = n_seq;
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
@@ -173,41 +194,78 @@ __global__ __launch_bounds__(PLAN_THREADS) void lstm_pipe_plan_kernel(const int3
             if (obj < best) { best = obj; bk1 = k1; bk2 = k2; }
         }
     }
-    s_obj[tid] = best; s_k1[tid] = bk1; s_k2[tid] = bk2;
-    __syncthreads();
-    for (int w = PLAN_THREADS / 2; w > 0; w >>= 1) {
-        if (tid < w) {
-            const float o = s_obj[tid + w];
-            const int o1 = s_k1[tid + w], o2 = s_k2[tid + w];
-            const bool take = o < s_obj[tid] || (o == s_obj[tid] && (o1 < s_k1[tid] || (o1 == s_k1[tid] && o2 < s_k2[tid])));
-            if (take) { s_obj[tid] = o; s_k1[tid] = o1; s_k2[tid] = o2; }
-        }
-        __syncthreads();
+    // smallest (objective, k1, k2) of each half: inside the waves by shuffles, then over the half's waves
+    auto better = [](float o, int o1, int o2, float m, int m1, int m2) { return o < m || (o == m && (o1 < m1 || (o1 == m1 && o2 < m2))); };
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) {
+        const float o = __shfl_xor(best, d, VER_WAVE);
+        const int o1 = __shfl_xor(bk1, d, VER_WAVE), o2 = __shfl_xor(bk2, d, VER_WAVE);
+        if (better(o, o1, o2, best, bk1, bk2)) { best = o; bk1 = o1; bk2 = o2; }
     }
-    if (tid == 0) {
-        s_kb[0] = 0; s_kb[1] = s_k1[0]; s_kb[2] = s_k2[0]; s_kb[3] = n_seq;
-        for (int g = 0; g <= PIPE_GROUPS; ++g) plan[PLAN_KB + g] = s_kb[g];
+    if ((tid & 63) == 0) { s_obj[tid >> 6] = best; s_k1[tid >> 6] = bk1; s_k2[tid >> 6] = bk2; }
+    __syncthreads();
+    if (rank == 0) {
+        for (int w = dir * (WAVES / PLAN_DIRS) + 1; w < (dir + 1) * (WAVES / PLAN_DIRS); ++w)
+            if (better(s_obj[w], s_k1[w], s_k2[w], best, bk1, bk2)) { best = s_obj[w]; bk1 = s_k1[w]; bk2 = s_k2[w]; }
+        s_kb[dir][0] = 0; s_kb[dir][1] = bk1; s_kb[dir][2] = bk2; s_kb[dir][3] = n_seq;
+        int* plan = dir == 0 ? plan_fwd : plan_bwd;
+        for (int g = 0; g <= PIPE_GROUPS; ++g) plan[PLAN_KB + g] = s_kb[dir][g];
     }
     __syncthreads();
-    for (int g = 0; g < PIPE_GROUPS; ++g) {
-        const int lo = s_kb[g], cap = s_kb[g + 1] - lo;
-        const int Tg = cap > 0 ? (int)len[lo] : 0;
+    // per plan and group: its timesteps, its chunk length, and its rows before every timestep (all six prefix sums at once)
+    int lo_[NR], cap_[NR], Tg_[NR], carry[NR];
+    int Tmax = 0;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+        const int d = r / PIPE_GROUPS, g = r % PIPE_GROUPS;
+        lo_[r] = s_kb[d][g];
+        cap_[r] = s_kb[d][g + 1] - lo_[r];
+        Tg_[r] = cap_[r] > 0 ? (int)len[lo_[r]] : 0;
+        carry[r] = 0;
+        Tmax = max(Tmax, Tg_[r]);
         if (tid == 0) {
-            plan[PLAN_T + g] = Tg;
-            plan[PLAN_CT + g] = min(g == 0 ? pc.ct0 : pc.ct, max(PIPE_CT_MIN, pc.chunk_rows / max(cap, 1)));
+            int* plan = d == 0 ? plan_fwd : plan_bwd;
+            const PlanCost& c = d == 0 ? pc_fwd : pc_bwd;
+            plan[PLAN_T + g] = Tg_[r];
+            plan[PLAN_CT + g] = min(g == 0 ? c.ct0 : c.ct, max(PIPE_CT_MIN, c.chunk_rows / max(cap_[r], 1)));
         }
-        int* rp = plan + PLAN_HDR + (size_t)g * ((size_t)M + 1);
-        int carry = 0;
-        for (int b0 = 0; b0 < Tg; b0 += PLAN_THREADS) {
-            const int t = b0 + tid;
-            const int cnt = t < Tg ? min(max(batch_sizes[t] - lo, 0), cap) : 0;
-            int tot;
-            const int e = plan_scan<int>(cnt, s_wi, tot);
-            if (t < Tg) rp[t] = carry + e;
-            carry += tot;
-        }
-        if (tid == 0) rp[Tg] = carry;
     }
+    for (int b0 = 0; b0 < Tmax; b0 += PLAN_THREADS) {
+        const int t = b0 + tid;
+        const int b = t < Tmax ? bs[t] : 0;
+        int cnt[NR], tot[NR];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) cnt[r] = t < Tg_[r] ? min(max(b - lo_[r], 0), cap_[r]) : 0;
+        plan_scan<int, NR>(cnt, s_wi, tot);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            int* rp = (r / PIPE_GROUPS == 0 ? plan_fwd : plan_bwd) + PLAN_HDR + (size_t)(r % PIPE_GROUPS) * ((size_t)M + 1);
+            if (t < Tg_[r]) rp[t] = carry[r] + cnt[r];
+            carry[r] += tot[r];
+        }
+    }
+    if (tid == 0)
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            int* rp = (r / PIPE_GROUPS == 0 ? plan_fwd : plan_bwd) + PLAN_HDR + (size_t)(r % PIPE_GROUPS) * ((size_t)M + 1);
+            rp[Tg_[r]] = carry[r];
+        }
+}
+
+// One workgroup, in front of the forward launch: clears that launch's synchronisation words and writes the plans of
+// the forward and of the backward launch (see the top of this file).  scratch: plan_scratch_floats(M) floats.
+__global__ __launch_bounds__(PLAN_THREADS) void lstm_pipe_plan_kernel(const int32_t* __restrict__ info, const int32_t* __restrict__ batch_sizes,
+                                                                      int M, int* __restrict__ plan_fwd, int* __restrict__ plan_bwd,
+                                                                      float* __restrict__ scratch, int* __restrict__ clear_first, int n_clear,
+                                                                      PlanCost pc_fwd, PlanCost pc_bwd) {
+    __shared__ int s_bs[PLAN_LDS_N];
+    __shared__ float s_len[PLAN_LDS_N], s_S1[PLAN_LDS_N + 1];
+    const int n_seq = min(max(info[0], 0), M), T = min(max(info[1], 0), M);
+    for (int i = threadIdx.x; i < n_clear; i += PLAN_THREADS) clear_first[i] = 0;
+    if (n_seq <= PLAN_LDS_N && T <= PLAN_LDS_N)
+        plan_body<true>(batch_sizes, M, n_seq, T, plan_fwd, plan_bwd, scratch, s_bs, s_len, s_S1, pc_fwd, pc_bwd);
+    else
+        plan_body<false>(batch_sizes, M, n_seq, T, plan_fwd, plan_bwd, scratch, s_bs, s_len, s_S1, pc_fwd, pc_bwd);
 }
 
 template <typename E, typename T> __device__ __forceinline__ Quad<E> load_quad_coh(__amdgpu_buffer_rsrc_t r, int byte_off);

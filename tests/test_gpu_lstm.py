@@ -125,12 +125,14 @@ def test_two_pieces_leave_a_group_empty(ver, compute):
                         minibatches=1, speed_sigma=1.0), seed=11, compute=compute)
 
 
-def test_thousands_of_pieces(ver):
-    """Two-layer launch over 4000 pieces of 2 timesteps: the plan's prefix sums run over several blocks of
-    pieces, a group holds more than 64 tiles of 16 pieces, a timestep of a group more rows than a GEMM tile."""
-    _, meta = case(ver, wl.scaled(wl.WORKLOADS["nav"], budget=8000, n_envs=4000, hidden=64, input_dim=8, p_done=0.0,
+@pytest.mark.parametrize("n_envs", [3000, 5000])
+def test_thousands_of_pieces(ver, n_envs):
+    """Two-layer launch over thousands of pieces of 2 timesteps: the plan's prefix sums run over several blocks of
+    pieces (held in LDS up to 4096 pieces, in global memory beyond), a group holds more than 64 tiles of 16 pieces,
+    a timestep of a group more rows than a GEMM tile."""
+    _, meta = case(ver, wl.scaled(wl.WORKLOADS["nav"], budget=2 * n_envs, n_envs=n_envs, hidden=64, input_dim=8, p_done=0.0,
                                   minibatches=1, speed_sigma=0.0), seed=12, compute=1)
-    assert meta["n_seq"] >= 4000
+    assert meta["n_seq"] >= n_envs
 
 
 def test_long_and_short_pieces(ver):
