@@ -239,47 +239,8 @@ __global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __r
     if (a < A) dW_a[(size_t)a * H + j] = s; else dw_v[j] = s;
 }
 
-// Column sums of a row-major [rows, cols] matrix in two deterministic stages.  When the shape allows it a block
-// covers 256 columns x CS_ROWS rows: a thread sums 4 adjacent columns (one 8- or 16-byte load per row) over a
-// quarter of the rows, and the four quarters are added in LDS in a fixed order.
-constexpr int CS_ROWS = 256;
-template <typename E>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const E* __restrict__ X, int rows, int cols, int ld,
-                                                             float* __restrict__ part) {
-    __shared__ float red[4][256];
-    const int rb = blockIdx.y;
-    const int r_lo = rb * CS_ROWS, r_hi = min(rows, r_lo + CS_ROWS);
-    if (cols % 4 == 0 && ld % 4 == 0) {
-        const int cq = threadIdx.x & 63, slice = threadIdx.x >> 6;
-        const int c = blockIdx.x * 256 + cq * 4;
-        float s[4] = {0.f, 0.f, 0.f, 0.f};
-        if (c < cols) {
-            for (int r = r_lo + slice * (CS_ROWS / 4); r < min(r_hi, r_lo + (slice + 1) * (CS_ROWS / 4)); r += 4) {
-                Quad<float> q[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    q[u] = (r + u < r_hi) ? load_quad<float, E>(X + (size_t)(r + u) * ld + c) : zero_quad<float>();
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) s[e] += q[u].v[e];
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) red[slice][cq * 4 + e] = s[e];
-        __syncthreads();
-        const int cc = blockIdx.x * 256 + threadIdx.x;
-        if (cc < cols)
-            part[(size_t)rb * cols + cc] = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
-    } else {
-        for (int c = blockIdx.x * 256 + threadIdx.x; c < min(cols, (int)(blockIdx.x + 1) * 256); c += 256) {
-            float s = 0.f;
-            for (int r = r_lo; r < r_hi; ++r) s += cvt_elem<float>(X[(size_t)r * ld + c]);
-            part[(size_t)rb * cols + c] = s;
-        }
-    }
-}
-// out[perm(c)] (and out2) = sum over row blocks; unperm_h > 0 maps interleaved column c to (c%4)*H + c/4.
+// out[perm(c)] (and out2) = sum over the n_rb rows of part[n_rb][cols], in row order (deterministic);
+// unperm_h > 0 maps interleaved column c to (c%4)*H + c/4.
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int n_rb, int cols,
                                                            int unperm_h, float* __restrict__ out,
                                                            float* __restrict__ out2) {
@@ -331,17 +292,13 @@ struct LstmWs {
     float* part;       // partial sums of the two-stage reductions
     float* gemm_part;  // partial tiles of GEMMs whose contraction is split over workgroups
     float* db_head;    // [A+1] scratch for bias sums
+    float* db_part;    // [2][8][4H]: per layer of a launch and group, the sum of the gate gradients over the group's rows
     size_t bytes;
 };
 
 inline size_t part_floats(const ver_lstm_cfg& c, int M) {
     const size_t rb_heads = (size_t)(M + HW_ROWS - 1) / HW_ROWS;
-    const size_t rb_cs = (size_t)(M + CS_ROWS - 1) / CS_ROWS;
-    const size_t a = rb_heads * (c.act_dim + 1) * c.hidden;
-    const size_t b = rb_cs * 4 * c.hidden;
-    const size_t d = rb_cs * (c.act_dim + 1);
-    size_t m = a > b ? a : b;
-    return m > d ? m : d;
+    return rb_heads * (c.act_dim + 1) * c.hidden;   // the row-block partial sums of the heads' weight gradient
 }
 
 // Largest split-K scratch any GEMM of the forward or backward pass asks for.
@@ -395,6 +352,7 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     ws->part = cv.take<float>(part_floats(c, M));
     ws->gemm_part = cv.take<float>(gemm_part_max(c, M));
     ws->db_head = cv.take<float>(64);
+    ws->db_part = cv.take<float>((size_t)2 * REC_GROUPS * 4 * H);
     ws->bytes = cv.used;
 }
 
@@ -611,7 +569,6 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     typedef typename RecGeom<MODE>::E E;
     const int H = c.hidden, A = c.act_dim, nl = c.n_layers;
     const float* h_top = ws.layer[nl - 1].hout;
-    const int rb_c = (M + CS_ROWS - 1) / CS_ROWS;
     // heads
     {
     ProfScope prof(VER_PROF_HEADS_BWD, s);
@@ -647,6 +604,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         // the two layers of a shared launch carry their state in separate halves of the scratch
         ra.dh_state = ws.dh_state + (pipelined ? (size_t)l * M * H : 0);
         ra.dc_state = ws.dc_state + (pipelined ? (size_t)l * M * H : 0);
+        ra.db_part = ws.db_part + (pipelined ? (size_t)l * REC_GROUPS * 4 * H : 0);
         ra.H = H; ra.seq_cap = seq_cap; ra.flags = ws.flags; ra.ticket = ws.flags + 8 * REC_MAX_GROUP;
         ra.err = ws.err; ra.prof = ws.prof + 16 + (pipelined && l == 0 ? 32 : 0); ra.prof_all = ws.prof;
         ra.G = H / (16 * mt); ra.ntc = ntc;
@@ -695,12 +653,11 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(L.hprev), H, gw[4 * l + 1], H, 4 * H, H, M,
                                       nullptr, H, ws.gemm_part, true, s);
         }
-        // db_ih = db_hh = column sums of dz
+        // db_ih = db_hh = column sums of dz: the time loop left one partial sum per group
         {
         ProfScope prof(VER_PROF_LSTM_DBIAS, s);
-        hipLaunchKernelGGL(colsum_partial_kernel<E>, dim3((4 * H + 255) / 256, rb_c), dim3(256), 0, s, dz, M, 4 * H,
-                           4 * H, ws.part);
-        hipLaunchKernelGGL(colsum_final_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, ws.part, rb_c, 4 * H, H,
+        hipLaunchKernelGGL(colsum_final_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s,
+                           ws.db_part + (pipelined ? (size_t)l * REC_GROUPS * 4 * H : 0), pipelined ? PIPE_GROUPS : REC_GROUPS, 4 * H, H,
                            gw[4 * l + 2], gw[4 * l + 3]);
         }
     };

@@ -744,6 +744,7 @@ struct RecBwdArgs {
     const void* whhT;       // [H, 4H] operand type: row k = column k of the interleaved W_hh
     float* dh_state;        // [n_cap, H] recurrent gradient carried to the previous timestep
     float* dc_state;        // [n_cap, H]
+    float* db_part;         // [groups, 4H] (out): every group's sum of dz over its rows, interleaved columns
     int H, seq_cap;
     int G;                  // participating workgroups; each owns 16*MT hidden units
     int ntc;
@@ -816,6 +817,10 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
     pre.g4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
     pre.c = pre.c_prev = pre.dh_above = 0.f;
     float dcreg = 0.f;   // cell-state gradient of that (piece, unit), carried from timestep to timestep
+    // Bias gradient: a thread always works on the same unit (the stride of its items is a multiple of UH), so it
+    // adds up that unit's four gate gradients over all its items in registers; summed over threads after the loop.
+    static_assert(REC_THREADS % UH == 0, "a thread keeps its unit");
+    float db0 = 0.f, db1 = 0.f, db2 = 0.f, db3 = 0.f;
     int c_wait = T > 0 ? (T - 1) / pl.ct : 0;   // consumer: the chunk of the timestep it runs next
     if (PIPE == PIPE_CONSUMER && T > 0 && !pipe_wait_chunk(pl, c_wait, a.err, REC_PROF_CHUNK_ACC(a, rank, ps))) return;
     // batch sizes of timesteps t+1, t, t-1, t-2 (t-3 is fetched a step ahead, see the forward kernel); row offsets
@@ -860,8 +865,10 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
             const float tc = tanhf_(sv.c);
             dc += dh * go * (1.f - tc * tc);
             // (written through in a two-layer launch: the rows are also read by the workers on other XCDs)
-                        st_row4_buf<E, PIPE == PIPE_PRODUCER ? 17 : 0>(rs_dzall, (n * K + j * 4) * (int)sizeof(E), so_dz, dc * gg * gi * (1.f - gi),
-                                                           dc * sv.c_prev * gf * (1.f - gf), dc * gi * (1.f - gg * gg), dh * tc * go * (1.f - go));
+                        const float dzi = dc * gg * gi * (1.f - gi), dzf = dc * sv.c_prev * gf * (1.f - gf), dzg = dc * gi * (1.f - gg * gg),
+                        dzo = dh * tc * go * (1.f - go);
+            st_row4_buf<E, PIPE == PIPE_PRODUCER ? 17 : 0>(rs_dzall, (n * K + j * 4) * (int)sizeof(E), so_dz, dzi, dzf, dzg, dzo);
+            db0 += dzi; db1 += dzf; db2 += dzg; db3 += dzo;
             if (first) dcreg = dc * gf;
             else a.dc_state[(size_t)n * H + j] = dc * gf;
         }
@@ -941,6 +948,19 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
         bs_m2 = bs_m3;
         REC_PROF_MARK(12);
         REC_PROF_STEP();
+    }
+    // bias gradient of this workgroup's units: the REC_THREADS / UH threads of a unit, added in thread order
+    bar_lds();   // (the staging area is free)
+    f32x4_t* s_db = reinterpret_cast<f32x4_t*>(smem);
+    s_db[tid] = f32x4_t{db0, db1, db2, db3};
+    bar_lds();
+    if (tid < UH) {
+        f32x4_t sum = s_db[tid];
+        for (int k = 1; k < REC_THREADS / UH; ++k) {
+            const f32x4_t o = s_db[k * UH + tid];
+            sum[0] += o[0]; sum[1] += o[1]; sum[2] += o[2]; sum[3] += o[3];
+        }
+        *reinterpret_cast<f32x4_t*>(a.db_part + (size_t)ps.id * K + (size_t)(j0 + tid) * 4) = sum;
     }
 }
 
