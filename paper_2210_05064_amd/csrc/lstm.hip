@@ -166,7 +166,7 @@ constexpr int HW_ROWS = 32;  // rows per row block
 __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* __restrict__ d_u,
                                                                   const float* __restrict__ d_v,
                                                                   const float* __restrict__ h, int M, int H, int A,
-                                                                  float* __restrict__ part) {
+                                                                  float* __restrict__ part, float* __restrict__ part_b) {
     __shared__ float s_g[HW_ROWS][64];   // the block's loss gradients: heads 0..A-1, then the value head, then zeros
     const int j = (blockIdx.x * 256 + threadIdx.x) * 4;
     const int rb = blockIdx.y;
@@ -176,6 +176,12 @@ __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* _
         s_g[r][a] = (p < p_hi) ? (a < A ? d_u[(size_t)p * A + a] : (a == A ? d_v[p] : 0.f)) : 0.f;
     }
     __syncthreads();
+    // bias gradients: the block's sum of every head's loss gradient (first column block only), rows in order
+    if (blockIdx.x == 0 && (int)threadIdx.x <= A) {
+        float sb = 0.f;
+        for (int r = 0; r < HW_ROWS; ++r) sb += s_g[r][threadIdx.x];
+        part_b[(size_t)rb * 64 + threadIdx.x] = sb;
+    }
     if (j >= H) return;
     for (int a0 = 0; a0 <= A; a0 += 8) {
         f32x4_t acc[8];
@@ -202,29 +208,27 @@ __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* _
     }
 }
 
-// Bias gradients of the heads: db_a[a] = sum_p d_u[p][a], db_v = sum_p d_v[p].  One block per head; a thread
-// adds a strided share of the rows, the block adds the shares in a fixed tree (deterministic).
-__global__ __launch_bounds__(256) void heads_bias_grad_kernel(const float* __restrict__ d_u, const float* __restrict__ d_v,
-                                                              int M, int A, float* __restrict__ db_a, float* __restrict__ db_v) {
+// Sums the row blocks' partial sums in block order: dW_a / dw_v column j of head a, and (first column block) the
+// head's bias gradient from part_b[n_rb][64], by a fixed tree over the block's threads.
+__global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __restrict__ part, const float* __restrict__ part_b, int n_rb,
+                                                                int H, int A, float* __restrict__ dW_a, float* __restrict__ dw_v,
+                                                                float* __restrict__ db_a, float* __restrict__ db_v) {
     __shared__ float red[256];
-    const int a = blockIdx.x;
-    float s = 0.f;
-    for (int p = threadIdx.x; p < M; p += 256) s += (a < A) ? d_u[(size_t)p * A + a] : d_v[p];
-    red[threadIdx.x] = s;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) {
-        if (a < A) db_a[a] = red[0]; else db_v[0] = red[0];
-    }
-}
-
-__global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __restrict__ part, int n_rb, int H, int A,
-                                                                float* __restrict__ dW_a, float* __restrict__ dw_v) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     const int a = blockIdx.y;
+    if (blockIdx.x == 0) {
+        float sb = 0.f;
+        for (int rb = threadIdx.x; rb < n_rb; rb += 256) sb += part_b[(size_t)rb * 64 + a];
+        red[threadIdx.x] = sb;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            if (a < A) db_a[a] = red[0]; else db_v[0] = red[0];
+        }
+    }
     if (j >= H) return;
     float s = 0.f;
     int rb = 0;
@@ -290,8 +294,8 @@ struct LstmWs {
     float* dh_state;   // [M, H]
     float* dc_state;   // [M, H]
     float* part;       // partial sums of the two-stage reductions
+    float* part_b;     // [row blocks][64]: the heads' bias gradients per row block
     float* gemm_part;  // partial tiles of GEMMs whose contraction is split over workgroups
-    float* db_head;    // [A+1] scratch for bias sums
     float* db_part;    // [2][8][4H]: per layer of a launch and group, the sum of the gate gradients over the group's rows
     size_t bytes;
 };
@@ -350,8 +354,8 @@ inline void lstm_ws_layout(const ver_lstm_cfg& c, int M, void* base, LstmWs* ws)
     ws->dh_state = cv.take<float>(2 * Mz * H);
     ws->dc_state = cv.take<float>(2 * Mz * H);
     ws->part = cv.take<float>(part_floats(c, M));
+    ws->part_b = cv.take<float>((size_t)(M + HW_ROWS - 1) / HW_ROWS * 64);
     ws->gemm_part = cv.take<float>(gemm_part_max(c, M));
-    ws->db_head = cv.take<float>(64);
     ws->db_part = cv.take<float>((size_t)2 * REC_GROUPS * 4 * H);
     ws->bytes = cv.used;
 }
@@ -576,10 +580,9 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
                        w[4 * nl + 2], ws.dh[0]);
     const int rb_h = (M + HW_ROWS - 1) / HW_ROWS;
     hipLaunchKernelGGL(heads_wgrad_partial_kernel, dim3((H / 4 + 255) / 256, rb_h), dim3(256), 0, s, d_u, d_v, h_top, M, H,
-                       A, ws.part);
-    hipLaunchKernelGGL(heads_wgrad_final_kernel, dim3((H + 255) / 256, A + 1), dim3(256), 0, s, ws.part, rb_h, H, A,
-                       gw[4 * nl], gw[4 * nl + 2]);
-    hipLaunchKernelGGL(heads_bias_grad_kernel, dim3(A + 1), dim3(256), 0, s, d_u, d_v, M, A, gw[4 * nl + 1], gw[4 * nl + 3]);
+                       A, ws.part, ws.part_b);
+    hipLaunchKernelGGL(heads_wgrad_final_kernel, dim3((H + 255) / 256, A + 1), dim3(256), 0, s, ws.part, ws.part_b, rb_h, H, A,
+                       gw[4 * nl], gw[4 * nl + 2], gw[4 * nl + 1], gw[4 * nl + 3]);
     }
 
     // one wave per (16 units, share of the 4H contraction): 2 tiles x 4 when H/16 > 32 workgroups, else 1 x 8
