@@ -27,7 +27,7 @@ def main(path):
            "`VER_PARITY_LOG=<log> python -m pytest tests -m gpu` on one MI355X.  Elementwise = max |x - ref| / "
            "max(|ref|, rms(ref)) over the tensor; 2-norm = ||x - ref|| / ||ref||.  Bars (tests/util.py): `bf16` "
            "elementwise 2e-2 (the stated bar); `bf16-bptt` (d_x and the LSTM weight and bias gradients with bf16 "
-           "operands) 2-norm 1e-2 and elementwise 1e-1; `update` (change of a weight tensor over a few optimiser "
+           "operands) 2-norm 7e-3 and elementwise 7e-2; `update` (change of a weight tensor over a few optimiser "
            "steps, fp32 path) 2-norm 2e-4 and elementwise 2.5e-2.", "",
            "## Largest error per bar and tensor over all tests", "",
            "| bar | tensor | comparisons | max elementwise | in test | max 2-norm | in test |", "|---|---|---|---|---|---|---|"]

@@ -58,14 +58,14 @@ def assert_close_bf16_bptt(x, ref, what=""):
     to bf16 as an MFMA operand, and themselves a product of saved gates that carry the forward pass's bf16
     rounding) with bf16 rows, over thousands of terms: an element's error is close to normal with a standard
     deviation of the tensor's relative 2-norm error (measured 1e-3 .. 4.7e-3), and the largest of 10^5 .. 10^7
-    such elements relative to max(|ref|, rms(ref)) sits at 5 to 12 standard deviations (measured up to 5.5e-2 for
-    W_hh, 4.6e-2 W_ih, 3.2e-2 d_x, 2.3e-2 biases): above the stated 2e-2 although the arithmetic is as accurate as
-    bf16 operands allow.  Asserted instead: 1e-2 in the 2-norm and 1e-1 elementwise, both about twice the largest
-    value measured over all tests (the log that VER_PARITY_LOG writes has every figure)."""
+    such elements relative to max(|ref|, rms(ref)) sits at 5 to 12 standard deviations (measured up to 5.1e-2 for
+    W_hh, 4.6e-2 W_ih, 3.4e-2 d_x, 2.2e-2 biases): above the stated 2e-2 although the arithmetic is as accurate as
+    bf16 operands allow.  Asserted instead: 7e-3 in the 2-norm and 7e-2 elementwise, both about one and a half
+    times the largest value measured over all tests (the log that VER_PARITY_LOG writes has every figure)."""
     e2, em = l2_rel_err(x, ref), rel_err(x, ref)
     _record("bf16-bptt", what, em, e2)
-    assert e2 <= 1e-2, f"{what}: relative 2-norm error {e2:.3e} > 1.0e-02"
-    assert em <= 1e-1, f"{what}: elementwise relative error {em:.3e} > 1.0e-01"
+    assert e2 <= 7e-3, f"{what}: relative 2-norm error {e2:.3e} > 7.0e-03"
+    assert em <= 7e-2, f"{what}: elementwise relative error {em:.3e} > 7.0e-02"
 
 
 def _is_bptt_tensor(what):
