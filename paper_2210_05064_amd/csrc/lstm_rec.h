@@ -530,6 +530,12 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, cons
             wreg[tt * NBW + i] = (STATIC || i < nb) ? *reinterpret_cast<const f32x4_t*>(wrow + blk_of<NBW, STATIC>(i, rot, nb) * KBLK)
                                                     : f32x4_t{0.f, 0.f, 0.f, 0.f};
     }
+    // The weights have arrived before the time loop starts, and the compiler has to know: without a use of the
+    // registers here it keeps the loads on its books into the loop, where it then makes the MFMAs that read them
+    // wait for whatever else is in flight (the prefetch of the next timestep's inputs, the stores of the saved
+    // activations), ending in a wait for everything after the last MFMA of every timestep.
+#pragma unroll
+    for (int i = 0; i < TPW * NBW; ++i) asm volatile("" : "+v"(wreg[i]));
     // initial hidden state of every piece, this workgroup's columns
     for (int i = tid; i < n_seq * (UH / 4); i += REC_THREADS) {
         const int n = (i / (UH / 4)) * X + x, u = (i % (UH / 4)) * 4;
@@ -802,6 +808,9 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
 #pragma unroll
         for (int i = 0; i < NW; ++i)
             wreg[i] = (i < ni) ? *reinterpret_cast<const f32x4_t*>(wrow + i * KBLK) : f32x4_t{0.f, 0.f, 0.f, 0.f};
+        // (a use of the registers: the loads are complete before the time loop, see the forward kernel)
+#pragma unroll
+        for (int i = 0; i < NW; ++i) asm volatile("" : "+v"(wreg[i]));
     }
     // The arrays as buffers that never change during the loop (host code guarantees that each is shorter than
     // 2^31 bytes); where a timestep's rows begin is the scalar offset of an access, and this thread's first
