@@ -846,7 +846,10 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
     REC_PROF_START();
     for (int t = T - 1; t >= 0; --t) {
         // bs, bs_next: this group's alive pieces; its piece m sits in packed row base + m * X + x
-        const int bs_m3 = t > 2 ? a.batch_sizes[t - 3] : 0;
+        // (kept in a vector register and made uniform only at the end of the step, where everything the step loaded
+        // has long arrived: see the forward kernel; read as a scalar right here, the step would open with a wait for
+        // this load and for every store still in flight)
+        int bs_m3_v = t > 2 ? a.batch_sizes[t - 3] : 0;
         const int bs = grp_count(bs_t, ps);
         const int bs_next = (t + 1 < T) ? grp_count(bs_up, ps) : 0;
         const int base_prev = base - bs_m1;     // rows of timestep t-1 (unused when t == 0)
@@ -954,7 +957,8 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
         bs_up = bs_t;
         bs_t = bs_m1;
         bs_m1 = bs_m2;
-        bs_m2 = bs_m3;
+        asm volatile("" : "+v"(bs_m3_v));
+        bs_m2 = __builtin_amdgcn_readfirstlane(bs_m3_v);
         REC_PROF_MARK(12);
         REC_PROF_STEP();
     }
