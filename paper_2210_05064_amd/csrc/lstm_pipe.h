@@ -404,8 +404,10 @@ constexpr int PIPE_STAGE_BYTES = (PIPE_BM + PIPE_BN) * 128;
 // COHERENT (a worker's tile): the tile's rows are rowmap[0 .. 127] (LDS; -1: none), A is being written by other
 // XCDs during this launch and C is read by them (loads and stores that bypass the non-coherent caches).
 // Otherwise (a launch of its own): the rows [row0, row_end).
+// nrows: the tile's rows are its first nrows (a worker's tile of a group with few pieces holds a handful): the waves
+// whose 64 rows hold none of them neither read operands from LDS nor multiply (they still load and synchronise).
 template <bool COHERENT>
-__device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, const int* rowmap, int row0, int row_end, int col0,
+__device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, const int* rowmap, int row0, int row_end, int nrows, int col0,
                                                    unsigned char* smem) {
     constexpr int BK = 64;
     constexpr int AUX = COHERENT ? 17 : 0;
@@ -471,6 +473,7 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, const int*
         bar_lds();   // ... and so have everyone's; everyone has also finished reading stage kt-1
         if (kt + 2 < nk) issue(kt + 2);   // into the stage that was read in iteration kt-1
         const unsigned char* st = smem + (kt % PIPE_STAGES) * PIPE_STAGE_BYTES;
+        if (COHERENT && nrows <= wm) continue;   // (uniform in the wave)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             u16x8_t a[4], b[4];
@@ -530,7 +533,7 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, const int*
 __global__ __launch_bounds__(REC_THREADS) void lstm_proj_dma_kernel(PipeWork w, int M, int tiles_n) {
     extern __shared__ __attribute__((aligned(16))) unsigned char proj_smem[];
     const int rt = blockIdx.x / tiles_n, ct = blockIdx.x % tiles_n;
-    pipe_gemm_tile_dma<false>(w, nullptr, rt * PIPE_BM, min(M, (rt + 1) * PIPE_BM), ct * PIPE_BN, proj_smem);
+    pipe_gemm_tile_dma<false>(w, nullptr, rt * PIPE_BM, min(M, (rt + 1) * PIPE_BM), PIPE_BM, ct * PIPE_BN, proj_smem);
 }
 
 // One group's view of the hand-over words, from the plan.
@@ -630,7 +633,7 @@ __device__ __forceinline__ void pipe_worker(const PipeWork& w, int tiles_n, int 
             }
             bar_lds();
             if constexpr (MODE == MODE_BF16)
-                pipe_gemm_tile_dma<true>(w, s_rowmap, 0, 0, ctile * PIPE_BN, smem);
+                pipe_gemm_tile_dma<true>(w, s_rowmap, 0, 0, min(PIPE_BM, s_rp[nt] - s_rp[0] - rt * PIPE_BM), ctile * PIPE_BN, smem);
             else
                 pipe_gemm_tile<MODE, typename LdsElem<MODE>::type>(w, s_rowmap, ctile * PIPE_BN, smem);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
