@@ -313,7 +313,7 @@ template <int WM> struct TnGeom {
     static constexpr int LDS = STAGES * STAGE;
 };
 #ifndef VER_TN_TARGET_WGS
-#define VER_TN_TARGET_WGS 512
+#define VER_TN_TARGET_WGS 256
 #endif
 constexpr int TN_TARGET_WGS = VER_TN_TARGET_WGS;
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
@@ -473,8 +473,11 @@ inline void gemm_launch(const TA* A, int lda, const TB* B, int ldb, float* C, in
     if constexpr (TRANS && MODE == MODE_BF16 && sizeof(TA) == 2 && sizeof(TB) == 2) {
         // both operands bf16 and K-minor: the LDS-direct kernel (bias is never used with these shapes)
         if (!bias && lda % 2 == 0 && ldb % 2 == 0 && (size_t)K * lda * 2 < 0x7fffffff && (size_t)K * ldb * 2 < 0x7fffffff) {
-            // two workgroups fit on a CU: aim at one full round of 512
-            const bool tall = Mr % 256 == 0 && Mr >= 2048;   // 256-row tiles when there are enough of them
+            // Aim at one workgroup per CU, split as little as possible: measured on the weight gradients of the largest
+            // configuration (4096 x 1024 outputs over 8192 rows), 256 tiles of 128 x 128 without any split (5.9 ms per
+            // update) beat 128 tiles of 256 x 128 split 4 ways (6.7 ms, a quarter of it the pass that adds the partial
+            // tiles) and the same 128 x 128 tiles split 2 or 3 ways (6.5, 7.1 ms); 3 or 5 stages instead of 4: 7.2, 7.5 ms.
+            const bool tall = Mr % 256 == 0 && (long)(Mr / 256) * grid.x >= TN_TARGET_WGS;   // 256-row tiles when they alone fill the chip
             if (tall) grid.y = Mr / 256;
             const int tiles = grid.x * grid.y;
             int sp = (allow_split && part) ? (TN_TARGET_WGS + tiles / 2) / tiles : 1;
