@@ -459,7 +459,11 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     // 8 waves = row groups x shares of the contraction (TPW tiles of 16 gate rows per wave): a workgroup owns
     // 8 tiles (32 units) when 32 workgroups need all of H/32 units each, else 4 tiles (16 units)
     const bool wide = H / 16 > REC_MAX_GROUP;
-    const bool quarter = MODE == MODE_F32 || H % 128 == 0;   // a quarter of H is a whole number of operand blocks
+    // Shares of the contraction: with 8 tiles per workgroup two (a wave then reads 16 operand blocks per piece tile
+    // and the cell update adds two partial sums; measured 2.7 % faster than four shares, which read less from LDS but
+    // reduce more: the group that bounds a launch has one or two alive pieces, whose reads are broadcasts; one share,
+    // without any reduction, is 9 % slower), with 4 tiles four (two was measured 0.4 % slower on H = 512).
+    const bool quarter = MODE == MODE_F32 || (!wide && H % 128 == 0);   // a quarter of H is a whole number of operand blocks
     const int ks = quarter ? 4 : 2;
     const int mt = wide ? 8 : 4;
     const size_t tile = (size_t)16 * (H + RecGeom<MODE>::PAD) * sizeof(E);
@@ -518,11 +522,11 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
 #define VER_FWD_DISPATCH(KERNEL, ARGS) do { \
         if constexpr (MODE == MODE_BF16) { \
             if (wide) { \
-                if (!quarter) VER_FWD_LAUNCH(KERNEL, ARGS, 2, 2, 16, false); \
-                else if (nb == 8) VER_FWD_LAUNCH(KERNEL, ARGS, 4, 4, 8, true); \
-                else VER_FWD_LAUNCH(KERNEL, ARGS, 4, 4, 8, false); \
+                if (!quarter && nb == 16) VER_FWD_LAUNCH(KERNEL, ARGS, 2, 2, 16, true); \
+                else VER_FWD_LAUNCH(KERNEL, ARGS, 2, 2, 16, false); \
             } else { \
-                if (!quarter) VER_FWD_LAUNCH(KERNEL, ARGS, 1, 2, 8, false); \
+                if (!quarter && nb == 8) VER_FWD_LAUNCH(KERNEL, ARGS, 1, 2, 8, true); \
+                else if (!quarter) VER_FWD_LAUNCH(KERNEL, ARGS, 1, 2, 8, false); \
                 else if (nb == 4) VER_FWD_LAUNCH(KERNEL, ARGS, 2, 4, 4, true); \
                 else VER_FWD_LAUNCH(KERNEL, ARGS, 2, 4, 4, false); \
             } \

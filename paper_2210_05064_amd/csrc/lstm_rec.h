@@ -433,29 +433,35 @@ __device__ __forceinline__ int blk_of(int i, int rot, int nb) {
     if (STATIC) return v % NBW;
     return v >= nb ? v - nb : v;
 }
-template <int MODE, int NBW, bool STATIC>
-__device__ __forceinline__ void load_b_lds(const typename RecGeom<MODE>::E* p, int nb, int rot, f32x4_t (&b)[NBW]) {
-#pragma unroll
-    for (int i = 0; i < NBW; ++i)
-        if (STATIC || i < nb) b[i] = *reinterpret_cast<const f32x4_t*>(p + blk_of<NBW, STATIC>(i, rot, nb) * RecGeom<MODE>::KBLK);
-}
+// acc[tt] = sum over the wave's operand blocks of W(tile tt, block) * B(block): the B blocks (16 bytes per lane from
+// the staged rows at p) are fetched from LDS a few at a time, ahead of the MFMAs that consume them; with fewer than
+// four tiles the sum is split over independent accumulator chains so that consecutive MFMAs do not wait for each
+// other's result.
 template <int MODE, int TPW, int NBW, bool STATIC>
-__device__ __forceinline__ void mma_step(const f32x4_t (&wreg)[TPW * NBW], const f32x4_t (&b)[NBW], int nb,
+__device__ __forceinline__ void mma_rows(const f32x4_t (&wreg)[TPW * NBW], const typename RecGeom<MODE>::E* p, int nb, int rot,
                                          f32x4_t (&acc)[TPW]) {
-    // with a single tile, two accumulator chains so that consecutive MFMAs do not wait for each other
-    constexpr int CH = TPW == 1 ? 2 : 1;
+    constexpr int CH = TPW >= 4 ? 1 : (TPW == 2 ? 2 : 4);
+    constexpr int BCH = NBW < 8 ? NBW : 8;
     f32x4_t part[TPW][CH];
 #pragma unroll
     for (int tt = 0; tt < TPW; ++tt)
 #pragma unroll
         for (int c = 0; c < CH; ++c) part[tt][c] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < NBW; ++i)
-        if (STATIC || i < nb) {
+    for (int c0 = 0; c0 < NBW; c0 += BCH) {
+        f32x4_t b[BCH];
 #pragma unroll
-            for (int tt = 0; tt < TPW; ++tt)
-                part[tt][i % CH] = mfma_block<MODE>(wreg[tt * NBW + i], b[i], part[tt][i % CH]);
-        }
+        for (int i = 0; i < BCH; ++i)
+            if (c0 + i < NBW && (STATIC || c0 + i < nb))
+                b[i] = *reinterpret_cast<const f32x4_t*>(p + blk_of<NBW, STATIC>(c0 + i, rot, nb) * RecGeom<MODE>::KBLK);
+#pragma unroll
+        for (int i = 0; i < BCH; ++i)
+            if (c0 + i < NBW && (STATIC || c0 + i < nb)) {
+#pragma unroll
+                for (int tt = 0; tt < TPW; ++tt)
+                    part[tt][(c0 + i) % CH] = mfma_block<MODE>(wreg[tt * NBW + c0 + i], b[i], part[tt][(c0 + i) % CH]);
+            }
+    }
 #pragma unroll
     for (int tt = 0; tt < TPW; ++tt) {
         f32x4_t sum = part[tt][0];
@@ -629,12 +635,10 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, cons
             REC_PROF_MARK(1);
 #pragma unroll 1
             for (int q = 0; q < nt; ++q) {
-                f32x4_t b[NBW];
                 // dead lanes of the last tile read its first row: equal addresses are broadcast by the LDS
                 const int r = q * 16 + ((q * 16 + lr < rows) ? lr : 0);
-                load_b_lds<MODE, NBW, STATIC>(sB + r * stride + k_lo + lk * VEC, nb, rot, b);
                 f32x4_t acc[TPW];
-                mma_step<MODE, TPW, NBW, STATIC>(wreg, b, nb, acc);
+                mma_rows<MODE, TPW, NBW, STATIC>(wreg, sB + r * stride + k_lo + lk * VEC, nb, rot, acc);
 #pragma unroll
                 for (int tt = 0; tt < TPW; ++tt) sRed[((ks * MT + rg * TPW + tt) * ntc + q) * 64 + lane] = acc[tt];
             }
