@@ -474,6 +474,21 @@ __device__ __forceinline__ void pipe_gemm_tile_dma(const PipeWork& w, const int*
         if (kt + 2 < nk) issue(kt + 2);   // into the stage that was read in iteration kt-1
         const unsigned char* st = smem + (kt % PIPE_STAGES) * PIPE_STAGE_BYTES;
         if (COHERENT && nrows <= wm) continue;   // (uniform in the wave)
+        if (COHERENT && nrows - wm <= 16) {
+            // at most 16 rows (the tiles of a group with one or two pieces): only the first of the four 16-row tiles
+            // (the workers' K is a whole number of K-tiles: no tail to clear)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const u16x8_t a0 = *reinterpret_cast<const u16x8_t*>(st + arow[0] + (((ks * 4 + lk) ^ asw[0]) << 4));
+                u16x8_t b[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    b[j] = *reinterpret_cast<const u16x8_t*>(st + brow[j] + (((ks * 4 + lk) ^ bsw[j]) << 4));
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[0][j] = mfma_bf16_16x16x32(a0, b[j], acc[0][j]);
+            }
+            continue;
+        }
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
             u16x8_t a[4], b[4];
