@@ -47,7 +47,7 @@ namespace ver {
 #define VER_REC_PROF_GROUP 0
 #endif
 #define REC_PROF_DECL long long prof_t = 0; long long* prof_out = a.prof; const bool prof_on = threadIdx.x == 0 && rank == 0 && ps.id == VER_REC_PROF_GROUP;
-#define REC_PROF_START() do { if (prof_on) prof_t = clock64(); } while (0)
+#define REC_PROF_START() do { if (prof_on) prof_t = clock64(); if (threadIdx.x == 0 && rank == 0 && PIPE != PIPE_NONE) a.prof_all[112 + ps.id + (PIPE == PIPE_CONSUMER ? 3 : 0)] = wall_clock64(); } while (0)
 #define REC_PROF_MARK(i) do { if (prof_on) { long long now_ = clock64(); prof_out[i] += now_ - prof_t; prof_t = now_; } } while (0)
 #define REC_PROF_STEP() do { if (prof_on) prof_out[15] += 1; } while (0)
 #else
