@@ -473,6 +473,39 @@ __device__ __forceinline__ void mma_rows(const f32x4_t (&wreg)[TPW * NBW], const
     }
 }
 
+// ---- few alive pieces in fp32: the vector ALUs instead of the matrix cores --------------------------------
+// An fp32 MFMA (16x16x4) takes a weight through the matrix core at 2 per cycle and SIMD whatever the number of
+// alive pieces; a vector FMA takes 16 per cycle and piece.  Up to REC_VALU_ROWS alive pieces of a group the
+// product of a timestep is therefore computed piece by piece on the vector ALUs, from the same registers: a lane
+// holds 4 consecutive weights of gate row lr per operand block (the MFMA's A layout), reads the matching 4 values
+// of the piece's row from LDS (the same address in the 16 lanes of a row group: a broadcast), and the four
+// partial sums of a row (lk = 0..3) are added across the wave.  The result goes where the MFMA's accumulator of
+// the same (tile, piece) would have gone: out[...] is the f32x4 fragment array of piece tile 0 (64 lanes: column
+// = piece, element e of lane group lk = row lk*4 + e).  bf16 gains nothing from this (a packed dot product takes
+// 32 weights per cycle, as the bf16 MFMA does).
+constexpr int REC_VALU_ROWS = 3;   // (measured on the 2 x 512 fp32 workloads: 2 to 4 within 1 % of each other, 6 and 8 slower)
+template <int NW>
+__device__ __forceinline__ float valu_row_sum(const f32x4_t (&wreg)[NW], int w0, int n, const float* prow, int nb_rt, int rot,
+                                              int nbw, bool is_static) {
+    float p0 = 0.f, p1 = 0.f;   // two chains
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        if (i >= n) break;
+        if (is_static || i < nb_rt) {
+            const int v = i + rot;
+            const int blk = is_static ? v % nbw : (v >= nb_rt ? v - nb_rt : v);
+            const f32x4_t b = *reinterpret_cast<const f32x4_t*>(prow + blk * RecGeom<MODE_F32>::KBLK);
+            const f32x4_t w = wreg[w0 + i];
+            p0 = fmaf(w[0], b[0], p0); p1 = fmaf(w[1], b[1], p1);
+            p0 = fmaf(w[2], b[2], p0); p1 = fmaf(w[3], b[3], p1);
+        }
+    }
+    float p = p0 + p1;
+    p += __shfl_xor(p, 16, VER_WAVE);
+    p += __shfl_xor(p, 32, VER_WAVE);
+    return p;
+}
+
 // ======================================================================================================
 struct RecFwdArgs {
     const int32_t* info;
@@ -633,6 +666,19 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, cons
                                                                 rs_g, qq * 16 + lr < bs_next ? goff[qq] : OUT_OF_RANGE, so_gnext, 0));
             }
             REC_PROF_MARK(1);
+            if (MODE == MODE_F32 && rows <= REC_VALU_ROWS) {
+                if constexpr (MODE == MODE_F32) {
+                    for (int pc = 0; pc < rows; ++pc) {
+                        const float* prow = reinterpret_cast<const float*>(sB) + pc * stride + k_lo + lk * VEC;
+#pragma unroll
+                        for (int tt = 0; tt < TPW; ++tt) {
+                            const float p = valu_row_sum<TPW * NBW>(wreg, tt * NBW, NBW, prow, nb, rot, NBW, STATIC);
+                            if (lk == 0)
+                                reinterpret_cast<float*>(&sRed[((ks * MT + rg * TPW + tt) * ntc + 0) * 64 + pc + 16 * (lr >> 2)])[lr & 3] = p;
+                        }
+                    }
+                }
+            } else
 #pragma unroll 1
             for (int q = 0; q < nt; ++q) {
                 // dead lanes of the last tile read its first row: equal addresses are broadcast by the LDS
@@ -930,11 +976,21 @@ __device__ __forceinline__ void rec_bwd_body(const RecBwdArgs& a, int rank, cons
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             bar_lds();
             REC_PROF_MARK(11);
+            if (MODE == MODE_F32 && rows <= REC_VALU_ROWS) {
+                if constexpr (MODE == MODE_F32) {   // few pieces in fp32: the vector ALUs (see valu_row_sum)
+                    for (int pc = 0; pc < rows; ++pc) {
+                        const float* prow = reinterpret_cast<const float*>(sB) + pc * stride + k_lo + lk * VEC;
+                        const float p = valu_row_sum<NW>(wreg, 0, NW, prow, ni, 0, NW, false);
+                        if (lk == 0) reinterpret_cast<float*>(&sRed[((ks * MT + mt) * ntc + 0) * 64 + pc + 16 * (lr >> 2)])[lr & 3] = p;
+                    }
+                }
+            } else {
             f32x4_t acc[REC_NTC];
             mma_dispatch<MODE, NI, NW>(wreg, sB + lr * stride + k_lo + lk * VEC, stride, ni, rows, lr, acc);
 #pragma unroll
             for (int q = 0; q < REC_NTC; ++q)
                 if (q * 16 < rows) sRed[((ks * MT + mt) * ntc + q) * 64 + lane] = acc[q];
+            }
             bar_lds();
             // wave w adds the KS partial sums of (unit tile w / REC_NTC, piece tile w % REC_NTC):
             // its lane holds units lk*4..lk*4+3 of piece n
