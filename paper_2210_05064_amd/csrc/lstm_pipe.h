@@ -285,8 +285,11 @@ constexpr int PIPE_NO_ROW = (int)0x80000000u;
 // One 128 x 256 tile of C = A B^T (+ bias) for the rows rowmap[0 .. 127] (LDS; -1: none) and columns from col0,
 // by 8 waves (2 x 4 of 64 x 64).  Same K-tile pipeline as gemm_kernel: the next K-tile's global loads are in
 // flight while the current one is multiplied out of LDS.
+// nrows: the tile's rows are its first nrows; a wave whose 64 rows hold none of them does not multiply, one that holds
+// at most 16 multiplies only its first 16-row tile (an fp32 tile is bound by its MFMAs, 16 times slower per FLOP
+// than bf16 ones: the tiles of a group with one or two pieces would otherwise cost as much as full ones).
 template <int MODE, typename TA>
-__device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, const int* rowmap, int col0, unsigned char* smem) {
+__device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, const int* rowmap, int nrows, int col0, unsigned char* smem) {
     typedef typename LdsElem<MODE>::type E;
     constexpr int BK = GemmGeom<MODE>::BK, STRIDE = GemmGeom<MODE>::LDS_STRIDE;
     constexpr int CPR = BK / 4, RPP = REC_THREADS / CPR, QA = PIPE_BM / RPP, QB = PIPE_BN / RPP;
@@ -333,7 +336,23 @@ __device__ __forceinline__ void pipe_gemm_tile(const PipeWork& w, const int* row
         for (int i = 0; i < QB; ++i) store_quad(sB + (r + i * RPP) * STRIDE + c * 4, rb[i]);
         bar_lds();
         if (k0 + BK < K) load_tiles(k0 + BK);
-        if (MODE == MODE_BF16) {
+        const int nr = nrows - wm;   // rows of the tile among this wave's 64 (uniform in the wave)
+        if (nr <= 0) {
+            // nothing to multiply
+        } else if (MODE == MODE_F32 && nr <= 16) {
+#pragma unroll
+            for (int ks = 0; ks < BK; ks += 16) {
+                const f32x4_t a0 = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(sA) + (wm + lr) * STRIDE + ks + lk * 4);
+                f32x4_t b[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    b[j] = *reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(sB) + (wn + j * 16 + lr) * STRIDE + ks + lk * 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[0][j] = mfma_f32_16x16x4(a0[e], b[j][e], acc[0][j]);
+            }
+        } else if (MODE == MODE_BF16) {
 #pragma unroll
             for (int ks = 0; ks < BK; ks += 32) {
                 u16x8_t a[4], b[4];
@@ -650,7 +669,7 @@ __device__ __forceinline__ void pipe_worker(const PipeWork& w, int tiles_n, int 
             if constexpr (MODE == MODE_BF16)
                 pipe_gemm_tile_dma<true>(w, s_rowmap, 0, 0, min(PIPE_BM, s_rp[nt] - s_rp[0] - rt * PIPE_BM), ctile * PIPE_BN, smem);
             else
-                pipe_gemm_tile<MODE, typename LdsElem<MODE>::type>(w, s_rowmap, ctile * PIPE_BN, smem);
+                pipe_gemm_tile<MODE, typename LdsElem<MODE>::type>(w, s_rowmap, min(PIPE_BM, s_rp[nt] - s_rp[0] - rt * PIPE_BM), ctile * PIPE_BN, smem);
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             bar_lds();
             if (tid == 0) __hip_atomic_fetch_add(&pl.done[c], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
