@@ -440,7 +440,7 @@ __device__ __forceinline__ int blk_of(int i, int rot, int nb) {
 template <int MODE, int TPW, int NBW, bool STATIC>
 __device__ __forceinline__ void mma_rows(const f32x4_t (&wreg)[TPW * NBW], const typename RecGeom<MODE>::E* p, int nb, int rot,
                                          f32x4_t (&acc)[TPW]) {
-    constexpr int CH = TPW >= 4 ? 1 : (TPW == 2 ? 2 : 4);
+    constexpr int CH = TPW >= 4 ? 1 : (TPW == 2 ? (STATIC ? 2 : 1) : 4);
     constexpr int BCH = NBW < 8 ? NBW : 8;
     f32x4_t part[TPW][CH];
 #pragma unroll

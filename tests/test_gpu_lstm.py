@@ -143,6 +143,14 @@ def test_long_and_short_pieces(ver):
     assert meta["T_max"] > 1024
 
 
+def test_wide_hidden_not_a_multiple_of_128(ver):
+    """hidden = 576 (bf16 operands; fp32 keeps its share of W_hh in registers only up to hidden = 512): more than 32
+    tiles of 16 units (workgroups of 32 units) and a contraction that does not split into whole operand blocks four
+    ways: the general (not width-specialised) forms of both time loops."""
+    case(ver, wl.scaled(wl.WORKLOADS["manip"], budget=200, n_envs=5, hidden=576, input_dim=20, p_done=0.02,
+                        minibatches=1), seed=17, compute=1)
+
+
 def test_three_layers_wide_input(ver):
     case(ver, wl.scaled(wl.WORKLOADS["manip"], budget=256, n_envs=6, hidden=192, input_dim=260, n_layers=3,
                         p_done=0.03, minibatches=1), seed=8)
