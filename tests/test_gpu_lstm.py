@@ -151,6 +151,18 @@ def test_wide_hidden_not_a_multiple_of_128(ver):
                         minibatches=1), seed=17, compute=1)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_two_layer_launch_random_packings(ver, seed):
+    """The plan of the two-layer launch (which pieces a group runs, its chunks, the gathered rows of the workers'
+    tiles) over packings of very different shape: 1 to 60 environments, 40 to 900 rows, few to many episode ends."""
+    rng = np.random.default_rng(1000 + seed)
+    n_envs = int(rng.integers(1, 61))
+    budget = int(rng.integers(max(40, 2 * n_envs), 901))
+    w = wl.scaled(wl.WORKLOADS["nav"], budget=budget, n_envs=n_envs, hidden=64, input_dim=8,
+                  p_done=float(rng.choice([0.0, 0.01, 0.05, 0.3])), minibatches=1, speed_sigma=float(rng.choice([0.0, 0.5, 1.5])))
+    case(ver, w, seed=50 + seed, compute=int(seed % 2))
+
+
 def test_three_layers_wide_input(ver):
     case(ver, wl.scaled(wl.WORKLOADS["manip"], budget=256, n_envs=6, hidden=192, input_dim=260, n_layers=3,
                         p_done=0.03, minibatches=1), seed=8)
