@@ -7,7 +7,7 @@
 // Per layer the work splits into what has no time dependence and what has:
 //   time-batched (one MFMA GEMM over all M rows):  W_ih x_t + b  (forward),
 //       dx = W_ih^T dz, dW_ih = dz^T x, dW_hh = dz^T h_{t-1}     (backward)
-//   sequential (persistent kernel, W_hh resident in LDS): h_{t-1} W_hh^T + gates
+//   sequential (persistent kernels, W_hh resident in registers): h_{t-1} W_hh^T + gates
 //       (forward), dz_t and W_hh dz_t (backward) - see lstm_rec.h.
 // Internally the 4H gate rows are interleaved (row = unit*4 + gate); user-facing
 // weights and gradients keep the gate-major order i,f,g,o of the declaration.
