@@ -722,11 +722,12 @@ __device__ __forceinline__ void rec_fwd_body(const RecFwdArgs& a, int rank, cons
                             const unsigned go_ = goff[q < REC_PRE ? q : 0];
                             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, f32x4_t{gi, gf, gg, go}), rs_g, go_, so_g, 0);
                             __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(cn), rs_c, go_ >> 2, so_c, 0);
-                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn), rs_h, go_ >> 2, so_c, 0);
+                            // (the producer layer of a two-layer launch hands h on in operand type only: hcopy below)
+                            if (PIPE != PIPE_PRODUCER) __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(hn), rs_h, go_ >> 2, so_c, 0);
                         } else {
                             *gp = f32x4_t{gi, gf, gg, go};
                             a.c[p * H + je] = cn;
-                            a.hout[p * H + je] = hn;
+                            if (PIPE != PIPE_PRODUCER) a.hout[p * H + je] = hn;
                         }
                     }
                     // h_t goes to the exchange row of the next timestep through LDS (below)
