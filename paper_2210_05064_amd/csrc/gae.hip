@@ -184,7 +184,15 @@ __global__ __launch_bounds__(GAE_THREADS) void gae_kernel(
             }
         }
     }
-    if ((FULL || group >= 0) && k_lo + g0 + 8 < S) v_after = values[k_lo + g0 + 8];
+    if (FULL) {
+        // the step after this thread's group is the first step of the group of the lane before: taken from its
+        // register; only the first lane of a wave fetches it (the first thread of the tile from the tile above)
+        if (lane == 0 && k_lo + g0 + 8 < S) v_after = values[k_lo + g0 + 8];
+        const float from_lane_before = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v8[0]), DPP_WAVE_SHR1, 0xf, 0xf, false));
+        if (lane != 0) v_after = from_lane_before;
+    } else if (group >= 0 && k_lo + g0 + 8 < S) {
+        v_after = values[k_lo + g0 + 8];
+    }
 
     // Which steps of the tile end an environment (wave 0; the loads above are in flight meanwhile).  Environments
     // of the tile's first and last step: from the second tile of a batch on they follow from the tile before (the
