@@ -520,12 +520,21 @@ __device__ __forceinline__ void is_weight_tile(OffPtr off, int n_env, int k_lo, 
     for (int r = 0; r < IS_TILE / (IS_THREADS * IS_ITEMS); ++r) {
         const int k0 = k_lo + (r * IS_THREADS + (int)threadIdx.x) * IS_ITEMS;
         if (k0 >= S) return;
-        int lo = 0, hi = n_env;   // off[lo] <= k0 < off[hi]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (off[mid] <= k0) lo = mid; else hi = mid;
+        // The environment of the wave's first step by a 64-ary search of the whole wave (every lane probes one offset,
+        // a ballot counts: one or two rounds instead of a binary search of a dozen dependent reads per lane), then
+        // every lane walks on from there to its own first step (the 256 steps of a wave span a few environments).
+        const int lane = threadIdx.x & (VER_WAVE - 1);
+        const int k_wave = k0 - lane * IS_ITEMS;
+        int lo = 0, len = n_env;   // off[lo] <= k_wave, the answer is in [lo, lo + len)
+        while (len > 1) {
+            const int step = (len + VER_WAVE - 1) / VER_WAVE, idx = lo + lane * step;
+            const unsigned long long below = __ballot(idx < lo + len && off[idx] <= k_wave);   // a prefix of the lanes, lane 0 among them
+            const int c = __popcll(below) - 1;
+            len = min(step, len - c * step);
+            lo += c * step;
         }
         int env = lo;
+        while (off[env + 1] <= k0) ++env;   // (off[n_env] lies beyond the tile's last step)
         int end = off[env + 1];
         float w = fminf(max_is, (float)(share / (double)(end - off[env])));
         float out[IS_ITEMS];
