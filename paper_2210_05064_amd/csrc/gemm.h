@@ -319,21 +319,25 @@ constexpr int TN_TARGET_WGS = VER_TN_TARGET_WGS;
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ int tn_swz(int k) { return ((k & 3) << 1) | (((k >> 3) & 1) << 3); }
 
-template <int WM>
+// XTRA: the output has a few columns (x_cols <= 32) beyond its last whole column tile, [Nc - x_cols, Nc).  Instead of
+// a column tile of their own they ride along with the whole tiles of the same row tile, which have the A operand
+// in LDS anyway: column tile bx < 8 / x_mt also multiplies the 16-row tiles bx * x_mt .. + x_mt - 1 of its 128 rows
+// with those columns (32 more columns of B per stage, two to four more MFMAs per K-tile in one wave).
+constexpr int TN_X_STAGE = TN_BK * 64;   // bytes per stage: 32 k-rows of 32 columns
+template <int WM, bool XTRA = false>
 __device__ __forceinline__ void gemm_tn_dma_body(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb, float* __restrict__ C, int ldc,
-    int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride, unsigned char* smem) {
+    int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride, unsigned char* smem, int bx, int by, int bz,
+    bool split, int x_cols = 0, int x_mt = 0) {
     typedef TnGeom<WM> G;
-    constexpr int TN_STAGES = G::STAGES, TN_STAGE_BYTES = G::STAGE, ROW_A = G::ROW_A, NA = G::NA;
+    constexpr int TN_STAGES = G::STAGES, TN_STAGE_BYTES = G::STAGE + (XTRA ? TN_X_STAGE : 0), ROW_A = G::ROW_A, NA = G::NA;
+    static_assert(!XTRA || WM == 4, "extra columns: 128-row tiles only");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = (wave >> 1) * 16 * WM, wn = (wave & 1) * 64;
-    int bx, by, bz;
-    gemm_tile_of_block(bx, by, bz);
     const int m0 = by * G::BM, n0 = bx * GEMM_BN;
     const int lr = lane & 15, lk = lane >> 4;
     const int k_begin = bz * k_chunk, k_end = min(K, k_begin + k_chunk);
     const int nk = (k_end - k_begin + TN_BK - 1) / TN_BK;
-    const bool split = gridDim.z > 1;
     if (split) C += (size_t)bz * split_stride;
     // rows beyond K read zero (buffer bounds); columns beyond the matrix only feed outputs that are not stored
     __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(A), 0, (int)min((size_t)K * lda * 2, (size_t)0x7fffffff), 0x00020000);
@@ -351,6 +355,13 @@ __device__ __forceinline__ void gemm_tn_dma_body(
         const int k = (wave * 2 + j) * 4 + (lane >> 4), c = (lane & 15) ^ tn_swz(k);
         voffB[j] = k * ldb * 2 + n0 * 2 + c * 16;
     }
+    // extra columns: half an instruction per wave and stage (lanes 0..31: row wave * 8 + lane / 4, 16-byte chunk
+    // lane % 4 of the row's 64 bytes); what lies beyond column Nc belongs to the next row (finite values that only
+    // feed outputs which are not stored) or, at the end of the buffer, reads zero
+    const bool x_here = XTRA && bx * x_mt < 8;
+    const int x_n0 = Nc - x_cols;                     // first extra column
+    const int x_wave = ((bx * x_mt) >> 2) << 1;       // the wave whose row tiles those are (column half 0)
+    const int voffX = (wave * 8 + ((lane & 31) >> 2)) * ldb * 2 + x_n0 * 2 + (lane & 3) * 16;
     auto issue = [&](int kt) {
         unsigned char* st = smem + (kt % TN_STAGES) * TN_STAGE_BYTES;
         const int k0 = k_begin + kt * TN_BK;
@@ -362,6 +373,8 @@ __device__ __forceinline__ void gemm_tn_dma_body(
         for (int j = 0; j < 2; ++j)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr_t)(st + TN_BK * ROW_A + (wave * 2 + j) * 1024), 16,
                                                      voffB[j] + k0 * ldb * 2, 0, 0, 0);
+        if (XTRA && lane < 32)   // (every wave issues it, so the counts of loads in flight below hold for all of them)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB, (lds_ptr_t)(st + G::STAGE + wave * 512), 16, voffX + k0 * ldb * 2, 0, 0, 0);
     };
     // operand read offsets: source row k = lk*8 + lr/4 (+4 for the second half), columns tile*16 + 4*(lr%4)..+3
     int offA[WM][2], offB[4][2];
@@ -379,6 +392,21 @@ __device__ __forceinline__ void gemm_tn_dma_body(
             offB[i][h] = TN_BK * ROW_A + k * 256 + ((((colB * 2) >> 4) ^ tn_swz(k)) << 4) + ((colB * 2) & 8);
         }
     }
+    int offAx[2][2], offBx[2][2];
+    f32x4_t accx[2][2];
+    if (XTRA) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = lk * 8 + (lr >> 2) + 4 * h;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int colA = ((bx * x_mt + i) & 7) * 16 + 4 * (lr & 3), colB = i * 16 + 4 * (lr & 3);
+                offAx[i][h] = k * ROW_A + ((((colA * 2) >> 4) ^ tn_swz(k)) << 4) + ((colA * 2) & 8);
+                offBx[i][h] = G::STAGE + k * 64 + colB * 2;
+                accx[i][h] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+    }
     f32x4_t acc[WM][4];
 #pragma unroll
     for (int i = 0; i < WM; ++i)
@@ -391,6 +419,10 @@ __device__ __forceinline__ void gemm_tn_dma_body(
         const int younger = min(nk - 1 - kt, TN_STAGES - 2);
         if (WM == 8) {
             if (younger >= 1) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else if (XTRA) {   // 7 loads per wave and stage
+            if (younger >= 2) asm volatile("s_waitcnt vmcnt(14)" ::: "memory");
+            else if (younger == 1) asm volatile("s_waitcnt vmcnt(7)" ::: "memory");
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         } else {
             if (younger >= 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
@@ -417,6 +449,42 @@ __device__ __forceinline__ void gemm_tn_dma_body(
         for (int i = 0; i < WM; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[i][j] = mfma_bf16_16x16x32(a[i], b[j], acc[i][j]);
+        if (XTRA && x_here && wave == x_wave) {
+            u16x8_t bxr[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offBx[j][0]));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offBx[j][1]));
+                bxr[j] = u16x8_t{(bf16_t)lo[0], (bf16_t)lo[1], (bf16_t)lo[2], (bf16_t)lo[3], (bf16_t)hi[0], (bf16_t)hi[1], (bf16_t)hi[2], (bf16_t)hi[3]};
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                if (i >= x_mt) break;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offAx[i][0]));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(st + offAx[i][1]));
+                const u16x8_t ax = u16x8_t{(bf16_t)lo[0], (bf16_t)lo[1], (bf16_t)lo[2], (bf16_t)lo[3], (bf16_t)hi[0], (bf16_t)hi[1], (bf16_t)hi[2], (bf16_t)hi[3]};
+#pragma unroll
+                for (int j = 0; j < 2; ++j) accx[i][j] = mfma_bf16_16x16x32(ax, bxr[j], accx[i][j]);
+            }
+        }
+    }
+    if (XTRA && x_here && wave == x_wave) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            if (i >= x_mt) break;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int n = x_n0 + j * 16 + lr;
+                if (n >= Nc) continue;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int m = m0 + (bx * x_mt + i) * 16 + lk * 4 + r;
+                    if (m >= Mr) continue;
+                    const int out_row = unperm_h > 0 ? (m & 3) * unperm_h + (m >> 2) : m;
+                    C[(size_t)out_row * ldc + n] = accx[i][j][r];
+                }
+            }
+        }
     }
     // C fragment: element r of lane l is row (l / 16) * 4 + r, column l % 16 of the 16x16 tile.
 #pragma unroll
@@ -440,14 +508,86 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_kernel(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb, float* __restrict__ C, int ldc,
     int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    gemm_tn_dma_body<4>(A, lda, B, ldb, C, ldc, Mr, Nc, K, unperm_h, k_chunk, split_stride, smem);
+    int bx, by, bz;
+    gemm_tile_of_block(bx, by, bz);
+    gemm_tn_dma_body<4>(A, lda, B, ldb, C, ldc, Mr, Nc, K, unperm_h, k_chunk, split_stride, smem, bx, by, bz, gridDim.z > 1);
 }
 __global__ __launch_bounds__(GEMM_THREADS) void gemm_tn_dma_tall_kernel(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ B, int ldb, float* __restrict__ C, int ldc,
     int Mr, int Nc, int K, int unperm_h, int k_chunk, size_t split_stride) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    gemm_tn_dma_body<8>(A, lda, B, ldb, C, ldc, Mr, Nc, K, unperm_h, k_chunk, split_stride, smem);
+    int bx, by, bz;
+    gemm_tile_of_block(bx, by, bz);
+    gemm_tn_dma_body<8>(A, lda, B, ldb, C, ldc, Mr, Nc, K, unperm_h, k_chunk, split_stride, smem, bx, by, bz, gridDim.z > 1);
 }
+
+// Several such contractions in one launch (the weight gradients of a minibatch: same row count, different
+// operands).  One launch of all their 128 x 128 tiles lets two workgroups share a CU (2 x 64 KB of LDS), so that one
+// multiplies while the other waits at its stage barrier, and the ramps and tails of the separate launches are gone.
+// XCD x (workgroups are dealt round-robin in launch order) takes the band of row tiles [x*R, (x+1)*R) of every
+// problem, problem after problem, a row tile's column tiles next to each other: workgroups that are resident
+// together walk the same rows of the A operand at the same time.  Needs Mr / 128 divisible by 8 for every problem.
+constexpr int TN_GROUP_MAX = 4;
+struct TnProblem {
+    const bf16_t* A; const bf16_t* B; float* C;
+    int lda, ldb, ldc, Mr, Nc, K, unperm_h;
+    int tiles_n;      // column tiles
+    int slot_end;     // per XCD: slots of this and all earlier problems
+    int x_cols, x_mt; // columns beyond the last whole column tile that ride along with the whole tiles (0: none)
+};
+struct TnGroupArgs { TnProblem p[TN_GROUP_MAX]; int n; };
+__global__ __launch_bounds__(GEMM_THREADS, 2) void gemm_tn_dma_group_kernel(TnGroupArgs g) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < TN_GROUP_MAX; ++i)
+        if (i < g.n && slot >= g.p[i - 1].slot_end) pi = i;
+    TnProblem q = g.p[0];   // uniform selects (an indexed copy of a kernel argument would live in scratch memory)
+#pragma unroll
+    for (int i = 1; i < TN_GROUP_MAX; ++i)
+        if (pi == i) q = g.p[i];
+    const int rem = slot - (pi > 0 ? g.p[pi - 1].slot_end : 0);
+    const int R = q.Mr / (GEMM_BM * 8);
+    const int by = xcd * R + rem / q.tiles_n, bx = rem % q.tiles_n;
+    if (q.x_cols > 0)
+        gemm_tn_dma_body<4, true>(q.A, q.lda, q.B, q.ldb, q.C, q.ldc, q.Mr, q.Nc, q.K, q.unperm_h, q.K, 0, smem, bx, by, 0, false,
+                                  q.x_cols, q.x_mt);
+    else
+        gemm_tn_dma_body<4>(q.A, q.lda, q.B, q.ldb, q.C, q.ldc, q.Mr, q.Nc, q.K, q.unperm_h, q.K, 0, smem, bx, by, 0, false);
+}
+
+// Whether a K-minor bf16 contraction can join a grouped launch, and the launch itself.
+inline bool tn_group_fits(int lda, int ldb, int Mr, int K) {
+    return lda % 2 == 0 && ldb % 2 == 0 && Mr % (GEMM_BM * 8) == 0 && (size_t)K * lda * 2 < 0x7fffffff &&
+           (size_t)K * ldb * 2 < 0x7fffffff;
+}
+struct TnGroup {
+    TnGroupArgs a{};
+    bool add(const bf16_t* A, int lda, const bf16_t* B, int ldb, float* C, int ldc, int Mr, int Nc, int K, int unperm_h) {
+        if (a.n >= TN_GROUP_MAX || !tn_group_fits(lda, ldb, Mr, K)) return false;
+        TnProblem& q = a.p[a.n];
+        q.A = A; q.B = B; q.C = C; q.lda = lda; q.ldb = ldb; q.ldc = ldc; q.Mr = Mr; q.Nc = Nc; q.K = K; q.unperm_h = unperm_h;
+        q.tiles_n = (Nc + GEMM_BN - 1) / GEMM_BN;
+        q.x_cols = q.x_mt = 0;
+        const int whole = Nc / GEMM_BN, rest = Nc % GEMM_BN;
+        if (rest > 0 && rest <= 32 && whole >= 4) {   // the last few columns ride along with the whole tiles
+            q.tiles_n = whole;
+            q.x_cols = rest;
+            q.x_mt = whole >= 8 ? 1 : 2;
+        }
+        q.slot_end = (a.n > 0 ? a.p[a.n - 1].slot_end : 0) + Mr / (GEMM_BM * 8) * q.tiles_n;
+        ++a.n;
+        return true;
+    }
+    void launch(hipStream_t s) {
+        if (a.n == 0) return;
+        constexpr int lds = TnGeom<4>::LDS + TnGeom<4>::STAGES * TN_X_STAGE;
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_tn_dma_group_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        hipLaunchKernelGGL(gemm_tn_dma_group_kernel, dim3(8 * a.p[a.n - 1].slot_end), dim3(GEMM_THREADS), lds, s, a);
+        a.n = 0;
+    }
+};
 
 // How many ways to split the contraction so that the grid has a few workgroups per CU.
 inline int gemm_splits(int Mr, int Nc, int K, int BK) {

@@ -630,7 +630,8 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
             else VER_BWD_LAUNCH(KERNEL, ARGS, 1, 8, 0); \
         } } while (0)
     // everything of layer l that is not the time loop: dx (optional), dW_ih, dW_hh, db
-    auto layer_grads = [&](int l, float* dx) {
+    TnGroup dw_group;
+    auto layer_grads = [&](int l, float* dx, bool flush_dw) {
         const int D = l == 0 ? c.input_dim : H;
         LayerWs& L = ws.layer[l];
         const E* dz = static_cast<const E*>(dz_of(l));
@@ -643,22 +644,32 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
                 gemm_launch<MODE, E, E, false>(dz, 4 * H, static_cast<const E*>(L.wihT), 4 * H, dx, D, M, D, 4 * H,
                                                nullptr, 0, ws.gemm_part, true, s);
         }
-        // dW_ih[4H, D] = dz^T x ; dW_hh[4H, H] = dz^T h_{t-1}; stored gate-major
+        // dW_ih[4H, D] = dz^T x ; dW_hh[4H, H] = dz^T h_{t-1}; stored gate-major.  Contractions whose operands are both
+        // bf16 join the grouped launch (dw_group) when they fit it; the others are launched on the spot.
         {
         ProfScope prof(VER_PROF_LSTM_GEMM_DW, s);
-        if (l > 0 && pipelined && ws.layer[l - 1].hcopy)   // the layer below left its h in operand type
-            gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(ws.layer[l - 1].hcopy), H, gw[4 * l], D, 4 * H, D, M,
-                                          nullptr, H, ws.gemm_part, true, s);
-        else if (l > 0)
+        auto grouped = [&](const void* B, int ldb, float* C, int Nc) {
+            if constexpr (MODE == MODE_BF16)
+                return dw_group.add(reinterpret_cast<const bf16_t*>(dz), 4 * H, static_cast<const bf16_t*>(B), ldb, C, Nc, 4 * H, Nc, M, H);
+            return false;
+        };
+        if (l > 0 && pipelined && ws.layer[l - 1].hcopy) {   // the layer below left its h in operand type
+            if (!grouped(ws.layer[l - 1].hcopy, H, gw[4 * l], D))
+                gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(ws.layer[l - 1].hcopy), H, gw[4 * l], D, 4 * H, D, M,
+                                              nullptr, H, ws.gemm_part, true, s);
+        } else if (l > 0)
             gemm_launch<MODE, E, float, true>(dz, 4 * H, ws.layer[l - 1].hout, H, gw[4 * l], D, 4 * H, D, M, nullptr, H, ws.gemm_part, true, s);
-        else if (c.x_bf16)
-            gemm_launch<MODE, E, bf16_t, true>(dz, 4 * H, static_cast<const bf16_t*>(x), D, gw[4 * l], D, 4 * H, D, M,
-                                               nullptr, H, ws.gemm_part, true, s);
-        else
+        else if (c.x_bf16) {
+            if (!grouped(x, D, gw[4 * l], D))
+                gemm_launch<MODE, E, bf16_t, true>(dz, 4 * H, static_cast<const bf16_t*>(x), D, gw[4 * l], D, 4 * H, D, M,
+                                                   nullptr, H, ws.gemm_part, true, s);
+        } else
             gemm_launch<MODE, E, float, true>(dz, 4 * H, static_cast<const float*>(x), D, gw[4 * l], D, 4 * H, D, M,
                                               nullptr, H, ws.gemm_part, true, s);
-        gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(L.hprev), H, gw[4 * l + 1], H, 4 * H, H, M,
-                                      nullptr, H, ws.gemm_part, true, s);
+        if (!grouped(L.hprev, H, gw[4 * l + 1], H))
+            gemm_launch<MODE, E, E, true>(dz, 4 * H, static_cast<const E*>(L.hprev), H, gw[4 * l + 1], H, 4 * H, H, M,
+                                          nullptr, H, ws.gemm_part, true, s);
+        if (flush_dw) dw_group.launch(s);
         }
         // db_ih = db_hh = column sums of dz: the time loop left one partial sum per group
         {
@@ -683,8 +694,8 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         VER_BWD_DISPATCH(lstm_pipe_bwd_kernel, pa);
         if (!ok) return VER_EHIP;
         }
-        layer_grads(1, nullptr);
-        layer_grads(0, d_x);
+        layer_grads(1, nullptr, false);   // the weight gradients of both layers leave in one grouped launch
+        layer_grads(0, d_x, true);
     } else {
         int cur = 0;  // ws.dh[cur] holds the gradient arriving at the current layer's h
         for (int l = nl - 1; l >= 0; --l) {
@@ -695,7 +706,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
             VER_BWD_DISPATCH(lstm_rec_bwd_kernel, ra);
             if (!ok) return VER_EHIP;
             }
-            layer_grads(l, l > 0 ? ws.dh[cur ^ 1] : d_x);
+            layer_grads(l, l > 0 ? ws.dh[cur ^ 1] : d_x, true);
             cur ^= 1;
         }
     }

@@ -221,3 +221,14 @@ def test_bf16_input_projection_any_width(ver, input_dim):
     at and just above a multiple of 64 (and narrower than one tile), over three row tiles with a ragged last one."""
     case(ver, wl.scaled(wl.WORKLOADS["large"], budget=300, n_envs=5, hidden=64, input_dim=input_dim, p_done=0.02,
                         minibatches=1), seed=40 + input_dim, compute=1, x_bf16=True)
+
+
+@pytest.mark.parametrize("input_dim,layer_by_layer", [(516, False), (1044, False), (544, False), (548, False), (1056, True),
+                                                      (512, False), (640, True)])
+def test_grouped_weight_gradients(ver, input_dim, layer_by_layer):
+    """bf16 operands at a hidden size whose weight gradients leave in one grouped launch (4H a multiple of 1024),
+    over input widths on both sides of its rules: a few columns beyond the last whole 128-column tile ride along
+    with the whole tiles (4 or 20 columns beyond four whole tiles: two 16-row slices per tile; 20 or 32 beyond
+    eight: one), more than 32 columns or no remainder take column tiles of their own."""
+    case(ver, wl.scaled(wl.WORKLOADS["manip"], budget=420, n_envs=9, hidden=256, input_dim=input_dim, p_done=0.02,
+                        minibatches=1), seed=41, compute=1, x_bf16=True, layer_by_layer=layer_by_layer)
