@@ -514,8 +514,11 @@ constexpr int IS_TILE = 4096;
 constexpr int IS_WIN = IS_TILE + 2;   // offsets kept in LDS (more only with many empty environments: then memory is searched)
 
 // off[0 .. n_env]: offsets of the tile's environments (off[0] <= first step, off[n_env] > last step).
+// wtab (may be null): the weight of environment i of the tile, when the caller has computed them once per
+// environment; without it a lane divides whenever it enters a stretch (a double division is ~40 instructions, and a
+// wave executes it in every unrolled position in which any of its lanes crosses a boundary).
 template <typename OffPtr>
-__device__ __forceinline__ void is_weight_tile(OffPtr off, int n_env, int k_lo, int S, double share, float max_is,
+__device__ __forceinline__ void is_weight_tile(OffPtr off, const float* wtab, int n_env, int k_lo, int S, double share, float max_is,
                                                float* __restrict__ weight) {
     for (int r = 0; r < IS_TILE / (IS_THREADS * IS_ITEMS); ++r) {
         const int k0 = k_lo + (r * IS_THREADS + (int)threadIdx.x) * IS_ITEMS;
@@ -536,7 +539,7 @@ __device__ __forceinline__ void is_weight_tile(OffPtr off, int n_env, int k_lo, 
         int env = lo;
         while (off[env + 1] <= k0) ++env;   // (off[n_env] lies beyond the tile's last step)
         int end = off[env + 1];
-        float w = fminf(max_is, (float)(share / (double)(end - off[env])));
+        float w = wtab ? wtab[env] : fminf(max_is, (float)(share / (double)(end - off[env])));
         float out[IS_ITEMS];
 #pragma unroll
         for (int i = 0; i < IS_ITEMS; ++i) {
@@ -547,7 +550,7 @@ __device__ __forceinline__ void is_weight_tile(OffPtr off, int n_env, int k_lo, 
                     begin = end;
                     end = off[++env + 1];
                 } while (k >= end);
-                w = fminf(max_is, (float)(share / (double)(end - begin)));
+                w = wtab ? wtab[env] : fminf(max_is, (float)(share / (double)(end - begin)));
             }
             out[i] = w;
         }
@@ -575,10 +578,84 @@ __global__ __launch_bounds__(IS_THREADS) void is_weight_kernel(const int32_t* __
     if (n_env + 1 <= IS_WIN) {
         for (int i = threadIdx.x; i <= n_env; i += IS_THREADS) s_off[i] = env_off[e0 + i];
         __syncthreads();
-        is_weight_tile(static_cast<const int*>(s_off), n_env, k_lo, S, share, max_is, weight);
+        is_weight_tile(static_cast<const int*>(s_off), static_cast<const float*>(nullptr), n_env, k_lo, S, share, max_is, weight);
     } else {
-        is_weight_tile(env_off + e0, n_env, k_lo, S, share, max_is, weight);
+        is_weight_tile(env_off + e0, static_cast<const float*>(nullptr), n_env, k_lo, S, share, max_is, weight);
     }
+}
+
+// Large buffers (from IS_MARK_FROM steps on) take two launches, because the two searches above are four dependent
+// rounds of loads each, and with every CU full of workgroups that wait for them the kernel runs at the pace of those
+// rounds, not of its stores.  First launch: one thread per environment writes its index into the output array at the
+// first step of every tile that begins inside its stretch (every tile start lies in exactly one non-empty stretch;
+// a stretch that spans many tiles is handed to the whole wave).  Second launch: a tile reads its first environment
+// from its own first output element (which only this tile overwrites, afterwards), loads the 256 offsets that follow
+// in one round and fills in its steps; a tile with more environments than that, or whose mark is not a valid index
+// (malformed offsets), searches as above.
+constexpr int IS_MARK_FROM = 1 << 20;
+constexpr int IS_MARK_WAVE_FROM = 8;   // tiles from which a stretch is marked by the whole wave
+__global__ __launch_bounds__(256) void is_weight_mark_kernel(const int32_t* __restrict__ env_off, int N, int S,
+                                                             int* __restrict__ mark) {
+    const int e = blockIdx.x * 256 + threadIdx.x, lane = threadIdx.x & (VER_WAVE - 1);
+    int lo = 0, hi = 0;
+    if (e < N) { lo = env_off[e]; hi = min(env_off[e + 1], S); }
+    lo = max(lo, 0);
+    // tiles t with lo <= t * IS_TILE < hi
+    int t0 = (lo + IS_TILE - 1) / IS_TILE, t1 = hi > lo ? (hi - 1) / IS_TILE : t0 - 1;   // [t0, t1]
+    const bool wide = t1 - t0 + 1 >= IS_MARK_WAVE_FROM;
+    if (!wide)
+        for (int t = t0; t <= t1; ++t) mark[(size_t)t * IS_TILE] = e;
+    unsigned long long todo = __ballot(wide);
+    while (todo) {
+        const int src = __ffsll((long long)todo) - 1;
+        todo &= todo - 1;
+        const int a = __shfl(t0, src, VER_WAVE), b = __shfl(t1, src, VER_WAVE), who = __shfl(e, src, VER_WAVE);
+        for (int t = a + lane; t <= b; t += VER_WAVE) mark[(size_t)t * IS_TILE] = who;
+    }
+}
+
+__global__ __launch_bounds__(IS_THREADS) void is_weight_fill_kernel(const int32_t* __restrict__ env_off, int N, int S,
+                                                                    double share, float max_is,
+                                                                    float* __restrict__ weight) {
+    __shared__ int s_off[IS_THREADS];
+    __shared__ float s_w[IS_THREADS];
+    __shared__ int s_env[2];
+    const int k_lo = blockIdx.x * IS_TILE, k_hi = min(S, k_lo + IS_TILE) - 1;
+    const int wave = threadIdx.x / VER_WAVE;
+    int e0 = reinterpret_cast<const int*>(weight)[k_lo];   // left by is_weight_mark_kernel
+    // the offsets that follow, one per thread (beyond off[N] = S: that one again)
+    const bool valid = e0 >= 0 && e0 < N;
+    if (!valid) e0 = 0;
+    const int mine = env_off[min(e0 + (int)threadIdx.x, N)];
+    s_off[threadIdx.x] = mine;
+    __syncthreads();   // (also: every thread has read the mark before any thread overwrites it)
+    // The tile is covered when the first offset is not beyond its first step and the last one is beyond its last
+    // step; its environments then end at the first offset beyond k_hi, found by counting (every wave counts for
+    // itself and gets the same number).  Whatever the offsets hold, the walk then stays inside s_off[0 .. n_env].
+    constexpr int last = IS_THREADS - 1;
+    int n_env = 0;
+    if (valid && s_off[0] <= k_lo && s_off[last] > k_hi) {
+        int cnt = 0;
+        for (int i = threadIdx.x & (VER_WAVE - 1); i <= last; i += VER_WAVE) cnt += s_off[i] <= k_hi ? 1 : 0;
+#pragma unroll
+        for (int d = VER_WAVE / 2; d > 0; d >>= 1) cnt += __shfl_xor(cnt, d, VER_WAVE);
+        n_env = cnt;
+    }
+    if (n_env > 0 && n_env <= last && s_off[n_env] > k_hi) {
+        // one division per environment of the tile (an empty one divides by zero: its weight belongs to no step)
+        if ((int)threadIdx.x < n_env) s_w[threadIdx.x] = fminf(max_is, (float)(share / (double)(s_off[threadIdx.x + 1] - mine)));
+        __syncthreads();
+        is_weight_tile(static_cast<const int*>(s_off), static_cast<const float*>(s_w), n_env, k_lo, S, share, max_is, weight);
+        return;
+    }
+    // not covered by 256 offsets (or no valid mark): search as the single-launch kernel does, offsets read in place
+    if (wave < 2) {
+        const int e = segment_of_wave(env_off, N, wave == 0 ? k_lo : k_hi);
+        if ((threadIdx.x & (VER_WAVE - 1)) == 0) s_env[wave] = e;
+    }
+    __syncthreads();
+    e0 = s_env[0];
+    is_weight_tile(env_off + e0, static_cast<const float*>(nullptr), s_env[1] - e0 + 1, k_lo, S, share, max_is, weight);
 }
 
 }  // namespace
@@ -592,8 +669,15 @@ extern "C" int ver_is_weight(const int32_t* env_off, int32_t N, int32_t S, float
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int per_block = ver::IS_TILE;
     ver::ProfScope prof(VER_PROF_IS_WEIGHT, s);
-    hipLaunchKernelGGL(ver::is_weight_kernel, dim3((S + per_block - 1) / per_block), dim3(ver::IS_THREADS), 0, s,
-                       env_off, N, S, (double)S / (double)N, max_is, weight);
+    if (S >= ver::IS_MARK_FROM) {
+        hipLaunchKernelGGL(ver::is_weight_mark_kernel, dim3((N + 255) / 256), dim3(256), 0, s, env_off, N, S,
+                           reinterpret_cast<int*>(weight));
+        hipLaunchKernelGGL(ver::is_weight_fill_kernel, dim3((S + per_block - 1) / per_block), dim3(ver::IS_THREADS), 0, s,
+                           env_off, N, S, (double)S / (double)N, max_is, weight);
+    } else {
+        hipLaunchKernelGGL(ver::is_weight_kernel, dim3((S + per_block - 1) / per_block), dim3(ver::IS_THREADS), 0, s,
+                           env_off, N, S, (double)S / (double)N, max_is, weight);
+    }
     return ver::launch_status();
 }
 

@@ -56,3 +56,25 @@ def test_large_buffer(ver):
     rng = np.random.default_rng(11)
     lengths = np.maximum(0, np.round(rng.lognormal(5.0, 1.0, 8192))).astype(np.int64)
     run(ver, lengths, 1.0)
+
+
+@pytest.mark.parametrize("case", ["one_owner", "empty_runs", "single_steps", "mixed"])
+def test_two_launch_path(ver, case):
+    """Buffers from 2^20 steps on take two launches (tile starts marked per environment, then filled): a stretch
+    that spans hundreds of tiles (marked by whole waves), runs of hundreds of empty environments and one-step
+    environments (more offsets per tile than a workgroup loads in one round: those tiles search instead), and a
+    mix with a ragged last tile."""
+    rng = np.random.default_rng(5)
+    if case == "one_owner":
+        lengths = np.array([0, 3, 1_500_001, 0, 0, 70_000, 5], np.int64)
+    elif case == "empty_runs":
+        lengths = np.zeros(6000, np.int64)
+        lengths[rng.choice(6000, 40, replace=False)] = rng.integers(20_000, 40_000, 40)
+    elif case == "single_steps":
+        lengths = np.concatenate([np.ones(700_000, np.int64), rng.integers(1, 3000, 300)])
+    else:
+        lengths = np.concatenate([rng.integers(0, 40, 20_000), rng.integers(1000, 90_000, 30), np.zeros(300, np.int64),
+                                  rng.integers(1, 9, 5000)])
+        lengths = lengths[rng.permutation(len(lengths))]
+    assert lengths.sum() >= 1 << 20
+    run(ver, lengths, 1.0)
