@@ -165,7 +165,10 @@ int ver_gae_static(const float* rewards, const float* values, const uint8_t* don
  *
  * env_off: device int32[N+1]; weight: device float[S], 16-byte aligned.  The quotient is
  * formed in double and rounded once.  max_is <= 0 or N <= 0 is VER_EINVAL;
- * S = 0 is legal (no work).
+ * S = 0 is legal (no work).  The weight array is also the call's scratch:
+ * from 2^20 steps on a first kernel leaves environment indices in it, which
+ * the second overwrites with the weights, so its contents are only meaningful
+ * once the call's work on the stream has finished.
  */
 int ver_is_weight(const int32_t* env_off, int32_t N, int32_t S, float max_is,
                   float* weight, void* stream);

@@ -92,7 +92,7 @@ def _gae(out, w, g, rng, randn, reps, scale):
     out.append(_row("gae_kernel", f"N={N} S={S}", 17 * S + 8 * N, ms, n, "17 B/step + 8 B/environment"))
     del rewards, values, dones, adv, ws
     ms, n = _timed("is_weight", lambda: ver.ver_is_weight(env_off, N, S, 1.0, ret), reps)
-    out.append(_row("is_weight_kernel", f"N={N} S={S}", 4 * S + 4 * N, ms, n, "4 B/step written + 4 B/environment"))
+    out.append(_row("is_weight_mark_kernel + is_weight_fill_kernel", f"N={N} S={S}", 4 * S + 4 * N, ms, n, "4 B/step written + 4 B/environment"))
     del ret, env_off, last_values
     torch.cuda.empty_cache()
 
