@@ -358,7 +358,7 @@ def main():
         try:
             from paper_2210_05064_amd import hbm_replica
             out["hbm_replica"] = [{k: r[k] for k in ("kernel", "shape", "bytes", "ms", "achieved", "peak", "unit", "frac")}
-                                  for r in hbm_replica.run(seed=args.seed + 3000, reps=4)]
+                                  for r in hbm_replica.run(seed=args.seed + 3000, reps=20)]
         except Exception as e:   # the headline figures above do not depend on this part
             out["hbm_replica_error"] = repr(e)
     if args.cpu_budget > 0:

@@ -23,7 +23,7 @@ from . import workloads as wl
 HBM_PEAK_GBPS = 8000.0   # MI355X, HBM3E
 
 
-def _timed(cls: str, call, reps: int, warmup: int = 2):
+def _timed(cls: str, call, reps: int, warmup: int = 3):
     """Average milliseconds per launch group of profile class `cls` over `reps` calls of call()."""
     for _ in range(warmup):
         call()
