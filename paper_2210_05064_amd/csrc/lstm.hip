@@ -183,10 +183,11 @@ __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* _
         part_b[(size_t)rb * 64 + threadIdx.x] = sb;
     }
     if (j >= H) return;
-    for (int a0 = 0; a0 <= A; a0 += 8) {
-        f32x4_t acc[8];
+    // 16 heads per pass over the block's rows (one pass for every policy of the paper: 4 or 11 outputs + the value)
+    for (int a0 = 0; a0 <= A; a0 += 16) {
+        f32x4_t acc[16];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int e = 0; e < 16; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
         for (int p = p_lo; p < p_hi; p += 4) {
             f32x4_t hv[4];
 #pragma unroll
@@ -196,25 +197,26 @@ __global__ __launch_bounds__(256) void heads_wgrad_partial_kernel(const float* _
             for (int u = 0; u < 4; ++u) {
                 if (p + u >= p_hi) continue;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int e = 0; e < 16; ++e) {
                     const float g = s_g[p + u - p_lo][a0 + e];   // same address in every lane: a broadcast read
                     acc[e][0] += g * hv[u][0]; acc[e][1] += g * hv[u][1]; acc[e][2] += g * hv[u][2]; acc[e][3] += g * hv[u][3];
                 }
             }
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+        for (int e = 0; e < 16; ++e)
             if (a0 + e <= A) *reinterpret_cast<f32x4_t*>(part + ((size_t)rb * (A + 1) + a0 + e) * H + j) = acc[e];
     }
 }
-
-// Sums the row blocks' partial sums in block order: dW_a / dw_v column j of head a, and (first column block) the
-// head's bias gradient from part_b[n_rb][64], by a fixed tree over the block's threads.
+// One workgroup adds the row blocks' partial sums for 64 columns of one head: its four waves take a quarter of the
+// row blocks each (in index order, 8 loads in flight), and the four shares are added in wave order.
+constexpr int HF_COLS = 64;
 __global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __restrict__ part, const float* __restrict__ part_b, int n_rb,
                                                                 int H, int A, float* __restrict__ dW_a, float* __restrict__ dw_v,
                                                                 float* __restrict__ db_a, float* __restrict__ db_v) {
     __shared__ float red[256];
-    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int lane = threadIdx.x & 63, share = threadIdx.x >> 6;
+    const int j = blockIdx.x * HF_COLS + lane;
     const int a = blockIdx.y;
     if (blockIdx.x == 0) {
         float sb = 0.f;
@@ -228,19 +230,27 @@ __global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __r
         if (threadIdx.x == 0) {
             if (a < A) db_a[a] = red[0]; else db_v[0] = red[0];
         }
+        __syncthreads();
     }
-    if (j >= H) return;
+    const int per = (n_rb + 3) / 4, rb_end = min(n_rb, (share + 1) * per);
     float s = 0.f;
-    int rb = 0;
-    for (; rb + 8 <= n_rb; rb += 8) {   // 8 loads in flight, added in index order
-        float v[8];
+    int rb = share * per;
+    if (j < H) {
+        for (; rb + 8 <= rb_end; rb += 8) {   // 8 loads in flight, added in index order
+            float v[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) v[u] = part[((size_t)(rb + u) * (A + 1) + a) * H + j];
+            for (int u = 0; u < 8; ++u) v[u] = part[((size_t)(rb + u) * (A + 1) + a) * H + j];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += v[u];
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; rb < rb_end; ++rb) s += part[((size_t)rb * (A + 1) + a) * H + j];
     }
-    for (; rb < n_rb; ++rb) s += part[((size_t)rb * (A + 1) + a) * H + j];
-    if (a < A) dW_a[(size_t)a * H + j] = s; else dw_v[j] = s;
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (share == 0 && j < H) {
+        s = ((red[lane] + red[64 + lane]) + red[128 + lane]) + red[192 + lane];
+        if (a < A) dW_a[(size_t)a * H + j] = s; else dw_v[j] = s;
+    }
 }
 
 // out[perm(c)] (and out2) = sum over the n_rb rows of part[n_rb][cols], in row order (deterministic);
@@ -585,7 +595,7 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     const int rb_h = (M + HW_ROWS - 1) / HW_ROWS;
     hipLaunchKernelGGL(heads_wgrad_partial_kernel, dim3((H / 4 + 255) / 256, rb_h), dim3(256), 0, s, d_u, d_v, h_top, M, H,
                        A, ws.part, ws.part_b);
-    hipLaunchKernelGGL(heads_wgrad_final_kernel, dim3((H + 255) / 256, A + 1), dim3(256), 0, s, ws.part, ws.part_b, rb_h, H, A,
+    hipLaunchKernelGGL(heads_wgrad_final_kernel, dim3((H + HF_COLS - 1) / HF_COLS, A + 1), dim3(256), 0, s, ws.part, ws.part_b, rb_h, H, A,
                        gw[4 * nl], gw[4 * nl + 2], gw[4 * nl + 1], gw[4 * nl + 3]);
     }
 
