@@ -31,11 +31,34 @@ __device__ __forceinline__ void st4(bf16_t* p, float a, float b, float c, float 
 }
 // A thread moves 4 adjacent elements at a time (16-byte loads, 8- or 16-byte stores; cols is a multiple of 4):
 // 16 lanes cover a tile row in either direction.
+// All matrices and bias vectors of a call in one launch (blockIdx.z: the job; a launch per matrix took ~10 us each,
+// most of it ramp and tail).
+constexpr int PREP_MAX_JOBS = 24;   // 2 matrices + 1 bias per layer, 8 layers
+struct PrepJob {
+    const float* W;      // matrix [4H, cols] gate-major, or b_ih when cols == 0
+    const float* b_hh;   // (bias jobs)
+    void* dst; void* dstT;
+    int cols;            // 0: bias job
+};
+struct PrepArgs { PrepJob job[PREP_MAX_JOBS]; };
 template <typename E>
-__global__ __launch_bounds__(256) void prep_matrix_kernel(const float* __restrict__ W, int H, int cols, E* __restrict__ dst,
-                                                          E* __restrict__ dstT) {
+__global__ __launch_bounds__(256) void prep_weights_kernel(PrepArgs a, int H) {
     __shared__ float tile[64][65];
+    const PrepJob& jb = a.job[blockIdx.z];   // (uniform index into the kernel arguments: scalar loads)
+    const int cols = jb.cols;
+    if (cols == 0) {   // bias: dst[q] = b_ih + b_hh, gate rows interleaved
+        const int q = (blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
+        if (q < 4 * H) {
+            const int src = (q & 3) * H + (q >> 2);
+            static_cast<float*>(jb.dst)[q] = jb.W[src] + jb.b_hh[src];
+        }
+        return;
+    }
     const int q0 = blockIdx.y * 64, d0 = blockIdx.x * 64;
+    if (d0 >= cols) return;
+    const float* __restrict__ W = jb.W;
+    E* __restrict__ dst = static_cast<E*>(jb.dst);
+    E* __restrict__ dstT = static_cast<E*>(jb.dstT);
     const int c4 = (threadIdx.x & 15) * 4, r0 = threadIdx.x >> 4;
 #pragma unroll
     for (int r = r0; r < 64; r += 16) {
@@ -52,15 +75,6 @@ __global__ __launch_bounds__(256) void prep_matrix_kernel(const float* __restric
     for (int r = r0; r < 64; r += 16) {
         const int d = d0 + r, q = q0 + c4;
         if (d < cols) st4(dstT + (size_t)d * 4 * H + q, tile[c4][r], tile[c4 + 1][r], tile[c4 + 2][r], tile[c4 + 3][r]);
-    }
-}
-
-__global__ void prep_bias_kernel(const float* __restrict__ b_ih, const float* __restrict__ b_hh, int H,
-                                 float* __restrict__ dst) {
-    const int q = blockIdx.x * blockDim.x + threadIdx.x;
-    if (q < 4 * H) {
-        const int src = (q & 3) * H + (q >> 2);
-        dst[q] = b_ih[src] + b_hh[src];
     }
 }
 
@@ -483,15 +497,20 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     if (pipelined && pipe_worker_lds<MODE>() > lds) lds = pipe_worker_lds<MODE>();
     const int nb = (H / ks) / RecGeom<MODE>::KBLK;
 
-    auto prep = [&](int l) {
-        const int D = l == 0 ? c.input_dim : H;
-        LayerWs& L = ws.layer[l];
+    // operand-type copies of every layer's weights (and their transposes) and the summed biases: one launch
+    auto prep_all = [&]() {
         ProfScope prof(VER_PROF_LSTM_PREP, s);
-        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3((D + 63) / 64, 4 * H / 64), dim3(256), 0, s, w[4 * l], H, D,
-                           static_cast<E*>(L.wih), static_cast<E*>(L.wihT));
-        hipLaunchKernelGGL(prep_matrix_kernel<E>, dim3((H + 63) / 64, 4 * H / 64), dim3(256), 0, s, w[4 * l + 1], H, H,
-                           static_cast<E*>(L.whh), static_cast<E*>(L.whhT));
-        hipLaunchKernelGGL(prep_bias_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s, w[4 * l + 2], w[4 * l + 3], H, L.bias);
+        PrepArgs pa{};
+        int n = 0, max_cols = H;
+        for (int l = 0; l < c.n_layers; ++l) {
+            const int D = l == 0 ? c.input_dim : H;
+            LayerWs& L = ws.layer[l];
+            max_cols = D > max_cols ? D : max_cols;
+            pa.job[n++] = PrepJob{w[4 * l], nullptr, L.wih, L.wihT, D};
+            pa.job[n++] = PrepJob{w[4 * l + 1], nullptr, L.whh, L.whhT, H};
+            pa.job[n++] = PrepJob{w[4 * l + 2], w[4 * l + 3], L.bias, nullptr, 0};
+        }
+        hipLaunchKernelGGL(prep_weights_kernel<E>, dim3((max_cols + 63) / 64, 4 * H / 64, n), dim3(256), 0, s, pa, H);
     };
     // time-batched input projection: gates[M, 4H] = x W_ih^T + (b_ih + b_hh), interleaved columns
     auto project = [&](int l) {
@@ -545,9 +564,8 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
             else VER_FWD_LAUNCH(KERNEL, ARGS, 2, 4, 8, false); \
         } } while (0)
 
+    prep_all();
     if (pipelined) {
-        prep(0);
-        prep(1);
         project(0);
         pipe_prepare_fwd(ws, M, info, batch_sizes, s);
         PipeFwdArgs pa;
@@ -562,7 +580,6 @@ int run_fwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
         if (!ok) return VER_EHIP;
     } else {
         for (int l = 0; l < c.n_layers; ++l) {
-            prep(l);
             project(l);
             fill_words(ws.flags, REC_FLAG_WORDS, 0, s);
             RecFwdArgs ra = rec_args(l);
