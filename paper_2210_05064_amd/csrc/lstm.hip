@@ -143,10 +143,15 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float* __restrict_
 constexpr int HB_ROWS = 8;
 __global__ __launch_bounds__(256) void heads_bwd_dh_kernel(const float* __restrict__ d_u, const float* __restrict__ d_v,
                                                            int M, int H, int A, const float* __restrict__ W_a,
-                                                           const float* __restrict__ w_v, float* __restrict__ dh) {
+                                                           const float* __restrict__ w_v, float* __restrict__ dh,
+                                                           int32_t* __restrict__ clear, int n_clear) {
     __shared__ float s_g[HB_ROWS][64];   // the block's loss gradients: heads 0..A-1, then the value head
     const int j = (blockIdx.x * 256 + threadIdx.x) * 4;
     const int p0 = blockIdx.y * HB_ROWS;
+    // (first kernel of the backward pass: it also clears the synchronisation words of the two-layer launch that
+    // follows, which saves a launch of its own)
+    if (blockIdx.x == 0)
+        for (int i = blockIdx.y * 256 + threadIdx.x; i < n_clear; i += gridDim.y * 256) clear[i] = 0;
     for (int i = threadIdx.x; i < HB_ROWS * 64; i += 256) {
         const int r = i >> 6, a = i & 63, p = p0 + r;
         s_g[r][a] = (p < M) ? (a < A ? d_u[(size_t)p * A + a] : (a == A ? d_v[p] : 0.f)) : 0.f;
@@ -269,11 +274,14 @@ __global__ __launch_bounds__(256) void heads_wgrad_final_kernel(const float* __r
 
 // out[perm(c)] (and out2) = sum over the n_rb rows of part[n_rb][cols], in row order (deterministic);
 // unperm_h > 0 maps interleaved column c to (c%4)*H + c/4.
+// blockIdx.y = 1: the second set (the other layer of a two-layer launch), whose partial sums follow at part_stride.
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, int n_rb, int cols,
                                                            int unperm_h, float* __restrict__ out,
-                                                           float* __restrict__ out2) {
+                                                           float* __restrict__ out2, size_t part_stride,
+                                                           float* __restrict__ out_b, float* __restrict__ out2_b) {
     const int c = blockIdx.x * 256 + threadIdx.x;
     if (c >= cols) return;
+    if (blockIdx.y == 1) { part += part_stride; out = out_b; out2 = out2_b; }
     float s = 0.f;
     int rb = 0;
     for (; rb + 8 <= n_rb; rb += 8) {   // 8 loads in flight, added in index order
@@ -459,9 +467,6 @@ inline void pipe_prepare_fwd(LstmWs& ws, int M, const int32_t* info, const int32
     hipLaunchKernelGGL(lstm_pipe_plan_kernel, dim3(1), dim3(PLAN_THREADS), 0, s, info, batch_sizes, M, ws.plan[0], ws.plan[1],
                        ws.plan_scratch, ws.err, (int)(last - ws.err), PLAN_COST_FWD, PLAN_COST_BWD);
 }
-inline void pipe_prepare_bwd(LstmWs& ws, hipStream_t s) {
-    fill_words(ws.flags, (size_t)(ws.pipe + ws.pipe_words - ws.flags), 0, s);
-}
 inline void pipe_work(const LstmWs& ws, int dir, int M, const int32_t* t_off, PipeWork* pw) {
     pw->M = M;
     pw->t_off = t_off;
@@ -604,11 +609,12 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     typedef typename RecGeom<MODE>::E E;
     const int H = c.hidden, A = c.act_dim, nl = c.n_layers;
     const float* h_top = ws.layer[nl - 1].hout;
+    const bool pipelined = nl == 2 && !c.layer_by_layer;   // both time loops in one launch
     // heads
     {
     ProfScope prof(VER_PROF_HEADS_BWD, s);
     hipLaunchKernelGGL(heads_bwd_dh_kernel, dim3((H / 4 + 255) / 256, (M + HB_ROWS - 1) / HB_ROWS), dim3(256), 0, s, d_u, d_v, M, H, A, w[4 * nl],
-                       w[4 * nl + 2], ws.dh[0]);
+                       w[4 * nl + 2], ws.dh[0], pipelined ? ws.flags : nullptr, pipelined ? (int)(ws.pipe + ws.pipe_words - ws.flags) : 0);
     const int rb_h = (M + HW_ROWS - 1) / HW_ROWS;
     hipLaunchKernelGGL(heads_wgrad_partial_kernel, dim3((H / 4 + 255) / 256, rb_h), dim3(256), 0, s, d_u, d_v, h_top, M, H,
                        A, ws.part, ws.part_b);
@@ -617,7 +623,6 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
     }
 
     // one wave per (16 units, share of the 4H contraction): 2 tiles x 4 when H/16 > 32 workgroups, else 1 x 8
-    const bool pipelined = nl == 2 && !c.layer_by_layer;   // both time loops in one launch
     const bool wide = H / 16 > REC_MAX_GROUP;
     const int mt = wide ? 2 : 1, ks = wide ? 4 : 8;
     const size_t tile = (size_t)16 * (4 * H + RecGeom<MODE>::PAD) * sizeof(E);
@@ -698,18 +703,22 @@ int run_bwd(const ver_lstm_cfg& c, const void* x, int M, const int32_t* info, co
                                           nullptr, H, ws.gemm_part, true, s);
         if (flush_dw) dw_group.launch(s);
         }
-        // db_ih = db_hh = column sums of dz: the time loop left one partial sum per group
-        {
+        // db_ih = db_hh = column sums of dz: the time loop left one partial sum per group (two-layer launch: both
+        // layers' sums in one launch, after the second call)
+        if (!pipelined || l == 0) {
         ProfScope prof(VER_PROF_LSTM_DBIAS, s);
-        hipLaunchKernelGGL(colsum_final_kernel, dim3((4 * H + 255) / 256), dim3(256), 0, s,
-                           ws.db_part + (pipelined ? (size_t)l * REC_GROUPS * 4 * H : 0), pipelined ? PIPE_GROUPS : REC_GROUPS, 4 * H, H,
-                           gw[4 * l + 2], gw[4 * l + 3]);
+        const size_t stride = (size_t)REC_GROUPS * 4 * H;
+        if (pipelined)
+            hipLaunchKernelGGL(colsum_final_kernel, dim3((4 * H + 255) / 256, 2), dim3(256), 0, s, ws.db_part, PIPE_GROUPS, 4 * H, H,
+                               gw[2], gw[3], stride, gw[6], gw[7]);
+        else
+            hipLaunchKernelGGL(colsum_final_kernel, dim3((4 * H + 255) / 256, 1), dim3(256), 0, s, ws.db_part, REC_GROUPS, 4 * H, H,
+                               gw[4 * l + 2], gw[4 * l + 3], stride, static_cast<float*>(nullptr), static_cast<float*>(nullptr));
         }
     };
 
     if (pipelined) {
-        pipe_prepare_bwd(ws, s);
-        PipeBwdArgs pa;
+        PipeBwdArgs pa;   // (the launch's synchronisation words were cleared by heads_bwd_dh_kernel)
         pa.l1 = rec_args(1, ws.dh[0]);
         pa.l0 = rec_args(0, ws.dh[1]);
         pa.work.A = ws.dz[1]; pa.work.B = ws.layer[1].wihT; pa.work.C = ws.dh[1]; pa.work.bias = nullptr;
