@@ -94,6 +94,15 @@ int ver_ingest(const int32_t* arr_env, const int32_t* arr_t, int32_t N, int32_t 
 int ver_ingest_dense(int32_t T, int32_t N, int32_t* env_off, int32_t* order, void* stream);
 int ver_ingest_gather(const int32_t* order, int32_t S, const void* src, int32_t row_bytes,
                       void* dst, void* stream);
+/* The same for several fields in one launch (a rollout has a dozen per-step
+ * fields, each a few microseconds of work at the paper's sizes): field f moves
+ * dst[f] row k = src[f] row order[k], rows of row_bytes[f] bytes.  src, dst and
+ * row_bytes are HOST arrays of n_fields entries (device pointers inside), read
+ * before the call returns; n_fields <= VER_INGEST_MAX_FIELDS, else VER_EINVAL. */
+#define VER_INGEST_MAX_FIELDS 24
+int ver_ingest_gather_batch(const int32_t* order, int32_t S, int32_t n_fields,
+                            const void* const* src, const int32_t* row_bytes,
+                            void* const* dst, void* stream);
 
 /* ------------------------------------------------------------------------
  * ver_gae - advantages and value targets over the ragged buffer.

@@ -68,6 +68,8 @@ lib.ver_ingest_dense.restype = C.c_int
 lib.ver_ingest_dense.argtypes = [_i32, _i32, _vp, _vp, _vp]
 lib.ver_ingest_gather.restype = C.c_int
 lib.ver_ingest_gather.argtypes = [_vp, _i32, _vp, _i32, _vp, _vp]
+lib.ver_ingest_gather_batch.restype = C.c_int
+lib.ver_ingest_gather_batch.argtypes = [_vp, _i32, _i32, _vp, _vp, _vp, _vp]
 lib.ver_is_weight.restype = C.c_int
 lib.ver_is_weight.argtypes = [_vp, _i32, _i32, _f, _vp, _vp]
 lib.ver_pack_workspace_bytes.restype = _sz
@@ -173,6 +175,15 @@ def ver_ingest_gather(order, S, src, dst):
     """dst[k] = src[order[k]] over the leading dimension; src, dst: contiguous tensors of equal shape and dtype."""
     row_bytes = src.element_size() * (src[0].numel() if S > 0 else 1)
     _check(lib.ver_ingest_gather(_ptr(order), S, _ptr(src), row_bytes, _ptr(dst), _stream()))
+
+
+def ver_ingest_gather_batch(order, S, pairs):
+    """dst[k] = src[order[k]] for every (src, dst) pair of contiguous tensors, in one launch."""
+    n = len(pairs)
+    srcs = (C.c_void_p * n)(*[_ptr(a) for a, _ in pairs])
+    dsts = (C.c_void_p * n)(*[_ptr(b) for _, b in pairs])
+    rows = (C.c_int32 * n)(*[a.element_size() * (a[0].numel() if S > 0 else 1) for a, _ in pairs])
+    _check(lib.ver_ingest_gather_batch(_ptr(order), S, n, srcs, rows, dsts, _stream()))
 
 
 def ver_is_weight(env_off, N, S, max_is, weight):

@@ -354,6 +354,45 @@ __global__ __launch_bounds__(ING_THREADS) void ingest_gather_kernel(const int32_
     }
 }
 
+// Several fields in one launch: a field takes the blocks [block_first[f], block_first[f + 1]) and moves its rows in
+// units of 16, 4 or 1 bytes (what its addresses and row size allow), exactly as a launch of its own would.
+struct GatherBatch {
+    const void* src[VER_INGEST_MAX_FIELDS];
+    void* dst[VER_INGEST_MAX_FIELDS];
+    int units[VER_INGEST_MAX_FIELDS];     // units per row
+    int unit[VER_INGEST_MAX_FIELDS];      // bytes per unit
+    int block_first[VER_INGEST_MAX_FIELDS + 1];
+    int n;
+};
+template <typename U>
+__device__ __forceinline__ void gather_field(const int32_t* __restrict__ order, long long total, int units, const void* src, void* dst,
+                                             int block, int blocks) {
+    const U* __restrict__ s = static_cast<const U*>(src);
+    U* __restrict__ d = static_cast<U*>(dst);
+    const long long stride = (long long)blocks * ING_THREADS;
+    for (long long i = (long long)block * ING_THREADS + threadIdx.x; i < total; i += stride) {
+        const long long k = i / units;
+        const int c = (int)(i - k * units);
+        d[i] = s[(long long)order[k] * units + c];
+    }
+}
+__global__ __launch_bounds__(ING_THREADS) void ingest_gather_batch_kernel(const int32_t* __restrict__ order, int S, GatherBatch g) {
+    int f = 0;
+#pragma unroll
+    for (int i = 1; i < VER_INGEST_MAX_FIELDS; ++i)
+        if (i < g.n && (int)blockIdx.x >= g.block_first[i]) f = i;
+    // (uniform selects: constant indices only, so that the arguments are read in place)
+    const void* src = g.src[0]; void* dst = g.dst[0];
+    int units = g.units[0], unit = g.unit[0], b0 = g.block_first[0], b1 = g.block_first[1];
+#pragma unroll
+    for (int i = 1; i < VER_INGEST_MAX_FIELDS; ++i)
+        if (f == i) { src = g.src[i]; dst = g.dst[i]; units = g.units[i]; unit = g.unit[i]; b0 = g.block_first[i]; b1 = g.block_first[i + 1]; }
+    const long long total = (long long)S * units;
+    if (unit == 16) gather_field<int4>(order, total, units, src, dst, blockIdx.x - b0, b1 - b0);
+    else if (unit == 4) gather_field<int32_t>(order, total, units, src, dst, blockIdx.x - b0, b1 - b0);
+    else gather_field<uint8_t>(order, total, units, src, dst, blockIdx.x - b0, b1 - b0);
+}
+
 inline int bits_for(int n) {   // bits needed to write the value n
     int b = 1;
     while ((n >> b) != 0) ++b;
@@ -494,5 +533,32 @@ extern "C" int ver_ingest_gather(const int32_t* order, int32_t S, const void* sr
     else
         hipLaunchKernelGGL(ingest_gather_kernel<uint8_t>, dim3((unsigned)blocks), dim3(ING_THREADS), 0, s, order, total,
                            units, static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst));
+    return launch_status();
+}
+
+extern "C" int ver_ingest_gather_batch(const int32_t* order, int32_t S, int32_t n_fields, const void* const* src,
+                                       const int32_t* row_bytes, void* const* dst, void* stream) {
+    using namespace ver;
+    if (S < 0 || n_fields < 0 || n_fields > VER_INGEST_MAX_FIELDS) return VER_EINVAL;
+    if (S == 0 || n_fields == 0) return VER_OK;
+    if (!order || !src || !row_bytes || !dst) return VER_EINVAL;
+    GatherBatch g{};
+    g.n = n_fields;
+    int blocks = 0;
+    for (int f = 0; f < n_fields; ++f) {
+        if (!src[f] || !dst[f] || src[f] == dst[f] || row_bytes[f] <= 0) return VER_EINVAL;
+        const uintptr_t both = reinterpret_cast<uintptr_t>(src[f]) | reinterpret_cast<uintptr_t>(dst[f]) | (uintptr_t)row_bytes[f];
+        const int unit = (both & 15) == 0 ? 16 : (both & 3) == 0 ? 4 : 1;
+        g.src[f] = src[f]; g.dst[f] = dst[f]; g.unit[f] = unit; g.units[f] = row_bytes[f] / unit;
+        const long long total = (long long)S * g.units[f];
+        long long b = (total + ING_THREADS - 1) / ING_THREADS;
+        if (b > 65536) b = 65536;
+        g.block_first[f] = blocks;
+        blocks += (int)b;
+    }
+    g.block_first[n_fields] = blocks;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ProfScope prof(VER_PROF_INGEST, s);
+    hipLaunchKernelGGL(ingest_gather_batch_kernel, dim3((unsigned)blocks), dim3(ING_THREADS), 0, s, order, S, g);
     return launch_status();
 }

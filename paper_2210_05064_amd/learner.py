@@ -176,12 +176,13 @@ class Learner:
 
     def ingest(self):
         ver.ver_ingest(self.arr_env, self.arr_t, self.N, self.S, self.env_off, self.order, self.ingest_info, self.ws_ingest)
+        pairs = []
         for src, dst, lead in self.arrival:
             if lead == 0:
-                ver.ver_ingest_gather(self.order, self.S, src, dst)
+                pairs.append((src, dst))
             else:
-                for j in range(src.shape[0]):
-                    ver.ver_ingest_gather(self.order, self.S, src[j], dst[j])
+                pairs += [(src[j], dst[j]) for j in range(src.shape[0])]
+        ver.ver_ingest_gather_batch(self.order, self.S, pairs)   # every per-step field in one launch
 
     def gae(self):
         ver.ver_gae(self.rewards, self.values, self.dones, self.last_values, self.env_off, self.N, self.S,

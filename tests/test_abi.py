@@ -145,6 +145,11 @@ def test_ingest_argument_checks(lib):
     assert lib.ver_ingest_gather(None, 0, None, 4, None, None) == 0        # nothing to move
     assert lib.ver_ingest_gather(None, 8, None, 4, None, None) == -1
     assert lib.ver_ingest_gather(None, 8, None, 0, None, None) == -1
+    lib.ver_ingest_gather_batch.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    assert lib.ver_ingest_gather_batch(None, 0, 3, None, None, None, None) == 0     # no steps: nothing to move
+    assert lib.ver_ingest_gather_batch(None, 8, 0, None, None, None, None) == 0     # no fields
+    assert lib.ver_ingest_gather_batch(None, 8, 2, None, None, None, None) == -1
+    assert lib.ver_ingest_gather_batch(None, 8, 25, None, None, None, None) == -1   # more than VER_INGEST_MAX_FIELDS
 
 
 def test_pack_index_batch_argument_checks(lib):

@@ -132,3 +132,31 @@ def test_argument_errors(ver):
         ver.ver_ingest(x, None, 4, 8, x, x, x, ver.workspace(16))      # workspace too small
     with pytest.raises(ver.VerError):
         ver.ver_ingest_gather(x, 8, x, x)                              # in place
+
+
+def test_gather_batch_matches_single_gathers(ver):
+    """Every field of a rollout in one launch: rows of 16-, 4- and 1-byte units, a field per layer of a state
+    array, against one ver_ingest_gather call per field."""
+    rng = np.random.default_rng(3)
+    S = 5000
+    order = dev(rng.permutation(S).astype(np.int32))
+    fields = [rng.standard_normal((S, 36)).astype(np.float32), rng.standard_normal((S, 5)).astype(np.float32),
+              rng.integers(0, 2, S).astype(np.uint8), rng.standard_normal(S).astype(np.float32),
+              rng.integers(0, 1 << 30, (S, 3)).astype(np.int32), rng.standard_normal((2, S, 64)).astype(np.float32)]
+    pairs, want = [], []
+    for f in fields:
+        src = dev(f)
+        for a in ([src] if f.ndim < 3 else [src[j] for j in range(f.shape[0])]):
+            single = torch.zeros_like(a)
+            ver.ver_ingest_gather(order, S, a, single)
+            pairs.append((a, torch.zeros_like(a)))
+            want.append(single)
+    ver.ver_ingest_gather_batch(order, S, pairs)
+    torch.cuda.synchronize()
+    for (_, got), ref in zip(pairs, want):
+        assert torch.equal(got, ref)
+    ver.ver_ingest_gather_batch(order, S, [])          # nothing to do
+    with pytest.raises(RuntimeError):
+        ver.ver_ingest_gather_batch(order, S, [(pairs[0][0], pairs[0][0])])   # in place
+    with pytest.raises(RuntimeError):
+        ver.ver_ingest_gather_batch(order, S, pairs * 4)                      # more fields than a launch takes
